@@ -1,0 +1,267 @@
+#!/usr/bin/env python3
+"""Benchmark of the DuHL hot path on one MI355X.
+
+A step is one round of the scheme over one synthetic problem: full gap evaluation -> top-m
+selection -> (column swap) -> one asynchronous coordinate-descent pass over the working set.
+Prints ONE JSON line: whole-step coordinate updates/s as `value`, the per-phase figures, the
+roofline of the dominant kernel (the dense gap pass, HBM-bound) and the CPU oracle timed beside.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--no-cpu] [--no-ttg]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+
+
+def build_problem(name, device, scale):
+    import torch
+    from paper_1708_05357_amd import synth
+    cfg = synth.CONFIGS[name]
+    out = None
+    if cfg.get("host_resident"):
+        n = max(8, int(cfg["n"] * scale)) if scale != 1.0 else cfg["n"]
+        out = torch.empty((n, cfg["d"]), dtype=torch.float32, pin_memory=True)
+    t0 = time.time()
+    prob = synth.make(name, seed=0, device=device, scale=scale, out=out)
+    torch.cuda.synchronize()
+    prob["gen_s"] = time.time() - t0
+    prob["host_resident"] = bool(cfg.get("host_resident"))
+    return prob
+
+
+def make_ctx(prob, budget):
+    from paper_1708_05357_amd import duhl
+    model = duhl.LASSO if prob["model"] == "lasso" else duhl.SVM
+    g = duhl.Duhl(model, prob["d"], prob["n"], budget)
+
+    def set_data():
+        if "cols" in prob:
+            g.set_data_dense(prob["cols"], prob["target"], prob["lam"],
+                             duhl.RESIDENT_HOST if prob["host_resident"] else duhl.RESIDENT_DEVICE)
+        else:
+            g.set_data_csr(prob["rowptr"], prob["colidx"], prob["val"], prob["target"], prob["lam"])
+    set_data()
+    return g, set_data
+
+
+def algorithmic_bytes(prob, m):
+    """Bytes one launch must move at least: the matrix once per gap pass (plus alpha, z), the
+    working set once per CD pass."""
+    d, n = prob["d"], prob["n"]
+    if "cols" in prob:
+        return 4.0 * d * n + 8.0 * n, 4.0 * d * m
+    nnz = int(prob["val"].numel())
+    per = 8.0 * nnz / n
+    return 8.0 * nnz + 8.0 * (n + 1) + 12.0 * n, per * m + 8.0 * m
+
+
+def one_step(g, prob, m, step, ev=None, sample_idx=None):
+    """gap -> select -> commit -> epoch.  With host residency the gaps are refreshed for the
+    resident columns plus a sample of the others (stale gap memory, Section 4.1)."""
+    from paper_1708_05357_amd import duhl
+    if ev:
+        ev[0].record()
+    g.gap(want_sum=False)
+    if prob["host_resident"] and sample_idx is not None:
+        g.gap(sample_idx[step % len(sample_idx)], want_sum=False)
+    if ev:
+        ev[1].record()
+    g.select(m, want_stats=False)
+    overlapped = prob["host_resident"] and g.working_set_size() > 0
+    if not overlapped:
+        g.commit_swap()
+    if ev:
+        ev[2].record()
+    g.cd_epoch(duhl.CD_ASYNC, seed=step)       # host residency: runs while the copies are in flight
+    if ev:
+        ev[3].record()
+    if overlapped:
+        g.commit_swap()
+
+
+def time_to_gap(g, set_data, prob, m, target, max_rounds, passes):
+    """Wall time from alpha = 0 until a fresh full gap pass reports total gap <= target
+    (absolute, with the paper's 1/d or 1/n normalisation) and <= target * O(0)."""
+    import torch
+    from paper_1708_05357_amd import duhl
+    set_data()
+    o0 = g.objective()
+    all_idx = None
+    if prob["host_resident"]:
+        all_idx = torch.arange(prob["n"], dtype=torch.int32, device="cuda")
+    torch.cuda.synchronize()
+    t0 = time.time()
+    t_abs = t_rel = None
+    rounds = 0
+    gap = float("inf")
+    for rnd in range(max_rounds):
+        gap = g.gap(all_idx) if all_idx is not None else g.gap()
+        now = time.time() - t0
+        if t_abs is None and gap <= target:
+            t_abs = now
+        if t_rel is None and gap <= target * abs(o0):
+            t_rel = now
+        if t_abs is not None and t_rel is not None:
+            break
+        g.select(m, want_stats=False)
+        g.commit_swap()
+        for k in range(passes):
+            g.cd_epoch(duhl.CD_ASYNC, seed=1000 + rnd * passes + k)
+        rounds = rnd + 1
+    return {"abs_1e-3_s": t_abs, "rel_1e-3_s": t_rel, "rounds": rounds, "final_gap": gap,
+            "objective_at_zero": o0, "final_objective": g.objective(), "passes_per_round": passes}
+
+
+def cpu_baseline(prob, m, budget_s=20.0):
+    """The oracle as it stands, single thread, on the same inputs: rounds of full gap pass,
+    selection and one CD pass from alpha = 0, for about budget_s seconds (at least one round;
+    on a column subsample when a round would not fit)."""
+    import numpy as np
+    from oracle import duhl_oracle as orc
+    model = orc.LASSO if prob["model"] == "lasso" else orc.SVM
+    n, d = prob["n"], prob["d"]
+    sample = "full workload"
+    frac = 1.0
+    if "cols" in prob:
+        bytes_total = 4.0 * n * d
+        if bytes_total > 8e9:                       # too large for the host: column subsample
+            frac = 8e9 / bytes_total
+        ns = int(n * frac)
+        cols = prob["cols"][:ns].cpu().numpy()
+        o = orc.Oracle(model, prob["target"].cpu().numpy(), prob["lam"], cols=cols)
+    else:
+        ns = n
+        o = orc.Oracle(model, prob["target"].cpu().numpy(), prob["lam"],
+                       csr=(prob["rowptr"].cpu().numpy(), prob["colidx"].cpu().numpy(),
+                            prob["val"].cpu().numpy()), d=d)
+    ms = max(1, int(m * frac))
+    if frac < 1.0:
+        sample = f"first {ns} of {n} columns at full length, m scaled to {ms}; rate is per update"
+    rng = np.random.default_rng(0)
+    t_gap = t_cd = 0.0
+    rounds = 0
+    t_start = time.time()
+    while True:
+        t0 = time.time()
+        o.gaps()
+        t1 = time.time()
+        P = o.select(ms)
+        order = P[rng.permutation(P.size)]
+        t2 = time.time()
+        o.cd_pass(order)
+        t3 = time.time()
+        t_gap += t1 - t0
+        t_cd += t3 - t2
+        rounds += 1
+        if time.time() - t_start > budget_s or rounds >= 50:
+            break
+    total = time.time() - t_start
+    return {"value": ms * rounds / total, "unit": "coordinate updates/s", "cores": 1, "kind": "oracle",
+            "sample": f"{sample}; {rounds} rounds of gap pass + top-m + one CD pass, fp64, 1 thread",
+            "gap_pass_s": t_gap / rounds, "cd_pass_s": t_cd / rounds,
+            "gap_GBps": (4.0 * d * ns if "cols" in prob else 8.0 * prob["val"].numel()) / (t_gap / rounds) / 1e9,
+            "cd_updates_per_s": ms / (t_cd / rounds)}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink n (and m) at fixed d")
+    ap.add_argument("--budget-factor", type=float, default=2.0,
+                    help="device slots per working-set column (host residency)")
+    ap.add_argument("--no-cpu", action="store_true")
+    ap.add_argument("--no-ttg", action="store_true")
+    ap.add_argument("--ttg-passes", type=int, default=1)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures the single-GPU hot path; this build has no multi-GPU path "
+              "(--gpus must be 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_1708_05357_amd import duhl
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    prob = build_problem(args.workload, "cuda", args.scale)
+    m = prob["m"]
+    budget = int(m * args.budget_factor) if prob["host_resident"] else m
+    g, set_data = make_ctx(prob, budget)
+    sample_idx = None
+    if prob["host_resident"]:
+        # 5 % of the columns per round, refreshed from host memory (Section 5.1)
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(1)
+        k = max(1, prob["n"] // 20)
+        sample_idx = [torch.randperm(prob["n"], generator=gen, device="cuda")[:k].to(torch.int32).contiguous()
+                      for _ in range(8)]
+
+    for s in range(args.warmup):
+        one_step(g, prob, m, s, sample_idx=sample_idx)
+    torch.cuda.synchronize()
+    set_data()                                  # back to alpha = 0: the timed rounds are rounds 1..K
+    torch.cuda.synchronize()
+
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.time()
+    for s in range(args.steps):
+        one_step(g, prob, m, s, evs[s], sample_idx)
+    torch.cuda.synchronize()
+    elapsed = time.time() - t0
+
+    gap_ms = [e[0].elapsed_time(e[1]) for e in evs]
+    sel_ms = [e[1].elapsed_time(e[2]) for e in evs]
+    cd_ms = [e[2].elapsed_time(e[3]) for e in evs]
+    avg = lambda x: sum(x) / len(x)
+    gap_bytes, cd_bytes = algorithmic_bytes(prob, m)
+    if prob["host_resident"]:
+        gap_bytes = 4.0 * prob["d"] * budget     # resident part only; the sample is link-bound
+    gap_gbps = gap_bytes / (avg(gap_ms) * 1e-3) / 1e9
+    cd_gbps = cd_bytes / (avg(cd_ms) * 1e-3) / 1e9
+    final_gap = g.gap() if not prob["host_resident"] else None
+    final_obj = g.objective()
+
+    out = {
+        "metric": "coordinate updates/s (whole round: gap pass + top-m + CD pass)",
+        "value": m * args.steps / elapsed,
+        "unit": "coordinate updates/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": elapsed / args.steps * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {prob['model']} d={prob['d']} n={prob['n']} m={m}"
+                               + (f" host-resident, {budget} device slots" if prob["host_resident"] else ""),
+                   "scale": args.scale, "rounds_timed": args.steps, "passes_per_round": 1},
+        "phases": {"gap_ms": avg(gap_ms), "select_ms": avg(sel_ms), "cd_ms": avg(cd_ms),
+                   "gap_GBps": gap_gbps, "gap_frac_of_hbm_peak": gap_gbps / HBM_PEAK_GBPS,
+                   "cd_updates_per_s": m / (avg(cd_ms) * 1e-3), "cd_GBps": cd_gbps,
+                   "cd_frac_of_hbm_peak": cd_gbps / HBM_PEAK_GBPS,
+                   "gap_ms_min": min(gap_ms), "cd_ms_min": min(cd_ms), "cd_ms_max": max(cd_ms)},
+        "roofline": {"kernel": "gap_dense_kernel" if "cols" in prob else "gap_csr_kernel",
+                     "bound": "hbm", "achieved": gap_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": gap_gbps / HBM_PEAK_GBPS, "traffic": None},
+        "after_timed_rounds": {"total_gap": final_gap, "objective": final_obj},
+        "gen_s": prob["gen_s"],
+    }
+    if not args.no_ttg:
+        out["time_to_gap"] = time_to_gap(g, set_data, prob, m, 1e-3, 400, args.ttg_passes)
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(prob, m)
+    else:
+        out["cpu_baseline"] = None
+    g.close()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,163 @@
+/*
+ * duhl.h -- C ABI of the DuHL hot path for AMD MI355X (gfx950).
+ *
+ * DuHL (Algorithm 2 of the paper) trains a generalized linear model
+ *     min_alpha  f(A alpha) + sum_i g_i(alpha_i),     A = [a_1 .. a_n] in R^{d x n}   (eq. (1))
+ * on a fast unit with limited memory: each round it picks the m coordinates with the
+ * largest coordinate-wise duality gap (eq. (4), (11), (13)), keeps their columns in the
+ * fast unit's memory and runs randomized coordinate descent on them against the shared
+ * vector v (Section 4.1, Appendix D).  This library is that per-round work on one GPU:
+ *
+ *     duhl_gap       per-coordinate gaps  z_i            (eq. (4); Appendix E)
+ *     duhl_select    top-m working set P, rho            (eq. (11)/(13); eq. (7))
+ *     duhl_cd_epoch  one pass of exact coordinate steps   (Algorithm 3; Appendix D)
+ *     column swap    host -> device copy of new columns   (Algorithm 2, "refresh memory B")
+ *     duhl_objective O(alpha)                             (Appendix C (b), (c))
+ *
+ * Models.  DUHL_LASSO:  O = ||A alpha - b||^2/(2d) + lambda ||alpha||_1, shared vector
+ * v = A alpha - b.  DUHL_SVM (hinge loss, dual): O = -(1/n) sum y_i alpha_i +
+ * ||A alpha||^2/(2 lambda n^2) with y_i alpha_i in [0,1], shared vector v = A alpha; a column
+ * of A is one sample.  All data and state are fp32; scalar results are returned as double.
+ *
+ * General rules.  Every call returns a duhl_status and never throws or aborts.  On error
+ * the out-parameters are untouched and duhl_last_error() describes the cause.  Arrays passed
+ * in stay owned by the caller; "borrowed" arrays (the matrix and the target vector) must
+ * outlive the context.  The library owns alpha, v, z, the column norms and the slot buffers
+ * (hipMalloc).  Work is enqueued on the two streams given at creation; a call that returns a
+ * scalar to the host waits for the compute stream.  A context is not thread-safe.
+ * "device" / "host" below says in which memory a pointer must live.
+ */
+#ifndef DUHL_H
+#define DUHL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct duhl_ctx duhl_ctx;
+
+typedef enum { DUHL_LASSO = 0, DUHL_SVM = 1 } duhl_model;
+
+typedef enum {
+    DUHL_OK = 0,
+    DUHL_EINVAL = -1,   /* bad argument (null pointer, size, lambda, malformed CSR, label)   */
+    DUHL_ENOMEM = -2,   /* device or host allocation failed                                  */
+    DUHL_EHIP = -3,     /* a HIP runtime call failed                                         */
+    DUHL_ESTATE = -4,   /* call out of order (no data yet, no working set, swap in flight)   */
+    DUHL_EBUDGET = -5   /* m exceeds the column budget given at creation                     */
+} duhl_status;
+
+/* Where the matrix lives (Assumption 1: unit A holds everything, unit B a subset). */
+typedef enum {
+    DUHL_RESIDENT_DEVICE = 0, /* whole matrix in HBM; the working set is an index list        */
+    DUHL_RESIDENT_HOST = 1    /* matrix in pinned, device-mapped host memory; the library
+                                 keeps budget_cols columns in device slots and swaps          */
+} duhl_residency;
+
+typedef enum { DUHL_ALPHA = 0, DUHL_V = 1, DUHL_Z = 2, DUHL_P = 3, DUHL_SQNORM = 4 } duhl_what;
+
+/* Visiting scheme of duhl_cd_epoch. */
+typedef enum {
+    DUHL_CD_SEQUENTIAL = 0, /* one coordinate at a time, in the given order (Algorithm 3)     */
+    DUHL_CD_ASYNC = 1       /* many coordinates in flight, atomic adds on v (Appendix D)      */
+} duhl_cd_mode;
+
+/* Create a context for a problem with columns of length d and n coordinates.
+ * budget_cols: the largest working set (and, for DUHL_RESIDENT_HOST, the number of device
+ * column slots); 1 <= budget_cols.  device: HIP device ordinal.  compute_stream / copy_stream:
+ * hipStream_t handles (NULL = the default stream); both must have the default priority. */
+duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n,
+                        int64_t budget_cols, int device, void *compute_stream, void *copy_stream);
+
+/* Dense data (Section 2: A in R^{d x n}, fp32 per Section 5.3).  A: column-major, column i at
+ * A + i*ld, ld >= d; a device pointer for DUHL_RESIDENT_DEVICE, a pinned host pointer that the
+ * device can read for DUHL_RESIDENT_HOST; borrowed.  target (device, borrowed): b of length d
+ * for the Lasso, labels y in {+1,-1} of length n for the SVM.  lambda: the lambda of the
+ * objectives above, finite and > 0.  Resets alpha = 0, v = -b (Lasso) or 0 (SVM), computes the
+ * column norms and a first full gap pass into z (one read of A).  Waits for completion. */
+duhl_status duhl_set_data_dense(duhl_ctx *ctx, const float *A, int64_t ld, duhl_residency res,
+                                const float *target, double lambda);
+
+/* Sparse data: CSR over coordinates, i.e. row i lists the non-zeros of column a_i (for the SVM
+ * dual: CSR of the sample matrix).  rowptr (n+1, non-decreasing, rowptr[0] = 0), colidx (each
+ * in [0,d)), val: device pointers, borrowed.  Only DUHL_RESIDENT_DEVICE.  Otherwise as above. */
+duhl_status duhl_set_data_csr(duhl_ctx *ctx, const int64_t *rowptr, const int32_t *colidx,
+                              const float *val, duhl_residency res, const float *target,
+                              double lambda);
+
+/* Coordinate-wise duality gaps (eq. (4)) at the current (alpha, v), written into the gap
+ * memory z of Section 4.1:
+ *   Lasso (Appendix E, Lipschitzing bound B = ||b||^2/(2 lambda d)), c_i = a_i^T v:
+ *       z_i = (1/d) [ alpha_i c_i + B [|c_i| - lambda d]_+ + lambda d |alpha_i| ]
+ *   SVM (Appendix E), s_i = a_i^T v / (lambda n):
+ *       z_i = (1/n) [ alpha_i s_i + max(0, 1 - y_i s_i) - y_i alpha_i ]
+ * clamped at 0.  idx (device, int32, each in [0,n), no duplicates) lists the `count`
+ * coordinates to refresh; idx == NULL refreshes all n coordinates (device residency) or every
+ * column currently held in a device slot (host residency), and count is then ignored.  Other
+ * entries of z keep their (stale) values.  gap_sum (host, may be NULL): sum of the entries
+ * written, the total gap when all were asked for; non-NULL makes the call wait. */
+duhl_status duhl_gap(duhl_ctx *ctx, const int32_t *idx, int64_t count, double *gap_sum);
+
+/* Working-set selection (eq. (13)): the m coordinates with the largest z, ties to the smaller
+ * index; 1 <= m <= min(n, budget_cols).  The set becomes the *pending* working set; with host
+ * residency the columns it lacks are copied into free device slots on the copy stream while
+ * the compute stream stays free for duhl_cd_epoch on the current set (Figure 2).  That overlap
+ * needs budget_cols >= |current| + m; with fewer slots the copy first waits for the compute
+ * stream and duhl_cd_epoch is refused (DUHL_ESTATE) until duhl_commit_swap.
+ * P_out (device, m int32, may be NULL): the set in ascending order.  n_swapped (host, may be
+ * NULL): columns that have to be copied.  rho (host, may be NULL): eq. (7) evaluated on z,
+ * (mean of z over P)/(mean of z over all).  Non-NULL host outputs make the call wait for the
+ * compute stream (not for the copies). */
+duhl_status duhl_select(duhl_ctx *ctx, int64_t m, int32_t *P_out, int64_t *n_swapped,
+                        double *rho);
+
+/* Make the pending working set current: the compute stream waits (on the device, not the
+ * host) for the column copies, then later calls see the new set.  DUHL_ESTATE if nothing is
+ * pending. */
+duhl_status duhl_commit_swap(duhl_ctx *ctx);
+
+/* One pass of exact coordinate steps over the current working set (Appendix D):
+ *   Lasso:  gamma = alpha_j - a_j^T v/||a_j||^2,  alpha_j <- sign(gamma)[|gamma| - lambda d/||a_j||^2]_+
+ *   SVM:    alpha_j <- y_j clip(y_j(alpha_j + (y_j - a_j^T v/(lambda n)) lambda n/||a_j||^2), 0, 1)
+ *   both:   v <- v + a_j (alpha_j_new - alpha_j_old)
+ * order (device, int32): the coordinates to visit, in visiting order; each must belong to the
+ * current working set; n_order entries.  order == NULL: the whole set -- ascending for
+ * DUHL_CD_SEQUENTIAL, a pseudo-random permutation drawn from (seed, pass counter) for
+ * DUHL_CD_ASYNC.  DUHL_CD_SEQUENTIAL solves one coordinate after the other and is
+ * reproducible.  DUHL_CD_ASYNC solves up to max_inflight coordinates concurrently (0 = chosen
+ * by the library), each against the v it happens to read; v is updated with atomic adds, so
+ * v = A alpha (- b) keeps holding up to rounding but iterates depend on timing. */
+duhl_status duhl_cd_epoch(duhl_ctx *ctx, duhl_cd_mode mode, const int32_t *order,
+                          int64_t n_order, uint64_t seed, int max_inflight);
+
+/* O(alpha) from the stored v and alpha (Appendix C).  objective: host.  Waits. */
+duhl_status duhl_objective(duhl_ctx *ctx, double *objective);
+
+/* v := A alpha - b (Lasso) or A alpha (SVM) from scratch; removes the rounding drift of many
+ * atomic adds.  Reads every column with alpha_j != 0 (from the host when not in a slot). */
+duhl_status duhl_recompute_v(duhl_ctx *ctx);
+
+/* Copy state to / from host memory (fp32; DUHL_P: int32, the current working set).  len must
+ * be n (ALPHA, Z, SQNORM), d (V) or the working-set size (P, see duhl_working_set_size).
+ * Both wait for the compute stream.  duhl_set accepts ALPHA, V and Z only. */
+duhl_status duhl_get(duhl_ctx *ctx, duhl_what what, void *dst_host, int64_t len);
+duhl_status duhl_set(duhl_ctx *ctx, duhl_what what, const void *src_host, int64_t len);
+
+/* Device address of a state array, for callers that keep their own views (borrowed). */
+duhl_status duhl_device_ptr(duhl_ctx *ctx, duhl_what what, void **ptr);
+
+/* Size of the current working set (0 before the first commit). */
+int64_t duhl_working_set_size(const duhl_ctx *ctx);
+
+/* Text of the last error of this context ("" if none); valid until the next call on it. */
+const char *duhl_last_error(const duhl_ctx *ctx);
+
+/* Release everything the library allocated.  NULL is allowed. */
+void duhl_destroy(duhl_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DUHL_H */

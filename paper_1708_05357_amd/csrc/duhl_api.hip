@@ -1,0 +1,446 @@
+// Host side of libduhl: the extern "C" entry points declared in duhl.h.
+// Argument checks, memory, stream/event choreography; all arithmetic is in the kernels.
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstdlib>
+#include <new>
+
+#include "duhl_internal.h"
+
+using namespace duhl;
+
+namespace {
+
+duhl_status fail(duhl_ctx *c, duhl_status st, const char *fmt, ...)
+{
+    if (c) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        c->err = buf;
+    }
+    return st;
+}
+
+#define HIPCHK(c, expr)                                                                       \
+    do {                                                                                      \
+        hipError_t e_ = (expr);                                                               \
+        if (e_ != hipSuccess)                                                                 \
+            return fail((c), e_ == hipErrorOutOfMemory ? DUHL_ENOMEM : DUHL_EHIP, "%s: %s",   \
+                        #expr, hipGetErrorString(e_));                                        \
+    } while (0)
+
+int env_int(const char *name, int dflt)
+{
+    const char *s = getenv(name);
+    return (s && *s) ? atoi(s) : dflt;
+}
+
+template <typename T>
+hipError_t dev_alloc(T **p, int64_t count)
+{
+    *p = nullptr;
+    return hipMalloc(reinterpret_cast<void **>(p), (size_t)(count > 0 ? count : 1) * sizeof(T));
+}
+
+void free_host_residency(duhl_ctx *c)
+{
+    (void)hipFree(c->slots); c->slots = nullptr;
+    (void)hipFree(c->col_slot); c->col_slot = nullptr;
+    (void)hipFree(c->slot_col); c->slot_col = nullptr;
+    (void)hipFree(c->fill_col); c->fill_col = nullptr;
+    (void)hipFree(c->fill_slot); c->fill_slot = nullptr;
+    (void)hipFree(c->evict_slot); c->evict_slot = nullptr;
+    if (c->ev_plan) { (void)hipEventDestroy(c->ev_plan); c->ev_plan = nullptr; }
+    if (c->ev_copy) { (void)hipEventDestroy(c->ev_copy); c->ev_copy = nullptr; }
+}
+
+// Read `count` doubles of the device scalar block after the compute stream has drained.
+duhl_status read_scalars(duhl_ctx *c, int first, int count)
+{
+    HIPCHK(c, hipMemcpyAsync(c->h_scalars + first, c->scalars + first, sizeof(double) * count,
+                             hipMemcpyDeviceToHost, c->compute));
+    HIPCHK(c, hipStreamSynchronize(c->compute));
+    return DUHL_OK;
+}
+
+// Everything set_data does after the matrix view is in place.
+duhl_status finish_set_data(duhl_ctx *c, const float *target, double lambda)
+{
+    c->target = target;
+    c->lambda = lambda;
+    c->cv.col_slot = c->col_slot;
+    c->cv.slots = c->slots;
+    c->cv.ld_s = c->ld_s;
+
+    HIPCHK(c, launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(&c->sel->error), 1, 0));
+    HIPCHK(c, launch_validate(c));
+    HIPCHK(c, hipMemcpyAsync(c->h_u32, &c->sel->error, sizeof(uint32_t), hipMemcpyDeviceToHost,
+                             c->compute));
+    HIPCHK(c, hipStreamSynchronize(c->compute));
+    const uint32_t flags = c->h_u32[0];
+    if (flags & 1u) return fail(c, DUHL_EINVAL, "labels must be +1 or -1");
+    if (flags & 8u) return fail(c, DUHL_EINVAL, "target vector holds a non-finite value");
+    if (flags & 2u) return fail(c, DUHL_EINVAL, "rowptr must start at 0 and be non-decreasing");
+    if (flags & 4u)
+        return fail(c, DUHL_EINVAL,
+                    "column indices must lie in [0,d) and increase strictly inside a row");
+
+    HIPCHK(c, launch_fill_f32(c->compute, c->alpha, c->n, 0.0f));
+    HIPCHK(c, launch_fill_f32(c->compute, c->z, c->n, 0.0f));
+    HIPCHK(c, launch_init_v(c));
+
+    ModelConst mc{};
+    mc.model = c->model;
+    const double d = (double)c->d, n = (double)c->n;
+    if (c->model == DUHL_LASSO) {
+        duhl_status st = read_scalars(c, S_BSQ, 1);
+        if (st != DUHL_OK) return st;
+        mc.Lam = (float)(lambda * d);
+        mc.B = (float)(c->h_scalars[S_BSQ] / (2.0 * lambda * d));   // Appendix E: ||b||^2/(2 lambda d)
+        mc.inv_d = (float)(1.0 / d);
+    } else {
+        mc.lam_n = (float)(lambda * n);
+        mc.inv_lam_n = (float)(1.0 / (lambda * n));
+        mc.inv_n = (float)(1.0 / n);
+    }
+    c->mc = mc;
+    c->m_cur = c->m_next = 0;
+    c->pending = c->swap_exclusive = false;
+    c->pass_counter = 0;
+    c->have_data = true;
+    // column norms and a first full gap pass in one read of the matrix
+    HIPCHK(c, launch_gap(c, nullptr, c->n, false, true));
+    HIPCHK(c, hipStreamSynchronize(c->compute));
+    HIPCHK(c, hipGetLastError());
+    return DUHL_OK;
+}
+
+duhl_status check_common(duhl_ctx *c, const void *target, double lambda)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!target) return fail(c, DUHL_EINVAL, "target is NULL");
+    if (!(lambda > 0.0) || !std::isfinite(lambda)) return fail(c, DUHL_EINVAL, "lambda must be finite and > 0");
+    return DUHL_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, int64_t budget_cols,
+                        int device, void *compute_stream, void *copy_stream)
+{
+    if (!out) return DUHL_EINVAL;
+    if (model != DUHL_LASSO && model != DUHL_SVM) return DUHL_EINVAL;
+    if (d <= 0 || n <= 0 || budget_cols <= 0 || n > 0x7fffffffll || d > 0x7fffffffll) return DUHL_EINVAL;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return DUHL_EHIP;
+    if (hipSetDevice(device) != hipSuccess) return DUHL_EHIP;
+    duhl_ctx *c = new (std::nothrow) duhl_ctx();
+    if (!c) return DUHL_ENOMEM;
+    c->model = model;
+    c->d = d;
+    c->n = n;
+    c->budget = budget_cols < n ? budget_cols : n;
+    c->device = device;
+    c->compute = reinterpret_cast<hipStream_t>(compute_stream);
+    c->copy = reinterpret_cast<hipStream_t>(copy_stream);
+    c->num_cu = 256;
+    (void)hipDeviceGetAttribute(&c->num_cu, hipDeviceAttributeMultiprocessorCount, device);
+    c->gap_cols = env_int("DUHL_GAP_COLS", d < 4096 ? 8 : 4);
+    if (c->gap_cols != 1 && c->gap_cols != 2 && c->gap_cols != 4 && c->gap_cols != 8) c->gap_cols = 4;
+    c->cd_threads = env_int("DUHL_CD_THREADS", 0);
+    c->copy_blocks = env_int("DUHL_COPY_BLOCKS", 32);
+    if (c->copy_blocks < 1) c->copy_blocks = 1;
+
+    c->partials_cap = n / 4 + 4096;
+    c->blk_cap = (n + 2047) / 2048 + 1;
+    hipError_t e = hipSuccess;
+    auto ok = [&](hipError_t r) { if (e == hipSuccess) e = r; };
+    ok(dev_alloc(&c->alpha, n));
+    ok(dev_alloc(&c->v, d + 4));
+    ok(dev_alloc(&c->z, n));
+    ok(dev_alloc(&c->q, n));
+    ok(dev_alloc(&c->P_cur, c->budget));
+    ok(dev_alloc(&c->P_next, c->budget));
+    ok(dev_alloc(&c->scalars, (int64_t)S_COUNT));
+    ok(dev_alloc(&c->partials, c->partials_cap));
+    ok(dev_alloc(&c->sel, (int64_t)1));
+    ok(dev_alloc(&c->blk_gt, c->blk_cap));
+    ok(dev_alloc(&c->blk_eq, c->blk_cap));
+    ok(dev_alloc(&c->mark, n));
+    ok(hipHostMalloc(reinterpret_cast<void **>(&c->h_scalars), sizeof(double) * S_COUNT, hipHostMallocDefault));
+    ok(hipHostMalloc(reinterpret_cast<void **>(&c->h_u32), sizeof(uint32_t) * 4, hipHostMallocDefault));
+    if (e == hipSuccess) e = hipMemset(c->sel, 0, sizeof(SelectState));
+    if (e != hipSuccess) {
+        duhl_destroy(c);
+        return e == hipErrorOutOfMemory ? DUHL_ENOMEM : DUHL_EHIP;
+    }
+    *out = c;
+    return DUHL_OK;
+}
+
+duhl_status duhl_set_data_dense(duhl_ctx *c, const float *A, int64_t ld, duhl_residency res,
+                                const float *target, double lambda)
+{
+    duhl_status st = check_common(c, target, lambda);
+    if (st != DUHL_OK) return st;
+    if (!A) return fail(c, DUHL_EINVAL, "A is NULL");
+    if (ld < c->d) return fail(c, DUHL_EINVAL, "ld (%lld) < d (%lld)", (long long)ld, (long long)c->d);
+    if (res != DUHL_RESIDENT_DEVICE && res != DUHL_RESIDENT_HOST) return fail(c, DUHL_EINVAL, "bad residency");
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, hipStreamSynchronize(c->compute));
+    c->have_data = false;
+    free_host_residency(c);
+    c->sparse = false;
+    c->res = res;
+    c->nnz = c->d * c->n;
+    c->cv = ColView{};
+    c->cv.ld = ld;
+    if (res == DUHL_RESIDENT_DEVICE) {
+        c->cv.base = A;
+        c->ld_s = 0;
+    } else {
+        void *dptr = nullptr;
+        if (hipHostGetDevicePointer(&dptr, const_cast<float *>(A), 0) != hipSuccess || !dptr) {
+            (void)hipGetLastError();
+            return fail(c, DUHL_EINVAL, "host-resident A must be pinned, device-mapped host memory");
+        }
+        c->cv.base = static_cast<const float *>(dptr);
+        c->ld_s = (c->d + 63) / 64 * 64;
+        HIPCHK(c, dev_alloc(&c->slots, c->budget * c->ld_s));
+        HIPCHK(c, dev_alloc(&c->col_slot, c->n));
+        HIPCHK(c, dev_alloc(&c->slot_col, c->budget));
+        HIPCHK(c, dev_alloc(&c->fill_col, c->budget));
+        HIPCHK(c, dev_alloc(&c->fill_slot, c->budget));
+        HIPCHK(c, dev_alloc(&c->evict_slot, c->budget));
+        HIPCHK(c, hipEventCreateWithFlags(&c->ev_plan, hipEventDisableTiming));
+        HIPCHK(c, hipEventCreateWithFlags(&c->ev_copy, hipEventDisableTiming));
+        HIPCHK(c, launch_fill_i32(c->compute, c->col_slot, c->n, -1));
+        HIPCHK(c, launch_fill_i32(c->compute, c->slot_col, c->budget, -1));
+    }
+    return finish_set_data(c, target, lambda);
+}
+
+duhl_status duhl_set_data_csr(duhl_ctx *c, const int64_t *rowptr, const int32_t *colidx,
+                              const float *val, duhl_residency res, const float *target, double lambda)
+{
+    duhl_status st = check_common(c, target, lambda);
+    if (st != DUHL_OK) return st;
+    if (!rowptr || !colidx || !val) return fail(c, DUHL_EINVAL, "CSR array is NULL");
+    if (res != DUHL_RESIDENT_DEVICE)
+        return fail(c, DUHL_EINVAL, "sparse data must be device-resident");
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, hipStreamSynchronize(c->compute));
+    c->have_data = false;
+    free_host_residency(c);
+    c->sparse = true;
+    c->res = res;
+    c->cv = ColView{};
+    c->cv.rowptr = rowptr;
+    c->cv.colidx = colidx;
+    c->cv.val = val;
+    c->ld_s = 0;
+    int64_t last = 0;
+    HIPCHK(c, hipMemcpy(&last, rowptr + c->n, sizeof(int64_t), hipMemcpyDeviceToHost));
+    if (last < 0) return fail(c, DUHL_EINVAL, "rowptr[n] is negative");
+    c->nnz = last;
+    return finish_set_data(c, target, lambda);
+}
+
+duhl_status duhl_gap(duhl_ctx *c, const int32_t *idx, int64_t count, double *gap_sum)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!c->have_data) return fail(c, DUHL_ESTATE, "no data set");
+    if (idx && (count < 0 || count > c->n)) return fail(c, DUHL_EINVAL, "count out of range");
+    HIPCHK(c, hipSetDevice(c->device));
+    if (idx)
+        HIPCHK(c, launch_gap(c, idx, count, false, false));
+    else if (c->res == DUHL_RESIDENT_HOST)
+        HIPCHK(c, launch_gap(c, nullptr, c->budget, true, false));
+    else
+        HIPCHK(c, launch_gap(c, nullptr, c->n, false, false));
+    if (gap_sum) {
+        duhl_status st = read_scalars(c, S_GAP_SUM, 1);
+        if (st != DUHL_OK) return st;
+        *gap_sum = c->h_scalars[S_GAP_SUM];
+    }
+    return DUHL_OK;
+}
+
+duhl_status duhl_select(duhl_ctx *c, int64_t m, int32_t *P_out, int64_t *n_swapped, double *rho)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!c->have_data) return fail(c, DUHL_ESTATE, "no data set");
+    if (m < 1 || m > c->n) return fail(c, DUHL_EINVAL, "m must be in [1, n]");
+    if (m > c->budget) return fail(c, DUHL_EBUDGET, "m (%lld) exceeds the column budget (%lld)",
+                                   (long long)m, (long long)c->budget);
+    const bool host = c->res == DUHL_RESIDENT_HOST;
+    if (host && c->pending)
+        return fail(c, DUHL_ESTATE, "the previous selection has not been committed");
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, launch_select(c, m, P_out));
+    c->m_next = m;
+    c->pending = true;
+    const bool overlap_safe = c->budget >= c->m_cur + m;
+    c->swap_exclusive = host && !overlap_safe;
+    HIPCHK(c, launch_plan_swap(c, host ? overlap_safe : true));
+    if (host) {
+        HIPCHK(c, hipEventRecord(c->ev_plan, c->compute));
+        HIPCHK(c, hipStreamWaitEvent(c->copy, c->ev_plan, 0));
+        HIPCHK(c, launch_copy_columns(c));
+        HIPCHK(c, hipEventRecord(c->ev_copy, c->copy));
+    }
+    if (n_swapped || rho) {
+        HIPCHK(c, hipMemcpyAsync(c->h_u32, &c->sel->n_fill, sizeof(uint32_t), hipMemcpyDeviceToHost,
+                                 c->compute));
+        duhl_status st = read_scalars(c, S_RHO, 1);
+        if (st != DUHL_OK) return st;
+        if (n_swapped) *n_swapped = (int64_t)c->h_u32[0];
+        if (rho) *rho = c->h_scalars[S_RHO];
+    }
+    return DUHL_OK;
+}
+
+duhl_status duhl_commit_swap(duhl_ctx *c)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!c->pending) return fail(c, DUHL_ESTATE, "no selection is pending");
+    HIPCHK(c, hipSetDevice(c->device));
+    if (c->res == DUHL_RESIDENT_HOST) {
+        HIPCHK(c, hipStreamWaitEvent(c->compute, c->ev_copy, 0));
+        HIPCHK(c, launch_publish(c));
+    }
+    int32_t *t = c->P_cur;
+    c->P_cur = c->P_next;
+    c->P_next = t;
+    c->m_cur = c->m_next;
+    c->pending = c->swap_exclusive = false;
+    return DUHL_OK;
+}
+
+duhl_status duhl_cd_epoch(duhl_ctx *c, duhl_cd_mode mode, const int32_t *order, int64_t n_order,
+                          uint64_t seed, int max_inflight)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!c->have_data) return fail(c, DUHL_ESTATE, "no data set");
+    if (mode != DUHL_CD_SEQUENTIAL && mode != DUHL_CD_ASYNC) return fail(c, DUHL_EINVAL, "bad mode");
+    if (c->m_cur <= 0) return fail(c, DUHL_ESTATE, "no working set: call duhl_select and duhl_commit_swap");
+    if (c->pending && c->swap_exclusive)
+        return fail(c, DUHL_ESTATE, "the working set is being replaced in place: call duhl_commit_swap first");
+    if (order && n_order < 0) return fail(c, DUHL_EINVAL, "n_order is negative");
+    if (max_inflight < 0) return fail(c, DUHL_EINVAL, "max_inflight is negative");
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, launch_cd(c, mode, order, n_order, seed, max_inflight));
+    c->pass_counter++;
+    return DUHL_OK;
+}
+
+duhl_status duhl_objective(duhl_ctx *c, double *objective)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!objective) return fail(c, DUHL_EINVAL, "objective is NULL");
+    if (!c->have_data) return fail(c, DUHL_ESTATE, "no data set");
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, launch_objective(c));
+    duhl_status st = read_scalars(c, S_OBJ_SQ, 2);
+    if (st != DUHL_OK) return st;
+    const double sq = c->h_scalars[S_OBJ_SQ], lin = c->h_scalars[S_OBJ_LIN];
+    const double d = (double)c->d, n = (double)c->n;
+    if (c->model == DUHL_LASSO)
+        *objective = sq / (2.0 * d) + c->lambda * lin;             // Appendix C (b)
+    else
+        *objective = -lin / n + sq / (2.0 * c->lambda * n * n);    // Appendix C (c)
+    return DUHL_OK;
+}
+
+duhl_status duhl_recompute_v(duhl_ctx *c)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!c->have_data) return fail(c, DUHL_ESTATE, "no data set");
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, launch_init_v(c));
+    HIPCHK(c, launch_accumulate_v(c));
+    return DUHL_OK;
+}
+
+static duhl_status locate(duhl_ctx *c, duhl_what what, void **ptr, int64_t *len, size_t *elem)
+{
+    *elem = 4;
+    switch (what) {
+    case DUHL_ALPHA: *ptr = c->alpha; *len = c->n; break;
+    case DUHL_V: *ptr = c->v; *len = c->d; break;
+    case DUHL_Z: *ptr = c->z; *len = c->n; break;
+    case DUHL_SQNORM: *ptr = c->q; *len = c->n; break;
+    case DUHL_P: *ptr = c->P_cur; *len = c->m_cur; break;
+    default: return fail(c, DUHL_EINVAL, "unknown array id");
+    }
+    return DUHL_OK;
+}
+
+duhl_status duhl_get(duhl_ctx *c, duhl_what what, void *dst, int64_t len)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!dst) return fail(c, DUHL_EINVAL, "dst is NULL");
+    void *p; int64_t n; size_t el;
+    duhl_status st = locate(c, what, &p, &n, &el);
+    if (st != DUHL_OK) return st;
+    if (len != n) return fail(c, DUHL_EINVAL, "len (%lld) must be %lld", (long long)len, (long long)n);
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, hipStreamSynchronize(c->compute));
+    if (n > 0) HIPCHK(c, hipMemcpy(dst, p, el * (size_t)n, hipMemcpyDeviceToHost));
+    return DUHL_OK;
+}
+
+duhl_status duhl_set(duhl_ctx *c, duhl_what what, const void *src, int64_t len)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!src) return fail(c, DUHL_EINVAL, "src is NULL");
+    if (what != DUHL_ALPHA && what != DUHL_V && what != DUHL_Z)
+        return fail(c, DUHL_EINVAL, "only alpha, v and z can be set");
+    void *p; int64_t n; size_t el;
+    duhl_status st = locate(c, what, &p, &n, &el);
+    if (st != DUHL_OK) return st;
+    if (len != n) return fail(c, DUHL_EINVAL, "len (%lld) must be %lld", (long long)len, (long long)n);
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, hipStreamSynchronize(c->compute));
+    HIPCHK(c, hipMemcpy(p, src, el * (size_t)n, hipMemcpyHostToDevice));
+    return DUHL_OK;
+}
+
+duhl_status duhl_device_ptr(duhl_ctx *c, duhl_what what, void **ptr)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!ptr) return fail(c, DUHL_EINVAL, "ptr is NULL");
+    void *p; int64_t n; size_t el;
+    duhl_status st = locate(c, what, &p, &n, &el);
+    if (st != DUHL_OK) return st;
+    *ptr = p;
+    return DUHL_OK;
+}
+
+int64_t duhl_working_set_size(const duhl_ctx *c) { return c ? c->m_cur : 0; }
+
+const char *duhl_last_error(const duhl_ctx *c) { return c ? c->err.c_str() : "null context"; }
+
+void duhl_destroy(duhl_ctx *c)
+{
+    if (!c) return;
+    (void)hipSetDevice(c->device);
+    (void)hipStreamSynchronize(c->compute);
+    if (c->copy) (void)hipStreamSynchronize(c->copy);
+    free_host_residency(c);
+    (void)hipFree(c->alpha); (void)hipFree(c->v); (void)hipFree(c->z); (void)hipFree(c->q);
+    (void)hipFree(c->P_cur); (void)hipFree(c->P_next);
+    (void)hipFree(c->scalars); (void)hipFree(c->partials); (void)hipFree(c->sel);
+    (void)hipFree(c->blk_gt); (void)hipFree(c->blk_eq); (void)hipFree(c->mark);
+    if (c->h_scalars) (void)hipHostFree(c->h_scalars);
+    if (c->h_u32) (void)hipHostFree(c->h_u32);
+    delete c;
+}
+
+}  // extern "C"

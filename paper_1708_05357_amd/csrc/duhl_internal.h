@@ -1,0 +1,189 @@
+// Internal declarations shared by the translation units of libduhl (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string>
+
+#include "duhl.h"
+
+namespace duhl {
+
+constexpr int kWave = 64;
+
+// How a kernel finds the non-zeros of column a_j (the paper's A = [a_1 .. a_n], Section 2).
+struct ColView {
+    // dense
+    const float *base;        // column j at base + j*ld (device memory, or device-mapped host memory)
+    int64_t ld;
+    const int32_t *col_slot;  // host residency: device slot holding column j, or -1; else nullptr
+    const float *slots;       // slot s at slots + s*ld_s
+    int64_t ld_s;
+    // sparse (CSR over coordinates); used when base == nullptr
+    const int64_t *rowptr;
+    const int32_t *colidx;
+    const float *val;
+
+    __device__ __forceinline__ const float *col(int64_t j) const
+    {
+        if (col_slot) {
+            const int32_t s = col_slot[j];
+            if (s >= 0) return slots + (int64_t)s * ld_s;
+        }
+        return base + j * ld;
+    }
+};
+
+// Constants of the model formulas (Appendix C, D, E), rounded once to fp32.
+struct ModelConst {
+    int model;        // duhl_model
+    float Lam;        // Lasso: lambda * d
+    float B;          // Lasso: Lipschitzing bound ||b||^2 / (2 lambda d)
+    float inv_d;      // Lasso: 1/d
+    float lam_n;      // SVM: lambda * n
+    float inv_lam_n;  // SVM: 1/(lambda n)
+    float inv_n;      // SVM: 1/n
+};
+
+// Coordinate gap from c = a_i^T v (Appendix E), clamped at 0 (Section 2: the gap is non-negative).
+template <int MODEL>
+__device__ __forceinline__ float gap_value(const ModelConst &mc, float c, float alpha, float y)
+{
+    float z;
+    if (MODEL == DUHL_LASSO) {
+        const float over = fmaxf(fabsf(c) - mc.Lam, 0.0f);
+        z = (fmaf(alpha, c, mc.Lam * fabsf(alpha)) + mc.B * over) * mc.inv_d;
+    } else {
+        const float s = c * mc.inv_lam_n;
+        const float hinge = fmaxf(1.0f - y * s, 0.0f);
+        z = (fmaf(alpha, s, hinge) - y * alpha) * mc.inv_n;
+    }
+    return z > 0.0f ? z : 0.0f;
+}
+
+// Exact minimiser over coordinate j given c = a_j^T v, q = ||a_j||^2 (Appendix D).
+template <int MODEL>
+__device__ __forceinline__ float cd_new_alpha(const ModelConst &mc, float c, float alpha, float q,
+                                              float y)
+{
+    if (MODEL == DUHL_LASSO) {
+        if (!(q > 0.0f)) return 0.0f;
+        const float gamma = alpha - c / q;
+        const float mag = fabsf(gamma) - mc.Lam / q;
+        return mag > 0.0f ? copysignf(mag, gamma) : 0.0f;
+    } else {
+        if (!(q > 0.0f)) return y;
+        const float step = (y - c * mc.inv_lam_n) * (mc.lam_n / q);
+        const float t = fminf(fmaxf(y * (alpha + step), 0.0f), 1.0f);
+        return y * t;
+    }
+}
+
+// Sum over the 64 lanes of a wavefront; every lane receives the result.
+__device__ __forceinline__ float wave_sum(float x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
+    return x;
+}
+__device__ __forceinline__ double wave_sum(double x)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
+    return x;
+}
+// Sum over aligned groups of G lanes (G a power of two <= 64).
+template <int G>
+__device__ __forceinline__ float group_sum(float x)
+{
+#pragma unroll
+    for (int o = G / 2; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
+    return x;
+}
+
+// Slots of the device scalar block (doubles), results of reductions.
+enum Scalar { S_GAP_SUM = 0, S_SUM_ALL, S_SUM_SEL, S_RHO, S_OBJ_SQ, S_OBJ_LIN, S_BSQ, S_COUNT };
+
+// Scratch of the selection kernels (device memory, one per context).
+struct SelectState {
+    uint32_t hist[3][2048];
+    uint32_t ticket[8];
+    uint32_t prefix;     // high bits of the threshold key decided so far
+    uint32_t remaining;  // how many of the current bucket are still needed
+    uint32_t n_fill;     // columns to copy (host residency)
+    uint32_t n_evict;    // evictable slots found
+    uint32_t error;      // validation flags
+    uint32_t pad[3];
+};
+
+}  // namespace duhl
+
+struct duhl_ctx {
+    duhl_model model;
+    int64_t d, n, budget;
+    int device;
+    hipStream_t compute, copy;
+    int num_cu;
+
+    bool have_data;
+    bool sparse;
+    duhl_residency res;
+    double lambda;
+    duhl::ModelConst mc;
+    duhl::ColView cv;
+    const float *target;   // b (Lasso) or y (SVM), device, borrowed
+    int64_t nnz;
+
+    // owned device state
+    float *alpha, *v, *z, *q;
+    int32_t *P_cur, *P_next;
+    int64_t m_cur, m_next;
+    bool pending;          // a selected set waits for duhl_commit_swap
+    bool swap_exclusive;   // the pending copies reuse slots of the current set
+    uint64_t pass_counter;
+
+    double *scalars;            // S_COUNT doubles
+    double *partials;           // per-block partial sums
+    int64_t partials_cap;
+    duhl::SelectState *sel;
+    uint32_t *blk_gt, *blk_eq;  // per-chunk counts of the selection scatter
+    int64_t blk_cap;
+
+    // host residency
+    float *slots;
+    int64_t ld_s;
+    int32_t *col_slot, *slot_col;
+    uint8_t *mark;
+    int32_t *fill_col, *fill_slot, *evict_slot;
+    hipEvent_t ev_plan, ev_copy;
+
+    double *h_scalars;          // pinned staging for scalar read-back
+    uint32_t *h_u32;
+
+    // tuning knobs (environment, read at creation)
+    int gap_cols;      // columns per wavefront in the dense gap kernel
+    int cd_threads;    // threads per coordinate in the async dense kernel (0 = by d)
+    int copy_blocks;   // workgroups of the column-copy kernel
+
+    std::string err;
+};
+
+namespace duhl {
+
+// ---- launchers (each enqueues on the given stream and returns the launch status) ----------
+hipError_t launch_gap(duhl_ctx *c, const int32_t *idx, int64_t count, bool slot_list,
+                      bool with_norms);
+hipError_t launch_select(duhl_ctx *c, int64_t m, int32_t *P_out);
+hipError_t launch_plan_swap(duhl_ctx *c, bool overlap_safe);
+hipError_t launch_copy_columns(duhl_ctx *c);
+hipError_t launch_publish(duhl_ctx *c);
+hipError_t launch_cd(duhl_ctx *c, duhl_cd_mode mode, const int32_t *order, int64_t count,
+                     uint64_t seed, int max_inflight);
+hipError_t launch_objective(duhl_ctx *c);
+hipError_t launch_init_v(duhl_ctx *c);
+hipError_t launch_accumulate_v(duhl_ctx *c);
+hipError_t launch_validate(duhl_ctx *c);
+hipError_t launch_fill_i32(hipStream_t s, int32_t *p, int64_t n, int32_t value);
+hipError_t launch_fill_f32(hipStream_t s, float *p, int64_t n, float value);
+hipError_t launch_sum_partials(duhl_ctx *c, int64_t count, int scalar_slot);
+
+}  // namespace duhl

@@ -1,0 +1,191 @@
+// Small kernels around the hot path: objective, (re)building the shared vector, input checks.
+#include "duhl_internal.h"
+
+namespace duhl {
+
+namespace {
+
+// Sum of squares of v (both models) and, over the coordinates, sum |alpha_i| (Lasso) or
+// sum y_i alpha_i (SVM): the two reductions of the objectives in Appendix C.
+template <int MODEL>
+__global__ __launch_bounds__(256) void objective_kernel(const float *v, int64_t d, const float *alpha,
+                                                        const float *y, int64_t n, double *partials)
+{
+    __shared__ double sh[2][4];
+    double sq = 0.0, lin = 0.0;
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < d; i += stride) {
+        const double x = (double)v[i];
+        sq += x * x;
+    }
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
+        if (MODEL == DUHL_LASSO) lin += fabs((double)alpha[i]);
+        else lin += (double)y[i] * (double)alpha[i];
+    }
+    sq = wave_sum(sq);
+    lin = wave_sum(lin);
+    if ((threadIdx.x & 63) == 0) { sh[0][threadIdx.x >> 6] = sq; sh[1][threadIdx.x >> 6] = lin; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        partials[2 * blockIdx.x] = (sh[0][0] + sh[0][1]) + (sh[0][2] + sh[0][3]);
+        partials[2 * blockIdx.x + 1] = (sh[1][0] + sh[1][1]) + (sh[1][2] + sh[1][3]);
+    }
+}
+
+__global__ __launch_bounds__(1024) void objective_finish_kernel(const double *partials, int64_t blocks,
+                                                                double *scalars)
+{
+    __shared__ double sh[2][16];
+    double sq = 0.0, lin = 0.0;
+    for (int64_t i = threadIdx.x; i < blocks; i += 1024) { sq += partials[2 * i]; lin += partials[2 * i + 1]; }
+    sq = wave_sum(sq);
+    lin = wave_sum(lin);
+    if ((threadIdx.x & 63) == 0) { sh[0][threadIdx.x >> 6] = sq; sh[1][threadIdx.x >> 6] = lin; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double a = 0.0, b = 0.0;
+        for (int w = 0; w < 16; ++w) { a += sh[0][w]; b += sh[1][w]; }
+        scalars[S_OBJ_SQ] = a;
+        scalars[S_OBJ_LIN] = b;
+    }
+}
+
+// v := -b (Lasso, Appendix D: v = A alpha - b) or 0 (SVM: v = A alpha).
+__global__ void init_v_kernel(float *v, const float *b, int64_t d)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < d) v[i] = b ? -b[i] : 0.0f;
+}
+
+// v += sum_j a_j alpha_j, one wavefront per column with alpha_j != 0.
+__global__ __launch_bounds__(256) void accumulate_v_kernel(const ColView cv, int64_t d, int64_t n,
+                                                           const float *alpha, float *v)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t j = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (j >= n) return;
+    const float aj = alpha[j];
+    if (aj == 0.0f) return;
+    if (cv.base) {
+        const float *col = cv.col(j);
+        for (int64_t r = lane; r < d; r += 64)
+            (void)__hip_atomic_fetch_add(v + r, col[r] * aj, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        for (int64_t e = cv.rowptr[j] + lane; e < cv.rowptr[j + 1]; e += 64)
+            (void)__hip_atomic_fetch_add(v + cv.colidx[e], cv.val[e] * aj, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// ||b||^2 in double (for the Lipschitzing bound of Appendix E).
+__global__ __launch_bounds__(1024) void sumsq_kernel(const float *b, int64_t d, double *out)
+{
+    __shared__ double sh[16];
+    double s = 0.0;
+    for (int64_t i = threadIdx.x; i < d; i += 1024) s += (double)b[i] * (double)b[i];
+    s = wave_sum(s);
+    if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+        for (int w = 0; w < 16; ++w) t += sh[w];
+        *out = t;
+    }
+}
+
+// Input checks; bits of *flags: 1 = label not +-1, 2 = rowptr[0] != 0 or decreasing,
+// 4 = column index out of range or not strictly increasing inside a row, 8 = non-finite target.
+__global__ void validate_kernel(int model, int64_t d, int64_t n, const float *target,
+                                const int64_t *rowptr, const int32_t *colidx, uint32_t *flags)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t f = 0;
+    if (model == DUHL_SVM) {
+        if (i < n && !(target[i] == 1.0f || target[i] == -1.0f)) f |= 1u;
+    } else {
+        if (i < d && !isfinite(target[i])) f |= 8u;
+    }
+    if (rowptr && i < n) {
+        const int64_t beg = rowptr[i], end = rowptr[i + 1];
+        if (i == 0 && beg != 0) f |= 2u;
+        if (end < beg) f |= 2u;
+        else {
+            int32_t prev = -1;
+            for (int64_t e = beg; e < end; ++e) {
+                const int32_t k = colidx[e];
+                if (k <= prev || k >= d) { f |= 4u; break; }
+                prev = k;
+            }
+        }
+    }
+    if (f) atomicOr(flags, f);
+}
+
+__global__ void fill_i32_kernel(int32_t *p, int64_t n, int32_t value)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = value;
+}
+__global__ void fill_f32_kernel(float *p, int64_t n, float value)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = value;
+}
+
+}  // namespace
+
+hipError_t launch_objective(duhl_ctx *c)
+{
+    const int64_t len = c->d > c->n ? c->d : c->n;
+    int64_t grid = (len + 255) / 256;
+    if (grid > 1024) grid = 1024;
+    if (c->model == DUHL_LASSO)
+        hipLaunchKernelGGL(objective_kernel<DUHL_LASSO>, dim3(grid), dim3(256), 0, c->compute, c->v,
+                           c->d, c->alpha, c->target, c->n, c->partials);
+    else
+        hipLaunchKernelGGL(objective_kernel<DUHL_SVM>, dim3(grid), dim3(256), 0, c->compute, c->v,
+                           c->d, c->alpha, c->target, c->n, c->partials);
+    hipLaunchKernelGGL(objective_finish_kernel, dim3(1), dim3(1024), 0, c->compute, c->partials, grid,
+                       c->scalars);
+    return hipGetLastError();
+}
+
+hipError_t launch_init_v(duhl_ctx *c)
+{
+    hipLaunchKernelGGL(init_v_kernel, dim3((c->d + 255) / 256), dim3(256), 0, c->compute, c->v,
+                       c->model == DUHL_LASSO ? c->target : nullptr, c->d);
+    if (c->model == DUHL_LASSO)
+        hipLaunchKernelGGL(sumsq_kernel, dim3(1), dim3(1024), 0, c->compute, c->target, c->d,
+                           c->scalars + S_BSQ);
+    return hipGetLastError();
+}
+
+hipError_t launch_accumulate_v(duhl_ctx *c)
+{
+    hipLaunchKernelGGL(accumulate_v_kernel, dim3((c->n + 3) / 4), dim3(256), 0, c->compute, c->cv, c->d,
+                       c->n, c->alpha, c->v);
+    return hipGetLastError();
+}
+
+hipError_t launch_validate(duhl_ctx *c)
+{
+    const int64_t len = c->d > c->n ? c->d : c->n;
+    hipLaunchKernelGGL(validate_kernel, dim3((len + 255) / 256), dim3(256), 0, c->compute, (int)c->model,
+                       c->d, c->n, c->target, c->cv.rowptr, c->cv.colidx, &c->sel->error);
+    return hipGetLastError();
+}
+
+hipError_t launch_fill_i32(hipStream_t s, int32_t *p, int64_t n, int32_t value)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, n, value);
+    return hipGetLastError();
+}
+hipError_t launch_fill_f32(hipStream_t s, float *p, int64_t n, float value)
+{
+    if (n <= 0) return hipSuccess;
+    hipLaunchKernelGGL(fill_f32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, p, n, value);
+    return hipGetLastError();
+}
+
+}  // namespace duhl

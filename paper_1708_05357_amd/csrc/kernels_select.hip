@@ -1,0 +1,410 @@
+// Working-set selection: the m coordinates with the largest gap-memory entries (eq. (11)/(13)),
+// ties to the smaller index, listed in ascending index order; rho of eq. (7) on the way.
+//
+// z is turned into order-preserving 32-bit keys.  Three histogram passes (11 + 11 + 10 bits)
+// find the key of the m-th largest entry exactly; a count pass and an ordered scatter then
+// write the indices.  The work is 4n bytes per pass -- negligible next to a gap pass -- so the
+// design goal is few launches: the last workgroup to finish each pass (atomic ticket, no
+// spinning) does that pass's serial step.
+// The second half plans the column swap for host residency: which selected columns are not in
+// a device slot yet and which slots may be overwritten (Algorithm 2, "refresh memory B").
+#include "duhl_internal.h"
+
+namespace duhl {
+
+namespace {
+
+constexpr int kChunk = 2048;   // elements per workgroup in the count / scatter passes
+
+__device__ __forceinline__ uint32_t zkey(float z)
+{
+    if (!(z > 0.0f) && !(z < 0.0f)) z = 0.0f;              // +0, -0 and NaN share one key
+    const uint32_t b = __float_as_uint(z);
+    return (b & 0x80000000u) ? ~b : (b | 0x80000000u);     // unsigned order == float order
+}
+
+template <typename T>
+__device__ __forceinline__ T coherent_load(const T *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// True in exactly one workgroup of the launch: the one that arrives last.  Everything the
+// other workgroups wrote before arriving is visible to it afterwards.
+__device__ __forceinline__ bool last_block_done(uint32_t *ticket)
+{
+    __shared__ bool last;
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) last = atomicAdd(ticket, 1u) == gridDim.x - 1;
+    __syncthreads();
+    if (last) __threadfence();
+    return last;
+}
+
+__global__ void select_reset_kernel(SelectState *st, uint32_t m)
+{
+    uint32_t *h = &st->hist[0][0];
+    for (int i = threadIdx.x; i < 3 * 2048; i += blockDim.x) h[i] = 0;
+    if (threadIdx.x < 8) st->ticket[threadIdx.x] = 0;
+    if (threadIdx.x == 0) {
+        st->prefix = 0;
+        st->remaining = m;
+        st->n_fill = 0;
+        st->n_evict = 0;
+    }
+}
+
+// Histogram of the next digit over the entries whose higher digits equal st->prefix; the last
+// workgroup then finds the digit that holds the `remaining`-th largest entry.
+template <int PASS>
+__global__ __launch_bounds__(256) void select_hist_kernel(const float *z, int64_t n,
+                                                          SelectState *st, double *partials,
+                                                          double *scalars)
+{
+    constexpr int kBits = PASS == 2 ? 10 : 11;
+    constexpr int kShift = PASS == 0 ? 21 : (PASS == 1 ? 10 : 0);
+    constexpr int kBins = 1 << kBits;
+    __shared__ uint32_t hist[2048];
+    __shared__ uint32_t tsum[256];
+    __shared__ double dsh[4];
+    for (int i = threadIdx.x; i < kBins; i += 256) hist[i] = 0;
+    __syncthreads();
+    const uint32_t prefix = st->prefix;
+    double zsum = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const float zi = z[i];
+        const uint32_t key = zkey(zi);
+        bool in_bucket = true;
+        if constexpr (PASS == 0) zsum += (double)zi;
+        else in_bucket = (key >> (kShift + kBits)) == prefix;
+        if (in_bucket) atomicAdd(&hist[(key >> kShift) & (kBins - 1)], 1u);
+    }
+    __syncthreads();
+    for (int i = threadIdx.x; i < kBins; i += 256)
+        if (hist[i]) atomicAdd(&st->hist[PASS][i], hist[i]);
+    if (PASS == 0) {
+        zsum = wave_sum(zsum);
+        if ((threadIdx.x & 63) == 0) dsh[threadIdx.x >> 6] = zsum;
+        __syncthreads();
+        if (threadIdx.x == 0) partials[blockIdx.x] = (dsh[0] + dsh[1]) + (dsh[2] + dsh[3]);
+    }
+    if (!last_block_done(&st->ticket[PASS])) return;
+
+    // ---- serial step, one workgroup --------------------------------------------------------
+    constexpr int kPer = kBins / 256;                    // consecutive bins per thread
+    uint32_t mine[kPer], total = 0;
+#pragma unroll
+    for (int b = 0; b < kPer; ++b) {
+        mine[b] = coherent_load(&st->hist[PASS][threadIdx.x * kPer + b]);
+        total += mine[b];
+    }
+    tsum[threadIdx.x] = total;
+    __syncthreads();
+    // entries in bins above this thread's range (exclusive suffix sum over 256 threads)
+    uint32_t above = 0;
+    for (int t = threadIdx.x + 1; t < 256; ++t) above += tsum[t];
+    const uint32_t need = st->remaining;
+    if (above < need && need <= above + total) {
+        uint32_t acc = above;
+#pragma unroll
+        for (int b = kPer - 1; b >= 0; --b) {
+            if (acc < need && need <= acc + mine[b]) {
+                st->prefix = (prefix << kBits) | (uint32_t)(threadIdx.x * kPer + b);
+                st->remaining = need - acc;      // still to take from that bin
+            }
+            acc += mine[b];
+        }
+    }
+    if (PASS == 0) {
+        double s = 0.0;
+        for (int i = threadIdx.x; i < (int)gridDim.x; i += 256) s += coherent_load(&partials[i]);
+        s = wave_sum(s);
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) dsh[threadIdx.x >> 6] = s;
+        __syncthreads();
+        if (threadIdx.x == 0) scalars[S_SUM_ALL] = (dsh[0] + dsh[1]) + (dsh[2] + dsh[3]);
+    }
+}
+
+// Per chunk of kChunk consecutive entries: how many lie above the threshold key and how many
+// equal it; the last workgroup turns the counts into exclusive prefixes.
+__global__ __launch_bounds__(256) void select_count_kernel(const float *z, int64_t n,
+                                                           SelectState *st, uint32_t *blk_gt,
+                                                           uint32_t *blk_eq)
+{
+    __shared__ uint32_t sg[4], se[4];
+    __shared__ uint32_t pg[256], pe[256];
+    const uint32_t thr = st->prefix;
+    const int64_t base = (int64_t)blockIdx.x * kChunk;
+    uint32_t g = 0, e = 0;
+#pragma unroll
+    for (int it = 0; it < kChunk / 256; ++it) {
+        const int64_t i = base + it * 256 + threadIdx.x;
+        if (i < n) {
+            const uint32_t key = zkey(z[i]);
+            g += key > thr;
+            e += key == thr;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        g += __shfl_xor(g, o, kWave);
+        e += __shfl_xor(e, o, kWave);
+    }
+    if ((threadIdx.x & 63) == 0) { sg[threadIdx.x >> 6] = g; se[threadIdx.x >> 6] = e; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        blk_gt[blockIdx.x] = sg[0] + sg[1] + sg[2] + sg[3];
+        blk_eq[blockIdx.x] = se[0] + se[1] + se[2] + se[3];
+    }
+    if (!last_block_done(&st->ticket[3])) return;
+
+    const int64_t nb = gridDim.x;
+    const int64_t per = (nb + 255) / 256;
+    const int64_t lo = threadIdx.x * per, hi = lo + per < nb ? lo + per : nb;
+    uint32_t tg = 0, te = 0;
+    for (int64_t b = lo; b < hi; ++b) { tg += coherent_load(&blk_gt[b]); te += coherent_load(&blk_eq[b]); }
+    pg[threadIdx.x] = tg;
+    pe[threadIdx.x] = te;
+    __syncthreads();
+    uint32_t og = 0, oe = 0;
+    for (int t = 0; t < (int)threadIdx.x; ++t) { og += pg[t]; oe += pe[t]; }
+    for (int64_t b = lo; b < hi; ++b) {
+        const uint32_t cg = coherent_load(&blk_gt[b]), ce = coherent_load(&blk_eq[b]);
+        blk_gt[b] = og;
+        blk_eq[b] = oe;
+        og += cg;
+        oe += ce;
+    }
+}
+
+// Ordered scatter: entry i goes to position (#selected entries with a smaller index).
+__global__ __launch_bounds__(256) void select_scatter_kernel(const float *z, int64_t n, int64_t m,
+                                                             SelectState *st,
+                                                             const uint32_t *blk_gt,
+                                                             const uint32_t *blk_eq, int32_t *P,
+                                                             int32_t *P_out, double *partials,
+                                                             double *scalars)
+{
+    __shared__ uint32_t wg[4], we[4];
+    __shared__ double dsh[4];
+    const uint32_t thr = st->prefix, take_eq = st->remaining;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t gt_before = blk_gt[blockIdx.x], eq_before = blk_eq[blockIdx.x];
+    const int64_t base = (int64_t)blockIdx.x * kChunk;
+    double ssel = 0.0;
+    for (int it = 0; it < kChunk / 256; ++it) {
+        const int64_t i = base + it * 256 + threadIdx.x;
+        float zi = 0.0f;
+        bool g = false, e = false;
+        if (i < n) {
+            zi = z[i];
+            const uint32_t key = zkey(zi);
+            g = key > thr;
+            e = key == thr;
+        }
+        const unsigned long long mg = __ballot(g), me = __ballot(e);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        if (lane == 0) { wg[w] = __popcll(mg); we[w] = __popcll(me); }
+        __syncthreads();
+        uint32_t og = gt_before + __popcll(mg & below), oe = eq_before + __popcll(me & below);
+        uint32_t tg = 0, te = 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (u < w) { og += wg[u]; oe += we[u]; }
+            tg += wg[u];
+            te += we[u];
+        }
+        if (g || (e && oe < take_eq)) {
+            const uint32_t pos = og + (oe < take_eq ? oe : take_eq);
+            P[pos] = (int32_t)i;
+            if (P_out) P_out[pos] = (int32_t)i;
+            ssel += (double)zi;
+        }
+        gt_before += tg;
+        eq_before += te;
+        __syncthreads();
+    }
+    ssel = wave_sum(ssel);
+    if (lane == 0) dsh[w] = ssel;
+    __syncthreads();
+    if (threadIdx.x == 0) partials[blockIdx.x] = (dsh[0] + dsh[1]) + (dsh[2] + dsh[3]);
+    if (!last_block_done(&st->ticket[4])) return;
+    double s = 0.0;
+    for (int i = threadIdx.x; i < (int)gridDim.x; i += 256) s += coherent_load(&partials[i]);
+    s = wave_sum(s);
+    __syncthreads();
+    if (lane == 0) dsh[w] = s;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const double sel = (dsh[0] + dsh[1]) + (dsh[2] + dsh[3]);
+        const double all = scalars[S_SUM_ALL];
+        scalars[S_SUM_SEL] = sel;
+        // eq. (7): (mean of z over P) / (mean of z over all coordinates)
+        scalars[S_RHO] = all > 0.0 ? (sel / (double)m) / (all / (double)n) : 1.0;
+    }
+}
+
+// ---- swap planning (host residency) ------------------------------------------------------------
+__global__ void mark_clear_kernel(uint8_t *mark, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) mark[i] = 0;
+}
+__global__ void mark_set_kernel(uint8_t *mark, const int32_t *list, int64_t count)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < count) mark[list[k]] = 1;
+}
+// Device residency: how many selected coordinates were not in the current set (marked).
+__global__ void count_new_kernel(const int32_t *P, int64_t m, const uint8_t *mark, SelectState *st)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const bool fresh = k < m && mark[P[k]] == 0;
+    const unsigned long long b = __ballot(fresh);
+    if ((threadIdx.x & 63) == 0 && b) atomicAdd(&st->n_fill, (uint32_t)__popcll(b));
+}
+// Selected columns that are in no device slot.
+__global__ void find_fill_kernel(const int32_t *P, int64_t m, const int32_t *col_slot,
+                                 SelectState *st, int32_t *fill_col)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < m && col_slot[P[k]] < 0) fill_col[atomicAdd(&st->n_fill, 1u)] = P[k];
+}
+// Slots that are empty or hold a column outside the marked (protected) sets.
+__global__ void find_evict_kernel(const int32_t *slot_col, int64_t budget, const uint8_t *mark,
+                                  SelectState *st, int32_t *evict_slot)
+{
+    const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (s < budget) {
+        const int32_t j = slot_col[s];
+        if (j < 0 || mark[j] == 0) evict_slot[atomicAdd(&st->n_evict, 1u)] = (int32_t)s;
+    }
+}
+// Pair the k-th missing column with the k-th evictable slot.  The evicted column loses its slot
+// at once (later reads of it go to host memory); the new column gains it only when published.
+__global__ void apply_plan_kernel(SelectState *st, const int32_t *fill_col,
+                                  const int32_t *evict_slot, int32_t *fill_slot, int32_t *slot_col,
+                                  int32_t *col_slot, int64_t limit)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= limit || k >= (int64_t)st->n_fill) return;
+    if (k >= (int64_t)st->n_evict) { atomicOr(&st->error, 1u); return; }   // cannot happen
+    const int32_t s = evict_slot[k];
+    const int32_t old = slot_col[s];
+    if (old >= 0) col_slot[old] = -1;
+    slot_col[s] = fill_col[k];
+    fill_slot[k] = s;
+}
+__global__ void publish_kernel(const SelectState *st, const int32_t *fill_col,
+                               const int32_t *fill_slot, int32_t *col_slot, int64_t limit)
+{
+    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (k < limit && k < (int64_t)st->n_fill) col_slot[fill_col[k]] = fill_slot[k];
+}
+
+// Host -> device copy of the planned columns by a few workgroups reading the device-mapped
+// pinned matrix directly; the list and its length stay on the device, so no host round trip.
+template <bool VEC4>
+__global__ __launch_bounds__(256) void copy_columns_kernel(const float *src, int64_t ld, float *slots,
+                                                           int64_t ld_s, int64_t d,
+                                                           const SelectState *st,
+                                                           const int32_t *fill_col,
+                                                           const int32_t *fill_slot)
+{
+    const int64_t count = st->n_fill;
+    for (int64_t k = blockIdx.x; k < count; k += gridDim.x) {
+        const float *s = src + (int64_t)fill_col[k] * ld;
+        float *t = slots + (int64_t)fill_slot[k] * ld_s;
+        int64_t done = 0;
+        if (VEC4) {
+            const int64_t d4 = d >> 2;
+            const float4 *s4 = reinterpret_cast<const float4 *>(s);
+            float4 *t4 = reinterpret_cast<float4 *>(t);
+            int64_t r = threadIdx.x;
+            for (; r + 768 < d4; r += 1024) {
+                const float4 a0 = s4[r], a1 = s4[r + 256], a2 = s4[r + 512], a3 = s4[r + 768];
+                t4[r] = a0; t4[r + 256] = a1; t4[r + 512] = a2; t4[r + 768] = a3;
+            }
+            for (; r < d4; r += 256) t4[r] = s4[r];
+            done = d4 << 2;
+        }
+        for (int64_t r = done + threadIdx.x; r < d; r += 256) t[r] = s[r];
+    }
+}
+
+}  // namespace
+
+hipError_t launch_select(duhl_ctx *c, int64_t m, int32_t *P_out)
+{
+    hipStream_t s = c->compute;
+    const int64_t n = c->n;
+    hipLaunchKernelGGL(select_reset_kernel, dim3(1), dim3(1024), 0, s, c->sel, (uint32_t)m);
+    int64_t hgrid = (n + 2047) / 2048;
+    if (hgrid > 1024) hgrid = 1024;
+    hipLaunchKernelGGL(select_hist_kernel<0>, dim3(hgrid), dim3(256), 0, s, c->z, n, c->sel,
+                       c->partials, c->scalars);
+    hipLaunchKernelGGL(select_hist_kernel<1>, dim3(hgrid), dim3(256), 0, s, c->z, n, c->sel,
+                       c->partials, c->scalars);
+    hipLaunchKernelGGL(select_hist_kernel<2>, dim3(hgrid), dim3(256), 0, s, c->z, n, c->sel,
+                       c->partials, c->scalars);
+    const int64_t nb = (n + kChunk - 1) / kChunk;
+    hipLaunchKernelGGL(select_count_kernel, dim3(nb), dim3(256), 0, s, c->z, n, c->sel, c->blk_gt,
+                       c->blk_eq);
+    hipLaunchKernelGGL(select_scatter_kernel, dim3(nb), dim3(256), 0, s, c->z, n, m, c->sel,
+                       c->blk_gt, c->blk_eq, c->P_next, P_out, c->partials, c->scalars);
+    return hipGetLastError();
+}
+
+hipError_t launch_plan_swap(duhl_ctx *c, bool overlap_safe)
+{
+    hipStream_t s = c->compute;
+    const int T = 256;
+    const int64_t m = c->m_next;
+    hipLaunchKernelGGL(mark_clear_kernel, dim3((c->n + T - 1) / T), dim3(T), 0, s, c->mark, c->n);
+    if (c->res != DUHL_RESIDENT_HOST) {     // nothing to copy: only count what changed
+        if (c->m_cur > 0)
+            hipLaunchKernelGGL(mark_set_kernel, dim3((c->m_cur + T - 1) / T), dim3(T), 0, s, c->mark,
+                               c->P_cur, c->m_cur);
+        hipLaunchKernelGGL(count_new_kernel, dim3((m + T - 1) / T), dim3(T), 0, s, c->P_next, m,
+                           c->mark, c->sel);
+        return hipGetLastError();
+    }
+    hipLaunchKernelGGL(mark_set_kernel, dim3((m + T - 1) / T), dim3(T), 0, s, c->mark, c->P_next, m);
+    if (overlap_safe && c->m_cur > 0)
+        hipLaunchKernelGGL(mark_set_kernel, dim3((c->m_cur + T - 1) / T), dim3(T), 0, s, c->mark,
+                           c->P_cur, c->m_cur);
+    hipLaunchKernelGGL(find_fill_kernel, dim3((m + T - 1) / T), dim3(T), 0, s, c->P_next, m,
+                       c->col_slot, c->sel, c->fill_col);
+    hipLaunchKernelGGL(find_evict_kernel, dim3((c->budget + T - 1) / T), dim3(T), 0, s, c->slot_col,
+                       c->budget, c->mark, c->sel, c->evict_slot);
+    hipLaunchKernelGGL(apply_plan_kernel, dim3((m + T - 1) / T), dim3(T), 0, s, c->sel, c->fill_col,
+                       c->evict_slot, c->fill_slot, c->slot_col, c->col_slot, m);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_columns(duhl_ctx *c)
+{
+    const bool vec = ((reinterpret_cast<uintptr_t>(c->cv.base) & 15) == 0) && (c->cv.ld % 4 == 0);
+    if (vec)
+        hipLaunchKernelGGL(copy_columns_kernel<true>, dim3(c->copy_blocks), dim3(256), 0, c->copy,
+                           c->cv.base, c->cv.ld, c->slots, c->ld_s, c->d, c->sel, c->fill_col,
+                           c->fill_slot);
+    else
+        hipLaunchKernelGGL(copy_columns_kernel<false>, dim3(c->copy_blocks), dim3(256), 0, c->copy,
+                           c->cv.base, c->cv.ld, c->slots, c->ld_s, c->d, c->sel, c->fill_col,
+                           c->fill_slot);
+    return hipGetLastError();
+}
+
+hipError_t launch_publish(duhl_ctx *c)
+{
+    const int T = 256;
+    const int64_t m = c->m_next;
+    hipLaunchKernelGGL(publish_kernel, dim3((m + T - 1) / T), dim3(T), 0, c->compute, c->sel,
+                       c->fill_col, c->fill_slot, c->col_slot, m);
+    return hipGetLastError();
+}
+
+}  // namespace duhl

@@ -1,0 +1,187 @@
+"""ctypes binding of libduhl.so -- argument marshalling only; every step runs in the HIP kernels.
+
+The names mirror the C ABI of ``include/duhl.h``.  torch is used for device memory and streams:
+tensors are passed as raw device pointers, the compute stream is torch's current stream at
+construction time (so ``torch.cuda.Event`` timing brackets the library's kernels) and the copy
+stream is a second torch stream of default priority.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libduhl.so")
+
+LASSO, SVM = 0, 1
+RESIDENT_DEVICE, RESIDENT_HOST = 0, 1
+ALPHA, V, Z, P, SQNORM = 0, 1, 2, 3, 4
+CD_SEQUENTIAL, CD_ASYNC = 0, 1
+OK, EINVAL, ENOMEM, EHIP, ESTATE, EBUDGET = 0, -1, -2, -3, -4, -5
+
+EXPORTS = ["duhl_create", "duhl_set_data_dense", "duhl_set_data_csr", "duhl_gap", "duhl_select",
+           "duhl_commit_swap", "duhl_cd_epoch", "duhl_objective", "duhl_recompute_v", "duhl_get",
+           "duhl_set", "duhl_device_ptr", "duhl_working_set_size", "duhl_last_error",
+           "duhl_destroy"]
+
+_lib = None
+
+
+class DuhlError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__(f"duhl status {status}: {text}")
+        self.status = status
+
+
+def load():
+    """Load the HIP library; fails loudly when it has not been built (no CPU fallback exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_1708_05357_amd.build`")
+    lib = C.CDLL(LIB_PATH)
+    p, i64, i32, dbl = C.c_void_p, C.c_int64, C.c_int, C.c_double
+    lib.duhl_create.argtypes = [C.POINTER(p), i32, i64, i64, i64, i32, p, p]
+    lib.duhl_set_data_dense.argtypes = [p, p, i64, i32, p, dbl]
+    lib.duhl_set_data_csr.argtypes = [p, p, p, p, i32, p, dbl]
+    lib.duhl_gap.argtypes = [p, p, i64, C.POINTER(dbl)]
+    lib.duhl_select.argtypes = [p, i64, p, C.POINTER(i64), C.POINTER(dbl)]
+    lib.duhl_commit_swap.argtypes = [p]
+    lib.duhl_cd_epoch.argtypes = [p, i32, p, i64, C.c_uint64, i32]
+    lib.duhl_objective.argtypes = [p, C.POINTER(dbl)]
+    lib.duhl_recompute_v.argtypes = [p]
+    lib.duhl_get.argtypes = [p, i32, p, i64]
+    lib.duhl_set.argtypes = [p, i32, p, i64]
+    lib.duhl_device_ptr.argtypes = [p, i32, C.POINTER(p)]
+    lib.duhl_working_set_size.argtypes = [p]
+    lib.duhl_working_set_size.restype = i64
+    lib.duhl_last_error.argtypes = [p]
+    lib.duhl_last_error.restype = C.c_char_p
+    lib.duhl_destroy.argtypes = [p]
+    lib.duhl_destroy.restype = None
+    for name in EXPORTS[:12]:
+        getattr(lib, name).restype = i32
+    _lib = lib
+    return lib
+
+
+def _dptr(t, dtype):
+    if t is None:
+        return None
+    assert isinstance(t, torch.Tensor) and t.dtype == dtype and t.is_contiguous(), (t.dtype, dtype)
+    return C.c_void_p(t.data_ptr())
+
+
+class Duhl:
+    """One problem on one GPU.  Methods are the C entry points, one to one."""
+
+    def __init__(self, model, d, n, budget_cols, device=0, copy_stream=None):
+        self.lib = load()
+        self.model, self.d, self.n, self.budget = model, int(d), int(n), int(budget_cols)
+        self.device = torch.device("cuda", device)
+        with torch.cuda.device(self.device):
+            self.compute_stream = torch.cuda.current_stream()
+            self.copy_stream = copy_stream if copy_stream is not None else torch.cuda.Stream()
+        self._h = C.c_void_p()
+        st = self.lib.duhl_create(C.byref(self._h), model, self.d, self.n, self.budget, device,
+                                  C.c_void_p(self.compute_stream.cuda_stream),
+                                  C.c_void_p(self.copy_stream.cuda_stream))
+        if st != OK:
+            raise DuhlError(st, "duhl_create failed")
+        self._keep = ()
+
+    def _chk(self, st):
+        if st != OK:
+            raise DuhlError(st, self.lib.duhl_last_error(self._h).decode())
+
+    def close(self):
+        if self._h:
+            self.lib.duhl_destroy(self._h)
+            self._h = C.c_void_p()
+            self._keep = ()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    # -- data -----------------------------------------------------------------------------
+    def set_data_dense(self, cols, target, lam, residency=RESIDENT_DEVICE):
+        """cols: float32 (n, d) tensor, row i = column a_i (device, or pinned host memory for
+        RESIDENT_HOST); row stride = leading dimension.  target: device float32."""
+        assert cols.dtype == torch.float32 and cols.dim() == 2 and cols.stride(1) == 1
+        assert tuple(cols.shape) == (self.n, self.d)
+        if residency == RESIDENT_HOST:
+            assert cols.device.type == "cpu" and cols.is_pinned()
+        self._keep = (cols, target)
+        self._chk(self.lib.duhl_set_data_dense(self._h, C.c_void_p(cols.data_ptr()), cols.stride(0),
+                                               residency, _dptr(target, torch.float32), float(lam)))
+
+    def set_data_csr(self, rowptr, colidx, val, target, lam, residency=RESIDENT_DEVICE):
+        self._keep = (rowptr, colidx, val, target)
+        self._chk(self.lib.duhl_set_data_csr(self._h, _dptr(rowptr, torch.int64),
+                                             _dptr(colidx, torch.int32), _dptr(val, torch.float32),
+                                             residency, _dptr(target, torch.float32), float(lam)))
+
+    # -- the hot path -----------------------------------------------------------------------
+    def gap(self, idx=None, want_sum=True):
+        out = C.c_double(0.0)
+        count = 0 if idx is None else idx.numel()
+        self._chk(self.lib.duhl_gap(self._h, _dptr(idx, torch.int32), count,
+                                    C.byref(out) if want_sum else None))
+        return out.value if want_sum else None
+
+    def select(self, m, P_out=None, want_stats=True):
+        nsw, rho = C.c_int64(0), C.c_double(0.0)
+        self._chk(self.lib.duhl_select(self._h, int(m), _dptr(P_out, torch.int32),
+                                       C.byref(nsw) if want_stats else None,
+                                       C.byref(rho) if want_stats else None))
+        return (nsw.value, rho.value) if want_stats else None
+
+    def commit_swap(self):
+        self._chk(self.lib.duhl_commit_swap(self._h))
+
+    def cd_epoch(self, mode=CD_ASYNC, order=None, seed=0, max_inflight=0):
+        count = 0 if order is None else order.numel()
+        self._chk(self.lib.duhl_cd_epoch(self._h, mode, _dptr(order, torch.int32), count,
+                                         C.c_uint64(seed), int(max_inflight)))
+
+    def objective(self):
+        out = C.c_double(0.0)
+        self._chk(self.lib.duhl_objective(self._h, C.byref(out)))
+        return out.value
+
+    def recompute_v(self):
+        self._chk(self.lib.duhl_recompute_v(self._h))
+
+    # -- state ------------------------------------------------------------------------------
+    def working_set_size(self):
+        return self.lib.duhl_working_set_size(self._h)
+
+    def _len(self, what):
+        return {ALPHA: self.n, Z: self.n, SQNORM: self.n, V: self.d}.get(what, self.working_set_size())
+
+    def get(self, what):
+        n = self._len(what)
+        out = np.empty(n, dtype=np.int32 if what == P else np.float32)
+        self._chk(self.lib.duhl_get(self._h, what, out.ctypes.data_as(C.c_void_p), n))
+        return out
+
+    def set(self, what, arr):
+        arr = np.ascontiguousarray(arr, dtype=np.float32)
+        self._chk(self.lib.duhl_set(self._h, what, arr.ctypes.data_as(C.c_void_p), arr.size))
+
+    def device_view(self, what):
+        """Zero-copy torch view of a state array (float32; P: int32)."""
+        ptr = C.c_void_p()
+        self._chk(self.lib.duhl_device_ptr(self._h, what, C.byref(ptr)))
+        n = self._len(what)
+        dtype = np.int32 if what == P else np.float32
+
+        class _Iface:
+            __cuda_array_interface__ = {"shape": (n,), "typestr": np.dtype(dtype).str,
+                                        "data": (ptr.value, False), "version": 2}
+        return torch.as_tensor(_Iface(), device=self.device)

@@ -1,0 +1,79 @@
+"""Helpers of the GPU parity tests: build the HIP context and the oracle on the same inputs."""
+import numpy as np
+import torch
+
+from oracle import duhl_oracle as orc
+from paper_1708_05357_amd import duhl, synth
+
+
+def to_np(t):
+    return t.detach().cpu().numpy()
+
+
+class Pair:
+    """The same seeded problem in the HIP library (self.g) and in the CPU oracle (self.o)."""
+
+    def __init__(self, prob, budget=None, host_resident=False, ld=None):
+        self.prob = prob
+        model = duhl.LASSO if prob["model"] == "lasso" else duhl.SVM
+        self.model = model
+        d, n = prob["d"], prob["n"]
+        dev = torch.device("cuda", 0)
+        self.target = prob["target"].to(dev).contiguous()
+        self.g = duhl.Duhl(model, d, n, budget if budget is not None else n)
+        if "cols" in prob:
+            ld_eff = ld if ld is not None else d
+            if host_resident:
+                store = torch.empty((n, ld_eff), dtype=torch.float32, pin_memory=True)
+            else:
+                store = torch.empty((n, ld_eff), dtype=torch.float32, device=dev)
+            if ld_eff > d:
+                store.fill_(float("nan"))                      # padding must never be read
+            store[:, :d].copy_(prob["cols"])
+            self.cols = store[:, :d]
+            self.g.set_data_dense(self.cols, self.target, prob["lam"],
+                                  duhl.RESIDENT_HOST if host_resident else duhl.RESIDENT_DEVICE)
+            self.o = orc.Oracle(model, to_np(prob["target"]), prob["lam"],
+                                cols=np.ascontiguousarray(to_np(prob["cols"])))
+        else:
+            self.rowptr = prob["rowptr"].to(dev)
+            self.colidx = prob["colidx"].to(dev)
+            self.val = prob["val"].to(dev)
+            self.g.set_data_csr(self.rowptr, self.colidx, self.val, self.target, prob["lam"])
+            self.o = orc.Oracle(model, to_np(prob["target"]), prob["lam"],
+                                csr=(to_np(prob["rowptr"]), to_np(prob["colidx"]), to_np(prob["val"])),
+                                d=d)
+
+    def sync_oracle_to_gpu_state(self):
+        """Put the GPU's (alpha, v) into the oracle so both evaluate at the same point."""
+        self.o.set_state(self.g.get(duhl.ALPHA).astype(np.float64), self.g.get(duhl.V).astype(np.float64))
+
+    def close(self):
+        self.g.close()
+
+
+def assert_gaps_close(z_gpu, z_or, tol=1e-4, floor=0.0):
+    """Normwise 1e-4 relative on the whole vector, entrywise 1e-4 relative on the entries that
+    matter (>= 1e-3 of the largest).  `floor` is the absolute rounding floor of the formula."""
+    zmax = float(np.max(z_or))
+    err = np.abs(z_gpu.astype(np.float64) - z_or)
+    assert err.max() <= tol * zmax + floor, (err.max(), zmax, floor)
+    big = z_or >= 1e-3 * zmax
+    if zmax > 0 and big.any():
+        rel = err[big] / z_or[big]
+        assert rel.max() <= tol + floor / max(zmax * 1e-3, 1e-300), rel.max()
+
+
+def lasso_gap_floor(pair):
+    """Rounding floor of the fp32 Lasso gap: the terms alpha_i c_i and Lambda |alpha_i| cancel
+    near the optimum, leaving an absolute error of a few ulps of Lambda |alpha_i| / d, plus the
+    error of the fp32 dot product scaled by |alpha_i| + B."""
+    o = pair.o
+    Lam = o.lam * o.d
+    eps = 2.0 ** -24
+    dot_err = 8 * eps * np.sqrt(o.d) * np.linalg.norm(o.v) * np.sqrt(o.q.max())
+    return float((4 * eps * Lam * np.abs(o.alpha).max() + dot_err * (np.abs(o.alpha).max() + o.B)) / o.d)
+
+
+def dev_i32(a):
+    return torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32), device="cuda:0")

@@ -1,0 +1,419 @@
+"""Parity of the HIP path with the CPU oracle, element by element, through the C ABI.
+
+Tolerances (the benchmark spec): gap vectors 1e-4 relative in fp32 (normwise, and entrywise on the
+entries that matter), selection bit-exact on the same fp32 z, sequential CD iterates 1e-5
+relative, asynchronous CD final objective 1e-5 relative.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+sys.path.insert(0, os.path.dirname(__file__))
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_common
+    return gpu_common
+
+
+def lasso_problem(d, n, frac=0.1, c=0.1, seed=0):
+    from paper_1708_05357_amd import synth
+    return synth.lasso_dense(d, n, frac, c, seed=seed)
+
+
+# ------------------------------------------------------------------------------------ gaps
+@pytest.mark.parametrize("d,n,ld", [(1000, 500, None), (1003, 37, None), (64, 9, None), (1, 5, None),
+                                    (257, 130, 300), (4100, 67, 4104), (10, 3, 13)])
+def test_dense_lasso_gaps_match_oracle(G, d, n, ld):
+    """App. E (Lasso): z from the first pass of set_data, from a full pass at a later state, and
+    from an index-list refresh; sizes cover whole tiles, ragged tails, unaligned leading
+    dimensions (scalar path) and fewer columns than one wavefront group."""
+    from paper_1708_05357_amd import duhl
+    p = G.Pair(lasso_problem(d, n, 0.2, 0.1, seed=d + n), ld=ld)
+    np.testing.assert_allclose(p.g.get(duhl.SQNORM), p.o.q, rtol=2e-6)
+    total_or = p.o.gaps()
+    G.assert_gaps_close(p.g.get(duhl.Z), p.o.z, floor=G.lasso_gap_floor(p))
+    rng = np.random.default_rng(1)
+    m = max(1, n // 2)
+    for rnd in range(3):
+        p.g.select(m)
+        p.g.commit_swap()
+        order = rng.permutation(p.g.get(duhl.P)).astype(np.int32)
+        p.g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(order))
+        p.sync_oracle_to_gpu_state()
+        total_gpu = p.g.gap()
+        total_or = p.o.gaps()
+        floor = G.lasso_gap_floor(p)
+        G.assert_gaps_close(p.g.get(duhl.Z), p.o.z, floor=floor)
+        assert total_gpu == pytest.approx(total_or, rel=1e-4, abs=n * floor)
+    # stale entries stay, listed entries are refreshed
+    zero = np.zeros(n, dtype=np.float32)
+    p.g.set(duhl.Z, zero)
+    idx = rng.permutation(n)[: max(1, n // 3)].astype(np.int32)
+    part = p.g.gap(G.dev_i32(idx))
+    z = p.g.get(duhl.Z)
+    mask = np.zeros(n, dtype=bool)
+    mask[idx] = True
+    assert np.all(z[~mask] == 0)
+    np.testing.assert_allclose(z[mask], p.o.z[mask], rtol=1e-4, atol=1e-4 * p.o.z.max() + floor)
+    assert part == pytest.approx(float(p.o.z[mask].sum()), rel=1e-4, abs=n * floor)
+    p.close()
+
+
+def test_svm_gaps_match_oracle_dense_and_csr(G):
+    """App. E (SVM): all gaps equal 1/n at alpha = 0; parity after some passes, both storages."""
+    from paper_1708_05357_amd import duhl, synth
+    for prob in (synth.svm_dense(300, 41, seed=3), synth.svm_csr(1500, 400, 0.02, seed=4)):
+        p = G.Pair(prob)
+        n = prob["n"]
+        np.testing.assert_allclose(p.g.get(duhl.Z), np.full(n, 1.0 / n), rtol=1e-6)
+        np.testing.assert_allclose(p.g.get(duhl.SQNORM), p.o.q, rtol=2e-6)
+        assert p.g.gap() == pytest.approx(1.0, rel=1e-6)
+        rng = np.random.default_rng(0)
+        for rnd in range(3):
+            p.g.select(n // 2)
+            p.g.commit_swap()
+            order = rng.permutation(p.g.get(duhl.P)).astype(np.int32)
+            p.g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(order))
+            p.sync_oracle_to_gpu_state()
+            total = p.g.gap()
+            assert total == pytest.approx(p.o.gaps(), rel=1e-4)
+            G.assert_gaps_close(p.g.get(duhl.Z), p.o.z, floor=4 * 2.0 ** -24 / n)
+        p.close()
+
+
+# ------------------------------------------------------------------------------------ selection
+@pytest.mark.parametrize("n", [7, 500, 2048, 2049, 70001])
+def test_selection_is_bit_exact_on_the_same_z(G, n):
+    """eq. (13): same fp32 z into both selectors -> identical sets (ascending), incl. heavy ties,
+    m = 1, m = n, and rho of eq. (7)."""
+    from oracle import duhl_oracle as orc
+    from paper_1708_05357_amd import duhl
+    p = G.Pair(lasso_problem(16, n, 0.1, 0.1, seed=n))
+    rng = np.random.default_rng(n)
+    cases = {
+        "random": rng.random(n).astype(np.float32) ** 4,
+        "many zeros": np.where(rng.random(n) < 0.9, 0.0, rng.random(n)).astype(np.float32),
+        "all equal": np.full(n, 1.0 / n, dtype=np.float32),
+        "few levels": rng.integers(0, 4, n).astype(np.float32),
+        "tiny spread": (1.0 + rng.integers(0, 3, n) * 2.0 ** -23).astype(np.float32),
+    }
+    for name, z in cases.items():
+        p.g.set(duhl.Z, z)
+        for m in sorted({1, 2, max(1, n // 10), max(1, n // 2), n - 1 if n > 1 else 1, n}):
+            out = torch.full((m,), -7, dtype=torch.int32, device="cuda:0")
+            nsw, rho = p.g.select(m, out)
+            want = orc.select_topm(z.astype(np.float64), m)
+            np.testing.assert_array_equal(out.cpu().numpy(), want, err_msg=f"{name} m={m}")
+            assert rho == pytest.approx(orc.rho(z.astype(np.float64), want), rel=1e-12), (name, m)
+            p.g.commit_swap()
+            np.testing.assert_array_equal(p.g.get(duhl.P), want)
+    p.close()
+
+
+def test_selection_counts_new_columns(G):
+    from paper_1708_05357_amd import duhl
+    n = 3000
+    p = G.Pair(lasso_problem(8, n, 0.1, 0.1, seed=1))
+    z = np.zeros(n, dtype=np.float32)
+    z[:100] = 1.0
+    p.g.set(duhl.Z, z)
+    assert p.g.select(100)[0] == 100
+    p.g.commit_swap()
+    z[:] = 0
+    z[50:150] = 1.0
+    p.g.set(duhl.Z, z)
+    assert p.g.select(100)[0] == 50
+    p.close()
+
+
+# ------------------------------------------------------------------------------------ sequential CD
+def run_rounds_sequential(G, p, m, rounds, seed=0, check_selection=True):
+    """The loop of Alg. 1 with rule (11) on both sides: fresh gaps, top-m, one pass in a random
+    order that is passed to both as data.  The oracle follows the GPU's working set after it has
+    been checked against its own choice outside the tie band."""
+    from paper_1708_05357_amd import duhl
+    rng = np.random.default_rng(seed)
+    worst_a = worst_v = 0.0
+    for rnd in range(rounds):
+        p.g.gap(want_sum=False)
+        p.g.select(m, want_stats=False)
+        p.g.commit_swap()
+        P = p.g.get(duhl.P)
+        if check_selection:
+            p.o.gaps()
+            Po = p.o.select(m)
+            if not np.array_equal(P, Po):
+                thr = np.sort(p.o.z)[-m]
+                band = 1e-4 * p.o.z.max()
+                diff = np.setxor1d(P, Po)
+                assert np.all(np.abs(p.o.z[diff] - thr) <= band), (rnd, diff, p.o.z[diff], thr)
+        order = rng.permutation(P).astype(np.int32)
+        p.g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(order))
+        p.o.cd_pass(order)
+        a, v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+        ea = np.abs(a - p.o.alpha).max() / max(np.abs(p.o.alpha).max(), 1e-30)
+        ev = np.abs(v - p.o.v).max() / max(np.abs(p.o.v).max(), 1e-30)
+        worst_a, worst_v = max(worst_a, ea), max(worst_v, ev)
+        assert ea <= 1e-5 and ev <= 1e-5, (rnd, ea, ev)
+    return worst_a, worst_v
+
+
+def test_sequential_cd_iterates_match_oracle_cfg1(G):
+    """Tiny dense Lasso of the benchmark plan: 1000 x 500, m = 125, 20 rounds of one pass."""
+    from paper_1708_05357_amd import duhl, synth
+    prob = synth.make("cfg1")
+    p = G.Pair(prob)
+    wa, wv = run_rounds_sequential(G, p, prob["m"], prob["rounds"])
+    print("cfg1 worst relative deviation alpha %.2e v %.2e" % (wa, wv))
+    assert np.count_nonzero(p.g.get(duhl.ALPHA)) > 10          # the regulariser leaves a support
+    assert p.g.objective() == pytest.approx(p.o.objective(), rel=1e-6)
+    p.close()
+
+
+@pytest.mark.parametrize("kind", ["lasso_ragged", "lasso_padded", "svm_dense", "svm_csr"])
+def test_sequential_cd_iterates_match_oracle_other_shapes(G, kind):
+    from paper_1708_05357_amd import synth
+    if kind == "lasso_ragged":
+        p = G.Pair(lasso_problem(4099, 300, 0.1, 0.1, seed=5))
+        m = 90
+    elif kind == "lasso_padded":
+        p = G.Pair(lasso_problem(515, 200, 0.1, 0.1, seed=6), ld=519)
+        m = 77
+    elif kind == "svm_dense":
+        p = G.Pair(synth.svm_dense(600, 50, seed=7))
+        m = 150
+    else:
+        p = G.Pair(synth.svm_csr(2000, 300, 0.03, seed=8))
+        m = 500
+    run_rounds_sequential(G, p, m, 8, seed=3)
+    assert p.g.objective() == pytest.approx(p.o.objective(), rel=1e-6)
+    p.close()
+
+
+def test_sequential_default_order_is_ascending(G):
+    from paper_1708_05357_amd import duhl
+    p = G.Pair(lasso_problem(200, 60, 0.2, 0.1, seed=9))
+    p.g.select(20)
+    p.g.commit_swap()
+    P = p.g.get(duhl.P)
+    p.g.cd_epoch(duhl.CD_SEQUENTIAL)
+    p.o.cd_pass(P)
+    np.testing.assert_allclose(p.g.get(duhl.ALPHA), p.o.alpha, rtol=1e-5, atol=1e-7)
+    p.close()
+
+
+# ------------------------------------------------------------------------------------ asynchronous CD
+def converge_async(G, p, m, max_rounds, passes, target_rel_gap):
+    from paper_1708_05357_amd import duhl
+    o0 = p.g.objective()
+    for rnd in range(max_rounds):
+        gap = p.g.gap()
+        if gap <= target_rel_gap * abs(o0):
+            break
+        p.g.select(m, want_stats=False)
+        p.g.commit_swap()
+        for k in range(passes):
+            p.g.cd_epoch(duhl.CD_ASYNC, seed=rnd * 131 + k)
+    return rnd
+
+
+def converge_oracle(p, m, max_rounds, passes, target_rel_gap):
+    o0 = p.o.objective()
+    rng = np.random.default_rng(0)
+    for rnd in range(max_rounds):
+        if p.o.gaps() <= target_rel_gap * abs(o0):
+            break
+        P = p.o.select(m)
+        for k in range(passes):
+            p.o.cd_pass(P[rng.permutation(P.size)])
+    return rnd
+
+
+@pytest.mark.parametrize("kind", ["cfg1", "lasso_mid", "svm_dense", "svm_csr"])
+def test_async_cd_reaches_the_oracle_objective(G, kind):
+    """The asynchronous scheme is compared on what is unique: the objective at convergence
+    (1e-5 relative), and on the invariant v = A alpha (- b) that the atomic adds must keep."""
+    from paper_1708_05357_amd import duhl, synth
+    if kind == "cfg1":
+        prob = synth.make("cfg1")
+        m = prob["m"]
+    elif kind == "lasso_mid":
+        prob = lasso_problem(5000, 3000, 0.03, 0.05, seed=11)
+        m = 300
+    elif kind == "svm_dense":
+        prob = synth.svm_dense(2000, 300, seed=12)
+        m = 500
+    else:
+        prob = synth.svm_csr(20000, 2000, 0.01, seed=13)
+        m = 4000
+    p = G.Pair(prob)
+    tol = 1e-7 if prob["model"] == "lasso" else 1e-6
+    r_gpu = converge_async(G, p, m, 400, 3, tol)
+    r_or = converge_oracle(p, m, 400, 3, tol)
+    og, oo = p.g.objective(), p.o.objective()
+    print(f"{kind}: rounds gpu {r_gpu} oracle {r_or} objective gpu {og:.9e} oracle {oo:.9e}")
+    assert abs(og - oo) <= 1e-5 * abs(oo)
+    # the shared vector still is what its definition says (App. D), up to fp32 accumulation
+    a, v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+    p.o.set_state(a.astype(np.float64))
+    scale = max(np.abs(p.o.v).max(), np.abs(G.to_np(prob["target"])).max() if prob["model"] == "lasso" else 1.0)
+    assert np.abs(v - p.o.v).max() <= 2e-4 * scale
+    p.g.recompute_v()
+    np.testing.assert_allclose(p.g.get(duhl.V), p.o.v, atol=2e-6 * scale)
+    p.close()
+
+
+# ------------------------------------------------------------------------------------ host residency
+def test_host_resident_swap_matches_oracle(G):
+    """Alg. 2 with the matrix in pinned host memory and fewer device slots than columns: the
+    copies run on the side stream while the previous set is being worked on; iterates must still
+    match the oracle, and the slots must hold the selected columns."""
+    from paper_1708_05357_amd import duhl
+    prob = lasso_problem(1028, 400, 0.1, 0.1, seed=21)
+    m = 60
+    for budget in (2 * m, m + 7):                  # overlapping copies / in-place replacement
+        p = G.Pair(prob, budget=budget, host_resident=True)
+        p.o.gaps()
+        G.assert_gaps_close(p.g.get(duhl.Z), p.o.z)
+        rng = np.random.default_rng(2)
+        all_idx = G.dev_i32(np.arange(prob["n"]))
+        nsw, rho = p.g.select(m)
+        assert nsw == m
+        p.g.commit_swap()
+        for rnd in range(10):
+            P = p.g.get(duhl.P)
+            order = rng.permutation(P).astype(np.int32)
+            if budget >= 2 * m:
+                # time-delayed scheme: choose the next set from the gaps before this pass,
+                # copy while the pass runs, then switch
+                p.g.gap(all_idx, want_sum=False)
+                nsw, rho = p.g.select(m)
+                p.g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(order))
+                p.g.commit_swap()
+            else:
+                p.g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(order))
+                p.g.gap(all_idx, want_sum=False)
+                nsw, rho = p.g.select(m)
+                with pytest.raises(duhl.DuhlError):
+                    p.g.cd_epoch(duhl.CD_SEQUENTIAL)       # slots are being overwritten
+                p.g.commit_swap()
+            p.o.cd_pass(order)
+            a, v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+            assert np.abs(a - p.o.alpha).max() <= 1e-5 * np.abs(p.o.alpha).max()
+            assert np.abs(v - p.o.v).max() <= 1e-5 * np.abs(p.o.v).max()
+            Pn = p.g.get(duhl.P)
+            fresh = np.setdiff1d(Pn, P).size       # spare slots may still hold some of them
+            assert fresh - (budget - m) <= nsw <= fresh
+            assert 1.0 - 1e-9 <= rho <= prob["n"] / m + 1e-9
+        # gaps of the resident columns (idx = NULL) equal the oracle's at the same state
+        p.sync_oracle_to_gpu_state()
+        p.o.gaps()
+        p.g.set(duhl.Z, np.full(prob["n"], -1.0, dtype=np.float32))
+        p.g.gap(want_sum=False)
+        z = p.g.get(duhl.Z)
+        Pn = p.g.get(duhl.P)
+        assert np.all(z[Pn] >= 0)
+        floor = G.lasso_gap_floor(p)
+        np.testing.assert_allclose(z[Pn], p.o.z[Pn], rtol=1e-4, atol=1e-4 * p.o.z.max() + floor)
+        assert np.count_nonzero(z >= 0) <= budget
+        p.close()
+
+
+# ------------------------------------------------------------------------------------ API behaviour
+def test_error_paths(G):
+    from paper_1708_05357_amd import duhl
+    dev = "cuda:0"
+    g = duhl.Duhl(duhl.LASSO, 8, 6, 3)
+    with pytest.raises(duhl.DuhlError) as e:
+        g.gap()
+    assert e.value.status == duhl.ESTATE
+    cols = torch.randn(6, 8, device=dev)
+    b = torch.randn(8, device=dev)
+    for lam in (0.0, -1.0, float("nan"), float("inf")):
+        with pytest.raises(duhl.DuhlError) as e:
+            g.set_data_dense(cols, b, lam)
+        assert e.value.status == duhl.EINVAL
+    with pytest.raises(duhl.DuhlError) as e:
+        g.set_data_dense(cols, torch.full((8,), float("nan"), device=dev), 0.1)
+    assert e.value.status == duhl.EINVAL
+    g.set_data_dense(cols, b, 0.1)
+    with pytest.raises(duhl.DuhlError) as e:
+        g.cd_epoch()
+    assert e.value.status == duhl.ESTATE
+    with pytest.raises(duhl.DuhlError) as e:
+        g.select(4)
+    assert e.value.status == duhl.EBUDGET
+    with pytest.raises(duhl.DuhlError) as e:
+        g.select(0)
+    assert e.value.status == duhl.EINVAL
+    with pytest.raises(duhl.DuhlError) as e:
+        g.commit_swap()
+    assert e.value.status == duhl.ESTATE
+    g.select(3)
+    g.commit_swap()
+    g.cd_epoch()
+    g.close()
+    s = duhl.Duhl(duhl.SVM, 8, 6, 6)
+    with pytest.raises(duhl.DuhlError) as e:
+        s.set_data_dense(cols, torch.tensor([1, -1, 1, 0.5, 1, -1.0], device=dev), 0.1)
+    assert e.value.status == duhl.EINVAL
+    rowptr = torch.tensor([0, 2, 2, 3, 3, 3, 4], dtype=torch.int64, device=dev)
+    val = torch.ones(4, device=dev)
+    y = torch.tensor([1, -1, 1, 1, 1, -1.0], device=dev)
+    for bad in ([1, 0, 2, 3], [0, 8, 2, 3], [0, 0, 2, 3]):
+        with pytest.raises(duhl.DuhlError) as e:
+            s.set_data_csr(rowptr, torch.tensor(bad, dtype=torch.int32, device=dev), val, y, 0.1)
+        assert e.value.status == duhl.EINVAL
+    bad_ptr = torch.tensor([0, 2, 1, 3, 3, 3, 4], dtype=torch.int64, device=dev)
+    with pytest.raises(duhl.DuhlError) as e:
+        s.set_data_csr(bad_ptr, torch.tensor([0, 1, 2, 3], dtype=torch.int32, device=dev), val, y, 0.1)
+    assert e.value.status == duhl.EINVAL
+    s.set_data_csr(rowptr, torch.tensor([0, 1, 2, 3], dtype=torch.int32, device=dev), val, y, 0.1)
+    assert s.gap() == pytest.approx(1.0)
+    s.close()
+
+
+def test_zero_columns_and_empty_rows(G):
+    """Degenerate coordinates: a zero column (Lasso -> alpha_j = 0) and an empty CSR row
+    (SVM -> alpha_j = y_j), both schemes."""
+    from paper_1708_05357_amd import duhl, synth
+    prob = lasso_problem(300, 40, 0.2, 0.1, seed=31)
+    prob["cols"][7] = 0
+    p = G.Pair(prob)
+    a0 = np.zeros(40, dtype=np.float32)
+    a0[7] = 0.3
+    for mode in (duhl.CD_SEQUENTIAL, duhl.CD_ASYNC):
+        p.g.set(duhl.ALPHA, a0)
+        p.g.set(duhl.Z, np.arange(40, 0, -1).astype(np.float32))
+        p.g.select(40)
+        p.g.commit_swap()
+        p.g.cd_epoch(mode, max_inflight=1)
+        assert p.g.get(duhl.ALPHA)[7] == 0.0
+    p.close()
+    sp = synth.svm_csr(64, 50, 0.1, seed=2)
+    rp = sp["rowptr"].clone()
+    cut = int(rp[6] - rp[5])
+    keep = torch.ones(sp["val"].numel(), dtype=torch.bool)
+    keep[int(rp[5]):int(rp[6])] = False
+    sp["val"], sp["colidx"] = sp["val"][keep], sp["colidx"][keep]
+    rp[6:] -= cut
+    sp["rowptr"] = rp
+    p = G.Pair(sp)
+    for mode in (duhl.CD_ASYNC, duhl.CD_SEQUENTIAL):
+        p.g.set(duhl.ALPHA, np.zeros(64, dtype=np.float32))
+        p.g.recompute_v()
+        p.g.select(64)
+        p.g.commit_swap()
+        p.g.cd_epoch(mode, max_inflight=1)
+        assert p.g.get(duhl.ALPHA)[5] == G.to_np(sp["target"])[5]
+    o = p.o
+    o.cd_pass(np.arange(64, dtype=np.int32))
+    np.testing.assert_allclose(p.g.get(duhl.ALPHA), o.alpha, rtol=1e-5, atol=1e-6)
+    p.close()
