@@ -111,7 +111,10 @@ def test_selection_is_bit_exact_on_the_same_z(G, n):
             nsw, rho = p.g.select(m, out)
             want = orc.select_topm(z.astype(np.float64), m)
             np.testing.assert_array_equal(out.cpu().numpy(), want, err_msg=f"{name} m={m}")
-            assert rho == pytest.approx(orc.rho(z.astype(np.float64), want), rel=1e-12), (name, m)
+            if z.sum() > 0:
+                assert rho == pytest.approx(orc.rho(z.astype(np.float64), want), rel=1e-12), (name, m)
+            else:
+                assert rho == 1.0               # all gaps zero: the ratio of eq. (7) is 0/0
             p.g.commit_swap()
             np.testing.assert_array_equal(p.g.get(duhl.P), want)
     p.close()
@@ -151,7 +154,8 @@ def run_rounds_sequential(G, p, m, rounds, seed=0, check_selection=True):
             Po = p.o.select(m)
             if not np.array_equal(P, Po):
                 thr = np.sort(p.o.z)[-m]
-                band = 1e-4 * p.o.z.max()
+                # tie band: the 1e-4 relative agreement of the gaps plus their fp32 rounding floor
+                band = 1e-4 * p.o.z.max() + (G.lasso_gap_floor(p) if p.model == duhl.LASSO else 1e-7 / p.o.n)
                 diff = np.setxor1d(P, Po)
                 assert np.all(np.abs(p.o.z[diff] - thr) <= band), (rnd, diff, p.o.z[diff], thr)
         order = rng.permutation(P).astype(np.int32)
