@@ -62,7 +62,7 @@ def algorithmic_bytes(prob, m):
     return 8.0 * nnz + 8.0 * (n + 1) + 12.0 * n, per * m + 8.0 * m
 
 
-def one_step(g, prob, m, step, ev=None, sample_idx=None):
+def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0):
     """gap -> select -> commit -> epoch.  With host residency the gaps are refreshed for the
     resident columns plus a sample of the others (stale gap memory, Section 4.1)."""
     from paper_1708_05357_amd import duhl
@@ -79,14 +79,14 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None):
         g.commit_swap()
     if ev:
         ev[2].record()
-    g.cd_epoch(duhl.CD_ASYNC, seed=step)       # host residency: runs while the copies are in flight
+    g.cd_epoch(mode, seed=step, max_inflight=inflight)   # host residency: overlaps the copies
     if ev:
         ev[3].record()
     if overlapped:
         g.commit_swap()
 
 
-def time_to_gap(g, set_data, prob, m, target, max_rounds, passes):
+def time_to_gap(g, set_data, prob, m, target, max_rounds, passes, mode=1, inflight=0):
     """Wall time from alpha = 0 until a fresh full gap pass reports total gap <= target
     (absolute, with the paper's 1/d or 1/n normalisation) and <= target * O(0)."""
     import torch
@@ -113,7 +113,7 @@ def time_to_gap(g, set_data, prob, m, target, max_rounds, passes):
         g.select(m, want_stats=False)
         g.commit_swap()
         for k in range(passes):
-            g.cd_epoch(duhl.CD_ASYNC, seed=1000 + rnd * passes + k)
+            g.cd_epoch(mode, seed=1000 + rnd * passes + k, max_inflight=inflight)
         rounds = rnd + 1
     return {"abs_1e-3_s": t_abs, "rel_1e-3_s": t_rel, "rounds": rounds, "final_gap": gap,
             "objective_at_zero": o0, "final_objective": g.objective(), "passes_per_round": passes}
@@ -182,6 +182,9 @@ def main():
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-ttg", action="store_true")
     ap.add_argument("--ttg-passes", type=int, default=1)
+    ap.add_argument("--cd-mode", default="async", choices=["async", "atomic"],
+                    help="concurrent CD scheme: the library's default, or per-update atomics")
+    ap.add_argument("--inflight", type=int, default=0, help="max_inflight of duhl_cd_epoch (0 = default)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the single-GPU hot path; this build has no multi-GPU path "
@@ -196,6 +199,7 @@ def main():
     m = prob["m"]
     budget = int(m * args.budget_factor) if prob["host_resident"] else m
     g, set_data = make_ctx(prob, budget)
+    mode = duhl.CD_ASYNC if args.cd_mode == "async" else duhl.CD_ATOMIC
     sample_idx = None
     if prob["host_resident"]:
         # 5 % of the columns per round, refreshed from host memory (Section 5.1)
@@ -206,7 +210,7 @@ def main():
                       for _ in range(8)]
 
     for s in range(args.warmup):
-        one_step(g, prob, m, s, sample_idx=sample_idx)
+        one_step(g, prob, m, s, sample_idx=sample_idx, mode=mode, inflight=args.inflight)
     torch.cuda.synchronize()
     set_data()                                  # back to alpha = 0: the timed rounds are rounds 1..K
     torch.cuda.synchronize()
@@ -215,7 +219,7 @@ def main():
     torch.cuda.synchronize()
     t0 = time.time()
     for s in range(args.steps):
-        one_step(g, prob, m, s, evs[s], sample_idx)
+        one_step(g, prob, m, s, evs[s], sample_idx, mode, args.inflight)
     torch.cuda.synchronize()
     elapsed = time.time() - t0
 
@@ -241,7 +245,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {prob['model']} d={prob['d']} n={prob['n']} m={m}"
                                + (f" host-resident, {budget} device slots" if prob["host_resident"] else ""),
-                   "scale": args.scale, "rounds_timed": args.steps, "passes_per_round": 1},
+                   "scale": args.scale, "rounds_timed": args.steps, "passes_per_round": 1,
+                   "cd_scheme": args.cd_mode, "max_inflight": args.inflight},
         "phases": {"gap_ms": avg(gap_ms), "select_ms": avg(sel_ms), "cd_ms": avg(cd_ms),
                    "gap_GBps": gap_gbps, "gap_frac_of_hbm_peak": gap_gbps / HBM_PEAK_GBPS,
                    "cd_updates_per_s": m / (avg(cd_ms) * 1e-3), "cd_GBps": cd_gbps,
@@ -254,7 +259,7 @@ def main():
         "gen_s": prob["gen_s"],
     }
     if not args.no_ttg:
-        out["time_to_gap"] = time_to_gap(g, set_data, prob, m, 1e-3, 400, args.ttg_passes)
+        out["time_to_gap"] = time_to_gap(g, set_data, prob, m, 1e-3, 400, args.ttg_passes, mode, args.inflight)
     if not args.no_cpu:
         out["cpu_baseline"] = cpu_baseline(prob, m)
     else:

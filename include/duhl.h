@@ -61,7 +61,9 @@ typedef enum { DUHL_ALPHA = 0, DUHL_V = 1, DUHL_Z = 2, DUHL_P = 3, DUHL_SQNORM =
 /* Visiting scheme of duhl_cd_epoch. */
 typedef enum {
     DUHL_CD_SEQUENTIAL = 0, /* one coordinate at a time, in the given order (Algorithm 3)     */
-    DUHL_CD_ASYNC = 1       /* many coordinates in flight, atomic adds on v (Appendix D)      */
+    DUHL_CD_ASYNC = 1,      /* many coordinates at once, the library's fastest scheme          */
+    DUHL_CD_ATOMIC = 2      /* many coordinates at once, one atomic update of v per step
+                               (the thread-block-per-coordinate scheme of Appendix D)          */
 } duhl_cd_mode;
 
 /* Create a context for a problem with columns of length d and n coordinates.
@@ -123,12 +125,19 @@ duhl_status duhl_commit_swap(duhl_ctx *ctx);
  *   SVM:    alpha_j <- y_j clip(y_j(alpha_j + (y_j - a_j^T v/(lambda n)) lambda n/||a_j||^2), 0, 1)
  *   both:   v <- v + a_j (alpha_j_new - alpha_j_old)
  * order (device, int32): the coordinates to visit, in visiting order; each must belong to the
- * current working set; n_order entries.  order == NULL: the whole set -- ascending for
- * DUHL_CD_SEQUENTIAL, a pseudo-random permutation drawn from (seed, pass counter) for
- * DUHL_CD_ASYNC.  DUHL_CD_SEQUENTIAL solves one coordinate after the other and is
- * reproducible.  DUHL_CD_ASYNC solves up to max_inflight coordinates concurrently (0 = chosen
- * by the library), each against the v it happens to read; v is updated with atomic adds, so
- * v = A alpha (- b) keeps holding up to rounding but iterates depend on timing. */
+ * current working set and, for the concurrent schemes, appear once; n_order entries.
+ * order == NULL: the whole set -- ascending for DUHL_CD_SEQUENTIAL, a pseudo-random permutation
+ * drawn from (seed, pass counter) otherwise.
+ * DUHL_CD_SEQUENTIAL solves one coordinate after the other and is reproducible.
+ * The concurrent schemes solve up to max_inflight coordinates (0 = a tenth-scale default,
+ * count/8) without seeing each other's update of v -- the asynchrony of Appendix D, bounded:
+ *   DUHL_CD_ATOMIC  each step reads the live v and adds a_j*delta to it with fp32 atomics;
+ *                   iterates depend on timing.
+ *   DUHL_CD_ASYNC   dense data: the pass is cut into sub-passes of max_inflight coordinates;
+ *                   workers solve their share one after the other against a private copy of v and
+ *                   the changes are merged after each sub-pass (no atomics, reproducible for a
+ *                   given seed).  Sparse data: same as DUHL_CD_ATOMIC.
+ * In all schemes v = A alpha (- b) keeps holding up to fp32 rounding. */
 duhl_status duhl_cd_epoch(duhl_ctx *ctx, duhl_cd_mode mode, const int32_t *order,
                           int64_t n_order, uint64_t seed, int max_inflight);
 

@@ -328,7 +328,8 @@ duhl_status duhl_cd_epoch(duhl_ctx *c, duhl_cd_mode mode, const int32_t *order, 
 {
     if (!c) return DUHL_EINVAL;
     if (!c->have_data) return fail(c, DUHL_ESTATE, "no data set");
-    if (mode != DUHL_CD_SEQUENTIAL && mode != DUHL_CD_ASYNC) return fail(c, DUHL_EINVAL, "bad mode");
+    if (mode != DUHL_CD_SEQUENTIAL && mode != DUHL_CD_ASYNC && mode != DUHL_CD_ATOMIC)
+        return fail(c, DUHL_EINVAL, "bad mode");
     if (c->m_cur <= 0) return fail(c, DUHL_ESTATE, "no working set: call duhl_select and duhl_commit_swap");
     if (c->pending && c->swap_exclusive)
         return fail(c, DUHL_ESTATE, "the working set is being replaced in place: call duhl_commit_swap first");
@@ -438,6 +439,7 @@ void duhl_destroy(duhl_ctx *c)
     (void)hipFree(c->P_cur); (void)hipFree(c->P_next);
     (void)hipFree(c->scalars); (void)hipFree(c->partials); (void)hipFree(c->sel);
     (void)hipFree(c->blk_gt); (void)hipFree(c->blk_eq); (void)hipFree(c->mark);
+    (void)hipFree(c->dv); (void)hipFree(c->dirty);
     if (c->h_scalars) (void)hipHostFree(c->h_scalars);
     if (c->h_u32) (void)hipHostFree(c->h_u32);
     delete c;

@@ -148,6 +148,11 @@ struct duhl_ctx {
     uint32_t *blk_gt, *blk_eq;  // per-chunk counts of the selection scatter
     int64_t blk_cap;
 
+    // private buffers of the asynchronous dense workers (allocated on first use)
+    float *dv;
+    int64_t dv_stride, dv_workers;
+    int32_t *dirty;
+
     // host residency
     float *slots;
     int64_t ld_s;

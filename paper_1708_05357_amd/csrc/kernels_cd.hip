@@ -3,14 +3,23 @@
 // Sequential scheme: a single workgroup (dense) or wavefront (sparse) visits the coordinates in
 // the given order; reductions run in a fixed order, so the pass is reproducible.
 //
-// Asynchronous scheme (the TPA-SCD idea of Appendix D re-designed for wave64 hardware): a group
-// of T threads owns one coordinate at a time.  It streams the column once from HBM with 16-byte
-// loads and KEEPS IT IN REGISTERS, forms a_j^T v against the live shared vector (loads at agent
-// scope, so updates made on other XCDs are seen), solves the coordinate exactly and, only if
-// alpha_j moved, adds a_j * delta to v with hardware fp32 atomics straight from those registers
-// -- the column is read from memory exactly once per update.  T is 64 (one wavefront, short
-// columns), 256 or 1024 so that a column fits the group's registers.  Groups take coordinates
-// with a fixed stride; the number of groups is the number of coordinates in flight.
+// Atomic scheme (the TPA-SCD idea of Appendix D on wave64 hardware): a group of T threads owns
+// one coordinate at a time.  It streams the column once from HBM with 16-byte loads and keeps it
+// in registers, forms a_j^T v against the live shared vector (16-byte buffer loads at agent scope,
+// so updates made on other XCDs are seen), solves the coordinate exactly and, only if alpha_j
+// moved, adds a_j * delta to v with hardware fp32 atomics straight from those registers.
+//
+// Asynchronous scheme for dense data, built around what the atomic units of this chip can
+// sustain (about 0.3 T fp32 atomic adds/s device-wide, far below the 2 T floats/s that HBM
+// streams): a pass is cut into sub-passes of at most `inflight` coordinates.  Inside a sub-pass
+// every worker (a group of T threads) keeps its OWN copy of v in registers, visits its share of
+// the coordinates one after the other -- each step exact against that copy, so a worker is a
+// sequential solver -- and finally stores its accumulated change of v to a private buffer; a
+// merge kernel adds the buffers to v in a fixed order.  Per update the only memory traffic is
+// the column itself, read once; there are no atomics and the result is reproducible.  Workers do
+// not see each other inside a sub-pass, exactly like concurrently running thread blocks that
+// read a stale v; `inflight` bounds that staleness.  Sparse data keeps the atomic scheme: its
+// scattered updates are few and spread over all of v.
 #include "duhl_internal.h"
 
 namespace duhl {
@@ -56,14 +65,31 @@ __device__ __forceinline__ float live_load(const float *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-__device__ __forceinline__ float4 live_load4(const float *p)
+// The same for 16 bytes in one instruction: a raw buffer load whose cache-policy operand carries
+// the agent-scope bit (sc1); rs describes v, byte_off is bounds-checked by the hardware.
+typedef int v4i_t __attribute__((ext_vector_type(4)));
+// Plain 16-byte buffer load / store: address = base + voff (per lane) + soff (uniform); accesses
+// past the size recorded in rs return 0 / are dropped, so ragged ends need no branch.
+__device__ __forceinline__ float4 buffer_load4(__amdgpu_buffer_rsrc_t rs, int voff, int soff)
 {
-    float4 r;
-    r.x = live_load(p);
-    r.y = live_load(p + 1);
-    r.z = live_load(p + 2);
-    r.w = live_load(p + 3);
-    return r;
+    const v4i_t raw = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 0);
+    return make_float4(__int_as_float(raw.x), __int_as_float(raw.y), __int_as_float(raw.z),
+                       __int_as_float(raw.w));
+}
+__device__ __forceinline__ void buffer_store4(__amdgpu_buffer_rsrc_t rs, int voff, int soff, float4 x)
+{
+    v4i_t raw;
+    raw.x = __float_as_int(x.x);
+    raw.y = __float_as_int(x.y);
+    raw.z = __float_as_int(x.z);
+    raw.w = __float_as_int(x.w);
+    __builtin_amdgcn_raw_buffer_store_b128(raw, rs, voff, soff, 0);
+}
+__device__ __forceinline__ float4 live_load4(__amdgpu_buffer_rsrc_t rs, int byte_off)
+{
+    const v4i_t raw = __builtin_amdgcn_raw_buffer_load_b128(rs, byte_off, 0, 16);
+    return make_float4(__int_as_float(raw.x), __int_as_float(raw.y), __int_as_float(raw.z),
+                       __int_as_float(raw.w));
 }
 __device__ __forceinline__ void live_add(float *p, float x)
 {
@@ -96,13 +122,14 @@ __device__ __forceinline__ float group_reduce(float x, float (*red)[16], int par
 
 // ---- asynchronous, dense ------------------------------------------------------------------------
 template <int MODEL, int T, int NREG, bool VEC4>
-__global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_async_kernel(const CdArgs a)
+__global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_atomic_kernel(const CdArgs a)
 {
     constexpr int BLOCK = T == 64 ? 256 : T;
     __shared__ float red[2][16];
     const int tid = threadIdx.x % T;
     const int64_t ngroups = (int64_t)gridDim.x * (BLOCK / T);
     const int64_t d4 = VEC4 ? (a.d >> 2) : 0;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(a.v, 0, (int)(a.d * 4), 0x00020000);
     int parity = 0;
     for (int64_t t = (int64_t)blockIdx.x * (BLOCK / T) + threadIdx.x / T; t < a.count;
          t += ngroups) {
@@ -117,18 +144,13 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_async_kernel(const
                 const int64_t r = tid + (int64_t)i * T;
                 x[i] = r < d4 ? c4[r] : make_float4(0.f, 0.f, 0.f, 0.f);
             }
-            // v is consumed four chunks at a time so that its values never crowd out the column
 #pragma unroll
-            for (int i0 = 0; i0 < NREG; i0 += 4) {
-#pragma unroll
-                for (int i = i0; i < (i0 + 4 < NREG ? i0 + 4 : NREG); ++i) {
-                    const int64_t r = tid + (int64_t)i * T;
-                    if (r < d4) acc = dot4(x[i], live_load4(a.v + 4 * r), acc);
-                }
-                if (i0 + 4 < NREG) __builtin_amdgcn_sched_barrier(0);
+            for (int i = 0; i < NREG; ++i) {
+                const int64_t r = tid + (int64_t)i * T;
+                if (r < d4) acc = dot4(x[i], live_load4(rs, (int)(r * 16)), acc);
             }
             for (int64_t r = tid + (int64_t)NREG * T; r < d4; r += T)     // beyond the registers
-                acc = dot4(c4[r], live_load4(a.v + 4 * r), acc);
+                acc = dot4(c4[r], live_load4(rs, (int)(r * 16)), acc);
         }
         for (int64_t r = (d4 << 2) + tid; r < a.d; r += T) acc = fmaf(col[r], live_load(a.v + r), acc);
         const float c = group_reduce<T>(acc, red, parity);
@@ -164,6 +186,116 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_async_kernel(const
             if (tid == 0) a.alpha[j] = now;
         }
     }
+}
+
+
+// ---- asynchronous, dense: workers with a private copy of v --------------------------------------
+// One sub-pass over positions [t_begin, t_end) of the visiting order.  CACHE_X keeps the column
+// in registers between the dot product and the update (one read per update); without it (very
+// long columns: the registers are needed for v) the column is read again, only when alpha_j moved.
+template <int MODEL, int T, int NREG, bool CACHE_X>
+__global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
+    const CdArgs a, const int64_t t_begin, const int64_t t_end, float *dv, const int64_t dv_stride,
+    int32_t *dirty)
+{
+    constexpr int BLOCK = T == 64 ? 256 : T;
+    constexpr int kStep = T * 16;                      // bytes between a thread's chunks
+    __shared__ float red[2][16];
+    const int tid = threadIdx.x % T;
+    // the worker index is the same in all lanes of a wavefront: say so to the compiler
+    const int w = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (BLOCK / T) + threadIdx.x / T));
+    const int64_t nworkers = (int64_t)gridDim.x * (BLOCK / T);
+    const int64_t d4 = a.d >> 2;
+    const int tail = (int)(a.d - (d4 << 2));
+    const int vec_bytes = (int)(d4 << 4);              // 16-byte part of a column; loads beyond it
+    const int off = tid * 16;                          // return 0 (buffer bounds check)
+    const __amdgpu_buffer_rsrc_t rs_v = __builtin_amdgcn_make_buffer_rsrc(a.v, 0, vec_bytes, 0x00020000);
+
+    float4 vl[NREG];                                   // this worker's v, rows 4*(tid + i*T) ..
+#pragma unroll
+    for (int i = 0; i < NREG; ++i) vl[i] = buffer_load4(rs_v, off, i * kStep);
+    float vt = tid < tail ? a.v[(d4 << 2) + tid] : 0.0f;
+    bool moved = false;
+    int parity = 0;
+    for (int64_t t = t_begin + w; t < t_end; t += nworkers) {
+        const int j = __builtin_amdgcn_readfirstlane((int)coord_at(a, t));
+        const float *col = a.cv.col(j);
+        const __amdgpu_buffer_rsrc_t rs_x =
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(col), 0, vec_bytes, 0x00020000);
+        float4 x[CACHE_X ? NREG : 1];
+        float acc = 0.0f;
+        if (CACHE_X) {
+#pragma unroll
+            for (int i = 0; i < NREG; ++i) x[i] = buffer_load4(rs_x, off, i * kStep);
+#pragma unroll
+            for (int i = 0; i < NREG; ++i) acc = dot4(x[i], vl[i], acc);
+        } else {
+            // four chunks in flight at a time: the registers are taken by the worker's v
+#pragma unroll
+            for (int i = 0; i < NREG; ++i) {
+                acc = dot4(buffer_load4(rs_x, off, i * kStep), vl[i], acc);
+                if ((i & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        const float xt = tid < tail ? col[(d4 << 2) + tid] : 0.0f;
+        acc = fmaf(xt, vt, acc);
+        const float c = group_reduce<T>(acc, red, parity);
+        parity ^= 1;
+
+        const float old = a.alpha[j];
+        const float y = MODEL == DUHL_SVM ? a.target[j] : 0.0f;
+        const float now = cd_new_alpha<MODEL>(a.mc, c, old, a.q[j], y);
+        const float delta = now - old;
+        if (delta != 0.0f) {
+#pragma unroll
+            for (int i = 0; i < NREG; ++i) {
+                const float4 xx = CACHE_X ? x[i] : buffer_load4(rs_x, off, i * kStep);
+                vl[i].x = fmaf(xx.x, delta, vl[i].x);
+                vl[i].y = fmaf(xx.y, delta, vl[i].y);
+                vl[i].z = fmaf(xx.z, delta, vl[i].z);
+                vl[i].w = fmaf(xx.w, delta, vl[i].w);
+                if (!CACHE_X && (i & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+            }
+            vt = fmaf(xt, delta, vt);
+            moved = true;
+            if (tid == 0) a.alpha[j] = now;
+        }
+    }
+    if (moved) {                                       // this worker's change of v
+        float *out = dv + (int64_t)w * dv_stride;
+        const __amdgpu_buffer_rsrc_t rs_o = __builtin_amdgcn_make_buffer_rsrc(out, 0, vec_bytes, 0x00020000);
+#pragma unroll
+        for (int i = 0; i < NREG; ++i) {
+            const float4 base = buffer_load4(rs_v, off, i * kStep);
+            buffer_store4(rs_o, off, i * kStep,
+                          make_float4(vl[i].x - base.x, vl[i].y - base.y, vl[i].z - base.z,
+                                      vl[i].w - base.w));                  // beyond the end: dropped
+            if ((i & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        }
+        if (tid < tail) out[(d4 << 2) + tid] = vt - a.v[(d4 << 2) + tid];
+    }
+    if (tid == 0) dirty[w] = moved ? 1 : 0;
+}
+
+// v += sum over workers of their stored changes, in worker order (reproducible).
+__global__ __launch_bounds__(256) void merge_workers_kernel(float *v, int64_t d, const float *dv,
+                                                            int64_t dv_stride, const int32_t *dirty,
+                                                            int nworkers)
+{
+    const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (k >= d) return;
+    float s = 0.0f;
+    int g = 0;
+    for (; g + 4 <= nworkers; g += 4) {                // dirty[] is uniform: scalar branches
+        const float a0 = dirty[g] ? dv[(int64_t)g * dv_stride + k] : 0.0f;
+        const float a1 = dirty[g + 1] ? dv[(int64_t)(g + 1) * dv_stride + k] : 0.0f;
+        const float a2 = dirty[g + 2] ? dv[(int64_t)(g + 2) * dv_stride + k] : 0.0f;
+        const float a3 = dirty[g + 3] ? dv[(int64_t)(g + 3) * dv_stride + k] : 0.0f;
+        s += (a0 + a1) + (a2 + a3);
+    }
+    for (; g < nworkers; ++g)
+        if (dirty[g]) s += dv[(int64_t)g * dv_stride + k];
+    if (s != 0.0f) v[k] += s;
 }
 
 // ---- asynchronous, sparse: G lanes per coordinate -------------------------------------------------
@@ -271,40 +403,134 @@ uint64_t splitmix64(uint64_t &s)
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
 template <int MODEL, int T, int NREG>
-hipError_t launch_async_dense_t(duhl_ctx *c, const CdArgs &a, int inflight, bool vec)
+hipError_t launch_atomic_dense_t(duhl_ctx *c, const CdArgs &a, int inflight, bool vec)
 {
     constexpr int BLOCK = T == 64 ? 256 : T;
     constexpr int PER = BLOCK / T;
     int64_t grid = (inflight + PER - 1) / PER;
     if (grid < 1) grid = 1;
     if (vec)
-        hipLaunchKernelGGL((cd_dense_async_kernel<MODEL, T, NREG, true>), dim3(grid), dim3(BLOCK), 0,
+        hipLaunchKernelGGL((cd_dense_atomic_kernel<MODEL, T, NREG, true>), dim3(grid), dim3(BLOCK), 0,
                            c->compute, a);
     else
-        hipLaunchKernelGGL((cd_dense_async_kernel<MODEL, T, 1, false>), dim3(grid), dim3(BLOCK), 0,
+        hipLaunchKernelGGL((cd_dense_atomic_kernel<MODEL, T, 1, false>), dim3(grid), dim3(BLOCK), 0,
                            c->compute, a);
     return hipGetLastError();
 }
 
 template <int MODEL, int T>
-hipError_t launch_async_dense_n(duhl_ctx *c, const CdArgs &a, int inflight, bool vec)
+hipError_t launch_atomic_dense_n(duhl_ctx *c, const CdArgs &a, int inflight, bool vec)
 {
     const int64_t chunks = ((c->d >> 2) + T - 1) / T;   // float4 per thread to hold a column
-    if (chunks <= 1) return launch_async_dense_t<MODEL, T, 1>(c, a, inflight, vec);
-    if (chunks <= 2) return launch_async_dense_t<MODEL, T, 2>(c, a, inflight, vec);
-    if (chunks <= 4) return launch_async_dense_t<MODEL, T, 4>(c, a, inflight, vec);
-    if (chunks <= 8) return launch_async_dense_t<MODEL, T, 8>(c, a, inflight, vec);
-    if (chunks <= 13) return launch_async_dense_t<MODEL, T, 13>(c, a, inflight, vec);
-    if (chunks <= 16) return launch_async_dense_t<MODEL, T, 16>(c, a, inflight, vec);
-    return launch_async_dense_t<MODEL, T, 20>(c, a, inflight, vec);
+    if (chunks <= 1) return launch_atomic_dense_t<MODEL, T, 1>(c, a, inflight, vec);
+    if (chunks <= 2) return launch_atomic_dense_t<MODEL, T, 2>(c, a, inflight, vec);
+    if (chunks <= 4) return launch_atomic_dense_t<MODEL, T, 4>(c, a, inflight, vec);
+    if (chunks <= 8) return launch_atomic_dense_t<MODEL, T, 8>(c, a, inflight, vec);
+    if (chunks <= 13) return launch_atomic_dense_t<MODEL, T, 13>(c, a, inflight, vec);
+    return launch_atomic_dense_t<MODEL, T, 16>(c, a, inflight, vec);
 }
 
 int threads_per_coordinate(const duhl_ctx *c)
 {
     if (c->cd_threads == 64 || c->cd_threads == 256 || c->cd_threads == 1024) return c->cd_threads;
     if (c->d <= 2048) return 64;
-    if (c->d <= 16384) return 256;
+    if (c->d <= 13312) return 256;
     return 1024;
+}
+
+// Coordinates that may be solved without seeing each other: the caller's bound, else count/8.
+int64_t inflight_limit(int64_t count, int max_inflight)
+{
+    int64_t lim = max_inflight > 0 ? max_inflight : count / 8;
+    if (lim < 1) lim = 1;
+    return lim < count ? lim : count;
+}
+
+template <int MODEL>
+hipError_t launch_atomic(duhl_ctx *c, const CdArgs &a, int max_inflight, bool vec)
+{
+    if (c->sparse) {
+        const int64_t avg = c->n > 0 ? c->nnz / c->n : 0;
+        const int G = avg > 256 ? 64 : 16;
+        const int64_t cap = (int64_t)c->num_cu * 8 * (256 / G);
+        int64_t inflight = inflight_limit(a.count, max_inflight);
+        if (inflight > cap) inflight = cap;
+        const int64_t grid = (inflight + 256 / G - 1) / (256 / G);
+        if (G == 64)
+            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 64>), dim3(grid), dim3(256), 0, c->compute, a);
+        else
+            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 16>), dim3(grid), dim3(256), 0, c->compute, a);
+        return hipGetLastError();
+    }
+    const int T = threads_per_coordinate(c);
+    const int64_t cap = (int64_t)c->num_cu * (2048 / T);
+    int64_t inflight = inflight_limit(a.count, max_inflight);
+    if (inflight > cap) inflight = cap;
+    if (T == 64) return launch_atomic_dense_n<MODEL, 64>(c, a, (int)inflight, vec);
+    if (T == 256) return launch_atomic_dense_n<MODEL, 256>(c, a, (int)inflight, vec);
+    return launch_atomic_dense_n<MODEL, 1024>(c, a, (int)inflight, vec);
+}
+
+template <int MODEL, int T, int NREG, bool CACHE_X>
+hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
+{
+    constexpr int BLOCK = T == 64 ? 256 : T;
+    constexpr int PER = BLOCK / T;
+    // Workers per sub-pass: enough to fill the chip; several coordinates per worker once the
+    // sub-pass is large, which keeps the private buffers a small fraction of the traffic.
+    const int64_t cap = c->dv_workers;
+    for (int64_t t0 = 0; t0 < a.count; t0 += inflight) {
+        const int64_t t1 = t0 + inflight < a.count ? t0 + inflight : a.count;
+        const int64_t len = t1 - t0;
+        int64_t workers = len >= 4 * (int64_t)c->num_cu ? len / 4 : (len < c->num_cu ? len : c->num_cu);
+        if (workers > cap) workers = cap;
+        const int64_t grid = (workers + PER - 1) / PER;
+        hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, T, NREG, CACHE_X>), dim3(grid), dim3(BLOCK), 0,
+                           c->compute, a, t0, t1, c->dv, c->dv_stride, c->dirty);
+        hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 255) / 256), dim3(256), 0, c->compute, a.v,
+                           c->d, c->dv, c->dv_stride, c->dirty, (int)(grid * PER));
+    }
+    return hipGetLastError();
+}
+
+// Dense asynchronous pass with private-v workers; false if this shape is not covered.
+template <int MODEL>
+bool launch_workers(duhl_ctx *c, const CdArgs &a, int max_inflight, bool vec, hipError_t *err)
+{
+    const int T = threads_per_coordinate(c);
+    const int64_t chunks = ((c->d >> 2) + T - 1) / T;
+    if (!vec || chunks > 25) return false;
+    if (!c->dv) {                                   // private buffers, allocated on first use
+        c->dv_stride = (c->d + 63) / 64 * 64;
+        int64_t workers = (int64_t)c->num_cu * (T == 1024 ? 1 : (T == 256 ? 4 : 16));
+        while (workers > c->num_cu && workers * c->dv_stride * 4 > (1ll << 30)) workers /= 2;
+        c->dv_workers = workers;
+        *err = hipMalloc(reinterpret_cast<void **>(&c->dv), (size_t)workers * c->dv_stride * 4);
+        if (*err == hipSuccess) *err = hipMalloc(reinterpret_cast<void **>(&c->dirty), (size_t)(workers + 4) * 4);
+        if (*err != hipSuccess) return true;
+    }
+    const int64_t inflight = inflight_limit(a.count, max_inflight);
+#define DUHL_W(TT, NN, CX) *err = launch_workers_t<MODEL, TT, NN, CX>(c, a, inflight)
+    if (T == 64) {
+        if (chunks <= 1) DUHL_W(64, 1, true);
+        else if (chunks <= 2) DUHL_W(64, 2, true);
+        else if (chunks <= 4) DUHL_W(64, 4, true);
+        else DUHL_W(64, 8, true);
+    } else if (T == 256) {
+        if (chunks <= 4) DUHL_W(256, 4, true);
+        else if (chunks <= 8) DUHL_W(256, 8, true);
+        else if (chunks <= 10) DUHL_W(256, 10, true);
+        else DUHL_W(256, 13, true);
+    } else {
+        if (chunks <= 4) DUHL_W(1024, 4, true);
+        else if (chunks <= 8) DUHL_W(1024, 8, true);
+        else if (chunks <= 13) DUHL_W(1024, 13, true);
+        else if (chunks <= 16) DUHL_W(1024, 16, false);
+        else if (chunks <= 20) DUHL_W(1024, 20, false);
+        else DUHL_W(1024, 25, false);
+    }
+#undef DUHL_W
+    return true;
 }
 
 template <int MODEL>
@@ -321,30 +547,11 @@ hipError_t launch_cd_model(duhl_ctx *c, duhl_cd_mode mode, const CdArgs &a, int 
             hipLaunchKernelGGL((cd_dense_seq_kernel<MODEL, false>), dim3(1), dim3(1024), 0, c->compute, a);
         return hipGetLastError();
     }
-    // Coordinates in flight: a hardware ceiling, and by default at most count/8 so that
-    // concurrent steps stay a small fraction of the block (each step sees a slightly stale v).
-    if (c->sparse) {
-        const int64_t avg = c->n > 0 ? c->nnz / c->n : 0;
-        const int G = avg > 256 ? 64 : 16;
-        int64_t cap = (int64_t)c->num_cu * 8 * (256 / G);
-        int64_t inflight = max_inflight > 0 ? max_inflight : (a.count / 8 > 0 ? a.count / 8 : 1);
-        if (inflight > cap) inflight = cap;
-        if (inflight > a.count) inflight = a.count;
-        const int64_t grid = (inflight + 256 / G - 1) / (256 / G);
-        if (G == 64)
-            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 64>), dim3(grid), dim3(256), 0, c->compute, a);
-        else
-            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 16>), dim3(grid), dim3(256), 0, c->compute, a);
-        return hipGetLastError();
+    if (mode == DUHL_CD_ASYNC && !c->sparse) {
+        hipError_t err = hipSuccess;
+        if (launch_workers<MODEL>(c, a, max_inflight, vec, &err)) return err;
     }
-    const int T = threads_per_coordinate(c);
-    int64_t cap = (int64_t)c->num_cu * (2048 / T);
-    int64_t inflight = max_inflight > 0 ? max_inflight : (a.count / 8 > 0 ? a.count / 8 : 1);
-    if (inflight > cap) inflight = cap;
-    if (inflight > a.count) inflight = a.count;
-    if (T == 64) return launch_async_dense_n<MODEL, 64>(c, a, (int)inflight, vec);
-    if (T == 256) return launch_async_dense_n<MODEL, 256>(c, a, (int)inflight, vec);
-    return launch_async_dense_n<MODEL, 1024>(c, a, (int)inflight, vec);
+    return launch_atomic<MODEL>(c, a, max_inflight, vec);
 }
 
 }  // namespace
@@ -359,7 +566,7 @@ hipError_t launch_cd(duhl_ctx *c, duhl_cd_mode mode, const int32_t *order, int64
     a.order = order;
     a.P = c->P_cur;
     a.count = order ? count : c->m_cur;
-    a.permute = (!order && mode == DUHL_CD_ASYNC) ? 1 : 0;
+    a.permute = (!order && mode != DUHL_CD_SEQUENTIAL) ? 1 : 0;
     a.alpha = c->alpha;
     a.v = c->v;
     a.q = c->q;

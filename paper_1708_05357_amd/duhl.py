@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libduhl.so")
 LASSO, SVM = 0, 1
 RESIDENT_DEVICE, RESIDENT_HOST = 0, 1
 ALPHA, V, Z, P, SQNORM = 0, 1, 2, 3, 4
-CD_SEQUENTIAL, CD_ASYNC = 0, 1
+CD_SEQUENTIAL, CD_ASYNC, CD_ATOMIC = 0, 1, 2
 OK, EINVAL, ENOMEM, EHIP, ESTATE, EBUDGET = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["duhl_create", "duhl_set_data_dense", "duhl_set_data_csr", "duhl_gap", "duhl_select",

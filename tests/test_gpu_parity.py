@@ -214,8 +214,9 @@ def test_sequential_default_order_is_ascending(G):
 
 
 # ------------------------------------------------------------------------------------ asynchronous CD
-def converge_async(G, p, m, max_rounds, passes, target_rel_gap):
+def converge_async(G, p, m, max_rounds, passes, target_rel_gap, mode=None):
     from paper_1708_05357_amd import duhl
+    mode = duhl.CD_ASYNC if mode is None else mode
     o0 = p.g.objective()
     for rnd in range(max_rounds):
         gap = p.g.gap()
@@ -224,7 +225,7 @@ def converge_async(G, p, m, max_rounds, passes, target_rel_gap):
         p.g.select(m, want_stats=False)
         p.g.commit_swap()
         for k in range(passes):
-            p.g.cd_epoch(duhl.CD_ASYNC, seed=rnd * 131 + k)
+            p.g.cd_epoch(mode, seed=rnd * 131 + k)
     return rnd
 
 
@@ -240,8 +241,9 @@ def converge_oracle(p, m, max_rounds, passes, target_rel_gap):
     return rnd
 
 
-@pytest.mark.parametrize("kind", ["cfg1", "lasso_mid", "svm_dense", "svm_csr"])
-def test_async_cd_reaches_the_oracle_objective(G, kind):
+@pytest.mark.parametrize("scheme", ["async", "atomic"])
+@pytest.mark.parametrize("kind", ["cfg1", "lasso_mid", "lasso_ragged", "svm_dense", "svm_csr"])
+def test_async_cd_reaches_the_oracle_objective(G, kind, scheme):
     """The asynchronous scheme is compared on what is unique: the objective at convergence
     (1e-5 relative), and on the invariant v = A alpha (- b) that the atomic adds must keep."""
     from paper_1708_05357_amd import duhl, synth
@@ -251,6 +253,9 @@ def test_async_cd_reaches_the_oracle_objective(G, kind):
     elif kind == "lasso_mid":
         prob = lasso_problem(5000, 3000, 0.03, 0.05, seed=11)
         m = 300
+    elif kind == "lasso_ragged":
+        prob = lasso_problem(14003, 700, 0.05, 0.05, seed=14)       # 1024-thread workers, tail rows
+        m = 200
     elif kind == "svm_dense":
         prob = synth.svm_dense(2000, 300, seed=12)
         m = 500
@@ -259,7 +264,8 @@ def test_async_cd_reaches_the_oracle_objective(G, kind):
         m = 4000
     p = G.Pair(prob)
     tol = 1e-7 if prob["model"] == "lasso" else 1e-6
-    r_gpu = converge_async(G, p, m, 400, 3, tol)
+    mode = duhl.CD_ASYNC if scheme == "async" else duhl.CD_ATOMIC
+    r_gpu = converge_async(G, p, m, 400, 3, tol, mode)
     r_or = converge_oracle(p, m, 400, 3, tol)
     og, oo = p.g.objective(), p.o.objective()
     print(f"{kind}: rounds gpu {r_gpu} oracle {r_or} objective gpu {og:.9e} oracle {oo:.9e}")
@@ -393,7 +399,7 @@ def test_zero_columns_and_empty_rows(G):
     p = G.Pair(prob)
     a0 = np.zeros(40, dtype=np.float32)
     a0[7] = 0.3
-    for mode in (duhl.CD_SEQUENTIAL, duhl.CD_ASYNC):
+    for mode in (duhl.CD_SEQUENTIAL, duhl.CD_ASYNC, duhl.CD_ATOMIC):
         p.g.set(duhl.ALPHA, a0)
         p.g.set(duhl.Z, np.arange(40, 0, -1).astype(np.float32))
         p.g.select(40)
@@ -410,7 +416,7 @@ def test_zero_columns_and_empty_rows(G):
     rp[6:] -= cut
     sp["rowptr"] = rp
     p = G.Pair(sp)
-    for mode in (duhl.CD_ASYNC, duhl.CD_SEQUENTIAL):
+    for mode in (duhl.CD_ASYNC, duhl.CD_ATOMIC, duhl.CD_SEQUENTIAL):
         p.g.set(duhl.ALPHA, np.zeros(64, dtype=np.float32))
         p.g.recompute_v()
         p.g.select(64)
