@@ -6,7 +6,10 @@ selection -> (column swap) -> one asynchronous coordinate-descent pass over the 
 Prints ONE JSON line: whole-step coordinate updates/s as `value`, the per-phase figures, the
 roofline of the dominant kernel (the dense gap pass, HBM-bound) and the CPU oracle timed beside.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg2] [--no-cpu] [--no-ttg]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg5] [--no-cpu] [--no-ttg]
+
+The default workload is the fully HBM-resident dense Lasso (50,000 x 500,000 fp32, 100 GB): the
+largest single-GPU configuration and the one the bandwidth targets are quoted on.
 """
 import argparse
 import json
@@ -18,6 +21,11 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+
+# HBM bytes per launch of the dominant kernel from the hardware counters (FETCH_SIZE x 2.000 KiB +
+# WRITE_SIZE x 1.000 KiB, scaled by a plain 4 GiB copy): profiles/pmc_hbm_traffic_*.txt.
+COUNTER_TRAFFIC_BYTES = {"cfg5": {"gap": 49_100_367 * 2 * 1024 + 6_130 * 1024,
+                                  "cd_pass": 8 * ((614_784 + 24_974) * 2 * 1024 + (174_747 + 195) * 1024)}}
 
 
 def build_problem(name, device, scale):
@@ -173,15 +181,18 @@ def cpu_baseline(prob, m, budget_s=20.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--scale", type=float, default=1.0, help="shrink n (and m) at fixed d")
     ap.add_argument("--budget-factor", type=float, default=2.0,
                     help="device slots per working-set column (host residency)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-ttg", action="store_true")
     ap.add_argument("--ttg-passes", type=int, default=1)
+    ap.add_argument("--copy-calibration-gib", type=float, default=0.0,
+                    help="also run plain device copies of this size (GiB), as a yardstick for the "
+                         "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
     ap.add_argument("--cd-mode", default="async", choices=["async", "atomic"],
                     help="concurrent CD scheme: the library's default, or per-update atomics")
     ap.add_argument("--inflight", type=int, default=0, help="max_inflight of duhl_cd_epoch (0 = default)")
@@ -254,7 +265,17 @@ def main():
                    "gap_ms_min": min(gap_ms), "cd_ms_min": min(cd_ms), "cd_ms_max": max(cd_ms)},
         "roofline": {"kernel": "gap_dense_kernel" if "cols" in prob else "gap_csr_kernel",
                      "bound": "hbm", "achieved": gap_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": gap_gbps / HBM_PEAK_GBPS, "traffic": None},
+                     "frac": gap_gbps / HBM_PEAK_GBPS,
+                     "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload, {}).get("gap")
+                     if args.scale == 1.0 else None,
+                     "algorithmic_bytes": gap_bytes, "avg_launch_ms": avg(gap_ms)},
+        "roofline_cd": {"kernel": "cd_dense_worker_kernel + merge_workers_kernel (one pass)"
+                        if "cols" in prob and args.cd_mode == "async" else "cd atomic kernel (one pass)",
+                        "bound": "hbm", "achieved": cd_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                        "frac": cd_gbps / HBM_PEAK_GBPS,
+                        "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload, {}).get("cd_pass")
+                        if args.scale == 1.0 and args.cd_mode == "async" and args.inflight == 0 else None,
+                        "algorithmic_bytes": cd_bytes, "avg_launch_ms": avg(cd_ms)},
         "after_timed_rounds": {"total_gap": final_gap, "objective": final_obj},
         "gen_s": prob["gen_s"],
     }
@@ -265,6 +286,14 @@ def main():
     else:
         out["cpu_baseline"] = None
     g.close()
+    if args.copy_calibration_gib > 0:
+        nfl = int(args.copy_calibration_gib * (1 << 30) / 4)
+        src = torch.ones(nfl, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        out["copy_calibration"] = {"bytes_read": nfl * 4, "bytes_written": nfl * 4, "copies": 3}
     print(json.dumps(out))
 
 
