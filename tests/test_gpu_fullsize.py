@@ -1,0 +1,127 @@
+"""Parity at the full sizes of the benchmark plan, in the launch configuration bench.py times.
+
+cfg2 (2 GB) still fits the oracle whole.  cfg5 (100 GB in HBM) does not: there the oracle
+recomputes sampled outputs one by one (gaps and exact steps of sampled columns, from the GPU's own
+alpha and v), and the rest is checked through properties that hold at any size.
+"""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+sys.path.insert(0, os.path.dirname(__file__))
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_common
+    return gpu_common
+
+
+def test_cfg2_full_size_against_the_whole_oracle(G):
+    """Dense Lasso 10,000 x 50,000, m = 5,000: gaps of all columns, exact selection, sequential
+    iterates over three rounds, then the asynchronous scheme's objective after further rounds."""
+    from oracle import duhl_oracle as orc
+    from paper_1708_05357_amd import duhl, synth
+    prob = synth.make("cfg2")
+    m = prob["m"]
+    p = G.Pair(prob)
+    assert p.g.gap() == pytest.approx(p.o.gaps(), rel=1e-4)
+    G.assert_gaps_close(p.g.get(duhl.Z), p.o.z, floor=G.lasso_gap_floor(p))
+    out = torch.empty(m, dtype=torch.int32, device="cuda:0")
+    nsw, rho = p.g.select(m, out)
+    z32 = p.g.get(duhl.Z)
+    want = orc.select_topm(z32.astype(np.float64), m)
+    np.testing.assert_array_equal(out.cpu().numpy(), want)
+    assert rho == pytest.approx(orc.rho(z32.astype(np.float64), want), rel=1e-10)
+    from test_gpu_parity import run_rounds_sequential, converge_oracle
+    wa, wv = run_rounds_sequential(G, p, m, 3, seed=1)
+    print("cfg2 sequential worst deviation alpha %.2e v %.2e" % (wa, wv))
+    # asynchronous scheme, as bench.py runs it (default in-flight limit), from the same state
+    for rnd in range(80):
+        p.g.gap(want_sum=False)
+        p.g.select(m, want_stats=False)
+        p.g.commit_swap()
+        p.g.cd_epoch(duhl.CD_ASYNC, seed=rnd)
+    rng = np.random.default_rng(0)
+    for rnd in range(60):
+        p.o.round(m, passes=1, rng=rng)
+    og, oo = p.g.objective(), p.o.objective()
+    print("cfg2 objective gpu %.9e oracle %.9e gap gpu %.3e" % (og, oo, p.g.gap()))
+    assert abs(og - oo) <= 1e-5 * abs(oo)
+    p.close()
+
+
+def test_cfg5_full_size_sampled_columns_and_invariants(G):
+    """Dense Lasso 50,000 x 500,000 (100 GB in HBM), m = 50,000, the default bench workload."""
+    from oracle import duhl_oracle as orc
+    from paper_1708_05357_amd import duhl, synth
+    free, total = torch.cuda.mem_get_info()
+    if free < 130e9:
+        pytest.skip("needs 130 GB of free HBM")
+    prob = synth.make("cfg5", device="cuda")
+    d, n, m = prob["d"], prob["n"], prob["m"]
+    g = duhl.Duhl(duhl.LASSO, d, n, m)
+    g.set_data_dense(prob["cols"], prob["target"], prob["lam"])
+    b = prob["target"].cpu().numpy()
+    rng = np.random.default_rng(5)
+
+    def check_sampled_gaps(total_gpu):
+        z = g.get(duhl.Z)
+        alpha, v = g.get(duhl.ALPHA), g.get(duhl.V)
+        assert total_gpu == pytest.approx(float(z.astype(np.float64).sum()), rel=1e-6)
+        assert z.min() >= 0
+        # columns that matter (largest gaps, non-zero alpha) plus a uniform sample
+        idx = np.unique(np.concatenate([np.argsort(z)[-300:], np.flatnonzero(alpha)[:300],
+                                        rng.integers(0, n, 600)])).astype(np.int64)
+        cols = prob["cols"][torch.as_tensor(idx, device="cuda")].cpu().numpy()
+        o = orc.Oracle(orc.LASSO, b, prob["lam"], cols=cols)      # same d, b, lambda -> same formula
+        o.set_state(alpha[idx].astype(np.float64), v.astype(np.float64))
+        o.gaps()
+
+        class _P:                                                 # floor wants the full state
+            pass
+        pp = _P()
+        pp.o = o
+        floor = G.lasso_gap_floor(pp)
+        err = np.abs(z[idx] - o.z)
+        assert err.max() <= 1e-4 * max(o.z.max(), z.max()) + floor, (err.max(), o.z.max(), floor)
+        return idx, cols, o
+
+    idx, cols, o = check_sampled_gaps(g.gap())
+    for rnd in range(3):
+        P_dev = torch.empty(m, dtype=torch.int32, device="cuda:0")
+        nsw, rho = g.select(m, P_dev)
+        g.commit_swap()
+        P = P_dev.cpu().numpy()
+        z = g.get(duhl.Z)
+        assert P.size == m and np.all(np.diff(P) > 0)
+        inP = np.zeros(n, dtype=bool)
+        inP[P] = True
+        assert z[inP].min() >= z[~inP].max()                      # eq. (13): the m largest
+        assert 1.0 <= rho <= n / m + 1e-9                          # eq. (7)
+        assert rho == pytest.approx((z[inP].astype(np.float64).mean()) / z.astype(np.float64).mean(), rel=1e-9)
+        g.cd_epoch(duhl.CD_ASYNC, seed=rnd)
+        idx, cols, o = check_sampled_gaps(g.gap())
+    # exact steps on sampled columns, one after the other, against the oracle on the same v
+    step_cols = idx[rng.permutation(idx.size)[:200]]
+    local = {int(j): k for k, j in enumerate(idx)}
+    order_local = np.array([local[int(j)] for j in step_cols], dtype=np.int32)
+    alpha, v = g.get(duhl.ALPHA), g.get(duhl.V)
+    o.set_state(alpha[idx].astype(np.float64), v.astype(np.float64))
+    g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(step_cols))
+    o.cd_pass(order_local)
+    a2, v2 = g.get(duhl.ALPHA), g.get(duhl.V)
+    assert np.abs(a2[idx] - o.alpha).max() <= 1e-5 * max(np.abs(o.alpha).max(), 1e-30)
+    assert np.abs(v2 - o.v).max() <= 1e-5 * np.abs(o.v).max()
+    # v = A alpha - b on sampled rows (App. D), from the columns that carry weight
+    nz = np.flatnonzero(a2)
+    rows = torch.as_tensor(rng.integers(0, d, 64), device="cuda")
+    sub = prob["cols"][torch.as_tensor(nz, device="cuda")][:, rows].double()       # (nnz, 64)
+    want = (sub.t() @ torch.as_tensor(a2[nz], device="cuda").double()).cpu().numpy() - b[rows.cpu().numpy()]
+    assert np.abs(v2[rows.cpu().numpy()] - want).max() <= 1e-4 * np.abs(b).max()
+    g.close()
