@@ -129,9 +129,11 @@ duhl_status duhl_commit_swap(duhl_ctx *ctx);
  * order == NULL: the whole set -- ascending for DUHL_CD_SEQUENTIAL, a pseudo-random permutation
  * drawn from (seed, pass counter) otherwise.
  * DUHL_CD_SEQUENTIAL solves one coordinate after the other and is reproducible.
- * The concurrent schemes solve up to max_inflight coordinates (0 = min(count/8, 4096)) without
- * seeing each other's update of v -- the asynchrony of Appendix D, bounded.  Strongly correlated
- * columns tolerate fewer concurrent steps; lower max_inflight if the objective stops decreasing.
+ * The concurrent schemes solve up to max_inflight coordinates without seeing each other's update
+ * of v -- the asynchrony of Appendix D, bounded.  max_inflight = 0 lets the library choose: about
+ * 2*count/sigma, at most count/4, where sigma estimates ||A_P||^2 from the block shape and the mean
+ * correlation of a column sample taken by duhl_set_data_*.  Strongly correlated columns tolerate
+ * fewer concurrent steps; lower max_inflight if the objective stops decreasing.
  *   DUHL_CD_ATOMIC  each step reads the live v and adds a_j*delta to it with fp32 atomics;
  *                   iterates depend on timing.
  *   DUHL_CD_ASYNC   dense data: the pass is cut into sub-passes of max_inflight coordinates;

@@ -114,6 +114,21 @@ duhl_status finish_set_data(duhl_ctx *c, const float *target, double lambda)
     c->have_data = true;
     // column norms and a first full gap pass in one read of the matrix
     HIPCHK(c, launch_gap(c, nullptr, c->n, false, true));
+    // how strongly the columns share a direction, from up to 1024 evenly spaced columns; it sets
+    // the default bound on concurrent coordinate steps
+    c->mean_corr = 0.0;
+    const int samples = (int)(c->n < 1024 ? c->n : 1024);
+    if (samples > 1) {
+        float *u = nullptr;
+        HIPCHK(c, dev_alloc(&u, c->d));
+        hipError_t e = launch_corr_sample(c, u, samples);
+        duhl_status st = e == hipSuccess ? read_scalars(c, S_CORR, 1) : DUHL_EHIP;
+        (void)hipFree(u);
+        if (st != DUHL_OK) return fail(c, st, "column correlation estimate failed");
+        const double uu = c->h_scalars[S_CORR];
+        const double mc_ = (uu / samples - 1.0) / (samples - 1.0);
+        c->mean_corr = mc_ > 0.0 ? mc_ : 0.0;
+    }
     HIPCHK(c, hipStreamSynchronize(c->compute));
     HIPCHK(c, hipGetLastError());
     return DUHL_OK;

@@ -101,7 +101,7 @@ __device__ __forceinline__ float group_sum(float x)
 }
 
 // Slots of the device scalar block (doubles), results of reductions.
-enum Scalar { S_GAP_SUM = 0, S_SUM_ALL, S_SUM_SEL, S_RHO, S_OBJ_SQ, S_OBJ_LIN, S_BSQ, S_COUNT };
+enum Scalar { S_GAP_SUM = 0, S_SUM_ALL, S_SUM_SEL, S_RHO, S_OBJ_SQ, S_OBJ_LIN, S_BSQ, S_CORR, S_COUNT };
 
 // Scratch of the selection kernels (device memory, one per context).
 struct SelectState {
@@ -140,6 +140,7 @@ struct duhl_ctx {
     bool pending;          // a selected set waits for duhl_commit_swap
     bool swap_exclusive;   // the pending copies reuse slots of the current set
     uint64_t pass_counter;
+    double mean_corr;      // mean cosine between columns, estimated on a sample (>= 0)
 
     double *scalars;            // S_COUNT doubles
     double *partials;           // per-block partial sums
@@ -186,6 +187,7 @@ hipError_t launch_cd(duhl_ctx *c, duhl_cd_mode mode, const int32_t *order, int64
 hipError_t launch_objective(duhl_ctx *c);
 hipError_t launch_init_v(duhl_ctx *c);
 hipError_t launch_accumulate_v(duhl_ctx *c);
+hipError_t launch_corr_sample(duhl_ctx *c, float *u, int samples);
 hipError_t launch_validate(duhl_ctx *c);
 hipError_t launch_fill_i32(hipStream_t s, int32_t *p, int64_t n, int32_t value);
 hipError_t launch_fill_f32(hipStream_t s, float *p, int64_t n, float value);

@@ -20,6 +20,8 @@
 // not see each other inside a sub-pass, exactly like concurrently running thread blocks that
 // read a stale v; `inflight` bounds that staleness.  Sparse data keeps the atomic scheme: its
 // scattered updates are few and spread over all of v.
+#include <cmath>
+
 #include "duhl_internal.h"
 
 namespace duhl {
@@ -190,17 +192,22 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_atomic_kernel(cons
 
 
 // ---- asynchronous, dense: workers with a private copy of v --------------------------------------
-// One sub-pass over positions [t_begin, t_end) of the visiting order.  CACHE_X keeps the column
-// in registers between the dot product and the update (one read per update); without it (very
-// long columns: the registers are needed for v) the column is read again, only when alpha_j moved.
-template <int MODEL, int T, int NREG, bool CACHE_X>
+// One sub-pass over positions [t_begin, t_end) of the visiting order.  The worker's copy of v is
+// NR 16-byte chunks per thread in registers plus NL chunks per thread in LDS (each thread only ever
+// touches its own LDS entries, so no barrier is needed for them).  CACHE_X keeps the column in
+// registers between the dot product and the update (one read per update); without it (very long
+// columns: the registers are needed for v) the column is read again, only when alpha_j moved.
+template <int MODEL, int T, int NR, int NL, bool CACHE_X>
 __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
     const CdArgs a, const int64_t t_begin, const int64_t t_end, float *dv, const int64_t dv_stride,
     int32_t *dirty)
 {
     constexpr int BLOCK = T == 64 ? 256 : T;
+    constexpr int NC = NR + NL;                        // chunks per thread that cover a column
     constexpr int kStep = T * 16;                      // bytes between a thread's chunks
+    constexpr int KB = NR >= 14 ? 4 : 8;               // column chunks in flight when not cached
     __shared__ float red[2][16];
+    __shared__ float4 vs[NL > 0 ? NL * BLOCK : 1];
     const int tid = threadIdx.x % T;
     // the worker index is the same in all lanes of a wavefront: say so to the compiler
     const int w = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (BLOCK / T) + threadIdx.x / T));
@@ -211,9 +218,11 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
     const int off = tid * 16;                          // return 0 (buffer bounds check)
     const __amdgpu_buffer_rsrc_t rs_v = __builtin_amdgcn_make_buffer_rsrc(a.v, 0, vec_bytes, 0x00020000);
 
-    float4 vl[NREG];                                   // this worker's v, rows 4*(tid + i*T) ..
+    float4 vr[NR > 0 ? NR : 1];                        // rows 4*(tid + i*T) .. of this worker's v
 #pragma unroll
-    for (int i = 0; i < NREG; ++i) vl[i] = buffer_load4(rs_v, off, i * kStep);
+    for (int i = 0; i < NR; ++i) vr[i] = buffer_load4(rs_v, off, i * kStep);
+#pragma unroll
+    for (int l = 0; l < NL; ++l) vs[l * BLOCK + threadIdx.x] = buffer_load4(rs_v, off, (NR + l) * kStep);
     float vt = tid < tail ? a.v[(d4 << 2) + tid] : 0.0f;
     bool moved = false;
     int parity = 0;
@@ -222,19 +231,33 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
         const float *col = a.cv.col(j);
         const __amdgpu_buffer_rsrc_t rs_x =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(col), 0, vec_bytes, 0x00020000);
-        float4 x[CACHE_X ? NREG : 1];
+        float4 x[CACHE_X ? NC : 1];
         float acc = 0.0f;
         if (CACHE_X) {
 #pragma unroll
-            for (int i = 0; i < NREG; ++i) x[i] = buffer_load4(rs_x, off, i * kStep);
+            for (int i = 0; i < NC; ++i) x[i] = buffer_load4(rs_x, off, i * kStep);
 #pragma unroll
-            for (int i = 0; i < NREG; ++i) acc = dot4(x[i], vl[i], acc);
+            for (int i = 0; i < NR; ++i) acc = dot4(x[i], vr[i], acc);
+#pragma unroll
+            for (int l = 0; l < NL; ++l) acc = dot4(x[NR + l], vs[l * BLOCK + threadIdx.x], acc);
         } else {
-            // four chunks in flight at a time: the registers are taken by the worker's v
+            // KB chunks of the column in flight at a time: the registers belong to v.  The
+            // empty asm makes the next batch's address depend on this batch's sum, which is what
+            // keeps the compiler from issuing all loads at once and spilling v.
+            int offb = off;
 #pragma unroll
-            for (int i = 0; i < NREG; ++i) {
-                acc = dot4(buffer_load4(rs_x, off, i * kStep), vl[i], acc);
-                if ((i & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+            for (int i0 = 0; i0 < NC; i0 += KB) {
+                float4 xb[KB];
+#pragma unroll
+                for (int u = 0; u < KB; ++u)
+                    if (i0 + u < NC) xb[u] = buffer_load4(rs_x, offb, (i0 + u) * kStep);
+#pragma unroll
+                for (int u = 0; u < KB; ++u) {
+                    const int i = i0 + u;
+                    if (i < NR) acc = dot4(xb[u], vr[i < NR ? i : 0], acc);
+                    else if (i < NC) acc = dot4(xb[u], vs[(i - NR) * BLOCK + threadIdx.x], acc);
+                }
+                asm volatile("" : "+v"(offb), "+v"(acc));
             }
         }
         const float xt = tid < tail ? col[(d4 << 2) + tid] : 0.0f;
@@ -247,14 +270,35 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
         const float now = cd_new_alpha<MODEL>(a.mc, c, old, a.q[j], y);
         const float delta = now - old;
         if (delta != 0.0f) {
+            int offu = off;
+            float tie = 0.0f;
 #pragma unroll
-            for (int i = 0; i < NREG; ++i) {
-                const float4 xx = CACHE_X ? x[i] : buffer_load4(rs_x, off, i * kStep);
-                vl[i].x = fmaf(xx.x, delta, vl[i].x);
-                vl[i].y = fmaf(xx.y, delta, vl[i].y);
-                vl[i].z = fmaf(xx.z, delta, vl[i].z);
-                vl[i].w = fmaf(xx.w, delta, vl[i].w);
-                if (!CACHE_X && (i & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+            for (int i0 = 0; i0 < NC; i0 += KB) {
+                float4 xb[KB];
+#pragma unroll
+                for (int u = 0; u < KB; ++u)
+                    if (i0 + u < NC) xb[u] = CACHE_X ? x[CACHE_X ? i0 + u : 0] : buffer_load4(rs_x, offu, (i0 + u) * kStep);
+#pragma unroll
+                for (int u = 0; u < KB; ++u) {
+                    const int i = i0 + u;
+                    if (i < NR) {
+                        float4 &vv = vr[i < NR ? i : 0];
+                        vv.x = fmaf(xb[u].x, delta, vv.x);
+                        vv.y = fmaf(xb[u].y, delta, vv.y);
+                        vv.z = fmaf(xb[u].z, delta, vv.z);
+                        vv.w = fmaf(xb[u].w, delta, vv.w);
+                    } else if (i < NC) {
+                        float4 vv = vs[(i - NR) * BLOCK + threadIdx.x];
+                        vv.x = fmaf(xb[u].x, delta, vv.x);
+                        vv.y = fmaf(xb[u].y, delta, vv.y);
+                        vv.z = fmaf(xb[u].z, delta, vv.z);
+                        vv.w = fmaf(xb[u].w, delta, vv.w);
+                        vs[(i - NR) * BLOCK + threadIdx.x] = vv;
+                        tie = vv.x;
+                    }
+                    if (i < NR) tie = vr[i < NR ? i : 0].x;
+                }
+                if (!CACHE_X) asm volatile("" : "+v"(offu), "+v"(tie));
             }
             vt = fmaf(xt, delta, vt);
             moved = true;
@@ -264,37 +308,42 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
     if (moved) {                                       // this worker's change of v
         float *out = dv + (int64_t)w * dv_stride;
         const __amdgpu_buffer_rsrc_t rs_o = __builtin_amdgcn_make_buffer_rsrc(out, 0, vec_bytes, 0x00020000);
+        int offo = off;
 #pragma unroll
-        for (int i = 0; i < NREG; ++i) {
-            const float4 base = buffer_load4(rs_v, off, i * kStep);
-            buffer_store4(rs_o, off, i * kStep,
-                          make_float4(vl[i].x - base.x, vl[i].y - base.y, vl[i].z - base.z,
-                                      vl[i].w - base.w));                  // beyond the end: dropped
-            if ((i & 3) == 3) __builtin_amdgcn_sched_barrier(0);
+        for (int i = 0; i < NC; ++i) {
+            float4 base = buffer_load4(rs_v, offo, i * kStep);
+            const float4 mine = i < NR ? vr[i < NR ? i : 0] : vs[(i < NR ? 0 : i - NR) * BLOCK + threadIdx.x];
+            buffer_store4(rs_o, offo, i * kStep,
+                          make_float4(mine.x - base.x, mine.y - base.y, mine.z - base.z,
+                                      mine.w - base.w));                   // beyond the end: dropped
+            if (!CACHE_X && (i & 3) == 3) asm volatile("" : "+v"(offo), "+v"(base.x));
         }
         if (tid < tail) out[(d4 << 2) + tid] = vt - a.v[(d4 << 2) + tid];
     }
     if (tid == 0) dirty[w] = moved ? 1 : 0;
 }
 
-// v += sum over workers of their stored changes, in worker order (reproducible).
+// v += sum over workers of their stored changes, in worker order (reproducible).  Sixteen
+// independent loads in flight per lane; dirty[] is uniform, so skipping a clean worker is a
+// scalar branch.
 __global__ __launch_bounds__(256) void merge_workers_kernel(float *v, int64_t d, const float *dv,
                                                             int64_t dv_stride, const int32_t *dirty,
                                                             int nworkers)
 {
     const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (k >= d) return;
+    const float *p = dv + k;
     float s = 0.0f;
     int g = 0;
-    for (; g + 4 <= nworkers; g += 4) {                // dirty[] is uniform: scalar branches
-        const float a0 = dirty[g] ? dv[(int64_t)g * dv_stride + k] : 0.0f;
-        const float a1 = dirty[g + 1] ? dv[(int64_t)(g + 1) * dv_stride + k] : 0.0f;
-        const float a2 = dirty[g + 2] ? dv[(int64_t)(g + 2) * dv_stride + k] : 0.0f;
-        const float a3 = dirty[g + 3] ? dv[(int64_t)(g + 3) * dv_stride + k] : 0.0f;
-        s += (a0 + a1) + (a2 + a3);
+    for (; g + 16 <= nworkers; g += 16) {
+        float t[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) t[u] = dirty[g + u] ? p[(int64_t)(g + u) * dv_stride] : 0.0f;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) s += t[u];
     }
     for (; g < nworkers; ++g)
-        if (dirty[g]) s += dv[(int64_t)g * dv_stride + k];
+        if (dirty[g]) s += p[(int64_t)g * dv_stride];
     if (s != 0.0f) v[k] += s;
 }
 
@@ -438,14 +487,25 @@ int threads_per_coordinate(const duhl_ctx *c)
     return 1024;
 }
 
-// Coordinates that may be solved without seeing each other: the caller's bound, else count/8 but
-// at most 4096.  How many concurrent steps a problem tolerates depends on how correlated its
-// columns are (about count / ||A_P||^2 for unit-norm columns); the default is a compromise that
-// converged on all synthetic workloads here, including non-negative sparse data whose rows share
-// a common direction and diverge beyond ~10^4 concurrent steps.
-int64_t inflight_limit(int64_t count, int max_inflight)
+// Coordinates that may be solved without seeing each other.  The caller's bound if given.
+// Otherwise from the data: concurrent exact steps on unit-norm columns stay stable up to about
+// count / sigma of them, sigma = ||A_P||^2 being the largest eigenvalue of the block's Gram
+// matrix.  sigma is estimated as (1 + sqrt(count/d))^2, the value for uncorrelated columns, plus
+// (count - 1) * mean_corr, the rank-one part that a common direction of the columns adds
+// (mean_corr is measured on a column sample when the data are set).  Twice that ratio, and never
+// more than a quarter of the pass, worked on every workload here; non-negative sparse rows, whose
+// mean correlation is ~1e-3, diverge with four times as many concurrent steps.
+int64_t inflight_limit(const duhl_ctx *c, int64_t count, int max_inflight)
 {
-    int64_t lim = max_inflight > 0 ? max_inflight : (count / 8 < 4096 ? count / 8 : 4096);
+    int64_t lim;
+    if (max_inflight > 0) {
+        lim = max_inflight;
+    } else {
+        const double r = 1.0 + std::sqrt((double)count / (double)c->d);
+        const double sigma = r * r + (double)(count - 1) * c->mean_corr;
+        lim = (int64_t)(2.0 * (double)count / sigma);
+        if (lim > count / 4) lim = count / 4;
+    }
     if (lim < 1) lim = 1;
     return lim < count ? lim : count;
 }
@@ -457,7 +517,7 @@ hipError_t launch_atomic(duhl_ctx *c, const CdArgs &a, int max_inflight, bool ve
         const int64_t avg = c->n > 0 ? c->nnz / c->n : 0;
         const int G = avg > 256 ? 64 : 16;
         const int64_t cap = (int64_t)c->num_cu * 8 * (256 / G);
-        int64_t inflight = inflight_limit(a.count, max_inflight);
+        int64_t inflight = inflight_limit(c, a.count, max_inflight);
         if (inflight > cap) inflight = cap;
         const int64_t grid = (inflight + 256 / G - 1) / (256 / G);
         if (G == 64)
@@ -468,14 +528,14 @@ hipError_t launch_atomic(duhl_ctx *c, const CdArgs &a, int max_inflight, bool ve
     }
     const int T = threads_per_coordinate(c);
     const int64_t cap = (int64_t)c->num_cu * (2048 / T);
-    int64_t inflight = inflight_limit(a.count, max_inflight);
+    int64_t inflight = inflight_limit(c, a.count, max_inflight);
     if (inflight > cap) inflight = cap;
     if (T == 64) return launch_atomic_dense_n<MODEL, 64>(c, a, (int)inflight, vec);
     if (T == 256) return launch_atomic_dense_n<MODEL, 256>(c, a, (int)inflight, vec);
     return launch_atomic_dense_n<MODEL, 1024>(c, a, (int)inflight, vec);
 }
 
-template <int MODEL, int T, int NREG, bool CACHE_X>
+template <int MODEL, int T, int NR, int NL, bool CACHE_X>
 hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
 {
     constexpr int BLOCK = T == 64 ? 256 : T;
@@ -489,7 +549,7 @@ hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
         int64_t workers = len >= 4 * (int64_t)c->num_cu ? len / 4 : (len < c->num_cu ? len : c->num_cu);
         if (workers > cap) workers = cap;
         const int64_t grid = (workers + PER - 1) / PER;
-        hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, T, NREG, CACHE_X>), dim3(grid), dim3(BLOCK), 0,
+        hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, T, NR, NL, CACHE_X>), dim3(grid), dim3(BLOCK), 0,
                            c->compute, a, t0, t1, c->dv, c->dv_stride, c->dirty);
         hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 255) / 256), dim3(256), 0, c->compute, a.v,
                            c->d, c->dv, c->dv_stride, c->dirty, (int)(grid * PER));
@@ -513,25 +573,27 @@ bool launch_workers(duhl_ctx *c, const CdArgs &a, int max_inflight, bool vec, hi
         if (*err == hipSuccess) *err = hipMalloc(reinterpret_cast<void **>(&c->dirty), (size_t)(workers + 4) * 4);
         if (*err != hipSuccess) return true;
     }
-    const int64_t inflight = inflight_limit(a.count, max_inflight);
-#define DUHL_W(TT, NN, CX) *err = launch_workers_t<MODEL, TT, NN, CX>(c, a, inflight)
+    const int64_t inflight = inflight_limit(c, a.count, max_inflight);
+    // (T, register chunks, LDS chunks, column cached?) by column length
+#define DUHL_W(TT, NR, NL, CX) *err = launch_workers_t<MODEL, TT, NR, NL, CX>(c, a, inflight)
     if (T == 64) {
-        if (chunks <= 1) DUHL_W(64, 1, true);
-        else if (chunks <= 2) DUHL_W(64, 2, true);
-        else if (chunks <= 4) DUHL_W(64, 4, true);
-        else DUHL_W(64, 8, true);
+        if (chunks <= 1) DUHL_W(64, 1, 0, true);
+        else if (chunks <= 2) DUHL_W(64, 2, 0, true);
+        else if (chunks <= 4) DUHL_W(64, 4, 0, true);
+        else DUHL_W(64, 8, 0, true);
     } else if (T == 256) {
-        if (chunks <= 4) DUHL_W(256, 4, true);
-        else if (chunks <= 8) DUHL_W(256, 8, true);
-        else if (chunks <= 10) DUHL_W(256, 10, true);
-        else DUHL_W(256, 13, true);
+        if (chunks <= 4) DUHL_W(256, 4, 0, true);
+        else if (chunks <= 8) DUHL_W(256, 8, 0, true);
+        else if (chunks <= 10) DUHL_W(256, 10, 0, true);
+        else DUHL_W(256, 13, 0, true);
     } else {
-        if (chunks <= 4) DUHL_W(1024, 4, true);
-        else if (chunks <= 8) DUHL_W(1024, 8, true);
-        else if (chunks <= 13) DUHL_W(1024, 13, true);
-        else if (chunks <= 16) DUHL_W(1024, 16, false);
-        else if (chunks <= 20) DUHL_W(1024, 20, false);
-        else DUHL_W(1024, 25, false);
+        if (chunks <= 4) DUHL_W(1024, 4, 0, true);
+        else if (chunks <= 8) DUHL_W(1024, 8, 0, true);
+        else if (chunks <= 10) DUHL_W(1024, 8, 2, true);
+        else if (chunks <= 13) DUHL_W(1024, 8, 5, true);
+        else if (chunks <= 16) DUHL_W(1024, 12, 4, false);
+        else if (chunks <= 20) DUHL_W(1024, 14, 6, false);
+        else DUHL_W(1024, 16, 9, false);
     }
 #undef DUHL_W
     return true;

@@ -77,6 +77,29 @@ __global__ __launch_bounds__(256) void accumulate_v_kernel(const ColView cv, int
     }
 }
 
+// u += a_j / ||a_j|| for `samples` evenly spaced columns j: ||u||^2 then tells how strongly the
+// columns share a direction (samples + samples*(samples-1)*mean cosine).
+__global__ __launch_bounds__(256) void corr_sample_kernel(const ColView cv, int64_t d, int64_t n,
+                                                          const float *q, int samples, float *u)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t s = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (s >= samples) return;
+    const int64_t j = s * (n / samples);
+    const float qj = q[j];
+    if (!(qj > 0.0f)) return;
+    const float w = rsqrtf(qj);
+    if (cv.base) {
+        const float *col = cv.col(j);
+        for (int64_t r = lane; r < d; r += 64)
+            (void)__hip_atomic_fetch_add(u + r, col[r] * w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else {
+        for (int64_t e = cv.rowptr[j] + lane; e < cv.rowptr[j + 1]; e += 64)
+            (void)__hip_atomic_fetch_add(u + cv.colidx[e], cv.val[e] * w, __ATOMIC_RELAXED,
+                                         __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 // ||b||^2 in double (for the Lipschitzing bound of Appendix E).
 __global__ __launch_bounds__(1024) void sumsq_kernel(const float *b, int64_t d, double *out)
 {
@@ -164,6 +187,15 @@ hipError_t launch_accumulate_v(duhl_ctx *c)
 {
     hipLaunchKernelGGL(accumulate_v_kernel, dim3((c->n + 3) / 4), dim3(256), 0, c->compute, c->cv, c->d,
                        c->n, c->alpha, c->v);
+    return hipGetLastError();
+}
+
+hipError_t launch_corr_sample(duhl_ctx *c, float *u, int samples)
+{
+    hipLaunchKernelGGL(fill_f32_kernel, dim3((c->d + 255) / 256), dim3(256), 0, c->compute, u, c->d, 0.0f);
+    hipLaunchKernelGGL(corr_sample_kernel, dim3((samples + 3) / 4), dim3(256), 0, c->compute, c->cv, c->d,
+                       c->n, c->q, samples, u);
+    hipLaunchKernelGGL(sumsq_kernel, dim3(1), dim3(1024), 0, c->compute, u, c->d, c->scalars + S_CORR);
     return hipGetLastError();
 }
 

@@ -242,7 +242,8 @@ def converge_oracle(p, m, max_rounds, passes, target_rel_gap):
 
 
 @pytest.mark.parametrize("scheme", ["async", "atomic"])
-@pytest.mark.parametrize("kind", ["cfg1", "lasso_mid", "lasso_ragged", "svm_dense", "svm_csr"])
+@pytest.mark.parametrize("kind", ["cfg1", "lasso_mid", "lasso_ragged", "lasso_long", "lasso_longer",
+                                  "lasso_longest", "svm_dense", "svm_csr"])
 def test_async_cd_reaches_the_oracle_objective(G, kind, scheme):
     """The asynchronous scheme is compared on what is unique: the objective at convergence
     (1e-5 relative), and on the invariant v = A alpha (- b) that the atomic adds must keep."""
@@ -256,6 +257,15 @@ def test_async_cd_reaches_the_oracle_objective(G, kind, scheme):
     elif kind == "lasso_ragged":
         prob = lasso_problem(14003, 700, 0.05, 0.05, seed=14)       # 1024-thread workers, tail rows
         m = 200
+    elif kind == "lasso_long":
+        prob = lasso_problem(50002, 300, 0.05, 0.05, seed=15)       # private v in registers + LDS
+        m = 120
+    elif kind == "lasso_longer":
+        prob = lasso_problem(75001, 260, 0.05, 0.05, seed=16)       # column re-read on update
+        m = 100
+    elif kind == "lasso_longest":
+        prob = lasso_problem(100003, 220, 0.05, 0.05, seed=17)      # largest register/LDS split
+        m = 90
     elif kind == "svm_dense":
         prob = synth.svm_dense(2000, 300, seed=12)
         m = 500
