@@ -78,6 +78,16 @@ __device__ __forceinline__ float cd_new_alpha(const ModelConst &mc, float c, flo
     }
 }
 
+// 16-byte load of matrix data that is read once per pass: the non-temporal hint keeps the stream
+// from displacing v and the other small arrays in the caches (measured: 6.7-7.0 TB/s against
+// 6.0-6.3 TB/s for plain loads on a 32 GB read).
+typedef float duhl_v4f __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ float4 stream_load4(const float4 *p)
+{
+    const duhl_v4f t = __builtin_nontemporal_load(reinterpret_cast<const duhl_v4f *>(p));
+    return make_float4(t.x, t.y, t.z, t.w);
+}
+
 // Sum over the 64 lanes of a wavefront; every lane receives the result.
 __device__ __forceinline__ float wave_sum(float x)
 {

@@ -78,6 +78,13 @@ __device__ __forceinline__ float4 buffer_load4(__amdgpu_buffer_rsrc_t rs, int vo
     return make_float4(__int_as_float(raw.x), __int_as_float(raw.y), __int_as_float(raw.z),
                        __int_as_float(raw.w));
 }
+// The same with the non-temporal hint, for column data that is read once per pass.
+__device__ __forceinline__ float4 buffer_stream4(__amdgpu_buffer_rsrc_t rs, int voff, int soff)
+{
+    const v4i_t raw = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 2);
+    return make_float4(__int_as_float(raw.x), __int_as_float(raw.y), __int_as_float(raw.z),
+                       __int_as_float(raw.w));
+}
 __device__ __forceinline__ void buffer_store4(__amdgpu_buffer_rsrc_t rs, int voff, int soff, float4 x)
 {
     v4i_t raw;
@@ -235,7 +242,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
         float acc = 0.0f;
         if (CACHE_X) {
 #pragma unroll
-            for (int i = 0; i < NC; ++i) x[i] = buffer_load4(rs_x, off, i * kStep);
+            for (int i = 0; i < NC; ++i) x[i] = buffer_stream4(rs_x, off, i * kStep);
 #pragma unroll
             for (int i = 0; i < NR; ++i) acc = dot4(x[i], vr[i], acc);
 #pragma unroll
@@ -250,7 +257,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
                 float4 xb[KB];
 #pragma unroll
                 for (int u = 0; u < KB; ++u)
-                    if (i0 + u < NC) xb[u] = buffer_load4(rs_x, offb, (i0 + u) * kStep);
+                    if (i0 + u < NC) xb[u] = buffer_stream4(rs_x, offb, (i0 + u) * kStep);
 #pragma unroll
                 for (int u = 0; u < KB; ++u) {
                     const int i = i0 + u;

@@ -89,8 +89,8 @@ __global__ __launch_bounds__(256) void gap_dense_kernel(const GapArgs a)
                 float4 x0[COLS], x1[COLS];
 #pragma unroll
                 for (int c = 0; c < COLS; ++c) {
-                    x0[c] = reinterpret_cast<const float4 *>(p[c])[r];
-                    x1[c] = reinterpret_cast<const float4 *>(p[c])[r + 64];
+                    x0[c] = stream_load4(reinterpret_cast<const float4 *>(p[c]) + r);
+                    x1[c] = stream_load4(reinterpret_cast<const float4 *>(p[c]) + r + 64);
                 }
 #pragma unroll
                 for (int c = 0; c < COLS; ++c) {
@@ -103,7 +103,7 @@ __global__ __launch_bounds__(256) void gap_dense_kernel(const GapArgs a)
                 const float4 v0 = vp[r];
 #pragma unroll
                 for (int c = 0; c < COLS; ++c) {
-                    const float4 x0 = reinterpret_cast<const float4 *>(p[c])[r];
+                    const float4 x0 = stream_load4(reinterpret_cast<const float4 *>(p[c]) + r);
                     acc0[c] = dot4(x0, v0, acc0[c]);
                     if (NORMS) nq[c] = dot4(x0, x0, nq[c]);
                 }
