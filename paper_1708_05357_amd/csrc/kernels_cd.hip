@@ -364,8 +364,24 @@ __global__ __launch_bounds__(256) void cd_csr_async_kernel(const CdArgs a)
         const int64_t j = coord_at(a, t);
         const int64_t beg = a.cv.rowptr[j], end = a.cv.rowptr[j + 1];
         float acc = 0.0f;
-        for (int64_t e = beg + sub; e < end; e += G)
-            acc = fmaf(a.cv.val[e], live_load(a.v + a.cv.colidx[e]), acc);
+        // index/value loads of a batch first, then the gathers that depend on them: K gathers
+        // of v in flight per lane
+        constexpr int K = 8;
+        for (int64_t e0 = beg + sub; e0 < end; e0 += (int64_t)G * K) {
+            int32_t ci[K];
+            float xv[K], vv[K];
+#pragma unroll
+            for (int u = 0; u < K; ++u) {
+                const int64_t e = e0 + (int64_t)u * G;
+                const bool in = e < end;
+                ci[u] = in ? a.cv.colidx[e] : 0;
+                xv[u] = in ? a.cv.val[e] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < K; ++u) vv[u] = live_load(a.v + ci[u]);
+#pragma unroll
+            for (int u = 0; u < K; ++u) acc = fmaf(xv[u], vv[u], acc);
+        }
         const float c = group_sum<G>(acc);
         const float old = a.alpha[j];
         const float y = MODEL == DUHL_SVM ? a.target[j] : 0.0f;

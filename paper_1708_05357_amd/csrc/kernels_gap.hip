@@ -140,6 +140,7 @@ template <int MODEL, int G, bool NORMS>
 __global__ __launch_bounds__(256) void gap_csr_kernel(const GapArgs a)
 {
     constexpr int ROWS = 256 / G;
+    constexpr int K = 8;                      // non-zeros per lane fetched at once
     const int sub = threadIdx.x % G;
     const int64_t k = (int64_t)blockIdx.x * ROWS + threadIdx.x / G;
     const int64_t j = list_entry(a, k);
@@ -147,10 +148,26 @@ __global__ __launch_bounds__(256) void gap_csr_kernel(const GapArgs a)
     float acc = 0.0f, nq = 0.0f;
     if (j >= 0) {
         const int64_t beg = a.cv.rowptr[j], end = a.cv.rowptr[j + 1];
-        for (int64_t e = beg + sub; e < end; e += G) {
-            const float x = a.cv.val[e];
-            acc = fmaf(x, a.v[a.cv.colidx[e]], acc);
-            if (NORMS) nq = fmaf(x, x, nq);
+        // all index/value loads of a batch are issued before the gathers that depend on them, so
+        // a lane has K gathers of v in flight instead of one
+        for (int64_t e0 = beg + sub; e0 < end; e0 += (int64_t)G * K) {
+            int32_t ci[K];
+            float xv[K];
+#pragma unroll
+            for (int u = 0; u < K; ++u) {
+                const int64_t e = e0 + (int64_t)u * G;
+                const bool in = e < end;
+                ci[u] = in ? a.cv.colidx[e] : 0;
+                xv[u] = in ? a.cv.val[e] : 0.0f;
+            }
+            float vv[K];
+#pragma unroll
+            for (int u = 0; u < K; ++u) vv[u] = a.v[ci[u]];
+#pragma unroll
+            for (int u = 0; u < K; ++u) {
+                acc = fmaf(xv[u], vv[u], acc);
+                if (NORMS) nq = fmaf(xv[u], xv[u], nq);
+            }
         }
     }
     acc = group_sum<G>(acc);
