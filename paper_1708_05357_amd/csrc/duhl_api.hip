@@ -169,7 +169,7 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->gap_cols = env_int("DUHL_GAP_COLS", d < 4096 ? 8 : 4);
     if (c->gap_cols != 1 && c->gap_cols != 2 && c->gap_cols != 4 && c->gap_cols != 8) c->gap_cols = 4;
     c->cd_threads = env_int("DUHL_CD_THREADS", 0);
-    c->copy_blocks = env_int("DUHL_COPY_BLOCKS", 32);
+    c->copy_blocks = env_int("DUHL_COPY_BLOCKS", 8);
     if (c->copy_blocks < 1) c->copy_blocks = 1;
 
     c->partials_cap = n / 4 + 4096;

@@ -330,28 +330,38 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
     if (tid == 0) dirty[w] = moved ? 1 : 0;
 }
 
-// v += sum over workers of their stored changes, in worker order (reproducible).  Sixteen
-// independent loads in flight per lane; dirty[] is uniform, so skipping a clean worker is a
-// scalar branch.
-__global__ __launch_bounds__(256) void merge_workers_kernel(float *v, int64_t d, const float *dv,
-                                                            int64_t dv_stride, const int32_t *dirty,
-                                                            int nworkers)
+// v += sum over workers of their stored changes, in a fixed order (reproducible).  A workgroup
+// owns 64 consecutive elements of v; each of its 16 wavefronts adds up every 16th worker's buffer
+// (eight independent 256-byte loads in flight), then the 16 partial sums are added in wavefront
+// order.  dirty[] is uniform, so skipping a clean worker is a scalar branch.
+__global__ __launch_bounds__(1024) void merge_workers_kernel(float *v, int64_t d, const float *dv,
+                                                             int64_t dv_stride, const int32_t *dirty,
+                                                             int nworkers)
 {
-    const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (k >= d) return;
-    const float *p = dv + k;
+    __shared__ float part[16][64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int64_t k = (int64_t)blockIdx.x * 64 + lane;
+    const bool in = k < d;
+    const float *p = dv + (in ? k : 0);
     float s = 0.0f;
-    int g = 0;
-    for (; g + 16 <= nworkers; g += 16) {
-        float t[16];
+    int g = w;
+    for (; g + 16 * 7 < nworkers; g += 16 * 8) {
+        float t[8];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) t[u] = dirty[g + u] ? p[(int64_t)(g + u) * dv_stride] : 0.0f;
+        for (int u = 0; u < 8; ++u) t[u] = dirty[g + 16 * u] ? p[(int64_t)(g + 16 * u) * dv_stride] : 0.0f;
 #pragma unroll
-        for (int u = 0; u < 16; ++u) s += t[u];
+        for (int u = 0; u < 8; ++u) s += t[u];
     }
-    for (; g < nworkers; ++g)
+    for (; g < nworkers; g += 16)
         if (dirty[g]) s += p[(int64_t)g * dv_stride];
-    if (s != 0.0f) v[k] += s;
+    part[w][lane] = s;
+    __syncthreads();
+    if (w == 0 && in) {
+        float t = 0.0f;
+#pragma unroll
+        for (int u = 0; u < 16; ++u) t += part[u][lane];
+        if (t != 0.0f) v[k] += t;
+    }
 }
 
 // ---- asynchronous, sparse: G lanes per coordinate -------------------------------------------------
@@ -574,7 +584,7 @@ hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
         const int64_t grid = (workers + PER - 1) / PER;
         hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, T, NR, NL, CACHE_X>), dim3(grid), dim3(BLOCK), 0,
                            c->compute, a, t0, t1, c->dv, c->dv_stride, c->dirty);
-        hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 255) / 256), dim3(256), 0, c->compute, a.v,
+        hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 63) / 64), dim3(1024), 0, c->compute, a.v,
                            c->d, c->dv, c->dv_stride, c->dirty, (int)(grid * PER));
     }
     return hipGetLastError();
