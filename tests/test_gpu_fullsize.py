@@ -125,3 +125,59 @@ def test_cfg5_full_size_sampled_columns_and_invariants(G):
     want = (sub.t() @ torch.as_tensor(a2[nz], device="cuda").double()).cpu().numpy() - b[rows.cpu().numpy()]
     assert np.abs(v2[rows.cpu().numpy()] - want).max() <= 1e-4 * np.abs(b).max()
     g.close()
+
+
+def test_cfg3_full_size_sparse_svm(G):
+    """Sparse SVM dual, 1,000,000 samples x 100,000 features (~1e8 non-zeros), m = 200,000: gaps of
+    all coordinates against the whole oracle, exact selection, one sequential pass over a sample of
+    the working set, and the asynchronous scheme's objective after the rounds bench.py runs."""
+    from oracle import duhl_oracle as orc
+    from paper_1708_05357_amd import duhl, synth
+    prob = synth.make("cfg3", device="cuda")
+    n, d, m = prob["n"], prob["d"], prob["m"]
+    host = {k: (v.cpu() if torch.is_tensor(v) else v) for k, v in prob.items()}
+    g = duhl.Duhl(duhl.SVM, d, n, m)
+    g.set_data_csr(prob["rowptr"], prob["colidx"], prob["val"], prob["target"], prob["lam"])
+    o = orc.Oracle(orc.SVM, host["target"].numpy(), prob["lam"],
+                   csr=(host["rowptr"].numpy(), host["colidx"].numpy(), host["val"].numpy()), d=d)
+    np.testing.assert_allclose(g.get(duhl.SQNORM), o.q, rtol=2e-6)
+    assert g.gap() == pytest.approx(1.0, rel=1e-6)                      # App. E: every z_i = 1/n at 0
+    rng = np.random.default_rng(3)
+    for rnd in range(12):
+        g.gap(want_sum=False)
+        g.select(m, want_stats=False)
+        g.commit_swap()
+        g.cd_epoch(duhl.CD_ASYNC, seed=rnd)
+    # same point in both: gaps of all 1e6 coordinates
+    o.set_state(g.get(duhl.ALPHA).astype(np.float64), g.get(duhl.V).astype(np.float64))
+    total = g.gap()
+    assert total == pytest.approx(o.gaps(), rel=1e-4)
+    G.assert_gaps_close(g.get(duhl.Z), o.z, floor=8 * 2.0 ** -24 / n)
+    out = torch.empty(m, dtype=torch.int32, device="cuda:0")
+    g.select(m, out)
+    z32 = g.get(duhl.Z)
+    np.testing.assert_array_equal(out.cpu().numpy(), orc.select_topm(z32.astype(np.float64), m))
+    g.commit_swap()
+    # exact steps, one after the other, on 2,000 coordinates of the working set
+    P = g.get(duhl.P)
+    order = rng.permutation(P)[:2000].astype(np.int32)
+    g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(order))
+    o.cd_pass(order)
+    a, v = g.get(duhl.ALPHA), g.get(duhl.V)
+    assert np.abs(a - o.alpha).max() <= 1e-5 * np.abs(o.alpha).max()
+    assert np.abs(v - o.v).max() <= 1e-5 * np.abs(o.v).max()
+    # objective of the asynchronous scheme against the oracle's own rounds
+    for rnd in range(80):
+        g.gap(want_sum=False)
+        g.select(m, want_stats=False)
+        g.commit_swap()
+        g.cd_epoch(duhl.CD_ASYNC, seed=100 + rnd)
+    o2 = orc.Oracle(orc.SVM, host["target"].numpy(), prob["lam"],
+                    csr=(host["rowptr"].numpy(), host["colidx"].numpy(), host["val"].numpy()), d=d)
+    rng2 = np.random.default_rng(0)
+    for rnd in range(90):
+        o2.round(m, passes=1, rng=rng2)
+    og, oo = g.objective(), o2.objective()
+    print("cfg3 objective gpu %.9e oracle %.9e gap gpu %.3e" % (og, oo, g.gap()))
+    assert abs(og - oo) <= 1e-5 * abs(oo)
+    g.close()

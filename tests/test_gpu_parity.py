@@ -296,8 +296,17 @@ def test_host_resident_swap_matches_oracle(G):
     copies run on the side stream while the previous set is being worked on; iterates must still
     match the oracle, and the slots must hold the selected columns."""
     from paper_1708_05357_amd import duhl
-    prob = lasso_problem(1028, 400, 0.1, 0.1, seed=21)
-    m = 60
+    run_host_resident(G, lasso_problem(1028, 400, 0.1, 0.1, seed=21), 60)
+
+
+def test_host_resident_swap_long_columns(G):
+    """The same with the column length of the out-of-budget workload (d = 100,000): slots with a
+    padded leading dimension, the longest register/LDS split of the workers."""
+    run_host_resident(G, lasso_problem(100000, 160, 0.1, 0.1, seed=22), 30, rounds=4)
+
+
+def run_host_resident(G, prob, m, rounds=10):
+    from paper_1708_05357_amd import duhl
     for budget in (2 * m, m + 7):                  # overlapping copies / in-place replacement
         p = G.Pair(prob, budget=budget, host_resident=True)
         p.o.gaps()
@@ -307,7 +316,7 @@ def test_host_resident_swap_matches_oracle(G):
         nsw, rho = p.g.select(m)
         assert nsw == m
         p.g.commit_swap()
-        for rnd in range(10):
+        for rnd in range(rounds):
             P = p.g.get(duhl.P)
             order = rng.permutation(P).astype(np.int32)
             if budget >= 2 * m:
@@ -343,6 +352,15 @@ def test_host_resident_swap_matches_oracle(G):
         floor = G.lasso_gap_floor(p)
         np.testing.assert_allclose(z[Pn], p.o.z[Pn], rtol=1e-4, atol=1e-4 * p.o.z.max() + floor)
         assert np.count_nonzero(z >= 0) <= budget
+        # the concurrent schemes read the working set from the slots too: the objective must not
+        # rise and v must stay A alpha - b (App. D)
+        for mode in (duhl.CD_ASYNC, duhl.CD_ATOMIC):
+            before = p.g.objective()
+            p.g.cd_epoch(mode, seed=5)
+            assert p.g.objective() <= before * (1 + 1e-6) + 1e-12
+            a, v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+            p.o.set_state(a.astype(np.float64))
+            assert np.abs(v - p.o.v).max() <= 1e-4 * max(np.abs(p.o.v).max(), np.abs(G.to_np(prob["target"])).max())
         p.close()
 
 
