@@ -15,7 +15,7 @@
  *   dense : column i is the contiguous run A[i*ld .. i*ld+d)
  *   sparse: CSR of A^T, i.e. row i of the CSR arrays lists the non-zeros of a_i
  *           (for the SVM dual a column of A is one sample, Appendix D).
- * Shared vector (Appendix D): Lasso v = A alpha - b, SVM v = A alpha.
+ * Shared vector (Appendix D): Lasso / elastic net v = A alpha - b, SVM v = A alpha.
  * Lambda := lambda * d is the product that the Lasso formulas use throughout.
  *
  * Pins: tests/test_oracle_pins.py (closed forms, brute force, invariants).
@@ -246,4 +246,58 @@ void or_svm_cd_pass(const or_matrix *M, const double *q, const float *y, double 
     const double lam_n = lambda * (double)M->n;
     for (int64_t k = 0; k < count; ++k)
         svm_step(M, order[k], q[order[k]], lam_n, (double)y[order[k]], alpha, v);
+}
+
+/* ---- elastic net with eta in (0,1]; eta = 1 is ridge regression (Appendix C(a), D) ---------- */
+
+/* Objective of Appendix D: ||A alpha - b||^2/(2d) + lambda (eta/2 ||alpha||^2 + (1-eta)||alpha||_1). */
+double or_enet_objective(const or_matrix *M, const double *v, const double *alpha, double lambda,
+                         double eta)
+{
+    double sq = 0.0, l1 = 0.0, l2 = 0.0;
+    for (int64_t k = 0; k < M->d; ++k) sq += v[k] * v[k];
+    for (int64_t j = 0; j < M->n; ++j) { l1 += fabs(alpha[j]); l2 += alpha[j] * alpha[j]; }
+    return sq / (2.0 * (double)M->d) + lambda * (0.5 * eta * l2 + (1.0 - eta) * l1);
+}
+
+/* Coordinate gaps from eq. (4) with w = A alpha - b, g_i(a) = lambda(eta/2 a^2 + (1-eta)|a|) and its
+ * conjugate g_i*(u) = [|u| - lambda(1-eta)]_+^2 / (2 lambda eta):
+ *   z_i = (1/d) [ alpha_i c_i + Lambda (eta/2 alpha_i^2 + (1-eta)|alpha_i|)
+ *                 + [|c_i| - Lambda(1-eta)]_+^2 / (2 Lambda eta) ],   c_i = a_i^T v, Lambda = lambda d.
+ * For eta = 1 this is the ridge gap printed in Appendix E. */
+double or_enet_gaps(const or_matrix *M, const double *v, const double *alpha, double lambda,
+                    double eta, const int32_t *idx, int64_t count, double *z)
+{
+    const double d = (double)M->d, Lam = lambda * d;
+    double total = 0.0;
+    for (int64_t k = 0; k < count; ++k) {
+        int64_t i = idx ? idx[k] : k;
+        double c = col_dot(M, i, v);
+        double over = fabs(c) - Lam * (1.0 - eta);
+        if (over < 0.0) over = 0.0;
+        z[i] = (alpha[i] * c + Lam * (0.5 * eta * alpha[i] * alpha[i] + (1.0 - eta) * fabs(alpha[i]))
+                + over * over / (2.0 * Lam * eta)) / d;
+        total += z[i];
+    }
+    return total;
+}
+
+/* Exact coordinate step of Appendix D:
+ *   gamma = (alpha_j q_j - a_j^T v)/(q_j + Lambda eta),  tau = Lambda(1-eta)/(q_j + Lambda eta),
+ *   alpha_j <- sign(gamma)[|gamma| - tau]_+ . */
+void or_enet_cd_pass(const or_matrix *M, const double *q, double lambda, double eta,
+                     const int32_t *order, int64_t count, double *alpha, double *v)
+{
+    const double Lam = lambda * (double)M->d;
+    for (int64_t k = 0; k < count; ++k) {
+        const int64_t j = order[k];
+        const double den = q[j] + Lam * eta;
+        const double gamma = (alpha[j] * q[j] - col_dot(M, j, v)) / den;
+        const double tau = Lam * (1.0 - eta) / den;
+        const double mag = fabs(gamma) - tau;
+        const double newa = mag > 0.0 ? (gamma > 0.0 ? mag : -mag) : 0.0;
+        const double delta = newa - alpha[j];
+        if (delta != 0.0) col_axpy(M, j, delta, v);
+        alpha[j] = newa;
+    }
 }

@@ -16,7 +16,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "duhl_oracle.c")
 _LIB = os.path.join(_HERE, "libduhl_oracle.so")
 
-LASSO, SVM = 0, 1
+LASSO, SVM, ENET = 0, 1, 2
 
 
 def build(force=False):
@@ -62,6 +62,12 @@ def _load():
         lib.or_lasso_cd_pass.argtypes = [p, p, dbl, p, C.c_int64, p, p]
         lib.or_svm_cd_pass.restype = None
         lib.or_svm_cd_pass.argtypes = [p, p, p, dbl, p, C.c_int64, p, p]
+        lib.or_enet_objective.restype = dbl
+        lib.or_enet_objective.argtypes = [p, p, p, dbl, dbl]
+        lib.or_enet_gaps.restype = dbl
+        lib.or_enet_gaps.argtypes = [p, p, p, dbl, dbl, p, C.c_int64, p]
+        lib.or_enet_cd_pass.restype = None
+        lib.or_enet_cd_pass.argtypes = [p, p, dbl, dbl, p, C.c_int64, p, p]
         _lib = lib
     return _lib
 
@@ -94,10 +100,11 @@ class Oracle:
     with ``d`` given.  ``target`` is b (length d) for the Lasso and y (length n, +-1) for the SVM.
     """
 
-    def __init__(self, model, target, lam, cols=None, csr=None, d=None):
+    def __init__(self, model, target, lam, cols=None, csr=None, d=None, eta=1.0):
         self.lib = _load()
         self.model = model
         self.lam = float(lam)
+        self.eta = float(eta)          # elastic-net mix (ENET only): 1 = ridge
         self.target = np.ascontiguousarray(target, dtype=np.float32)
         M = _Matrix()
         if cols is not None:
@@ -116,7 +123,7 @@ class Oracle:
         self.M = M
         self._Mp = C.cast(C.pointer(M), C.c_void_p)
         self.n, self.d = int(M.n), int(M.d)
-        assert self.target.size == (self.d if model == LASSO else self.n)
+        assert self.target.size == (self.n if model == SVM else self.d)
         self.q = np.empty(self.n, dtype=np.float64)
         self.lib.or_col_sqnorms(self._Mp, _ptr(self.q))
         self.alpha = np.zeros(self.n, dtype=np.float64)
@@ -129,7 +136,7 @@ class Oracle:
     # -- state ---------------------------------------------------------------------------
     def recompute_v(self):
         """v := A alpha - b (Lasso) or A alpha (SVM), from its definition."""
-        shift = self.target if self.model == LASSO else None
+        shift = None if self.model == SVM else self.target
         self.lib.or_matvec(self._Mp, _ptr(self.alpha), _ptr(shift), _ptr(self.v))
         return self.v
 
@@ -144,6 +151,8 @@ class Oracle:
     def objective(self):
         if self.model == LASSO:
             return self.lib.or_lasso_objective(self._Mp, _ptr(self.v), _ptr(self.alpha), self.lam)
+        if self.model == ENET:
+            return self.lib.or_enet_objective(self._Mp, _ptr(self.v), _ptr(self.alpha), self.lam, self.eta)
         return self.lib.or_svm_objective(self._Mp, _ptr(self.v), _ptr(self.alpha),
                                          _ptr(self.target), self.lam)
 
@@ -155,6 +164,9 @@ class Oracle:
         if self.model == LASSO:
             return self.lib.or_lasso_gaps(self._Mp, _ptr(self.v), _ptr(self.alpha), self.lam,
                                           self.B, _ptr(idx), count, _ptr(self.z))
+        if self.model == ENET:
+            return self.lib.or_enet_gaps(self._Mp, _ptr(self.v), _ptr(self.alpha), self.lam, self.eta,
+                                         _ptr(idx), count, _ptr(self.z))
         return self.lib.or_svm_gaps(self._Mp, _ptr(self.v), _ptr(self.alpha), _ptr(self.target),
                                     self.lam, _ptr(idx), count, _ptr(self.z))
 
@@ -166,6 +178,9 @@ class Oracle:
         if self.model == LASSO:
             self.lib.or_lasso_cd_pass(self._Mp, _ptr(self.q), self.lam, _ptr(order), order.size,
                                       _ptr(self.alpha), _ptr(self.v))
+        elif self.model == ENET:
+            self.lib.or_enet_cd_pass(self._Mp, _ptr(self.q), self.lam, self.eta, _ptr(order),
+                                     order.size, _ptr(self.alpha), _ptr(self.v))
         else:
             self.lib.or_svm_cd_pass(self._Mp, _ptr(self.q), _ptr(self.target), self.lam,
                                     _ptr(order), order.size, _ptr(self.alpha), _ptr(self.v))

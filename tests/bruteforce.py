@@ -29,6 +29,46 @@ def svm_primal_objective(A, y, w, lam):
     return float(np.maximum(0.0, 1.0 - y * (A.T @ w)).sum()) / n + 0.5 * lam * float(w @ w)
 
 
+def enet_objective(A, b, alpha, lam, eta):
+    """||A alpha - b||^2/(2d) + lam (eta/2 ||alpha||^2 + (1-eta) ||alpha||_1)."""
+    d = A.shape[0]
+    r = A @ alpha - b
+    return float(r @ r) / (2 * d) + lam * (0.5 * eta * float(alpha @ alpha) + (1 - eta) * float(np.abs(alpha).sum()))
+
+
+def enet_gap(A, b, alpha, lam, eta):
+    """Total duality gap of Section 2, eq. (2), from the conjugates written out: f(u) =
+    ||u - b||^2/(2d), f*(w) = w^T b + (d/2)||w||^2, g_i*(u) = [|u| - lam(1-eta)]_+^2/(2 lam eta),
+    at w = grad f(A alpha)."""
+    d = A.shape[0]
+    w = (A @ alpha - b) / d
+    u = -(A.T @ w)
+    gstar = np.maximum(np.abs(u) - lam * (1 - eta), 0.0) ** 2 / (2 * lam * eta)
+    return enet_objective(A, b, alpha, lam, eta) + float(w @ b) + 0.5 * d * float(w @ w) + float(gstar.sum())
+
+
+def enet_optimum(A, b, lam, eta):
+    """Exact elastic-net minimiser by enumerating sign patterns (n <= ~8); eta = 1 has the single
+    pattern-free solution of the ridge normal equations."""
+    d, n = A.shape
+    best = (enet_objective(A, b, np.zeros(n), lam, eta), np.zeros(n))
+    for s in itertools.product((-1, 0, 1), repeat=n):
+        s = np.array(s, dtype=np.float64)
+        S = np.flatnonzero(s)
+        if S.size == 0:
+            continue
+        AS = A[:, S]
+        aS = np.linalg.solve(AS.T @ AS / d + lam * eta * np.eye(S.size), AS.T @ b / d - lam * (1 - eta) * s[S])
+        if np.any(np.sign(aS) != s[S]):
+            continue
+        alpha = np.zeros(n)
+        alpha[S] = aS
+        val = enet_objective(A, b, alpha, lam, eta)
+        if val < best[0]:
+            best = (val, alpha)
+    return best
+
+
 def lasso_optimum(A, b, lam):
     """Exact Lasso minimiser by enumerating sign patterns (n <= ~8).
 

@@ -401,3 +401,60 @@ def test_planted_mistakes_are_caught(which, tmp_path, monkeypatch):
             break
     monkeypatch.setattr(orc, "_lib", good)
     assert caught, f"mutation {old!r} -> {new!r} slipped through"
+
+
+# ----------------------------------------------------------------------------- elastic net / ridge
+ENET = orc.ENET
+
+
+@pytest.mark.parametrize("eta", [1.0, 0.5, 0.1])
+def test_enet_gap_is_primal_minus_dual_and_cd_reaches_the_optimum(eta):
+    """App. D (elastic-net step), App. E (ridge gap = the eta = 1 case): the gap equals eq. (2)
+    written from the conjugates; the CD limit is the enumerated KKT solution; for eta = 1 that is
+    the ridge normal-equations solution; every step is the 1-D argmin."""
+    cols, b, A, lam = tiny_lasso(3, d=9, n=6, c=0.2)
+    b64 = b.astype(np.float64)
+    o = orc.Oracle(ENET, b, lam, cols=cols, eta=eta)
+    ostar, astar = bf.enet_optimum(A, b64, lam, eta)
+    if eta == 1.0:
+        ridge = np.linalg.solve(A.T @ A / 9 + lam * np.eye(6), A.T @ b64 / 9)
+        np.testing.assert_allclose(astar, ridge, atol=1e-12)
+    rng = np.random.default_rng(0)
+    prev = o.objective()
+    for it in range(300):
+        total = o.gaps()
+        assert total == pytest.approx(bf.enet_gap(A, b64, o.alpha, lam, eta), rel=1e-10, abs=1e-15)
+        assert o.z.min() >= -1e-15
+        assert total >= o.objective() - ostar - 1e-12
+        if it < 30:
+            j = int(rng.integers(6))
+            base = o.alpha.copy()
+
+            def line(t):
+                a = base.copy()
+                a[j] = t
+                return bf.enet_objective(A, b64, a, lam, eta)
+            res = minimize_scalar(line, bracket=(-3, 3), tol=1e-13)
+            o.cd_pass(np.array([j], dtype=np.int32))
+            assert line(o.alpha[j]) <= res.fun + 1e-12
+            np.testing.assert_allclose(o.v, A @ o.alpha - b64, atol=1e-13)
+        else:
+            o.cd_pass(rng.permutation(6).astype(np.int32))
+        obj = o.objective()
+        assert obj == pytest.approx(bf.enet_objective(A, b64, o.alpha, lam, eta), rel=1e-12)
+        assert obj <= prev + 1e-15
+        prev = obj
+    assert o.objective() == pytest.approx(ostar, rel=1e-10)
+    np.testing.assert_allclose(o.alpha, astar, atol=1e-8)
+    assert o.gaps() < 1e-12
+
+
+def test_enet_tends_to_lasso_for_small_eta():
+    """eta -> 0 recovers the Lasso step (App. D with eta = 0)."""
+    cols, b, A, lam = tiny_lasso(2)
+    e = orc.Oracle(ENET, b, lam, cols=cols, eta=1e-12)
+    l = orc.Oracle(LASSO, b, lam, cols=cols)
+    for _ in range(50):
+        e.cd_pass(np.arange(6, dtype=np.int32))
+        l.cd_pass(np.arange(6, dtype=np.int32))
+    np.testing.assert_allclose(e.alpha, l.alpha, atol=1e-9)
