@@ -17,7 +17,10 @@
  * Models.  DUHL_LASSO:  O = ||A alpha - b||^2/(2d) + lambda ||alpha||_1, shared vector
  * v = A alpha - b.  DUHL_SVM (hinge loss, dual): O = -(1/n) sum y_i alpha_i +
  * ||A alpha||^2/(2 lambda n^2) with y_i alpha_i in [0,1], shared vector v = A alpha; a column
- * of A is one sample.  All data and state are fp32; scalar results are returned as double.
+ * of A is one sample.  DUHL_ELASTIC_NET (Appendix D): O = ||A alpha - b||^2/(2d) +
+ * lambda (eta/2 ||alpha||^2 + (1-eta) ||alpha||_1) with 0 < eta <= 1, shared vector v = A alpha - b;
+ * eta = 1 is the ridge regression of Appendix C (a).  All data and state are fp32; scalar results
+ * are returned as double.
  *
  * General rules.  Every call returns a duhl_status and never throws or aborts.  On error
  * the out-parameters are untouched and duhl_last_error() describes the cause.  Arrays passed
@@ -38,7 +41,7 @@ extern "C" {
 
 typedef struct duhl_ctx duhl_ctx;
 
-typedef enum { DUHL_LASSO = 0, DUHL_SVM = 1 } duhl_model;
+typedef enum { DUHL_LASSO = 0, DUHL_SVM = 1, DUHL_ELASTIC_NET = 2 } duhl_model;
 
 typedef enum {
     DUHL_OK = 0,
@@ -73,10 +76,14 @@ typedef enum {
 duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n,
                         int64_t budget_cols, int device, void *compute_stream, void *copy_stream);
 
+/* Mixing parameter eta of DUHL_ELASTIC_NET, 0 < eta <= 1 (default 1 = ridge).  Takes effect at the
+ * next duhl_set_data_* call.  DUHL_EINVAL for other models or values. */
+duhl_status duhl_set_eta(duhl_ctx *ctx, double eta);
+
 /* Dense data (Section 2: A in R^{d x n}, fp32 per Section 5.3).  A: column-major, column i at
  * A + i*ld, ld >= d; a device pointer for DUHL_RESIDENT_DEVICE, a pinned host pointer that the
  * device can read for DUHL_RESIDENT_HOST; borrowed.  target (device, borrowed): b of length d
- * for the Lasso, labels y in {+1,-1} of length n for the SVM.  lambda: the lambda of the
+ * for the Lasso and the elastic net, labels y in {+1,-1} of length n for the SVM.  lambda: the lambda of the
  * objectives above, finite and > 0.  Resets alpha = 0, v = -b (Lasso) or 0 (SVM), computes the
  * column norms and a first full gap pass into z (one read of A).  Waits for completion. */
 duhl_status duhl_set_data_dense(duhl_ctx *ctx, const float *A, int64_t ld, duhl_residency res,
@@ -95,6 +102,8 @@ duhl_status duhl_set_data_csr(duhl_ctx *ctx, const int64_t *rowptr, const int32_
  *       z_i = (1/d) [ alpha_i c_i + B [|c_i| - lambda d]_+ + lambda d |alpha_i| ]
  *   SVM (Appendix E), s_i = a_i^T v / (lambda n):
  *       z_i = (1/n) [ alpha_i s_i + max(0, 1 - y_i s_i) - y_i alpha_i ]
+ *   elastic net (eq. (4) with the conjugate of g_i; for eta = 1 the ridge gap of Appendix E), L = lambda d:
+ *       z_i = (1/d) [ alpha_i c_i + L (eta/2 alpha_i^2 + (1-eta)|alpha_i|) + [|c_i| - L(1-eta)]_+^2 / (2 L eta) ]
  * clamped at 0.  idx (device, int32, each in [0,n), no duplicates) lists the `count`
  * coordinates to refresh; idx == NULL refreshes all n coordinates (device residency) or every
  * column currently held in a device slot (host residency), and count is then ignored.  Other
@@ -123,6 +132,8 @@ duhl_status duhl_commit_swap(duhl_ctx *ctx);
 /* One pass of exact coordinate steps over the current working set (Appendix D):
  *   Lasso:  gamma = alpha_j - a_j^T v/||a_j||^2,  alpha_j <- sign(gamma)[|gamma| - lambda d/||a_j||^2]_+
  *   SVM:    alpha_j <- y_j clip(y_j(alpha_j + (y_j - a_j^T v/(lambda n)) lambda n/||a_j||^2), 0, 1)
+ *   e.net:  gamma = (alpha_j ||a_j||^2 - a_j^T v)/(||a_j||^2 + lambda eta d),
+ *           alpha_j <- sign(gamma)[|gamma| - lambda d (1-eta)/(||a_j||^2 + lambda eta d)]_+
  *   both:   v <- v + a_j (alpha_j_new - alpha_j_old)
  * order (device, int32): the coordinates to visit, in visiting order; each must belong to the
  * current working set and, for the concurrent schemes, appear once; n_order entries.

@@ -102,6 +102,13 @@ duhl_status finish_set_data(duhl_ctx *c, const float *target, double lambda)
         mc.Lam = (float)(lambda * d);
         mc.B = (float)(c->h_scalars[S_BSQ] / (2.0 * lambda * d));   // Appendix E: ||b||^2/(2 lambda d)
         mc.inv_d = (float)(1.0 / d);
+    } else if (c->model == DUHL_ELASTIC_NET) {
+        c->eta_active = c->eta;
+        mc.Lam = (float)(lambda * d);
+        mc.lam_eta = (float)(lambda * d * c->eta);
+        mc.lam_l1 = (float)(lambda * d * (1.0 - c->eta));
+        mc.inv_2lam_eta = (float)(1.0 / (2.0 * lambda * d * c->eta));
+        mc.inv_d = (float)(1.0 / d);
     } else {
         mc.lam_n = (float)(lambda * n);
         mc.inv_lam_n = (float)(1.0 / (lambda * n));
@@ -150,7 +157,7 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
                         int device, void *compute_stream, void *copy_stream)
 {
     if (!out) return DUHL_EINVAL;
-    if (model != DUHL_LASSO && model != DUHL_SVM) return DUHL_EINVAL;
+    if (model != DUHL_LASSO && model != DUHL_SVM && model != DUHL_ELASTIC_NET) return DUHL_EINVAL;
     if (d <= 0 || n <= 0 || budget_cols <= 0 || n > 0x7fffffffll || d > 0x7fffffffll) return DUHL_EINVAL;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return DUHL_EHIP;
@@ -162,6 +169,7 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->n = n;
     c->budget = budget_cols < n ? budget_cols : n;
     c->device = device;
+    c->eta = c->eta_active = 1.0;
     c->compute = reinterpret_cast<hipStream_t>(compute_stream);
     c->copy = reinterpret_cast<hipStream_t>(copy_stream);
     c->num_cu = 256;
@@ -196,6 +204,15 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
         return e == hipErrorOutOfMemory ? DUHL_ENOMEM : DUHL_EHIP;
     }
     *out = c;
+    return DUHL_OK;
+}
+
+duhl_status duhl_set_eta(duhl_ctx *c, double eta)
+{
+    if (!c) return DUHL_EINVAL;
+    if (c->model != DUHL_ELASTIC_NET) return fail(c, DUHL_EINVAL, "eta applies to DUHL_ELASTIC_NET only");
+    if (!(eta > 0.0) || !(eta <= 1.0)) return fail(c, DUHL_EINVAL, "eta must be in (0, 1]");
+    c->eta = eta;
     return DUHL_OK;
 }
 
@@ -367,8 +384,8 @@ duhl_status duhl_objective(duhl_ctx *c, double *objective)
     if (st != DUHL_OK) return st;
     const double sq = c->h_scalars[S_OBJ_SQ], lin = c->h_scalars[S_OBJ_LIN];
     const double d = (double)c->d, n = (double)c->n;
-    if (c->model == DUHL_LASSO)
-        *objective = sq / (2.0 * d) + c->lambda * lin;             // Appendix C (b)
+    if (c->model != DUHL_SVM)
+        *objective = sq / (2.0 * d) + c->lambda * lin;             // Appendix C (a), (b); Appendix D
     else
         *objective = -lin / n + sq / (2.0 * c->lambda * n * n);    // Appendix C (c)
     return DUHL_OK;

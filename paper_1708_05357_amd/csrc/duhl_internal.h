@@ -42,6 +42,9 @@ struct ModelConst {
     float lam_n;      // SVM: lambda * n
     float inv_lam_n;  // SVM: 1/(lambda n)
     float inv_n;      // SVM: 1/n
+    float lam_eta;    // elastic net: lambda d eta
+    float lam_l1;     // elastic net: lambda d (1 - eta)
+    float inv_2lam_eta;  // elastic net: 1 / (2 lambda d eta)
 };
 
 // Coordinate gap from c = a_i^T v (Appendix E), clamped at 0 (Section 2: the gap is non-negative).
@@ -52,6 +55,10 @@ __device__ __forceinline__ float gap_value(const ModelConst &mc, float c, float 
     if (MODEL == DUHL_LASSO) {
         const float over = fmaxf(fabsf(c) - mc.Lam, 0.0f);
         z = (fmaf(alpha, c, mc.Lam * fabsf(alpha)) + mc.B * over) * mc.inv_d;
+    } else if (MODEL == DUHL_ELASTIC_NET) {
+        const float over = fmaxf(fabsf(c) - mc.lam_l1, 0.0f);
+        const float reg = fmaf(0.5f * mc.lam_eta * alpha, alpha, mc.lam_l1 * fabsf(alpha));
+        z = (fmaf(alpha, c, reg) + over * over * mc.inv_2lam_eta) * mc.inv_d;
     } else {
         const float s = c * mc.inv_lam_n;
         const float hinge = fmaxf(1.0f - y * s, 0.0f);
@@ -69,6 +76,11 @@ __device__ __forceinline__ float cd_new_alpha(const ModelConst &mc, float c, flo
         if (!(q > 0.0f)) return 0.0f;
         const float gamma = alpha - c / q;
         const float mag = fabsf(gamma) - mc.Lam / q;
+        return mag > 0.0f ? copysignf(mag, gamma) : 0.0f;
+    } else if (MODEL == DUHL_ELASTIC_NET) {
+        const float den = q + mc.lam_eta;
+        const float gamma = fmaf(alpha, q, -c) / den;
+        const float mag = fabsf(gamma) - mc.lam_l1 / den;
         return mag > 0.0f ? copysignf(mag, gamma) : 0.0f;
     } else {
         if (!(q > 0.0f)) return y;
@@ -151,6 +163,8 @@ struct duhl_ctx {
     bool swap_exclusive;   // the pending copies reuse slots of the current set
     uint64_t pass_counter;
     double mean_corr;      // mean cosine between columns, estimated on a sample (>= 0)
+    double eta;            // elastic-net mix requested through duhl_set_eta
+    double eta_active;     // the mix the current data were set with
 
     double *scalars;            // S_COUNT doubles
     double *partials;           // per-block partial sums

@@ -678,8 +678,9 @@ hipError_t launch_cd(duhl_ctx *c, duhl_cd_mode mode, const int32_t *order, int64
         a.padd[r] = (uint32_t)splitmix64(s);
     }
     if (a.count <= 0) return hipSuccess;
-    return c->model == DUHL_LASSO ? launch_cd_model<DUHL_LASSO>(c, mode, a, max_inflight)
-                                  : launch_cd_model<DUHL_SVM>(c, mode, a, max_inflight);
+    if (c->model == DUHL_LASSO) return launch_cd_model<DUHL_LASSO>(c, mode, a, max_inflight);
+    if (c->model == DUHL_ELASTIC_NET) return launch_cd_model<DUHL_ELASTIC_NET>(c, mode, a, max_inflight);
+    return launch_cd_model<DUHL_SVM>(c, mode, a, max_inflight);
 }
 
 }  // namespace duhl

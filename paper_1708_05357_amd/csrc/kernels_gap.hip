@@ -274,6 +274,9 @@ hipError_t launch_gap(duhl_ctx *c, const int32_t *idx, int64_t count, bool slot_
     if (c->model == DUHL_LASSO)
         e = with_norms ? launch_gap_model<DUHL_LASSO, true>(c, a, &grid)
                        : launch_gap_model<DUHL_LASSO, false>(c, a, &grid);
+    else if (c->model == DUHL_ELASTIC_NET)
+        e = with_norms ? launch_gap_model<DUHL_ELASTIC_NET, true>(c, a, &grid)
+                       : launch_gap_model<DUHL_ELASTIC_NET, false>(c, a, &grid);
     else
         e = with_norms ? launch_gap_model<DUHL_SVM, true>(c, a, &grid)
                        : launch_gap_model<DUHL_SVM, false>(c, a, &grid);

@@ -5,11 +5,13 @@ namespace duhl {
 
 namespace {
 
-// Sum of squares of v (both models) and, over the coordinates, sum |alpha_i| (Lasso) or
-// sum y_i alpha_i (SVM): the two reductions of the objectives in Appendix C.
+// Sum of squares of v (all models) and, over the coordinates, sum |alpha_i| (Lasso),
+// sum y_i alpha_i (SVM) or eta/2 sum alpha_i^2 + (1-eta) sum |alpha_i| (elastic net): the two
+// reductions of the objectives in Appendix C / D.
 template <int MODEL>
 __global__ __launch_bounds__(256) void objective_kernel(const float *v, int64_t d, const float *alpha,
-                                                        const float *y, int64_t n, double *partials)
+                                                        const float *y, int64_t n, double *partials,
+                                                        double eta)
 {
     __shared__ double sh[2][4];
     double sq = 0.0, lin = 0.0;
@@ -19,8 +21,10 @@ __global__ __launch_bounds__(256) void objective_kernel(const float *v, int64_t 
         sq += x * x;
     }
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += stride) {
-        if (MODEL == DUHL_LASSO) lin += fabs((double)alpha[i]);
-        else lin += (double)y[i] * (double)alpha[i];
+        const double ai = (double)alpha[i];
+        if (MODEL == DUHL_LASSO) lin += fabs(ai);
+        else if (MODEL == DUHL_ELASTIC_NET) lin += 0.5 * eta * ai * ai + (1.0 - eta) * fabs(ai);
+        else lin += (double)y[i] * ai;
     }
     sq = wave_sum(sq);
     lin = wave_sum(lin);
@@ -164,10 +168,13 @@ hipError_t launch_objective(duhl_ctx *c)
     if (grid > 1024) grid = 1024;
     if (c->model == DUHL_LASSO)
         hipLaunchKernelGGL(objective_kernel<DUHL_LASSO>, dim3(grid), dim3(256), 0, c->compute, c->v,
-                           c->d, c->alpha, c->target, c->n, c->partials);
+                           c->d, c->alpha, c->target, c->n, c->partials, 0.0);
+    else if (c->model == DUHL_ELASTIC_NET)
+        hipLaunchKernelGGL(objective_kernel<DUHL_ELASTIC_NET>, dim3(grid), dim3(256), 0, c->compute, c->v,
+                           c->d, c->alpha, c->target, c->n, c->partials, c->eta_active);
     else
         hipLaunchKernelGGL(objective_kernel<DUHL_SVM>, dim3(grid), dim3(256), 0, c->compute, c->v,
-                           c->d, c->alpha, c->target, c->n, c->partials);
+                           c->d, c->alpha, c->target, c->n, c->partials, 0.0);
     hipLaunchKernelGGL(objective_finish_kernel, dim3(1), dim3(1024), 0, c->compute, c->partials, grid,
                        c->scalars);
     return hipGetLastError();
@@ -176,7 +183,7 @@ hipError_t launch_objective(duhl_ctx *c)
 hipError_t launch_init_v(duhl_ctx *c)
 {
     hipLaunchKernelGGL(init_v_kernel, dim3((c->d + 255) / 256), dim3(256), 0, c->compute, c->v,
-                       c->model == DUHL_LASSO ? c->target : nullptr, c->d);
+                       c->model != DUHL_SVM ? c->target : nullptr, c->d);
     if (c->model == DUHL_LASSO)
         hipLaunchKernelGGL(sumsq_kernel, dim3(1), dim3(1024), 0, c->compute, c->target, c->d,
                            c->scalars + S_BSQ);

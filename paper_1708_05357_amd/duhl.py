@@ -14,13 +14,13 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libduhl.so")
 
-LASSO, SVM = 0, 1
+LASSO, SVM, ELASTIC_NET = 0, 1, 2
 RESIDENT_DEVICE, RESIDENT_HOST = 0, 1
 ALPHA, V, Z, P, SQNORM = 0, 1, 2, 3, 4
 CD_SEQUENTIAL, CD_ASYNC, CD_ATOMIC = 0, 1, 2
 OK, EINVAL, ENOMEM, EHIP, ESTATE, EBUDGET = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ["duhl_create", "duhl_set_data_dense", "duhl_set_data_csr", "duhl_gap", "duhl_select",
+EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_data_dense", "duhl_set_data_csr", "duhl_gap", "duhl_select",
            "duhl_commit_swap", "duhl_cd_epoch", "duhl_objective", "duhl_recompute_v", "duhl_get",
            "duhl_set", "duhl_device_ptr", "duhl_working_set_size", "duhl_last_error",
            "duhl_destroy"]
@@ -44,6 +44,7 @@ def load():
     lib = C.CDLL(LIB_PATH)
     p, i64, i32, dbl = C.c_void_p, C.c_int64, C.c_int, C.c_double
     lib.duhl_create.argtypes = [C.POINTER(p), i32, i64, i64, i64, i32, p, p]
+    lib.duhl_set_eta.argtypes = [p, dbl]
     lib.duhl_set_data_dense.argtypes = [p, p, i64, i32, p, dbl]
     lib.duhl_set_data_csr.argtypes = [p, p, p, p, i32, p, dbl]
     lib.duhl_gap.argtypes = [p, p, i64, C.POINTER(dbl)]
@@ -61,7 +62,7 @@ def load():
     lib.duhl_last_error.restype = C.c_char_p
     lib.duhl_destroy.argtypes = [p]
     lib.duhl_destroy.restype = None
-    for name in EXPORTS[:12]:
+    for name in EXPORTS[:13]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -109,6 +110,9 @@ class Duhl:
             pass
 
     # -- data -----------------------------------------------------------------------------
+    def set_eta(self, eta):
+        self._chk(self.lib.duhl_set_eta(self._h, float(eta)))
+
     def set_data_dense(self, cols, target, lam, residency=RESIDENT_DEVICE):
         """cols: float32 (n, d) tensor, row i = column a_i (device, or pinned host memory for
         RESIDENT_HOST); row stride = leading dimension.  target: device float32."""

@@ -15,12 +15,15 @@ class Pair:
 
     def __init__(self, prob, budget=None, host_resident=False, ld=None):
         self.prob = prob
-        model = duhl.LASSO if prob["model"] == "lasso" else duhl.SVM
+        model = {"lasso": duhl.LASSO, "svm": duhl.SVM, "enet": duhl.ELASTIC_NET}[prob["model"]]
         self.model = model
+        eta = float(prob.get("eta", 1.0))
         d, n = prob["d"], prob["n"]
         dev = torch.device("cuda", 0)
         self.target = prob["target"].to(dev).contiguous()
         self.g = duhl.Duhl(model, d, n, budget if budget is not None else n)
+        if model == duhl.ELASTIC_NET:
+            self.g.set_eta(eta)
         if "cols" in prob:
             ld_eff = ld if ld is not None else d
             if host_resident:
@@ -34,7 +37,7 @@ class Pair:
             self.g.set_data_dense(self.cols, self.target, prob["lam"],
                                   duhl.RESIDENT_HOST if host_resident else duhl.RESIDENT_DEVICE)
             self.o = orc.Oracle(model, to_np(prob["target"]), prob["lam"],
-                                cols=np.ascontiguousarray(to_np(prob["cols"])))
+                                cols=np.ascontiguousarray(to_np(prob["cols"])), eta=eta)
         else:
             self.rowptr = prob["rowptr"].to(dev)
             self.colidx = prob["colidx"].to(dev)
@@ -73,6 +76,19 @@ def lasso_gap_floor(pair):
     eps = 2.0 ** -24
     dot_err = 8 * eps * np.sqrt(o.d) * np.linalg.norm(o.v) * np.sqrt(o.q.max())
     return float((4 * eps * Lam * np.abs(o.alpha).max() + dot_err * (np.abs(o.alpha).max() + o.B)) / o.d)
+
+
+def enet_gap_floor(pair):
+    """Rounding floor of the fp32 elastic-net gap: the three terms cancel to ~0 at the optimum, each
+    carrying a few ulps of its own size, plus the fp32 dot error times |alpha_i| + |c_i|/(Lambda eta)."""
+    o = pair.o
+    Lam = o.lam * o.d
+    eps = 2.0 ** -24
+    amax = np.abs(o.alpha).max()
+    dot_err = 8 * eps * np.sqrt(o.d) * np.linalg.norm(o.v) * np.sqrt(o.q.max())
+    cmax = np.linalg.norm(o.v) * np.sqrt(o.q.max())
+    terms = amax * cmax + Lam * (o.eta * amax * amax + amax) + cmax * cmax / (Lam * o.eta)
+    return float((8 * eps * terms + dot_err * (amax + cmax / (Lam * o.eta))) / o.d)
 
 
 def dev_i32(a):

@@ -46,6 +46,7 @@ def test_bad_arguments_are_rejected_without_a_gpu():
     assert h.value is None
     assert lib.duhl_gap(None, None, 0, None) == duhl.EINVAL
     assert lib.duhl_objective(None, None) == duhl.EINVAL
+    assert lib.duhl_set_eta(None, 0.5) == duhl.EINVAL
     assert lib.duhl_working_set_size(None) == 0
     assert lib.duhl_last_error(None) == b"null context"
     lib.duhl_destroy(None)

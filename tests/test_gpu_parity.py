@@ -88,6 +88,45 @@ def test_svm_gaps_match_oracle_dense_and_csr(G):
         p.close()
 
 
+@pytest.mark.parametrize("eta", [1.0, 0.3])
+def test_elastic_net_gaps_steps_and_objective_match_oracle(G, eta):
+    """App. D elastic-net step and the gap of eq. (4) (ridge gap of App. E for eta = 1): gap vectors,
+    sequential iterates and the concurrent schemes' objective, on ragged shapes."""
+    from paper_1708_05357_amd import duhl
+    prob = lasso_problem(1503, 260, 0.1, 0.02, seed=41)
+    prob["model"], prob["eta"] = "enet", eta
+    p = G.Pair(prob)
+    m = 80
+    rng = np.random.default_rng(4)
+    assert p.g.gap() == pytest.approx(p.o.gaps(), rel=1e-4)
+    G.assert_gaps_close(p.g.get(duhl.Z), p.o.z, floor=G.enet_gap_floor(p))
+    for rnd in range(6):
+        p.g.gap(want_sum=False)
+        p.g.select(m, want_stats=False)
+        p.g.commit_swap()
+        order = rng.permutation(p.g.get(duhl.P)).astype(np.int32)
+        p.g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(order))
+        p.o.cd_pass(order)
+        a, v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+        assert np.abs(a - p.o.alpha).max() <= 1e-5 * np.abs(p.o.alpha).max()
+        assert np.abs(v - p.o.v).max() <= 1e-5 * np.abs(p.o.v).max()
+        p.sync_oracle_to_gpu_state()
+        total = p.g.gap()
+        floor = G.enet_gap_floor(p)
+        assert total == pytest.approx(p.o.gaps(), rel=1e-4, abs=prob["n"] * floor)
+        G.assert_gaps_close(p.g.get(duhl.Z), p.o.z, floor=floor)
+        assert p.g.objective() == pytest.approx(p.o.objective(), rel=1e-6)
+        p.o.set_state(a.astype(np.float64))            # back to the oracle's own v
+    for mode in (duhl.CD_ASYNC, duhl.CD_ATOMIC):
+        p.g.set(duhl.ALPHA, np.zeros(prob["n"], dtype=np.float32))
+        p.g.recompute_v()
+        p.o.set_state(np.zeros(prob["n"]))
+        converge_async(G, p, m, 150, 2, 1e-9, mode)
+        converge_oracle(p, m, 150, 2, 1e-11)
+        assert abs(p.g.objective() - p.o.objective()) <= 1e-5 * abs(p.o.objective())
+    p.close()
+
+
 # ------------------------------------------------------------------------------------ selection
 @pytest.mark.parametrize("n", [7, 500, 2048, 2049, 70001])
 def test_selection_is_bit_exact_on_the_same_z(G, n):
@@ -398,6 +437,16 @@ def test_error_paths(G):
     g.commit_swap()
     g.cd_epoch()
     g.close()
+    with pytest.raises(duhl.DuhlError) as e:
+        duhl.Duhl(duhl.LASSO, 8, 6, 3).set_eta(0.5)              # eta belongs to the elastic net
+    assert e.value.status == duhl.EINVAL
+    en = duhl.Duhl(duhl.ELASTIC_NET, 8, 6, 3)
+    for bad in (0.0, -0.1, 1.5, float("nan")):
+        with pytest.raises(duhl.DuhlError) as e:
+            en.set_eta(bad)
+        assert e.value.status == duhl.EINVAL
+    en.set_eta(0.25)
+    en.close()
     s = duhl.Duhl(duhl.SVM, 8, 6, 6)
     with pytest.raises(duhl.DuhlError) as e:
         s.set_data_dense(cols, torch.tensor([1, -1, 1, 0.5, 1, -1.0], device=dev), 0.1)
