@@ -124,6 +124,17 @@ duhl_status duhl_gap(duhl_ctx *ctx, const int32_t *idx, int64_t count, double *g
 duhl_status duhl_select(duhl_ctx *ctx, int64_t m, int32_t *P_out, int64_t *n_swapped,
                         double *rho);
 
+/* Selection rules.  DUHL_SELECT_GAP is eq. (13) and what duhl_select does.  The other two are the
+ * reference schemes the paper compares against: DUHL_SELECT_RANDOM draws a uniformly random
+ * subset of size m (Section 5.1; arg = seed), DUHL_SELECT_BLOCK takes the arg-th contiguous block
+ * of m coordinates, wrapping around at n (the sequential block scheme of Section 5.2). */
+typedef enum { DUHL_SELECT_GAP = 0, DUHL_SELECT_RANDOM = 1, DUHL_SELECT_BLOCK = 2 } duhl_select_rule;
+
+/* duhl_select with a choice of rule; everything else (pending set, copies, outputs, rho of eq. (7)
+ * evaluated on the gap memory z for the chosen set) as for duhl_select. */
+duhl_status duhl_select_rule_apply(duhl_ctx *ctx, duhl_select_rule rule, uint64_t arg, int64_t m,
+                                   int32_t *P_out, int64_t *n_swapped, double *rho);
+
 /* Make the pending working set current: the compute stream waits (on the device, not the
  * host) for the column copies, then later calls see the new set.  DUHL_ESTATE if nothing is
  * pending. */

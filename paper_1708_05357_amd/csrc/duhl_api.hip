@@ -304,10 +304,13 @@ duhl_status duhl_gap(duhl_ctx *c, const int32_t *idx, int64_t count, double *gap
     return DUHL_OK;
 }
 
-duhl_status duhl_select(duhl_ctx *c, int64_t m, int32_t *P_out, int64_t *n_swapped, double *rho)
+duhl_status duhl_select_rule_apply(duhl_ctx *c, duhl_select_rule rule, uint64_t arg, int64_t m,
+                                   int32_t *P_out, int64_t *n_swapped, double *rho)
 {
     if (!c) return DUHL_EINVAL;
     if (!c->have_data) return fail(c, DUHL_ESTATE, "no data set");
+    if (rule != DUHL_SELECT_GAP && rule != DUHL_SELECT_RANDOM && rule != DUHL_SELECT_BLOCK)
+        return fail(c, DUHL_EINVAL, "unknown selection rule");
     if (m < 1 || m > c->n) return fail(c, DUHL_EINVAL, "m must be in [1, n]");
     if (m > c->budget) return fail(c, DUHL_EBUDGET, "m (%lld) exceeds the column budget (%lld)",
                                    (long long)m, (long long)c->budget);
@@ -315,7 +318,13 @@ duhl_status duhl_select(duhl_ctx *c, int64_t m, int32_t *P_out, int64_t *n_swapp
     if (host && c->pending)
         return fail(c, DUHL_ESTATE, "the previous selection has not been committed");
     HIPCHK(c, hipSetDevice(c->device));
-    HIPCHK(c, launch_select(c, m, P_out));
+    const float *keys = c->z;
+    if (rule != DUHL_SELECT_GAP) {
+        if (!c->score) HIPCHK(c, dev_alloc(&c->score, c->n));
+        HIPCHK(c, launch_score(c, (int)rule, m, arg));
+        keys = c->score;
+    }
+    HIPCHK(c, launch_select(c, m, P_out, keys));
     c->m_next = m;
     c->pending = true;
     const bool overlap_safe = c->budget >= c->m_cur + m;
@@ -336,6 +345,11 @@ duhl_status duhl_select(duhl_ctx *c, int64_t m, int32_t *P_out, int64_t *n_swapp
         if (rho) *rho = c->h_scalars[S_RHO];
     }
     return DUHL_OK;
+}
+
+duhl_status duhl_select(duhl_ctx *c, int64_t m, int32_t *P_out, int64_t *n_swapped, double *rho)
+{
+    return duhl_select_rule_apply(c, DUHL_SELECT_GAP, 0, m, P_out, n_swapped, rho);
 }
 
 duhl_status duhl_commit_swap(duhl_ctx *c)
@@ -471,7 +485,7 @@ void duhl_destroy(duhl_ctx *c)
     (void)hipFree(c->P_cur); (void)hipFree(c->P_next);
     (void)hipFree(c->scalars); (void)hipFree(c->partials); (void)hipFree(c->sel);
     (void)hipFree(c->blk_gt); (void)hipFree(c->blk_eq); (void)hipFree(c->mark);
-    (void)hipFree(c->dv); (void)hipFree(c->dirty);
+    (void)hipFree(c->dv); (void)hipFree(c->dirty); (void)hipFree(c->score);
     if (c->h_scalars) (void)hipHostFree(c->h_scalars);
     if (c->h_u32) (void)hipHostFree(c->h_u32);
     delete c;

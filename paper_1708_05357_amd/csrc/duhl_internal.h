@@ -173,6 +173,8 @@ struct duhl_ctx {
     uint32_t *blk_gt, *blk_eq;  // per-chunk counts of the selection scatter
     int64_t blk_cap;
 
+    float *score;               // scores of the non-gap selection rules (allocated on first use)
+
     // private buffers of the asynchronous dense workers (allocated on first use)
     float *dv;
     int64_t dv_stride, dv_workers;
@@ -202,7 +204,8 @@ namespace duhl {
 // ---- launchers (each enqueues on the given stream and returns the launch status) ----------
 hipError_t launch_gap(duhl_ctx *c, const int32_t *idx, int64_t count, bool slot_list,
                       bool with_norms);
-hipError_t launch_select(duhl_ctx *c, int64_t m, int32_t *P_out);
+hipError_t launch_select(duhl_ctx *c, int64_t m, int32_t *P_out, const float *keys);
+hipError_t launch_score(duhl_ctx *c, int scheme, int64_t m, uint64_t arg);
 hipError_t launch_plan_swap(duhl_ctx *c, bool overlap_safe);
 hipError_t launch_copy_columns(duhl_ctx *c);
 hipError_t launch_publish(duhl_ctx *c);

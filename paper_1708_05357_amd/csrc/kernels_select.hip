@@ -58,9 +58,9 @@ __global__ void select_reset_kernel(SelectState *st, uint32_t m)
 // Histogram of the next digit over the entries whose higher digits equal st->prefix; the last
 // workgroup then finds the digit that holds the `remaining`-th largest entry.
 template <int PASS>
-__global__ __launch_bounds__(256) void select_hist_kernel(const float *z, int64_t n,
-                                                          SelectState *st, double *partials,
-                                                          double *scalars)
+__global__ __launch_bounds__(256) void select_hist_kernel(const float *z, const float *zval,
+                                                          int64_t n, SelectState *st,
+                                                          double *partials, double *scalars)
 {
     constexpr int kBits = PASS == 2 ? 10 : 11;
     constexpr int kShift = PASS == 0 ? 21 : (PASS == 1 ? 10 : 0);
@@ -76,7 +76,7 @@ __global__ __launch_bounds__(256) void select_hist_kernel(const float *z, int64_
         const float zi = z[i];
         const uint32_t key = zkey(zi);
         bool in_bucket = true;
-        if constexpr (PASS == 0) zsum += (double)zi;
+        if constexpr (PASS == 0) zsum += (double)zval[i];
         else in_bucket = (key >> (kShift + kBits)) == prefix;
         if (in_bucket) atomicAdd(&hist[(key >> kShift) & (kBins - 1)], 1u);
     }
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(256) void select_scatter_kernel(const float *z, int
                                                              const uint32_t *blk_gt,
                                                              const uint32_t *blk_eq, int32_t *P,
                                                              int32_t *P_out, double *partials,
-                                                             double *scalars)
+                                                             double *scalars, const float *zval)
 {
     __shared__ uint32_t wg[4], we[4];
     __shared__ double dsh[4];
@@ -220,7 +220,7 @@ __global__ __launch_bounds__(256) void select_scatter_kernel(const float *z, int
             const uint32_t pos = og + (oe < take_eq ? oe : take_eq);
             P[pos] = (int32_t)i;
             if (P_out) P_out[pos] = (int32_t)i;
-            ssel += (double)zi;
+            ssel += (double)zval[i];
         }
         gt_before += tg;
         eq_before += te;
@@ -244,6 +244,28 @@ __global__ __launch_bounds__(256) void select_scatter_kernel(const float *z, int
         // eq. (7): (mean of z over P) / (mean of z over all coordinates)
         scalars[S_RHO] = all > 0.0 ? (sel / (double)m) / (all / (double)n) : 1.0;
     }
+}
+
+// ---- other selection rules, as scores fed to the same top-m machinery ---------------------------
+// Uniformly random subset (the random reference scheme of Section 5.1): score = a hash of
+// (seed, i) mapped to [1,2); the m largest scores are a uniform sample.  Contiguous block (the
+// sequential reference scheme of Section 5.2): score 1 on {start + k mod n, k < m}, else 0.
+__global__ void score_random_kernel(float *score, int64_t n, uint64_t seed)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    uint64_t x = seed + 0x9E3779B97F4A7C15ull * (uint64_t)(i + 1);
+    x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
+    x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
+    x ^= x >> 31;
+    score[i] = __uint_as_float(0x3F800000u | (uint32_t)(x >> 41));      // 23 random mantissa bits
+}
+__global__ void score_block_kernel(float *score, int64_t n, int64_t start, int64_t m)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= n) return;
+    const int64_t rel = i >= start ? i - start : i + n - start;
+    score[i] = rel < m ? 1.0f : 0.0f;
 }
 
 // ---- swap planning (host residency) ------------------------------------------------------------
@@ -338,24 +360,36 @@ __global__ __launch_bounds__(256) void copy_columns_kernel(const float *src, int
 
 }  // namespace
 
-hipError_t launch_select(duhl_ctx *c, int64_t m, int32_t *P_out)
+hipError_t launch_score(duhl_ctx *c, int scheme, int64_t m, uint64_t arg)
+{
+    const int T = 256;
+    const int64_t n = c->n;
+    if (scheme == DUHL_SELECT_RANDOM)
+        hipLaunchKernelGGL(score_random_kernel, dim3((n + T - 1) / T), dim3(T), 0, c->compute, c->score, n, arg);
+    else
+        hipLaunchKernelGGL(score_block_kernel, dim3((n + T - 1) / T), dim3(T), 0, c->compute, c->score, n,
+                           (int64_t)((arg % (uint64_t)((n + m - 1) / m)) * (uint64_t)m % (uint64_t)n), m);
+    return hipGetLastError();
+}
+
+hipError_t launch_select(duhl_ctx *c, int64_t m, int32_t *P_out, const float *keys)
 {
     hipStream_t s = c->compute;
     const int64_t n = c->n;
     hipLaunchKernelGGL(select_reset_kernel, dim3(1), dim3(1024), 0, s, c->sel, (uint32_t)m);
     int64_t hgrid = (n + 2047) / 2048;
     if (hgrid > 1024) hgrid = 1024;
-    hipLaunchKernelGGL(select_hist_kernel<0>, dim3(hgrid), dim3(256), 0, s, c->z, n, c->sel,
+    hipLaunchKernelGGL(select_hist_kernel<0>, dim3(hgrid), dim3(256), 0, s, keys, c->z, n, c->sel,
                        c->partials, c->scalars);
-    hipLaunchKernelGGL(select_hist_kernel<1>, dim3(hgrid), dim3(256), 0, s, c->z, n, c->sel,
+    hipLaunchKernelGGL(select_hist_kernel<1>, dim3(hgrid), dim3(256), 0, s, keys, c->z, n, c->sel,
                        c->partials, c->scalars);
-    hipLaunchKernelGGL(select_hist_kernel<2>, dim3(hgrid), dim3(256), 0, s, c->z, n, c->sel,
+    hipLaunchKernelGGL(select_hist_kernel<2>, dim3(hgrid), dim3(256), 0, s, keys, c->z, n, c->sel,
                        c->partials, c->scalars);
     const int64_t nb = (n + kChunk - 1) / kChunk;
-    hipLaunchKernelGGL(select_count_kernel, dim3(nb), dim3(256), 0, s, c->z, n, c->sel, c->blk_gt,
+    hipLaunchKernelGGL(select_count_kernel, dim3(nb), dim3(256), 0, s, keys, n, c->sel, c->blk_gt,
                        c->blk_eq);
-    hipLaunchKernelGGL(select_scatter_kernel, dim3(nb), dim3(256), 0, s, c->z, n, m, c->sel,
-                       c->blk_gt, c->blk_eq, c->P_next, P_out, c->partials, c->scalars);
+    hipLaunchKernelGGL(select_scatter_kernel, dim3(nb), dim3(256), 0, s, keys, n, m, c->sel,
+                       c->blk_gt, c->blk_eq, c->P_next, P_out, c->partials, c->scalars, c->z);
     return hipGetLastError();
 }
 

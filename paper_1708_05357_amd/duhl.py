@@ -18,9 +18,11 @@ LASSO, SVM, ELASTIC_NET = 0, 1, 2
 RESIDENT_DEVICE, RESIDENT_HOST = 0, 1
 ALPHA, V, Z, P, SQNORM = 0, 1, 2, 3, 4
 CD_SEQUENTIAL, CD_ASYNC, CD_ATOMIC = 0, 1, 2
+SELECT_GAP, SELECT_RANDOM, SELECT_BLOCK = 0, 1, 2
 OK, EINVAL, ENOMEM, EHIP, ESTATE, EBUDGET = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_data_dense", "duhl_set_data_csr", "duhl_gap", "duhl_select",
+           "duhl_select_rule_apply",
            "duhl_commit_swap", "duhl_cd_epoch", "duhl_objective", "duhl_recompute_v", "duhl_get",
            "duhl_set", "duhl_device_ptr", "duhl_working_set_size", "duhl_last_error",
            "duhl_destroy"]
@@ -49,6 +51,7 @@ def load():
     lib.duhl_set_data_csr.argtypes = [p, p, p, p, i32, p, dbl]
     lib.duhl_gap.argtypes = [p, p, i64, C.POINTER(dbl)]
     lib.duhl_select.argtypes = [p, i64, p, C.POINTER(i64), C.POINTER(dbl)]
+    lib.duhl_select_rule_apply.argtypes = [p, i32, C.c_uint64, i64, p, C.POINTER(i64), C.POINTER(dbl)]
     lib.duhl_commit_swap.argtypes = [p]
     lib.duhl_cd_epoch.argtypes = [p, i32, p, i64, C.c_uint64, i32]
     lib.duhl_objective.argtypes = [p, C.POINTER(dbl)]
@@ -62,7 +65,7 @@ def load():
     lib.duhl_last_error.restype = C.c_char_p
     lib.duhl_destroy.argtypes = [p]
     lib.duhl_destroy.restype = None
-    for name in EXPORTS[:13]:
+    for name in EXPORTS[:14]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -138,11 +141,12 @@ class Duhl:
                                     C.byref(out) if want_sum else None))
         return out.value if want_sum else None
 
-    def select(self, m, P_out=None, want_stats=True):
+    def select(self, m, P_out=None, want_stats=True, rule=SELECT_GAP, arg=0):
         nsw, rho = C.c_int64(0), C.c_double(0.0)
-        self._chk(self.lib.duhl_select(self._h, int(m), _dptr(P_out, torch.int32),
-                                       C.byref(nsw) if want_stats else None,
-                                       C.byref(rho) if want_stats else None))
+        self._chk(self.lib.duhl_select_rule_apply(self._h, rule, C.c_uint64(arg), int(m),
+                                                  _dptr(P_out, torch.int32),
+                                                  C.byref(nsw) if want_stats else None,
+                                                  C.byref(rho) if want_stats else None))
         return (nsw.value, rho.value) if want_stats else None
 
     def commit_swap(self):

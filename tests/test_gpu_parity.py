@@ -504,3 +504,52 @@ def test_zero_columns_and_empty_rows(G):
     o.cd_pass(np.arange(64, dtype=np.int32))
     np.testing.assert_allclose(p.g.get(duhl.ALPHA), o.alpha, rtol=1e-5, atol=1e-6)
     p.close()
+
+
+# ------------------------------------------------------------------------------------ reference selection rules
+def test_block_and_random_selection_rules(G):
+    """The sequential-block and random reference schemes (Sections 5.1, 5.2): exact block contents
+    with wrap-around, random subsets that are valid, seed-dependent and roughly uniform, rho of
+    eq. (7) evaluated on z for the chosen set; and the paper's qualitative claim that gap selection
+    converges faster than random selection."""
+    from oracle import duhl_oracle as orc
+    from paper_1708_05357_amd import duhl
+    n, m = 5003, 700
+    p = G.Pair(lasso_problem(64, n, 0.05, 0.1, seed=51))
+    z = p.g.get(duhl.Z)
+    out = torch.empty(m, dtype=torch.int32, device="cuda:0")
+    nblocks = -(-n // m)
+    for arg in (0, 1, nblocks - 1, nblocks, 3 * nblocks + 2):
+        nsw, rho = p.g.select(m, out, rule=duhl.SELECT_BLOCK, arg=arg)
+        start = (arg % nblocks) * m % n
+        want = np.sort((start + np.arange(m)) % n).astype(np.int32)
+        np.testing.assert_array_equal(out.cpu().numpy(), want)
+        assert rho == pytest.approx(orc.rho(z.astype(np.float64), want), rel=1e-10)
+    counts = np.zeros(n)
+    seen = []
+    for seed in range(60):
+        nsw, rho = p.g.select(m, out, rule=duhl.SELECT_RANDOM, arg=seed)
+        P = out.cpu().numpy()
+        assert P.size == m and np.all(np.diff(P) > 0) and P[0] >= 0 and P[-1] < n
+        assert rho == pytest.approx(orc.rho(z.astype(np.float64), P), rel=1e-10)
+        counts[P] += 1
+        seen.append(P.copy())
+    assert not np.array_equal(seen[0], seen[1])
+    expect = 60 * m / n
+    assert abs(counts.mean() - expect) < 1e-9 and counts.std() < 2.0 * np.sqrt(expect)
+    assert np.abs(counts.reshape(-1)[: n // 2].mean() - counts[n // 2:].mean()) < 0.5   # no positional bias
+    p.close()
+
+    prob = lasso_problem(1000, 500, 0.1, 0.1, seed=0)
+    finals = {}
+    for rule in (duhl.SELECT_GAP, duhl.SELECT_RANDOM, duhl.SELECT_BLOCK):
+        q = G.Pair(prob)
+        for rnd in range(12):
+            q.g.gap(want_sum=False)
+            q.g.select(125, want_stats=False, rule=rule, arg=rnd)
+            q.g.commit_swap()
+            q.g.cd_epoch(duhl.CD_ASYNC, seed=rnd)
+        finals[rule] = q.g.gap()
+        q.close()
+    assert finals[duhl.SELECT_GAP] < 0.1 * finals[duhl.SELECT_RANDOM]
+    assert finals[duhl.SELECT_GAP] < 0.1 * finals[duhl.SELECT_BLOCK]
