@@ -135,6 +135,18 @@ typedef enum { DUHL_SELECT_GAP = 0, DUHL_SELECT_RANDOM = 1, DUHL_SELECT_BLOCK = 
 duhl_status duhl_select_rule_apply(duhl_ctx *ctx, duhl_select_rule rule, uint64_t arg, int64_t m,
                                    int32_t *P_out, int64_t *n_swapped, double *rho);
 
+/* Unit A's task in Algorithm 2 (lines 7-10: "while B not finished: sample j, z_j := gap_j(alpha_j^(t))"),
+ * for a dense matrix with DUHL_RESIDENT_HOST.  duhl_host_sample_begin snapshots alpha and v at the
+ * current point of the compute stream and starts nthreads host threads (1..256) that evaluate the
+ * coordinate gaps of idx_host[0..count) (host, int32, each in [0,n)) from the matrix in host memory,
+ * in list order, while the caller goes on enqueueing GPU work; the host link is not used.
+ * duhl_host_sample_end stops them (wait_all == 0: after the column each is working on; != 0: after
+ * the whole list), writes the refreshed entries into the gap memory z on the compute stream and
+ * waits for that; n_done (host, may be NULL) = entries refreshed.  One round at a time per context;
+ * the list must not repeat a coordinate. */
+duhl_status duhl_host_sample_begin(duhl_ctx *ctx, const int32_t *idx_host, int64_t count, int nthreads);
+duhl_status duhl_host_sample_end(duhl_ctx *ctx, int wait_all, int64_t *n_done);
+
 /* Make the pending working set current: the compute stream waits (on the device, not the
  * host) for the column copies, then later calls see the new set.  DUHL_ESTATE if nothing is
  * pending. */

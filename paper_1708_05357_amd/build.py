@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libduhl.so")
-SOURCES = ["duhl_api.hip", "kernels_gap.hip", "kernels_select.hip", "kernels_cd.hip", "kernels_misc.hip"]
+SOURCES = ["duhl_api.hip", "kernels_gap.hip", "kernels_select.hip", "kernels_cd.hip", "kernels_misc.hip",
+           "host_sampler.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
@@ -23,10 +24,10 @@ def _compile(src, force):
     return obj
 
 
-def build(force=True, jobs=5):
+def build(force=True, jobs=6):
     with ThreadPoolExecutor(max_workers=jobs) as ex:
         objs = list(ex.map(lambda s: _compile(s, force), SOURCES))
-    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs])
+    subprocess.check_call(["hipcc", "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs, "-lpthread"])
     return LIB
 
 

@@ -48,6 +48,8 @@ hipError_t dev_alloc(T **p, int64_t count)
 
 void free_host_residency(duhl_ctx *c)
 {
+    host_sampler_destroy(c);
+    c->host_base = nullptr;
     (void)hipFree(c->slots); c->slots = nullptr;
     (void)hipFree(c->col_slot); c->col_slot = nullptr;
     (void)hipFree(c->slot_col); c->slot_col = nullptr;
@@ -243,6 +245,7 @@ duhl_status duhl_set_data_dense(duhl_ctx *c, const float *A, int64_t ld, duhl_re
             return fail(c, DUHL_EINVAL, "host-resident A must be pinned, device-mapped host memory");
         }
         c->cv.base = static_cast<const float *>(dptr);
+        c->host_base = A;
         c->ld_s = (c->d + 63) / 64 * 64;
         HIPCHK(c, dev_alloc(&c->slots, c->budget * c->ld_s));
         HIPCHK(c, dev_alloc(&c->col_slot, c->n));

@@ -6,6 +6,8 @@
 
 #include "duhl.h"
 
+struct duhl_host_sampler;   // host-thread gap sampler (host_sampler.hip)
+
 namespace duhl {
 
 constexpr int kWave = 64;
@@ -181,6 +183,8 @@ struct duhl_ctx {
     int32_t *dirty;
 
     // host residency
+    const float *host_base;     // the caller's host address of the matrix
+    duhl_host_sampler *sampler; // unit A's gap sampler, created on first use
     float *slots;
     int64_t ld_s;
     int32_t *col_slot, *slot_col;
@@ -219,5 +223,6 @@ hipError_t launch_validate(duhl_ctx *c);
 hipError_t launch_fill_i32(hipStream_t s, int32_t *p, int64_t n, int32_t value);
 hipError_t launch_fill_f32(hipStream_t s, float *p, int64_t n, float value);
 hipError_t launch_sum_partials(duhl_ctx *c, int64_t count, int scalar_slot);
+void host_sampler_destroy(duhl_ctx *c);
 
 }  // namespace duhl

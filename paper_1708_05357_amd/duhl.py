@@ -22,7 +22,7 @@ SELECT_GAP, SELECT_RANDOM, SELECT_BLOCK = 0, 1, 2
 OK, EINVAL, ENOMEM, EHIP, ESTATE, EBUDGET = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_data_dense", "duhl_set_data_csr", "duhl_gap", "duhl_select",
-           "duhl_select_rule_apply",
+           "duhl_select_rule_apply", "duhl_host_sample_begin", "duhl_host_sample_end",
            "duhl_commit_swap", "duhl_cd_epoch", "duhl_objective", "duhl_recompute_v", "duhl_get",
            "duhl_set", "duhl_device_ptr", "duhl_working_set_size", "duhl_last_error",
            "duhl_destroy"]
@@ -52,6 +52,8 @@ def load():
     lib.duhl_gap.argtypes = [p, p, i64, C.POINTER(dbl)]
     lib.duhl_select.argtypes = [p, i64, p, C.POINTER(i64), C.POINTER(dbl)]
     lib.duhl_select_rule_apply.argtypes = [p, i32, C.c_uint64, i64, p, C.POINTER(i64), C.POINTER(dbl)]
+    lib.duhl_host_sample_begin.argtypes = [p, p, i64, i32]
+    lib.duhl_host_sample_end.argtypes = [p, i32, C.POINTER(i64)]
     lib.duhl_commit_swap.argtypes = [p]
     lib.duhl_cd_epoch.argtypes = [p, i32, p, i64, C.c_uint64, i32]
     lib.duhl_objective.argtypes = [p, C.POINTER(dbl)]
@@ -65,7 +67,7 @@ def load():
     lib.duhl_last_error.restype = C.c_char_p
     lib.duhl_destroy.argtypes = [p]
     lib.duhl_destroy.restype = None
-    for name in EXPORTS[:14]:
+    for name in EXPORTS[:16]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -148,6 +150,17 @@ class Duhl:
                                                   C.byref(nsw) if want_stats else None,
                                                   C.byref(rho) if want_stats else None))
         return (nsw.value, rho.value) if want_stats else None
+
+    def host_sample_begin(self, idx, nthreads=8):
+        """idx: int32 numpy array (host) of coordinates whose gaps the host threads refresh."""
+        idx = np.ascontiguousarray(idx, dtype=np.int32)
+        self._chk(self.lib.duhl_host_sample_begin(self._h, idx.ctypes.data_as(C.c_void_p), idx.size,
+                                                  int(nthreads)))
+
+    def host_sample_end(self, wait_all=True):
+        done = C.c_int64(0)
+        self._chk(self.lib.duhl_host_sample_end(self._h, 1 if wait_all else 0, C.byref(done)))
+        return done.value
 
     def commit_swap(self):
         self._chk(self.lib.duhl_commit_swap(self._h))

@@ -553,3 +553,60 @@ def test_block_and_random_selection_rules(G):
         q.close()
     assert finals[duhl.SELECT_GAP] < 0.1 * finals[duhl.SELECT_RANDOM]
     assert finals[duhl.SELECT_GAP] < 0.1 * finals[duhl.SELECT_BLOCK]
+
+
+# ------------------------------------------------------------------------------------ unit A's gap sampler
+def test_host_gap_sampler_matches_oracle(G):
+    """Alg. 2, lines 7-10: host threads refresh z_j := gap_j(alpha^(t)) from the host matrix while
+    the GPU runs the pass on the current block.  The refreshed entries must equal the oracle's gaps
+    at the snapshot alpha^(t) (not at the state after the pass); other entries stay untouched."""
+    from paper_1708_05357_amd import duhl
+    prob = lasso_problem(2051, 600, 0.1, 0.1, seed=61)
+    m = 90
+    p = G.Pair(prob, budget=2 * m, host_resident=True)
+    rng = np.random.default_rng(7)
+    p.g.select(m)
+    p.g.commit_swap()
+    for rnd in range(4):
+        p.g.cd_epoch(duhl.CD_ASYNC, seed=rnd)                 # some state alpha^(t)
+        p.sync_oracle_to_gpu_state()
+        p.o.gaps()
+        snapshot = p.o.z.copy()
+        floor = G.lasso_gap_floor(p)
+        marker = np.full(prob["n"], -3.0, dtype=np.float32)
+        p.g.set(duhl.Z, marker)
+        idx = rng.permutation(prob["n"])[:250].astype(np.int32)
+        p.g.host_sample_begin(idx, nthreads=4)
+        with pytest.raises(duhl.DuhlError) as e:
+            p.g.host_sample_begin(idx, nthreads=4)            # one round at a time
+        assert e.value.status == duhl.ESTATE
+        p.g.cd_epoch(duhl.CD_ASYNC, seed=100 + rnd)           # B works meanwhile and moves alpha, v
+        done = p.g.host_sample_end(wait_all=True)
+        assert done == idx.size
+        z = p.g.get(duhl.Z)
+        mask = np.zeros(prob["n"], dtype=bool)
+        mask[idx] = True
+        assert np.all(z[~mask] == -3.0)
+        np.testing.assert_allclose(z[mask], snapshot[mask], rtol=1e-4, atol=1e-4 * snapshot.max() + floor)
+    # stopping early refreshes a prefix-like subset only, and only with valid values
+    p.sync_oracle_to_gpu_state()
+    p.o.gaps()
+    p.g.set(duhl.Z, np.full(prob["n"], -3.0, dtype=np.float32))
+    idx = rng.permutation(prob["n"]).astype(np.int32)
+    p.g.host_sample_begin(idx, nthreads=2)
+    done = p.g.host_sample_end(wait_all=False)
+    z = p.g.get(duhl.Z)
+    touched = z != -3.0
+    assert 0 <= done <= idx.size and touched.sum() == done
+    if done:
+        np.testing.assert_allclose(z[touched], p.o.z[touched], rtol=1e-4,
+                                   atol=1e-4 * p.o.z.max() + G.lasso_gap_floor(p))
+    with pytest.raises(duhl.DuhlError) as e:
+        p.g.host_sample_end()
+    assert e.value.status == duhl.ESTATE
+    p.close()
+    q = G.Pair(lasso_problem(64, 40, 0.1, 0.1, seed=1))           # device residency: not applicable
+    with pytest.raises(duhl.DuhlError) as e:
+        q.g.host_sample_begin(np.arange(5, dtype=np.int32))
+    assert e.value.status == duhl.EINVAL
+    q.close()
