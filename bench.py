@@ -13,6 +13,8 @@ largest single-GPU configuration and the one the bandwidth targets are quoted on
 """
 import argparse
 import json
+
+import numpy as np
 import os
 import sys
 import time
@@ -76,14 +78,15 @@ def algorithmic_bytes(prob, m):
 
 
 def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swap_log=None,
-             rule=0, passes=1):
+             rule=0, passes=1, host_threads=0, sample_host=None):
     """gap -> select -> commit -> epoch.  With host residency the gaps are refreshed for the
     resident columns plus a sample of the others (stale gap memory, Section 4.1), and the copies
     of the next working set run on the side stream while the pass works on the current one."""
     if ev:
         ev[0].record()
     g.gap(want_sum=False)
-    if prob["host_resident"] and sample_idx is not None:
+    on_host = prob["host_resident"] and host_threads > 0 and sample_host is not None
+    if prob["host_resident"] and sample_idx is not None and not on_host:
         g.gap(sample_idx[step % len(sample_idx)], want_sum=False)
     if ev:
         ev[1].record()
@@ -95,10 +98,22 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
         ev[2].record()
         if len(ev) > 4:
             ev[4].record(g.copy_stream)             # completes when the column copies are done
+    if on_host:                                 # unit A samples gaps while unit B runs the pass
+        # the list continues where the previous round was stopped, so that every column is
+        # refreshed once per sweep of the permutation however long the rounds are
+        perm, cur, k = sample_host["perm"], sample_host["cursor"], sample_host["k"]
+        g.host_sample_begin(perm[cur:cur + k], host_threads)
     for k in range(passes):                     # passes per round: the accuracy knob theta (Section 5.2)
         g.cd_epoch(mode, seed=step * passes + k, max_inflight=inflight)
     if ev:
         ev[3].record()
+    if on_host:
+        g.compute_stream.synchronize()          # "while B not finished": the pass and the copies
+        g.copy_stream.synchronize()
+        done = g.host_sample_end(wait_all=False)
+        sample_host["cursor"] = (cur + max(done - 2 * host_threads, 0)) % sample_host["n"]
+        if swap_log is not None:
+            swap_log.append({"host_sampled": done})
     if overlapped:
         g.commit_swap()
     if swap_log is not None:
@@ -106,7 +121,7 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
 
 
 def time_to_gap(g, set_data, prob, m, target, max_rounds, mode=1, inflight=0, sample_idx=None,
-                rule=0, passes=1):
+                rule=0, passes=1, host_threads=0, sample_host=None):
     """Time of the rounds, from alpha = 0, until the total duality gap of a fresh full pass is
     <= target (absolute, with the paper's 1/d or 1/n normalisation) and <= target * gap(alpha=0).
     Device residency: the round's own full gap pass is the check.  Host residency: the rounds
@@ -132,7 +147,7 @@ def time_to_gap(g, set_data, prob, m, target, max_rounds, mode=1, inflight=0, sa
         if host:
             if rnd > 0:
                 one_step(g, prob, m, rnd, sample_idx=sample_idx, mode=mode, inflight=inflight, rule=rule,
-                         passes=passes)
+                         passes=passes, host_threads=host_threads, sample_host=sample_host)
             torch.cuda.synchronize()
             clock += time.time() - t0
             if rnd % check_every != 0:
@@ -162,7 +177,8 @@ def time_to_gap(g, set_data, prob, m, target, max_rounds, mode=1, inflight=0, sa
             clock += time.time() - t0
         elif rnd == 0:
             t0 = time.time()
-            one_step(g, prob, m, 0, sample_idx=sample_idx, mode=mode, inflight=inflight, rule=rule, passes=passes)
+            one_step(g, prob, m, 0, sample_idx=sample_idx, mode=mode, inflight=inflight, rule=rule, passes=passes,
+                     host_threads=host_threads, sample_host=sample_host)
             torch.cuda.synchronize()
             clock += time.time() - t0
         rounds = rnd + 1
@@ -244,6 +260,9 @@ def main():
     ap.add_argument("--select-rule", default="gap", choices=["gap", "random", "block"],
                     help="working-set rule: eq. (13), or one of the paper's reference schemes")
     ap.add_argument("--passes", type=int, default=1, help="CD passes per round (theta of Section 5.2)")
+    ap.add_argument("--host-sampler-threads", type=int, default=0,
+                    help="host residency: refresh the gap sample with this many host threads while the "
+                         "GPU runs the pass (Algorithm 2, lines 7-10) instead of over the host link")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the single-GPU hot path; this build has no multi-GPU path "
@@ -264,7 +283,7 @@ def main():
     g, set_data = make_ctx(prob, budget)
     mode = duhl.CD_ASYNC if args.cd_mode == "async" else duhl.CD_ATOMIC
     rule = {"gap": duhl.SELECT_GAP, "random": duhl.SELECT_RANDOM, "block": duhl.SELECT_BLOCK}[args.select_rule]
-    sample_idx = None
+    sample_idx = sample_host = None
     if prob["host_resident"]:
         # 5 % of the columns per round, refreshed from host memory (Section 5.1): a window that
         # slides over one random permutation, so every column is refreshed once in 20 rounds
@@ -274,10 +293,12 @@ def main():
         perm = torch.randperm(prob["n"], generator=gen, device="cuda").to(torch.int32)
         perm = torch.cat([perm, perm[:k]]).contiguous()
         sample_idx = [perm[(r * k) % prob["n"]:(r * k) % prob["n"] + k] for r in range(20)]
+        hp = perm[:prob["n"]].cpu().numpy()
+        sample_host = {"perm": np.concatenate([hp, hp[:k]]), "cursor": 0, "k": k, "n": prob["n"]}
     log(f"warm-up: {args.warmup} rounds")
     for s in range(args.warmup):
         one_step(g, prob, m, s, sample_idx=sample_idx, mode=mode, inflight=args.inflight, rule=rule,
-                 passes=args.passes)
+                 passes=args.passes, host_threads=args.host_sampler_threads, sample_host=sample_host)
     torch.cuda.synchronize()
     set_data()                                  # back to alpha = 0: the timed rounds are rounds 1..K
     torch.cuda.synchronize()
@@ -288,7 +309,8 @@ def main():
     torch.cuda.synchronize()
     t0 = time.time()
     for s in range(args.steps):
-        one_step(g, prob, m, s, evs[s], sample_idx, mode, args.inflight, swap_log, rule, args.passes)
+        one_step(g, prob, m, s, evs[s], sample_idx, mode, args.inflight, swap_log, rule, args.passes,
+                 args.host_sampler_threads, sample_host)
     torch.cuda.synchronize()
     elapsed = time.time() - t0
     log(f"timed {args.steps} rounds in {elapsed:.3f}s")
@@ -342,6 +364,8 @@ def main():
         # column swap (Algorithm 2, "refresh memory B"): copies start after the selection and run
         # on the side stream; how much of them the concurrent pass hides
         rows = []
+        sampled = [x["host_sampled"] for x in swap_log if "host_sampled" in x]
+        swap_log = [x for x in swap_log if "columns" in x]
         for e, sw in zip(evs, swap_log):
             copy_ms = e[2].elapsed_time(e[4])
             cd = e[2].elapsed_time(e[3])
@@ -354,10 +378,12 @@ def main():
                        "copy_ms_per_round": [round(r["copy_ms"], 3) for r in rows],
                        "host_link_GBps": (moved * 4.0 * prob["d"] / (busy * 1e-3) / 1e9) if busy > 0 else None,
                        "hidden_frac_per_round": [round(r["hidden_frac"], 3) for r in rows],
-                       "rho_per_round": [round(r["rho"], 2) for r in rows]}
+                       "rho_per_round": [round(r["rho"], 2) for r in rows],
+                       "host_sampled_per_round": sampled}
     if not args.no_ttg:
         log("time to gap 1e-3")
-        out["time_to_gap"] = time_to_gap(g, set_data, prob, m, 1e-3, 400, mode, args.inflight, sample_idx, rule, args.passes)
+        out["time_to_gap"] = time_to_gap(g, set_data, prob, m, 1e-3, 400, mode, args.inflight, sample_idx, rule, args.passes,
+                                         args.host_sampler_threads, sample_host)
     if not args.no_cpu:
         log("CPU baseline (oracle, one thread, about 20 s)")
         out["cpu_baseline"] = cpu_baseline(prob, m)
