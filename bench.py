@@ -123,7 +123,8 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
 def time_to_gap(g, set_data, prob, m, target, max_rounds, mode=1, inflight=0, sample_idx=None,
                 rule=0, passes=1, host_threads=0, sample_host=None):
     """Time of the rounds, from alpha = 0, until the total duality gap of a fresh full pass is
-    <= target (absolute, with the paper's 1/d or 1/n normalisation) and <= target * gap(alpha=0).
+    <= target (absolute, with the paper's 1/d or 1/n normalisation) and <= target * O(alpha=0)
+    (target * gap(alpha=0) for the SVM dual, whose objective is 0 at alpha = 0).
     Device residency: the round's own full gap pass is the check.  Host residency: the rounds
     use stale gaps (residents + sample); the check is an extra full pass over host memory that
     is not part of the scheme, so it is left out of the clock and z is restored after it."""
@@ -164,7 +165,7 @@ def time_to_gap(g, set_data, prob, m, target, max_rounds, mode=1, inflight=0, sa
             gap0 = gap
         if t_abs is None and gap <= target:
             t_abs = clock
-        if t_rel is None and gap <= target * gap0:
+        if t_rel is None and gap <= target * (abs(o0) if o0 != 0.0 else gap0):
             t_rel = clock
         if t_abs is not None and t_rel is not None:
             break
