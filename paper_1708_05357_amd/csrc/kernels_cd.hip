@@ -521,23 +521,44 @@ int threads_per_coordinate(const duhl_ctx *c)
 }
 
 // Coordinates that may be solved without seeing each other.  The caller's bound if given.
-// Otherwise from the data: concurrent exact steps on unit-norm columns stay stable up to about
-// count / sigma of them, sigma = ||A_P||^2 being the largest eigenvalue of the block's Gram
-// matrix.  sigma is estimated as (1 + sqrt(count/d))^2, the value for uncorrelated columns, plus
-// (count - 1) * mean_corr, the rank-one part that a common direction of the columns adds
-// (mean_corr is measured on a column sample when the data are set).  Twice that ratio, and never
-// more than a quarter of the pass, worked on every workload here; non-negative sparse rows, whose
-// mean correlation is ~1e-3, diverge with four times as many concurrent steps.
+// Otherwise from the data: exact steps taken concurrently on L unit-norm columns behave like a
+// block-Jacobi step, governed by sigma(L), the largest eigenvalue of the block's Gram matrix.
+// sigma(L) is estimated as (1 + sqrt(L/d))^2, the value for uncorrelated columns, plus
+// (L - 1) * mean_corr, the rank-one part that a common direction of the columns adds (mean_corr
+// is measured on a column sample when the data are set).  While sigma(L) <= 2 the concurrent
+// step contracts, so a whole pass may be one group (wide rows, few selected columns).  Past
+// that point 2 * count / sigma(count), and never more than a quarter of the pass, worked on
+// every workload here (each worker still sees its own earlier steps); non-negative sparse rows,
+// whose mean correlation is ~1e-3, diverge with four times as many concurrent steps.
 int64_t inflight_limit(const duhl_ctx *c, int64_t count, int max_inflight)
 {
     int64_t lim;
     if (max_inflight > 0) {
         lim = max_inflight;
     } else {
-        const double r = 1.0 + std::sqrt((double)count / (double)c->d);
-        const double sigma = r * r + (double)(count - 1) * c->mean_corr;
-        lim = (int64_t)(2.0 * (double)count / sigma);
-        if (lim > count / 4) lim = count / 4;
+        // Two estimates, the larger wins.  (i) The largest group L whose block-Jacobi step is
+        // still a contraction: sigma(L) = (1 + sqrt(L/d))^2 + (L - 1) * mean cosine <= 2 (the
+        // first term is the spectral norm of an L-column Gram block of near-orthogonal unit
+        // columns, the second the shift a common direction adds).  (ii) The looser empirical
+        // rule 2 * count / sigma(count), never more than a quarter of the pass.
+        auto sigma = [&](double L) {
+            const double r = 1.0 + std::sqrt(L / (double)c->d);
+            return r * r + (L - 1.0) * c->mean_corr;
+        };
+        int64_t lo = 1, hi = count;                      // sigma is increasing in L
+        if (sigma((double)count) <= 2.0) lo = count;
+        while (hi - lo > 1) {
+            const int64_t mid = lo + (hi - lo) / 2;
+            if (sigma((double)mid) <= 2.0) lo = mid; else hi = mid;
+        }
+        int64_t loose = (int64_t)(2.0 * (double)count / sigma((double)count));
+        if (loose > count / 4) loose = count / 4;
+        lim = lo > loose ? lo : loose;
+        // equal sub-passes rather than a short last one
+        if (lim >= 1 && lim < count) {
+            const int64_t S = (count + lim - 1) / lim;
+            lim = (count + S - 1) / S;
+        }
     }
     if (lim < 1) lim = 1;
     return lim < count ? lim : count;
