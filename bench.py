@@ -84,9 +84,16 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
     of the next working set run on the side stream while the pass works on the current one."""
     if ev:
         ev[0].record()
-    g.gap(want_sum=False)
     on_host = prob["host_resident"] and host_threads > 0 and sample_host is not None
-    if prob["host_resident"] and sample_idx is not None and not on_host:
+    if not prob["host_resident"] and sample_idx is not None:
+        # device-resident matrix with a gap memory kept stale on purpose (--gap-sample): only the
+        # working set just updated and this round's sample are refreshed
+        if g.working_set_size() > 0:
+            from paper_1708_05357_amd import duhl
+            g.gap(g.device_view(duhl.P), want_sum=False)
+    else:
+        g.gap(want_sum=False)
+    if sample_idx is not None and not on_host:
         g.gap(sample_idx[step % len(sample_idx)], want_sum=False)
     if ev:
         ev[1].record()
@@ -125,23 +132,24 @@ def time_to_gap(g, set_data, prob, m, target, max_rounds, mode=1, inflight=0, sa
     """Time of the rounds, from alpha = 0, until the total duality gap of a fresh full pass is
     <= target (absolute, with the paper's 1/d or 1/n normalisation) and <= target * O(alpha=0)
     (target * gap(alpha=0) for the SVM dual, whose objective is 0 at alpha = 0).
-    Device residency: the round's own full gap pass is the check.  Host residency: the rounds
-    use stale gaps (residents + sample); the check is an extra full pass over host memory that
-    is not part of the scheme, so it is left out of the clock and z is restored after it."""
+    Device residency: the round's own full gap pass is the check.  Host residency, or a gap
+    memory kept stale on purpose: the rounds use stale gaps (working set + sample); the check
+    is an extra full pass that is not part of the scheme, so it is left out of the clock and z
+    is restored after it."""
     import torch
     from paper_1708_05357_amd import duhl
     set_data()
     o0 = g.objective()
-    host = prob["host_resident"]
-    all_idx = torch.arange(prob["n"], dtype=torch.int32, device="cuda") if host else None
+    host = prob["host_resident"] or sample_idx is not None     # rounds run on a stale gap memory
+    all_idx = torch.arange(prob["n"], dtype=torch.int32, device="cuda") if prob["host_resident"] else None
     torch.cuda.synchronize()
     t_abs = t_rel = None
     clock = 0.0
     rounds = 0
     gap0 = None
     gap = float("inf")
-    check_every = 4 if host else 1              # host: each check is a pass over host memory
-    if host:
+    check_every = 4 if prob["host_resident"] else 1   # host: each check is a pass over host memory
+    if prob["host_resident"]:
         max_rounds = min(max_rounds, 160)
     for rnd in range(max_rounds):
         t0 = time.time()
@@ -155,7 +163,7 @@ def time_to_gap(g, set_data, prob, m, target, max_rounds, mode=1, inflight=0, sa
                 rounds = rnd + 1
                 continue
             keep = g.get(duhl.Z)
-            gap = g.gap(all_idx)
+            gap = g.gap(all_idx) if all_idx is not None else g.gap()
             g.set(duhl.Z, keep)
             log(f"time-to-gap: round {rnd} total gap {gap:.3e} clock {clock:.3f}s")
         else:
@@ -261,6 +269,9 @@ def main():
     ap.add_argument("--select-rule", default="gap", choices=["gap", "random", "block"],
                     help="working-set rule: eq. (13), or one of the paper's reference schemes")
     ap.add_argument("--passes", type=int, default=1, help="CD passes per round (theta of Section 5.2)")
+    ap.add_argument("--gap-sample", type=float, default=1.0,
+                    help="device residency: refresh only the working set and this fraction of all "
+                         "coordinates per round (stale gap memory, Section 4.1) instead of every gap")
     ap.add_argument("--host-sampler-threads", type=int, default=0,
                     help="host residency: refresh the gap sample with this many host threads while the "
                          "GPU runs the pass (Algorithm 2, lines 7-10) instead of over the host link")
@@ -285,15 +296,17 @@ def main():
     mode = duhl.CD_ASYNC if args.cd_mode == "async" else duhl.CD_ATOMIC
     rule = {"gap": duhl.SELECT_GAP, "random": duhl.SELECT_RANDOM, "block": duhl.SELECT_BLOCK}[args.select_rule]
     sample_idx = sample_host = None
-    if prob["host_resident"]:
+    if prob["host_resident"] or args.gap_sample < 1.0:
         # 5 % of the columns per round, refreshed from host memory (Section 5.1): a window that
         # slides over one random permutation, so every column is refreshed once in 20 rounds
+        # (device residency: the fraction asked for)
         gen = torch.Generator(device="cuda")
         gen.manual_seed(1)
-        k = max(1, prob["n"] // 20)
+        windows = 20 if prob["host_resident"] else max(1, int(round(1.0 / max(args.gap_sample, 1e-6))))
+        k = max(1, prob["n"] // windows)
         perm = torch.randperm(prob["n"], generator=gen, device="cuda").to(torch.int32)
         perm = torch.cat([perm, perm[:k]]).contiguous()
-        sample_idx = [perm[(r * k) % prob["n"]:(r * k) % prob["n"] + k] for r in range(20)]
+        sample_idx = [perm[(r * k) % prob["n"]:(r * k) % prob["n"] + k] for r in range(windows)]
         hp = perm[:prob["n"]].cpu().numpy()
         sample_host = {"perm": np.concatenate([hp, hp[:k]]), "cursor": 0, "k": k, "n": prob["n"]}
     log(f"warm-up: {args.warmup} rounds")
@@ -323,9 +336,11 @@ def main():
     gap_bytes, cd_bytes = algorithmic_bytes(prob, m)
     if prob["host_resident"]:
         gap_bytes = 4.0 * prob["d"] * budget     # resident part only; the sample is link-bound
+    elif sample_idx is not None:
+        gap_bytes *= (m + sample_idx[0].numel()) / prob["n"]   # working set + sample
     gap_gbps = gap_bytes / (avg(gap_ms) * 1e-3) / 1e9
     cd_gbps = cd_bytes * args.passes / (avg(cd_ms) * 1e-3) / 1e9
-    final_gap = g.gap() if not prob["host_resident"] else None
+    final_gap = g.gap() if not prob["host_resident"] else None   # (fresh z; rounds are over)
     final_obj = g.objective()
 
     out = {
@@ -339,7 +354,8 @@ def main():
         "config": {"workload": f"{args.workload}: {prob['model']} d={prob['d']} n={prob['n']} m={m}"
                                + (f" host-resident, {budget} device slots" if prob["host_resident"] else ""),
                    "scale": args.scale, "rounds_timed": args.steps, "passes_per_round": args.passes,
-                   "cd_scheme": args.cd_mode, "max_inflight": args.inflight, "select_rule": args.select_rule},
+                   "cd_scheme": args.cd_mode, "max_inflight": args.inflight, "select_rule": args.select_rule,
+                   "gap_sample": args.gap_sample},
         "phases": {"gap_ms": avg(gap_ms), "select_ms": avg(sel_ms), "cd_ms": avg(cd_ms),
                    "gap_GBps": gap_gbps, "gap_frac_of_hbm_peak": gap_gbps / HBM_PEAK_GBPS,
                    "cd_updates_per_s": m * args.passes / (avg(cd_ms) * 1e-3), "cd_GBps": cd_gbps,
@@ -349,7 +365,7 @@ def main():
                      "bound": "hbm", "achieved": gap_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gap_gbps / HBM_PEAK_GBPS,
                      "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload, {}).get("gap")
-                     if args.scale == 1.0 else None,
+                     if args.scale == 1.0 and sample_idx is None else None,
                      "algorithmic_bytes": gap_bytes, "avg_launch_ms": avg(gap_ms)},
         "roofline_cd": {"kernel": "cd_dense_worker_kernel + merge_workers_kernel (one pass)"
                         if "cols" in prob and args.cd_mode == "async" else "cd atomic kernel (one pass)",
