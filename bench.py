@@ -88,13 +88,16 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
     if not prob["host_resident"] and sample_idx is not None:
         # device-resident matrix with a gap memory kept stale on purpose (--gap-sample): only the
         # working set just updated and this round's sample are refreshed
-        if g.working_set_size() > 0:
+        refreshed = g.working_set_size()
+        if refreshed > 0:
             from paper_1708_05357_amd import duhl
             g.gap(g.device_view(duhl.P), want_sum=False)
     else:
+        refreshed = g.working_set_size() if prob["host_resident"] else prob["n"]
         g.gap(want_sum=False)
     if sample_idx is not None and not on_host:
         g.gap(sample_idx[step % len(sample_idx)], want_sum=False)
+        refreshed += sample_idx[step % len(sample_idx)].numel()
     if ev:
         ev[1].record()
     stats = g.select(m, want_stats=swap_log is not None, rule=rule, arg=step)
@@ -125,6 +128,7 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
         g.commit_swap()
     if swap_log is not None:
         swap_log.append({"columns": stats[0], "rho": stats[1], "overlapped": bool(overlapped)})
+    return refreshed                            # gaps evaluated by the GPU in this round
 
 
 def time_to_gap(g, set_data, prob, m, target, max_rounds, mode=1, inflight=0, sample_idx=None,
@@ -322,9 +326,10 @@ def main():
     swap_log = [] if host else None
     torch.cuda.synchronize()
     t0 = time.time()
+    refreshed = 0
     for s in range(args.steps):
-        one_step(g, prob, m, s, evs[s], sample_idx, mode, args.inflight, swap_log, rule, args.passes,
-                 args.host_sampler_threads, sample_host)
+        refreshed += one_step(g, prob, m, s, evs[s], sample_idx, mode, args.inflight, swap_log, rule, args.passes,
+                              args.host_sampler_threads, sample_host)
     torch.cuda.synchronize()
     elapsed = time.time() - t0
     log(f"timed {args.steps} rounds in {elapsed:.3f}s")
@@ -337,7 +342,7 @@ def main():
     if prob["host_resident"]:
         gap_bytes = 4.0 * prob["d"] * budget     # resident part only; the sample is link-bound
     elif sample_idx is not None:
-        gap_bytes *= (m + sample_idx[0].numel()) / prob["n"]   # working set + sample
+        gap_bytes *= refreshed / args.steps / prob["n"]        # working set + sample, as refreshed
     gap_gbps = gap_bytes / (avg(gap_ms) * 1e-3) / 1e9
     cd_gbps = cd_bytes * args.passes / (avg(cd_ms) * 1e-3) / 1e9
     final_gap = g.gap() if not prob["host_resident"] else None   # (fresh z; rounds are over)
