@@ -78,7 +78,7 @@ def algorithmic_bytes(prob, m):
 
 
 def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swap_log=None,
-             rule=0, passes=1, host_threads=0, sample_host=None):
+             rule=0, passes=1, host_threads=0, sample_host=None, auto=None):
     """gap -> select -> commit -> epoch.  With host residency the gaps are refreshed for the
     resident columns plus a sample of the others (stale gap memory, Section 4.1), and the copies
     of the next working set run on the side stream while the pass works on the current one."""
@@ -100,8 +100,17 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
         refreshed += sample_idx[step % len(sample_idx)].numel()
     if ev:
         ev[1].record()
-    stats = g.select(m, want_stats=swap_log is not None, rule=rule, arg=step)
+    stats = g.select(m, want_stats=swap_log is not None or passes == 0, rule=rule, arg=step)
     overlapped = prob["host_resident"] and g.working_set_size() > 0
+    if passes == 0:
+        # theta chosen per round so that the passes take about as long as the column copies they
+        # run beside (Section 5.2): copy time from the number of columns the selection replaces
+        passes = auto["min_passes"] if auto is not None else 1
+        if auto is not None and overlapped and stats[0] > 0:
+            copy_ms = stats[0] * 4.0 * prob["d"] / (auto["link_GBps"] * 1e6)
+            passes = int(min(auto["max_passes"], max(passes, round(copy_ms / auto["cd_ms"]))))
+        if auto is not None:
+            auto["passes"].append(passes)
     if not overlapped:
         g.commit_swap()
     if ev:
@@ -114,7 +123,7 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
         perm, cur, k = sample_host["perm"], sample_host["cursor"], sample_host["k"]
         g.host_sample_begin(perm[cur:cur + k], host_threads)
     for k in range(passes):                     # passes per round: the accuracy knob theta (Section 5.2)
-        g.cd_epoch(mode, seed=step * passes + k, max_inflight=inflight)
+        g.cd_epoch(mode, seed=step * (passes if auto is None else 8) + k, max_inflight=inflight)
     if ev:
         ev[3].record()
     if on_host:
@@ -132,7 +141,7 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
 
 
 def time_to_gap(g, set_data, prob, m, target, max_rounds, mode=1, inflight=0, sample_idx=None,
-                rule=0, passes=1, host_threads=0, sample_host=None):
+                rule=0, passes=1, host_threads=0, sample_host=None, auto=None):
     """Time of the rounds, from alpha = 0, until the total duality gap of a fresh full pass is
     <= target (absolute, with the paper's 1/d or 1/n normalisation) and <= target * O(alpha=0)
     (target * gap(alpha=0) for the SVM dual, whose objective is 0 at alpha = 0).
@@ -160,7 +169,7 @@ def time_to_gap(g, set_data, prob, m, target, max_rounds, mode=1, inflight=0, sa
         if host:
             if rnd > 0:
                 one_step(g, prob, m, rnd, sample_idx=sample_idx, mode=mode, inflight=inflight, rule=rule,
-                         passes=passes, host_threads=host_threads, sample_host=sample_host)
+                         passes=passes, host_threads=host_threads, sample_host=sample_host, auto=auto)
             torch.cuda.synchronize()
             clock += time.time() - t0
             if rnd % check_every != 0:
@@ -185,19 +194,19 @@ def time_to_gap(g, set_data, prob, m, target, max_rounds, mode=1, inflight=0, sa
             t0 = time.time()
             g.select(m, want_stats=False, rule=rule, arg=rnd)
             g.commit_swap()
-            for k in range(passes):
+            for k in range(max(passes, 1)):
                 g.cd_epoch(mode, seed=1000 + rnd * passes + k, max_inflight=inflight)
             clock += time.time() - t0
         elif rnd == 0:
             t0 = time.time()
             one_step(g, prob, m, 0, sample_idx=sample_idx, mode=mode, inflight=inflight, rule=rule, passes=passes,
-                     host_threads=host_threads, sample_host=sample_host)
+                     host_threads=host_threads, sample_host=sample_host, auto=auto)
             torch.cuda.synchronize()
             clock += time.time() - t0
         rounds = rnd + 1
     return {"abs_1e-3_s": t_abs, "rel_1e-3_s": t_rel, "rounds": rounds, "final_gap": gap,
             "gap_at_zero": gap0, "objective_at_zero": o0, "final_objective": g.objective(),
-            "passes_per_round": passes}
+            "passes_per_round": passes if passes > 0 else auto["passes"]}
 
 
 def cpu_baseline(prob, m, budget_s=20.0):
@@ -272,7 +281,10 @@ def main():
     ap.add_argument("--inflight", type=int, default=0, help="max_inflight of duhl_cd_epoch (0 = default)")
     ap.add_argument("--select-rule", default="gap", choices=["gap", "random", "block"],
                     help="working-set rule: eq. (13), or one of the paper's reference schemes")
-    ap.add_argument("--passes", type=int, default=1, help="CD passes per round (theta of Section 5.2)")
+    ap.add_argument("--passes", type=int, default=1,
+                    help="CD passes per round (theta of Section 5.2); 0 with host residency: as many, "
+                         "up to 8, as fit beside the round's column copies")
+    ap.add_argument("--min-passes", type=int, default=1, help="lower bound for --passes 0")
     ap.add_argument("--gap-sample", type=float, default=1.0,
                     help="device residency: refresh only the working set and this fraction of all "
                          "coordinates per round (stale gap memory, Section 4.1) instead of every gap")
@@ -316,8 +328,18 @@ def main():
     log(f"warm-up: {args.warmup} rounds")
     for s in range(args.warmup):
         one_step(g, prob, m, s, sample_idx=sample_idx, mode=mode, inflight=args.inflight, rule=rule,
-                 passes=args.passes, host_threads=args.host_sampler_threads, sample_host=sample_host)
+                 passes=max(args.passes, 1), host_threads=args.host_sampler_threads, sample_host=sample_host)
     torch.cuda.synchronize()
+    auto = None
+    if args.passes == 0:
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(g.compute_stream)
+        g.cd_epoch(mode, seed=99, max_inflight=args.inflight)
+        e1.record(g.compute_stream)
+        torch.cuda.synchronize()
+        # 55 GB/s: what the copy kernel sustains on the host link of the test machines
+        auto = {"cd_ms": e0.elapsed_time(e1), "link_GBps": 55.0, "max_passes": 8, "passes": [],
+                "min_passes": args.min_passes}
     set_data()                                  # back to alpha = 0: the timed rounds are rounds 1..K
     torch.cuda.synchronize()
 
@@ -329,7 +351,9 @@ def main():
     refreshed = 0
     for s in range(args.steps):
         refreshed += one_step(g, prob, m, s, evs[s], sample_idx, mode, args.inflight, swap_log, rule, args.passes,
-                              args.host_sampler_threads, sample_host)
+                              args.host_sampler_threads, sample_host, auto)
+    total_passes = args.passes * args.steps if auto is None else sum(auto["passes"])
+    passes_timed = None if auto is None else list(auto["passes"])
     torch.cuda.synchronize()
     elapsed = time.time() - t0
     log(f"timed {args.steps} rounds in {elapsed:.3f}s")
@@ -344,13 +368,13 @@ def main():
     elif sample_idx is not None:
         gap_bytes *= refreshed / args.steps / prob["n"]        # working set + sample, as refreshed
     gap_gbps = gap_bytes / (avg(gap_ms) * 1e-3) / 1e9
-    cd_gbps = cd_bytes * args.passes / (avg(cd_ms) * 1e-3) / 1e9
+    cd_gbps = cd_bytes * total_passes / args.steps / (avg(cd_ms) * 1e-3) / 1e9
     final_gap = g.gap() if not prob["host_resident"] else None   # (fresh z; rounds are over)
     final_obj = g.objective()
 
     out = {
         "metric": "coordinate updates/s (whole round: gap pass + top-m + CD pass)",
-        "value": m * args.passes * args.steps / elapsed,
+        "value": m * total_passes / elapsed,
         "unit": "coordinate updates/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3,
@@ -358,12 +382,12 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {prob['model']} d={prob['d']} n={prob['n']} m={m}"
                                + (f" host-resident, {budget} device slots" if prob["host_resident"] else ""),
-                   "scale": args.scale, "rounds_timed": args.steps, "passes_per_round": args.passes,
+                   "scale": args.scale, "rounds_timed": args.steps, "passes_per_round": args.passes if auto is None else passes_timed,
                    "cd_scheme": args.cd_mode, "max_inflight": args.inflight, "select_rule": args.select_rule,
                    "gap_sample": args.gap_sample},
         "phases": {"gap_ms": avg(gap_ms), "select_ms": avg(sel_ms), "cd_ms": avg(cd_ms),
                    "gap_GBps": gap_gbps, "gap_frac_of_hbm_peak": gap_gbps / HBM_PEAK_GBPS,
-                   "cd_updates_per_s": m * args.passes / (avg(cd_ms) * 1e-3), "cd_GBps": cd_gbps,
+                   "cd_updates_per_s": m * total_passes / args.steps / (avg(cd_ms) * 1e-3), "cd_GBps": cd_gbps,
                    "cd_frac_of_hbm_peak": cd_gbps / HBM_PEAK_GBPS,
                    "gap_ms_min": min(gap_ms), "cd_ms_min": min(cd_ms), "cd_ms_max": max(cd_ms)},
         "roofline": {"kernel": "gap_dense_kernel" if "cols" in prob else "gap_csr_kernel",
@@ -404,8 +428,10 @@ def main():
                        "host_sampled_per_round": sampled}
     if not args.no_ttg:
         log("time to gap 1e-3")
+        if auto is not None:
+            auto["passes"] = []
         out["time_to_gap"] = time_to_gap(g, set_data, prob, m, 1e-3, 400, mode, args.inflight, sample_idx, rule, args.passes,
-                                         args.host_sampler_threads, sample_host)
+                                         args.host_sampler_threads, sample_host, auto)
     if not args.no_cpu:
         log("CPU baseline (oracle, one thread, about 20 s)")
         out["cpu_baseline"] = cpu_baseline(prob, m)
