@@ -1,8 +1,9 @@
 """Parity at the full sizes of the benchmark plan, in the launch configuration bench.py times.
 
-cfg2 (2 GB) still fits the oracle whole.  cfg5 (100 GB in HBM) does not: there the oracle
-recomputes sampled outputs one by one (gaps and exact steps of sampled columns, from the GPU's own
-alpha and v), and the rest is checked through properties that hold at any size.
+cfg2 (2 GB) still fits the oracle whole.  cfg5 (100 GB in HBM) and the host-resident cfg4 shape
+do not: there the oracle recomputes sampled outputs one by one (gaps and exact steps of sampled
+columns, from the GPU's own alpha and v), and the rest is checked through properties that hold at
+any size.
 """
 import os
 import sys
@@ -180,4 +181,99 @@ def test_cfg3_full_size_sparse_svm(G):
     og, oo = g.objective(), o2.objective()
     print("cfg3 objective gpu %.9e oracle %.9e gap gpu %.3e" % (og, oo, g.gap()))
     assert abs(og - oo) <= 1e-5 * abs(oo)
+    g.close()
+
+
+def test_cfg4_shape_host_resident_sampled_columns_and_swap(G):
+    """Dense Lasso with 100,000-long columns in pinned host memory (32 GB: the share of the
+    out-of-budget workload that one pinned allocation of the test machines holds, which is also
+    what bench.py times), m = 8,000 and 16,000 device slots.  Rounds run as in the benchmark
+    (time-delayed selection, copies beside the pass); the oracle recomputes sampled gaps and
+    exact steps from the GPU's own alpha and v, and the working set is checked through what must
+    hold at any size."""
+    from oracle import duhl_oracle as orc
+    from paper_1708_05357_amd import duhl, synth
+    cfg = synth.CONFIGS["cfg4"]
+    scale = 0.4
+    n, d = int(cfg["n"] * scale), cfg["d"]
+    try:
+        pinned = torch.empty((n, d), dtype=torch.float32, pin_memory=True)
+    except RuntimeError as e:                       # the machine cannot pin 32 GB
+        pytest.skip(f"cannot pin {4.0 * n * d / 1e9:.0f} GB of host memory: {e}")
+    print("generating", flush=True)
+    prob = synth.make("cfg4", device="cuda", scale=scale, out=pinned)
+    m = prob["m"]
+    budget = 2 * m
+    g = duhl.Duhl(duhl.LASSO, d, n, budget)
+    print("set_data (one streamed pass over host memory)", flush=True)
+    g.set_data_dense(pinned, prob["target"], prob["lam"], duhl.RESIDENT_HOST)
+    b = prob["target"].cpu().numpy()
+    rng = np.random.default_rng(7)
+
+    def oracle_on(idx):
+        cols = pinned[torch.as_tensor(idx)].numpy()
+        o = orc.Oracle(orc.LASSO, b, prob["lam"], cols=cols)
+        o.set_state(g.get(duhl.ALPHA)[idx].astype(np.float64), g.get(duhl.V).astype(np.float64))
+        return o
+
+    def check_gaps(idx):
+        z = g.get(duhl.Z)
+        o = oracle_on(idx)
+        o.gaps()
+
+        class _P:
+            pass
+        pp = _P()
+        pp.o = o
+        err = np.abs(z[idx] - o.z)
+        assert err.max() <= 1e-4 * max(o.z.max(), z[idx].max()) + G.lasso_gap_floor(pp), (err.max(), o.z.max())
+
+    # the first pass of set_data left the gaps at alpha = 0 for every column
+    np.testing.assert_allclose(g.get(duhl.SQNORM), 1.0, rtol=1e-5)
+    check_gaps(np.sort(rng.choice(n, 400, replace=False)))
+    sample = G.dev_i32(np.sort(rng.choice(n, n // 20, replace=False)))
+    nsw, rho = g.select(m)
+    assert nsw == m
+    g.commit_swap()
+    for rnd in range(3):
+        print("round", rnd, flush=True)
+        P = g.get(duhl.P)
+        alpha0, v0 = g.get(duhl.ALPHA), g.get(duhl.V)
+        g.gap(want_sum=False)                       # residents, from their slots
+        g.gap(sample, want_sum=False)               # a sample of the others, over the host link
+        # both lists were evaluated at this alpha and v: check residents and sampled columns
+        check_gaps(np.unique(np.concatenate([rng.choice(P, 200, replace=False),
+                                             sample.cpu().numpy()[:200]])))
+        nsw, rho = g.select(m)                      # plans and starts the copies
+        g.cd_epoch(duhl.CD_ASYNC, seed=rnd)         # works on the previous set meanwhile
+        a1 = g.get(duhl.ALPHA)
+        moved = np.flatnonzero(a1 != alpha0)
+        assert np.all(np.isin(moved, P))            # only the current working set is updated
+        g.commit_swap()
+        Pn = g.get(duhl.P)
+        z = g.get(duhl.Z)
+        inP = np.zeros(n, dtype=bool)
+        inP[Pn] = True
+        assert Pn.size == m and np.all(np.diff(Pn) > 0)
+        assert z[inP].min() >= z[~inP].max()        # eq. (13) on the gap memory as it stood
+        fresh = np.setdiff1d(Pn, P).size
+        assert fresh - (budget - m) <= nsw <= fresh
+        assert 1.0 <= rho <= n / m + 1e-9
+    # the slots hold the selected columns: exact steps on sampled members of the new set, read
+    # from the slots by the GPU and from host memory by the oracle
+    Pn = g.get(duhl.P)
+    step_cols = np.sort(rng.choice(Pn, 150, replace=False))
+    o = oracle_on(step_cols)
+    order = rng.permutation(step_cols.size).astype(np.int32)
+    g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(step_cols[order]))
+    o.cd_pass(order)
+    a2, v2 = g.get(duhl.ALPHA), g.get(duhl.V)
+    assert np.abs(a2[step_cols] - o.alpha).max() <= 1e-5 * max(np.abs(o.alpha).max(), 1e-30)
+    assert np.abs(v2 - o.v).max() <= 1e-5 * np.abs(o.v).max()
+    # v = A alpha - b on sampled rows, from host memory
+    nz = np.flatnonzero(a2)
+    rows = rng.integers(0, d, 48)
+    sub = pinned[torch.as_tensor(nz)[:, None], torch.as_tensor(rows)[None, :]].double().numpy()
+    want = sub.T @ a2[nz].astype(np.float64) - b[rows]
+    assert np.abs(v2[rows] - want).max() <= 1e-4 * np.abs(b).max()
     g.close()
