@@ -370,6 +370,10 @@ def main():
     gap_gbps = gap_bytes / (avg(gap_ms) * 1e-3) / 1e9
     cd_gbps = cd_bytes * total_passes / args.steps / (avg(cd_ms) * 1e-3) / 1e9
     final_gap = g.gap() if not prob["host_resident"] else None   # (fresh z; rounds are over)
+    # yardstick: a plain read-only streaming kernel over the same device memory the gap pass reads
+    stream_gbps = None
+    if "cols" in prob and not prob["host_resident"] and prob["cols"].is_contiguous():
+        stream_gbps = prob["cols"].numel() * 4.0 / (g.probe_stream_read(prob["cols"], reps=3) * 1e-3) / 1e9
     final_obj = g.objective()
 
     out = {
@@ -395,14 +399,17 @@ def main():
                      "frac": gap_gbps / HBM_PEAK_GBPS,
                      "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload, {}).get("gap")
                      if args.scale == 1.0 and sample_idx is None else None,
-                     "algorithmic_bytes": gap_bytes, "avg_launch_ms": avg(gap_ms)},
+                     "algorithmic_bytes": gap_bytes, "avg_launch_ms": avg(gap_ms),
+                     "stream_read_GBps": stream_gbps,
+                     "frac_of_stream_read": gap_gbps / stream_gbps if stream_gbps else None},
         "roofline_cd": {"kernel": "cd_dense_worker_kernel + merge_workers_kernel (one pass)"
                         if "cols" in prob and args.cd_mode == "async" else "cd atomic kernel (one pass)",
                         "bound": "hbm", "achieved": cd_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                         "frac": cd_gbps / HBM_PEAK_GBPS,
                         "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload, {}).get("cd_pass")
                         if args.scale == 1.0 and args.cd_mode == "async" and args.inflight == 0 else None,
-                        "algorithmic_bytes": cd_bytes, "avg_launch_ms": avg(cd_ms)},
+                        "algorithmic_bytes": cd_bytes, "avg_launch_ms": avg(cd_ms),
+                        "frac_of_stream_read": cd_gbps / stream_gbps if stream_gbps else None},
         "after_timed_rounds": {"total_gap": final_gap, "objective": final_obj},
         "gen_s": prob["gen_s"],
     }

@@ -194,6 +194,14 @@ duhl_status duhl_set(duhl_ctx *ctx, duhl_what what, const void *src_host, int64_
 /* Device address of a state array, for callers that keep their own views (borrowed). */
 duhl_status duhl_device_ptr(duhl_ctx *ctx, duhl_what what, void **ptr);
 
+/* Measurement aid, no part of the method: read `bytes` (a multiple of 16) of device memory at
+ * dev (16-byte aligned) `reps` times with a plain streaming kernel on the compute stream and
+ * return the shortest launch time in milliseconds.  It is the yardstick the gap pass (Section 3,
+ * eq. (4): one read of every column) is compared with: what a read-only pass over the same
+ * memory can reach on the device at hand.  Waits. */
+duhl_status duhl_probe_stream_read(duhl_ctx *ctx, const void *dev, int64_t bytes, int reps,
+                                   double *best_ms);
+
 /* Size of the current working set (0 before the first commit). */
 int64_t duhl_working_set_size(const duhl_ctx *ctx);
 

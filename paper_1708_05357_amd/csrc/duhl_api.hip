@@ -418,6 +418,35 @@ duhl_status duhl_recompute_v(duhl_ctx *c)
     return DUHL_OK;
 }
 
+duhl_status duhl_probe_stream_read(duhl_ctx *c, const void *dev, int64_t bytes, int reps, double *best_ms)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!dev || !best_ms || bytes <= 0 || bytes % 16 != 0 || reps < 1 ||
+        (reinterpret_cast<uintptr_t>(dev) & 15) != 0)
+        return fail(c, DUHL_EINVAL, "probe: need a 16-byte aligned device pointer, bytes % 16 == 0, reps >= 1");
+    HIPCHK(c, hipSetDevice(c->device));
+    hipEvent_t e0, e1;
+    HIPCHK(c, hipEventCreate(&e0));
+    HIPCHK(c, hipEventCreate(&e1));
+    float *sink = reinterpret_cast<float *>(c->scalars + S_SINK);
+    double best = 0.0;
+    duhl_status st = DUHL_OK;
+    for (int r = 0; r <= reps && st == DUHL_OK; ++r) {         // first launch is a warm-up
+        hipError_t e = hipEventRecord(e0, c->compute);
+        if (e == hipSuccess) e = launch_stream_read(c, dev, bytes, sink);
+        if (e == hipSuccess) e = hipEventRecord(e1, c->compute);
+        if (e == hipSuccess) e = hipEventSynchronize(e1);
+        float ms = 0.0f;
+        if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+        if (e != hipSuccess) st = fail(c, DUHL_EHIP, "probe: %s", hipGetErrorString(e));
+        else if (r > 0 && (best == 0.0 || ms < best)) best = ms;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    if (st == DUHL_OK) *best_ms = best;
+    return st;
+}
+
 static duhl_status locate(duhl_ctx *c, duhl_what what, void **ptr, int64_t *len, size_t *elem)
 {
     *elem = 4;

@@ -125,7 +125,7 @@ __device__ __forceinline__ float group_sum(float x)
 }
 
 // Slots of the device scalar block (doubles), results of reductions.
-enum Scalar { S_GAP_SUM = 0, S_SUM_ALL, S_SUM_SEL, S_RHO, S_OBJ_SQ, S_OBJ_LIN, S_BSQ, S_CORR, S_COUNT };
+enum Scalar { S_GAP_SUM = 0, S_SUM_ALL, S_SUM_SEL, S_RHO, S_OBJ_SQ, S_OBJ_LIN, S_BSQ, S_CORR, S_SINK, S_COUNT };
 
 // Scratch of the selection kernels (device memory, one per context).
 struct SelectState {
@@ -220,6 +220,7 @@ hipError_t launch_init_v(duhl_ctx *c);
 hipError_t launch_accumulate_v(duhl_ctx *c);
 hipError_t launch_corr_sample(duhl_ctx *c, float *u, int samples);
 hipError_t launch_validate(duhl_ctx *c);
+hipError_t launch_stream_read(duhl_ctx *c, const void *dev, int64_t bytes, float *sink);
 hipError_t launch_fill_i32(hipStream_t s, int32_t *p, int64_t n, int32_t value);
 hipError_t launch_fill_f32(hipStream_t s, float *p, int64_t n, float value);
 hipError_t launch_sum_partials(duhl_ctx *c, int64_t count, int scalar_slot);

@@ -206,6 +206,34 @@ hipError_t launch_corr_sample(duhl_ctx *c, float *u, int samples)
     return hipGetLastError();
 }
 
+// Read-only streaming yardstick: grid-stride 16-byte non-temporal loads, 8 in flight per lane.
+// The sum is compared with a value it cannot take so that the loads stay.
+__global__ __launch_bounds__(256) void stream_read_kernel(const float4 *p, int64_t n4, float *sink)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    float acc = 0.0f;
+    for (; i + stride * 7 < n4; i += stride * 8) {
+        float4 x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) x[u] = stream_load4(p + i + stride * u);
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += (x[u].x + x[u].y) + (x[u].z + x[u].w);
+    }
+    for (; i < n4; i += stride) {
+        const float4 x = stream_load4(p + i);
+        acc += (x.x + x.y) + (x.z + x.w);
+    }
+    if (acc == -1.2345678e38f) *sink = acc;
+}
+
+hipError_t launch_stream_read(duhl_ctx *c, const void *dev, int64_t bytes, float *sink)
+{
+    hipLaunchKernelGGL(stream_read_kernel, dim3(c->num_cu * 32), dim3(256), 0, c->compute,
+                       static_cast<const float4 *>(dev), bytes / 16, sink);
+    return hipGetLastError();
+}
+
 hipError_t launch_validate(duhl_ctx *c)
 {
     const int64_t len = c->d > c->n ? c->d : c->n;

@@ -24,7 +24,7 @@ OK, EINVAL, ENOMEM, EHIP, ESTATE, EBUDGET = 0, -1, -2, -3, -4, -5
 EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_data_dense", "duhl_set_data_csr", "duhl_gap", "duhl_select",
            "duhl_select_rule_apply", "duhl_host_sample_begin", "duhl_host_sample_end",
            "duhl_commit_swap", "duhl_cd_epoch", "duhl_objective", "duhl_recompute_v", "duhl_get",
-           "duhl_set", "duhl_device_ptr", "duhl_working_set_size", "duhl_last_error",
+           "duhl_set", "duhl_device_ptr", "duhl_probe_stream_read", "duhl_working_set_size", "duhl_last_error",
            "duhl_destroy"]
 
 _lib = None
@@ -67,7 +67,8 @@ def load():
     lib.duhl_last_error.restype = C.c_char_p
     lib.duhl_destroy.argtypes = [p]
     lib.duhl_destroy.restype = None
-    for name in EXPORTS[:16]:
+    lib.duhl_probe_stream_read.argtypes = [p, p, i64, i32, C.POINTER(dbl)]
+    for name in EXPORTS[:17]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -177,6 +178,15 @@ class Duhl:
 
     def recompute_v(self):
         self._chk(self.lib.duhl_recompute_v(self._h))
+
+    def probe_stream_read(self, tensor, reps=5):
+        """Shortest time (ms) of a plain read-only streaming pass over a device tensor."""
+        nbytes = tensor.numel() * tensor.element_size()
+        nbytes -= nbytes % 16
+        ms = C.c_double(0.0)
+        self._chk(self.lib.duhl_probe_stream_read(self._h, C.c_void_p(tensor.data_ptr()), nbytes, int(reps),
+                                                  C.byref(ms)))
+        return ms.value
 
     # -- state ------------------------------------------------------------------------------
     def working_set_size(self):

@@ -610,3 +610,17 @@ def test_host_gap_sampler_matches_oracle(G):
         q.g.host_sample_begin(np.arange(5, dtype=np.int32))
     assert e.value.status == duhl.EINVAL
     q.close()
+
+
+def test_stream_read_probe(G):
+    """The measurement aid reads what it is given and rejects what it cannot read."""
+    from paper_1708_05357_amd import duhl
+    g = duhl.Duhl(duhl.LASSO, 64, 8, 8)
+    x = torch.ones(1 << 22, dtype=torch.float32, device="cuda:0")
+    ms = g.probe_stream_read(x, reps=2)
+    assert 0.0 < ms < 50.0
+    with pytest.raises(duhl.DuhlError):
+        g.probe_stream_read(x[1:], reps=1)               # not 16-byte aligned
+    with pytest.raises(duhl.DuhlError):
+        g.probe_stream_read(x, reps=0)
+    g.close()
