@@ -69,7 +69,8 @@ typedef enum {
                                (the thread-block-per-coordinate scheme of Appendix D)          */
 } duhl_cd_mode;
 
-/* Create a context for a problem with columns of length d and n coordinates.
+/* Create a context for a problem with columns of length d (1 <= d < 2^29) and n coordinates
+ * (1 <= n < 2^31).
  * budget_cols: the largest working set (and, for DUHL_RESIDENT_HOST, the number of device
  * column slots); 1 <= budget_cols.  device: HIP device ordinal.  compute_stream / copy_stream:
  * hipStream_t handles (NULL = the default stream); both must have the default priority. */
@@ -104,8 +105,8 @@ duhl_status duhl_set_data_csr(duhl_ctx *ctx, const int64_t *rowptr, const int32_
  *       z_i = (1/n) [ alpha_i s_i + max(0, 1 - y_i s_i) - y_i alpha_i ]
  *   elastic net (eq. (4) with the conjugate of g_i; for eta = 1 the ridge gap of Appendix E), L = lambda d:
  *       z_i = (1/d) [ alpha_i c_i + L (eta/2 alpha_i^2 + (1-eta)|alpha_i|) + [|c_i| - L(1-eta)]_+^2 / (2 L eta) ]
- * clamped at 0.  idx (device, int32, each in [0,n), no duplicates) lists the `count`
- * coordinates to refresh; idx == NULL refreshes all n coordinates (device residency) or every
+ * clamped at 0.  idx (device, int32, each in [0,n) -- other values are skipped --, no
+ * duplicates) lists the `count` coordinates to refresh; idx == NULL refreshes all n coordinates (device residency) or every
  * column currently held in a device slot (host residency), and count is then ignored.  Other
  * entries of z keep their (stale) values.  gap_sum (host, may be NULL): sum of the entries
  * written, the total gap when all were asked for; non-NULL makes the call wait. */
@@ -159,15 +160,19 @@ duhl_status duhl_commit_swap(duhl_ctx *ctx);
  *           alpha_j <- sign(gamma)[|gamma| - lambda d (1-eta)/(||a_j||^2 + lambda eta d)]_+
  *   both:   v <- v + a_j (alpha_j_new - alpha_j_old)
  * order (device, int32): the coordinates to visit, in visiting order; each must belong to the
- * current working set and, for the concurrent schemes, appear once; n_order entries.
+ * current working set and, for the concurrent schemes, appear once (a repeated coordinate may be
+ * solved by two workers at the same time, which leaves v inconsistent with alpha); values outside
+ * [0,n) are skipped; n_order entries.
  * order == NULL: the whole set -- ascending for DUHL_CD_SEQUENTIAL, a pseudo-random permutation
  * drawn from (seed, pass counter) otherwise.
  * DUHL_CD_SEQUENTIAL solves one coordinate after the other and is reproducible.
  * The concurrent schemes solve up to max_inflight coordinates without seeing each other's update
- * of v -- the asynchrony of Appendix D, bounded.  max_inflight = 0 lets the library choose: about
- * 2*count/sigma, at most count/4, where sigma estimates ||A_P||^2 from the block shape and the mean
- * correlation of a column sample taken by duhl_set_data_*.  Strongly correlated columns tolerate
- * fewer concurrent steps; lower max_inflight if the objective stops decreasing.
+ * of v -- the asynchrony of Appendix D, bounded.  max_inflight = 0 lets the library choose from
+ * sigma(L), an estimate of the largest eigenvalue of an L-column Gram block made from the block
+ * shape and the mean correlation of a column sample taken by duhl_set_data_*: the largest L with
+ * sigma(L) <= 2 (concurrent exact steps still contract), or 2*count/sigma(count) capped at count/4
+ * if that is more.  Strongly correlated columns tolerate fewer concurrent steps; lower
+ * max_inflight if the objective stops decreasing.
  *   DUHL_CD_ATOMIC  each step reads the live v and adds a_j*delta to it with fp32 atomics;
  *                   iterates depend on timing.
  *   DUHL_CD_ASYNC   dense data: the pass is cut into sub-passes of max_inflight coordinates;

@@ -160,7 +160,8 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
 {
     if (!out) return DUHL_EINVAL;
     if (model != DUHL_LASSO && model != DUHL_SVM && model != DUHL_ELASTIC_NET) return DUHL_EINVAL;
-    if (d <= 0 || n <= 0 || budget_cols <= 0 || n > 0x7fffffffll || d > 0x7fffffffll) return DUHL_EINVAL;
+    // n: coordinates are int32.  d: kernels address a column and v with 32-bit byte offsets.
+    if (d <= 0 || n <= 0 || budget_cols <= 0 || n > 0x7fffffffll || d >= (1ll << 29)) return DUHL_EINVAL;
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) return DUHL_EHIP;
     if (hipSetDevice(device) != hipSuccess) return DUHL_EHIP;

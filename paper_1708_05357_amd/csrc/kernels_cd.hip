@@ -31,7 +31,8 @@ namespace {
 struct CdArgs {
     ColView cv;
     ModelConst mc;
-    int64_t d, count;
+    int64_t d, n, count;
+    int64_t groups;         // concurrent schemes: groups of threads that take coordinates
     const int32_t *order;   // explicit visiting order, or nullptr
     const int32_t *P;       // working set (used when order == nullptr)
     int permute;            // visit P through a pseudo-random bijection
@@ -56,9 +57,14 @@ __device__ __forceinline__ int64_t permuted(const CdArgs &a, int64_t t)
     return (int64_t)x;
 }
 
+// Coordinate visited at position t; -1 for an entry of a caller's list that names no coordinate
+// (such entries are skipped: the value is the same in all threads that share the coordinate).
 __device__ __forceinline__ int64_t coord_at(const CdArgs &a, int64_t t)
 {
-    if (a.order) return a.order[t];
+    if (a.order) {
+        const int64_t j = a.order[t];
+        return (uint64_t)j < (uint64_t)a.n ? j : -1;
+    }
     return a.P[a.permute ? permuted(a, t) : t];
 }
 
@@ -136,13 +142,17 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_atomic_kernel(cons
     constexpr int BLOCK = T == 64 ? 256 : T;
     __shared__ float red[2][16];
     const int tid = threadIdx.x % T;
-    const int64_t ngroups = (int64_t)gridDim.x * (BLOCK / T);
+    // a.groups of the launched groups work (the last workgroup may hold idle ones, which only
+    // happens for T = 64, where a group is a wavefront and shares no barrier with its neighbours)
+    const int64_t ngroups = a.groups;
     const int64_t d4 = VEC4 ? (a.d >> 2) : 0;
     const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(a.v, 0, (int)(a.d * 4), 0x00020000);
     int parity = 0;
-    for (int64_t t = (int64_t)blockIdx.x * (BLOCK / T) + threadIdx.x / T; t < a.count;
-         t += ngroups) {
+    const int64_t first = (int64_t)blockIdx.x * (BLOCK / T) + threadIdx.x / T;
+    if (first >= ngroups) return;
+    for (int64_t t = first; t < a.count; t += ngroups) {
         const int64_t j = coord_at(a, t);
+        if (j < 0) continue;
         const float *col = a.cv.col(j);
         const float4 *c4 = reinterpret_cast<const float4 *>(col);
         float4 x[NREG];
@@ -235,6 +245,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
     int parity = 0;
     for (int64_t t = t_begin + w; t < t_end; t += nworkers) {
         const int j = __builtin_amdgcn_readfirstlane((int)coord_at(a, t));
+        if (j < 0) continue;
         const float *col = a.cv.col(j);
         const __amdgpu_buffer_rsrc_t rs_x =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(col), 0, vec_bytes, 0x00020000);
@@ -369,9 +380,12 @@ template <int MODEL, int G>
 __global__ __launch_bounds__(256) void cd_csr_async_kernel(const CdArgs a)
 {
     const int sub = threadIdx.x % G;
-    const int64_t ngroups = (int64_t)gridDim.x * (256 / G);
-    for (int64_t t = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G; t < a.count; t += ngroups) {
+    const int64_t ngroups = a.groups;              // idle groups of the last workgroup leave at once
+    const int64_t first = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
+    if (first >= ngroups) return;
+    for (int64_t t = first; t < a.count; t += ngroups) {
         const int64_t j = coord_at(a, t);
+        if (j < 0) continue;
         const int64_t beg = a.cv.rowptr[j], end = a.cv.rowptr[j + 1];
         float acc = 0.0f;
         // index/value loads of a batch first, then the gathers that depend on them: K gathers
@@ -419,6 +433,7 @@ __global__ __launch_bounds__(1024) void cd_dense_seq_kernel(const CdArgs a)
     int parity = 0;
     for (int64_t t = 0; t < a.count; ++t) {
         const int64_t j = coord_at(a, t);
+        if (j < 0) continue;
         const float *col = a.cv.col(j);
         const float4 *c4 = reinterpret_cast<const float4 *>(col);
         float acc = 0.0f;
@@ -454,6 +469,7 @@ __global__ __launch_bounds__(64) void cd_csr_seq_kernel(const CdArgs a)
     const int lane = threadIdx.x;
     for (int64_t t = 0; t < a.count; ++t) {
         const int64_t j = coord_at(a, t);
+        if (j < 0) continue;
         const int64_t beg = a.cv.rowptr[j], end = a.cv.rowptr[j + 1];
         float acc = 0.0f;
         for (int64_t e = beg + lane; e < end; e += 64) acc = fmaf(a.cv.val[e], a.v[a.cv.colidx[e]], acc);
@@ -489,14 +505,16 @@ hipError_t launch_atomic_dense_t(duhl_ctx *c, const CdArgs &a, int inflight, boo
 {
     constexpr int BLOCK = T == 64 ? 256 : T;
     constexpr int PER = BLOCK / T;
-    int64_t grid = (inflight + PER - 1) / PER;
-    if (grid < 1) grid = 1;
+    if (inflight < 1) inflight = 1;
+    const int64_t grid = (inflight + PER - 1) / PER;
+    CdArgs b = a;
+    b.groups = inflight;
     if (vec)
         hipLaunchKernelGGL((cd_dense_atomic_kernel<MODEL, T, NREG, true>), dim3(grid), dim3(BLOCK), 0,
-                           c->compute, a);
+                           c->compute, b);
     else
         hipLaunchKernelGGL((cd_dense_atomic_kernel<MODEL, T, 1, false>), dim3(grid), dim3(BLOCK), 0,
-                           c->compute, a);
+                           c->compute, b);
     return hipGetLastError();
 }
 
@@ -574,10 +592,12 @@ hipError_t launch_atomic(duhl_ctx *c, const CdArgs &a, int max_inflight, bool ve
         int64_t inflight = inflight_limit(c, a.count, max_inflight);
         if (inflight > cap) inflight = cap;
         const int64_t grid = (inflight + 256 / G - 1) / (256 / G);
+        CdArgs b = a;
+        b.groups = inflight;
         if (G == 64)
-            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 64>), dim3(grid), dim3(256), 0, c->compute, a);
+            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 64>), dim3(grid), dim3(256), 0, c->compute, b);
         else
-            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 16>), dim3(grid), dim3(256), 0, c->compute, a);
+            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 16>), dim3(grid), dim3(256), 0, c->compute, b);
         return hipGetLastError();
     }
     const int T = threads_per_coordinate(c);
@@ -683,6 +703,8 @@ hipError_t launch_cd(duhl_ctx *c, duhl_cd_mode mode, const int32_t *order, int64
     a.cv = c->cv;
     a.mc = c->mc;
     a.d = c->d;
+    a.n = c->n;
+    a.groups = 1;
     a.order = order;
     a.P = c->P_cur;
     a.count = order ? count : c->m_cur;

@@ -15,7 +15,7 @@ namespace duhl {
 struct GapArgs {
     ColView cv;
     ModelConst mc;
-    int64_t d, count;
+    int64_t d, n, count;
     const int32_t *idx;       // coordinates to refresh, or nullptr for 0..count-1
     const int32_t *slot_col;  // non-null: entry k is device slot k, refresh the column it holds
     const float *v, *alpha, *target;
@@ -31,7 +31,9 @@ __device__ __forceinline__ int64_t list_entry(const GapArgs &a, int64_t k)
         const int32_t j = a.slot_col[k];
         return (j >= 0 && a.cv.col_slot[j] == (int32_t)k) ? j : -1;   // skip empty / unpublished
     }
-    return a.idx ? (int64_t)a.idx[k] : k;
+    if (!a.idx) return k;
+    const int64_t j = a.idx[k];
+    return (uint64_t)j < (uint64_t)a.n ? j : -1;        // entries that name no coordinate are skipped
 }
 
 __device__ __forceinline__ float dot4(const float4 x, const float4 y, float acc)
@@ -257,6 +259,7 @@ hipError_t launch_gap(duhl_ctx *c, const int32_t *idx, int64_t count, bool slot_
     a.cv = c->cv;
     a.mc = c->mc;
     a.d = c->d;
+    a.n = c->n;
     a.count = count;
     a.idx = idx;
     a.slot_col = slot_list ? c->slot_col : nullptr;

@@ -467,6 +467,41 @@ def test_error_paths(G):
     s.close()
 
 
+def test_list_entries_outside_the_problem_are_skipped(G):
+    """Index lists come from the caller: entries that name no coordinate must neither be read
+    through nor change anything, in every kernel that takes a list."""
+    from paper_1708_05357_amd import duhl
+    from paper_1708_05357_amd import synth
+    prob = lasso_problem(300, 40, 0.2, 0.1, seed=31)
+    csr = synth.svm_csr(60, 30, 0.2, seed=32)
+    for pr in (prob, csr):
+        p = G.Pair(pr)
+        n = pr["n"]
+        m = 12
+        p.g.select(m)
+        p.g.commit_swap()
+        P = p.g.get(duhl.P)
+        good = P[:6].astype(np.int32)
+        mixed = np.array([good[0], -1, good[1], n, good[2], 2 ** 31 - 1, good[3], -2 ** 31, good[4], good[5]],
+                         dtype=np.int32)
+        for mode in (duhl.CD_SEQUENTIAL, duhl.CD_ASYNC, duhl.CD_ATOMIC):
+            p.g.set(duhl.ALPHA, np.zeros(n, dtype=np.float32))
+            p.g.recompute_v()
+            p.g.cd_epoch(mode, G.dev_i32(good), max_inflight=1)
+            want_a, want_v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+            p.g.set(duhl.ALPHA, np.zeros(n, dtype=np.float32))
+            p.g.recompute_v()
+            p.g.cd_epoch(mode, G.dev_i32(mixed), max_inflight=1)
+            np.testing.assert_allclose(p.g.get(duhl.ALPHA), want_a, rtol=1e-6, atol=1e-9)
+            np.testing.assert_allclose(p.g.get(duhl.V), want_v, rtol=1e-5, atol=1e-7)
+        p.g.set(duhl.Z, np.full(n, -1.0, dtype=np.float32))
+        p.g.gap(G.dev_i32(mixed), want_sum=False)
+        z = p.g.get(duhl.Z)
+        assert np.all(z[good] >= 0)
+        assert np.count_nonzero(z >= 0) == good.size
+        p.close()
+
+
 def test_zero_columns_and_empty_rows(G):
     """Degenerate coordinates: a zero column (Lasso -> alpha_j = 0) and an empty CSR row
     (SVM -> alpha_j = y_j), both schemes."""
