@@ -183,6 +183,59 @@ duhl_status duhl_commit_swap(duhl_ctx *ctx);
 duhl_status duhl_cd_epoch(duhl_ctx *ctx, duhl_cd_mode mode, const int32_t *order,
                           int64_t n_order, uint64_t seed, int max_inflight);
 
+/* The outer loop, run natively: Algorithm 1 with the selection of eq. (11) when every gap is
+ * refreshed each round, Algorithm 2 (selection by eq. (13) on a gap memory that may be stale,
+ * columns copied beside the passes) otherwise.  One round is
+ *     refresh gap memory -> select m (rule, seed + round) -> `passes` x duhl_cd_epoch(mode) -> commit
+ * with the commit before the passes when the copies cannot overlap them (device residency, first
+ * round, or fewer than |current| + m slots).  What a round refreshes:
+ *   device residency, no sample list:  all n gaps (the working set is the exact top m);
+ *   device residency with sample_dev:  the current working set and this round's window of the list;
+ *   host residency:  every column held in a device slot, plus this round's window of the list --
+ *                    evaluated by the GPU over the host link (sample_dev), or by host_threads host
+ *                    threads from host memory while the passes run (sample_host, Algorithm 2
+ *                    lines 7-10; their result enters the gap memory at the end of the round).
+ * The window is sample_per_round consecutive entries of the list (sample_len entries, each in
+ * [0,n), no duplicates), advancing and wrapping from round to round.
+ * Every check_every-th round (0 = 1) the sum of the gap memory as the selection saw it is read
+ * back (this waits for the compute stream): with all gaps fresh it is the duality gap of eq. (2),
+ * otherwise an estimate from stale entries, which is not trusted before the windows have covered
+ * the whole list once.  The loop ends when it is <= gap_tol (pass a negative gap_tol to run
+ * max_rounds rounds; see `confirm`) or after max_rounds rounds, and waits for the compute stream.
+ * Requires data, no pending selection; 1 <= m <= min(n, budget_cols). */
+typedef struct duhl_run_opts {
+    int64_t m;                  /* working-set size                                              */
+    int passes;                 /* theta of Section 5.2: passes per round, >= 1                  */
+    duhl_cd_mode mode;
+    int max_inflight;           /* as for duhl_cd_epoch                                          */
+    duhl_select_rule rule;
+    uint64_t seed;
+    int64_t max_rounds;
+    double gap_tol;
+    int check_every;
+    const int32_t *sample_dev;  /* device list, or NULL                                          */
+    const int32_t *sample_host; /* the same list in host memory (only read when host_threads > 0) */
+    int64_t sample_len, sample_per_round;
+    int host_threads;           /* 0: the GPU evaluates the window                               */
+    int confirm;                /* != 0 with a sample list: when the estimate passes gap_tol, refresh
+                                   all n gaps (host residency: one pass over the host link), test
+                                   their sum -- the true total gap -- and go on if it fails       */
+} duhl_run_opts;
+
+typedef struct duhl_run_stats {
+    int64_t rounds;             /* rounds whose passes were run                                  */
+    int64_t passes;             /* passes run in total                                           */
+    int converged;              /* 1 if the loop ended on gap_tol                                */
+    int confirmations;          /* full refreshes made to confirm the estimate                   */
+    double gap_memory_sum;      /* sum of the gap memory at the last check                       */
+    double rho;                 /* eq. (7) at the last check                                     */
+    int64_t columns_swapped;    /* columns copied into slots, summed over the checked rounds     */
+    int64_t host_sampled;       /* gap-memory entries refreshed by host threads                  */
+    double seconds;             /* wall time of the call                                         */
+} duhl_run_stats;
+
+duhl_status duhl_run(duhl_ctx *ctx, const duhl_run_opts *opts, duhl_run_stats *stats);
+
 /* O(alpha) from the stored v and alpha (Appendix C).  objective: host.  Waits. */
 duhl_status duhl_objective(duhl_ctx *ctx, double *objective);
 

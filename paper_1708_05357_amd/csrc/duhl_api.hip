@@ -229,6 +229,7 @@ duhl_status duhl_set_data_dense(duhl_ctx *c, const float *A, int64_t ld, duhl_re
     if (res != DUHL_RESIDENT_DEVICE && res != DUHL_RESIDENT_HOST) return fail(c, DUHL_EINVAL, "bad residency");
     HIPCHK(c, hipSetDevice(c->device));
     HIPCHK(c, hipStreamSynchronize(c->compute));
+    HIPCHK(c, hipStreamSynchronize(c->copy));       // column copies of a pending selection
     c->have_data = false;
     free_host_residency(c);
     c->sparse = false;
@@ -272,6 +273,7 @@ duhl_status duhl_set_data_csr(duhl_ctx *c, const int64_t *rowptr, const int32_t 
         return fail(c, DUHL_EINVAL, "sparse data must be device-resident");
     HIPCHK(c, hipSetDevice(c->device));
     HIPCHK(c, hipStreamSynchronize(c->compute));
+    HIPCHK(c, hipStreamSynchronize(c->copy));       // column copies of a pending selection
     c->have_data = false;
     free_host_residency(c);
     c->sparse = true;
@@ -343,7 +345,8 @@ duhl_status duhl_select_rule_apply(duhl_ctx *c, duhl_select_rule rule, uint64_t 
     if (n_swapped || rho) {
         HIPCHK(c, hipMemcpyAsync(c->h_u32, &c->sel->n_fill, sizeof(uint32_t), hipMemcpyDeviceToHost,
                                  c->compute));
-        duhl_status st = read_scalars(c, S_RHO, 1);
+        static_assert(S_SUM_SEL == S_SUM_ALL + 1 && S_RHO == S_SUM_ALL + 2, "read back as one block");
+        duhl_status st = read_scalars(c, S_SUM_ALL, 3);      // sum of all keys' gaps, of the set's, rho
         if (st != DUHL_OK) return st;
         if (n_swapped) *n_swapped = (int64_t)c->h_u32[0];
         if (rho) *rho = c->h_scalars[S_RHO];
@@ -512,7 +515,7 @@ void duhl_destroy(duhl_ctx *c)
     if (!c) return;
     (void)hipSetDevice(c->device);
     (void)hipStreamSynchronize(c->compute);
-    if (c->copy) (void)hipStreamSynchronize(c->copy);
+    (void)hipStreamSynchronize(c->copy);
     free_host_residency(c);
     (void)hipFree(c->alpha); (void)hipFree(c->v); (void)hipFree(c->z); (void)hipFree(c->q);
     (void)hipFree(c->P_cur); (void)hipFree(c->P_next);

@@ -1,0 +1,170 @@
+// The outer loop (Algorithm 1; Algorithm 2 when the gap memory is allowed to go stale): rounds of
+// gap refresh -> working-set selection -> passes over the working set, driven from native code so
+// that nothing but kernel launches sits between the steps.  It only sequences the library's own
+// entry points; all arithmetic stays in their kernels.
+#include <chrono>
+#include <cmath>
+
+#include "duhl_internal.h"
+
+namespace {
+
+duhl_status set_error(duhl_ctx *c, duhl_status st, const char *text)
+{
+    c->err = text;
+    return st;
+}
+
+// Every gap at the current point, wherever the column lives (slot, device or host memory), and
+// their sum: the duality gap of eq. (2).  With host residency this is a pass over the host link.
+duhl_status refresh_all(duhl_ctx *c, double *total)
+{
+    hipError_t e = duhl::launch_gap(c, nullptr, c->n, false, false);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(c->h_scalars + duhl::S_GAP_SUM, c->scalars + duhl::S_GAP_SUM, sizeof(double),
+                           hipMemcpyDeviceToHost, c->compute);
+    if (e == hipSuccess) e = hipStreamSynchronize(c->compute);
+    if (e != hipSuccess) return set_error(c, DUHL_EHIP, hipGetErrorString(e));
+    *total = c->h_scalars[duhl::S_GAP_SUM];
+    return DUHL_OK;
+}
+
+// Entries [start, start + len) of a list of `total` entries, wrapping at the end: at most two runs.
+template <typename F>
+duhl_status for_window(int64_t total, int64_t start, int64_t len, F &&f)
+{
+    start %= total;
+    const int64_t first = len < total - start ? len : total - start;
+    duhl_status st = f(start, first);
+    if (st == DUHL_OK && len > first) st = f(0, len - first);
+    return st;
+}
+
+}  // namespace
+
+extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_stats *out)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!o || !out) return set_error(c, DUHL_EINVAL, "options or statistics pointer is NULL");
+    if (!c->have_data) return set_error(c, DUHL_ESTATE, "no data set");
+    if (o->passes < 1 || o->max_rounds < 0 || o->check_every < 0 || o->max_inflight < 0)
+        return set_error(c, DUHL_EINVAL, "passes >= 1, max_rounds >= 0, check_every >= 0, max_inflight >= 0 required");
+    if (std::isnan(o->gap_tol)) return set_error(c, DUHL_EINVAL, "gap_tol is NaN");
+    const bool host = c->res == DUHL_RESIDENT_HOST;
+    const bool threads = o->host_threads > 0;
+    if (threads && (!host || !o->sample_host))
+        return set_error(c, DUHL_EINVAL, "host threads need DUHL_RESIDENT_HOST data and sample_host");
+    const bool sampled = threads ? true : o->sample_dev != nullptr;
+    if (sampled && (o->sample_len < 1 || o->sample_per_round < 1 || o->sample_per_round > o->sample_len ||
+                    o->sample_len > c->n))
+        return set_error(c, DUHL_EINVAL, "need 1 <= sample_per_round <= sample_len <= n");
+    if (c->pending) return set_error(c, DUHL_ESTATE, "a selection is pending: call duhl_commit_swap first");
+    const int check_every = o->check_every > 0 ? o->check_every : 1;
+
+    duhl_run_stats s{};
+    const auto t0 = std::chrono::steady_clock::now();
+    duhl_status st = DUHL_OK;
+    int64_t cursor = 0;                                     // where the next sample window starts
+    int64_t swept = 0;                                      // list entries refreshed since the last full refresh
+    for (int64_t rnd = 0; rnd < o->max_rounds; ++rnd) {
+        // -- refresh the gap memory (Section 4.1) --------------------------------------------
+        if (!host && !sampled) {
+            st = duhl_gap(c, nullptr, 0, nullptr);          // every coordinate: eq. (11) exactly
+        } else {
+            // what was just worked on, from device memory: residents / the current working set
+            if (host) st = duhl_gap(c, nullptr, 0, nullptr);
+            else if (c->m_cur > 0) st = duhl_gap(c, c->P_cur, c->m_cur, nullptr);
+            else st = duhl_gap(c, nullptr, 0, nullptr);     // first round: no set yet, all are fresh
+            if (st == DUHL_OK && sampled && !threads) {
+                st = for_window(o->sample_len, cursor, o->sample_per_round, [&](int64_t a, int64_t len) {
+                    return duhl_gap(c, o->sample_dev + a, len, nullptr);
+                });
+                cursor = (cursor + o->sample_per_round) % o->sample_len;
+                swept += o->sample_per_round;
+            }
+        }
+        if (st != DUHL_OK) return st;
+
+        // -- select; the sum of the gap memory comes with it ---------------------------------
+        const bool check = rnd % check_every == 0;
+        int64_t nsw = 0;
+        double rho = 1.0;
+        st = duhl_select_rule_apply(c, o->rule, o->seed + (uint64_t)rnd, o->m, nullptr,
+                                    check ? &nsw : nullptr, check ? &rho : nullptr);
+        if (st != DUHL_OK) return st;
+        if (check) {
+            s.gap_memory_sum = c->h_scalars[duhl::S_SUM_ALL];   // read back together with rho
+            s.rho = rho;
+            s.columns_swapped += nsw;
+            // With a stale gap memory the sum is only an estimate, and a poor one before every
+            // listed entry has been refreshed at least once: entries still hold their values from
+            // the starting point (for the Lasso most of those are exactly zero).
+            bool reached = s.gap_memory_sum <= o->gap_tol && (!sampled || swept >= o->sample_len);
+            if (reached && sampled && o->confirm) {
+                // make every entry fresh at the current point and test the true total gap
+                st = duhl_commit_swap(c);
+                if (st != DUHL_OK) return st;
+                double total = 0.0;
+                st = refresh_all(c, &total);
+                if (st != DUHL_OK) return st;
+                s.confirmations++;
+                s.gap_memory_sum = total;
+                swept = o->sample_len;
+                if (total <= o->gap_tol) {
+                    s.converged = 1;
+                    break;
+                }
+                continue;                                   // next round selects from the fresh memory
+            }
+            if (reached) {
+                // done: the selection just made becomes the current set, nothing stays pending
+                st = duhl_commit_swap(c);
+                if (st != DUHL_OK) return st;
+                s.converged = 1;
+                break;
+            }
+        }
+        // -- passes over the working set, next to the column copies when they may overlap ----
+        const bool overlap = host && c->m_cur > 0 && !c->swap_exclusive;
+        if (!overlap) {
+            st = duhl_commit_swap(c);
+            if (st != DUHL_OK) return st;
+        }
+        int64_t begun = 0;
+        if (threads) {
+            begun = o->sample_per_round;
+            if (cursor + begun > o->sample_len) begun = o->sample_len - cursor;   // no wrap inside a round
+            st = duhl_host_sample_begin(c, o->sample_host + cursor, begun, o->host_threads);
+            if (st != DUHL_OK) return st;
+        }
+        for (int k = 0; k < o->passes && st == DUHL_OK; ++k)
+            st = duhl_cd_epoch(c, o->mode, nullptr, 0, o->seed + (uint64_t)(rnd * o->passes + k), o->max_inflight);
+        if (threads) {
+            // "while B not finished": the threads sample until the passes and the copies are done
+            if (st == DUHL_OK && hipStreamSynchronize(c->compute) != hipSuccess) st = DUHL_EHIP;
+            if (st == DUHL_OK && hipStreamSynchronize(c->copy) != hipSuccess) st = DUHL_EHIP;
+            int64_t done = 0;
+            const duhl_status st2 = duhl_host_sample_end(c, 0, &done);
+            if (st == DUHL_OK) st = st2;
+            // entries the threads had claimed when they were stopped may be missing: start the next
+            // window early enough to cover them again
+            int64_t adv = done - 2 * (int64_t)o->host_threads;
+            if (adv < 0) adv = 0;
+            if (done >= begun) adv = begun;
+            cursor = (cursor + adv) % o->sample_len;
+            swept += adv;
+            s.host_sampled += done;
+        }
+        if (st != DUHL_OK) return st;
+        if (overlap) {
+            st = duhl_commit_swap(c);
+            if (st != DUHL_OK) return st;
+        }
+        s.rounds = rnd + 1;
+        s.passes += o->passes;
+    }
+    if (hipStreamSynchronize(c->compute) != hipSuccess) return set_error(c, DUHL_EHIP, "stream synchronisation failed");
+    s.seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
+    *out = s;
+    return DUHL_OK;
+}

@@ -23,11 +23,25 @@ OK, EINVAL, ENOMEM, EHIP, ESTATE, EBUDGET = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_data_dense", "duhl_set_data_csr", "duhl_gap", "duhl_select",
            "duhl_select_rule_apply", "duhl_host_sample_begin", "duhl_host_sample_end",
-           "duhl_commit_swap", "duhl_cd_epoch", "duhl_objective", "duhl_recompute_v", "duhl_get",
+           "duhl_commit_swap", "duhl_cd_epoch", "duhl_run", "duhl_objective", "duhl_recompute_v", "duhl_get",
            "duhl_set", "duhl_device_ptr", "duhl_probe_stream_read", "duhl_working_set_size", "duhl_last_error",
            "duhl_destroy"]
 
 _lib = None
+
+
+class RunOpts(C.Structure):
+    _fields_ = [("m", C.c_int64), ("passes", C.c_int), ("mode", C.c_int), ("max_inflight", C.c_int),
+                ("rule", C.c_int), ("seed", C.c_uint64), ("max_rounds", C.c_int64), ("gap_tol", C.c_double),
+                ("check_every", C.c_int), ("sample_dev", C.c_void_p), ("sample_host", C.c_void_p),
+                ("sample_len", C.c_int64), ("sample_per_round", C.c_int64), ("host_threads", C.c_int),
+                ("confirm", C.c_int)]
+
+
+class RunStats(C.Structure):
+    _fields_ = [("rounds", C.c_int64), ("passes", C.c_int64), ("converged", C.c_int), ("confirmations", C.c_int),
+                ("gap_memory_sum", C.c_double), ("rho", C.c_double), ("columns_swapped", C.c_int64),
+                ("host_sampled", C.c_int64), ("seconds", C.c_double)]
 
 
 class DuhlError(RuntimeError):
@@ -68,7 +82,8 @@ def load():
     lib.duhl_destroy.argtypes = [p]
     lib.duhl_destroy.restype = None
     lib.duhl_probe_stream_read.argtypes = [p, p, i64, i32, C.POINTER(dbl)]
-    for name in EXPORTS[:17]:
+    lib.duhl_run.argtypes = [p, C.POINTER(RunOpts), C.POINTER(RunStats)]
+    for name in EXPORTS[:18]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -170,6 +185,27 @@ class Duhl:
         count = 0 if order is None else order.numel()
         self._chk(self.lib.duhl_cd_epoch(self._h, mode, _dptr(order, torch.int32), count,
                                          C.c_uint64(seed), int(max_inflight)))
+
+    def run(self, m, max_rounds, passes=1, mode=CD_ASYNC, gap_tol=-1.0, max_inflight=0, rule=SELECT_GAP,
+            seed=0, check_every=1, sample=None, sample_per_round=0, host_threads=0, confirm=False):
+        """The native round loop.  sample: int32 device tensor with the coordinates whose gaps are
+        refreshed window by window (None: see duhl_run); returns a dict of the statistics."""
+        o = RunOpts(m=int(m), passes=int(passes), mode=mode, max_inflight=int(max_inflight), rule=rule,
+                    seed=int(seed), max_rounds=int(max_rounds), gap_tol=float(gap_tol),
+                    check_every=int(check_every), host_threads=int(host_threads), confirm=1 if confirm else 0)
+        keep = None
+        if sample is not None:
+            assert sample.dtype == torch.int32 and sample.is_contiguous() and sample.is_cuda
+            o.sample_dev = sample.data_ptr()
+            o.sample_len = sample.numel()
+            o.sample_per_round = int(sample_per_round)
+            if host_threads > 0:
+                keep = np.ascontiguousarray(sample.cpu().numpy(), dtype=np.int32)
+                o.sample_host = keep.ctypes.data
+        st = RunStats()
+        self._chk(self.lib.duhl_run(self._h, C.byref(o), C.byref(st)))
+        del keep
+        return {name: getattr(st, name) for name, _ in RunStats._fields_}
 
     def objective(self):
         out = C.c_double(0.0)

@@ -1,0 +1,158 @@
+"""The native round loop (duhl_run) against the oracle's own loop of Algorithm 1, and its
+stopping rule, sampling windows and host-thread sampler against what they must satisfy."""
+import os
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+sys.path.insert(0, os.path.dirname(__file__))
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def G():
+    import gpu_common
+    return gpu_common
+
+
+def _lasso(d, n, frac=0.1, c=0.1, seed=0):
+    from paper_1708_05357_amd import synth
+    return synth.lasso_dense(d, n, frac, c, seed=seed)
+
+
+@pytest.mark.parametrize("kind,passes", [("lasso", 1), ("lasso", 3), ("svm_csr", 2)])
+def test_sequential_rounds_match_the_oracle_loop(G, kind, passes):
+    """Alg. 1 with eq. (11): every round refreshes all gaps, takes the top m and runs `passes`
+    sequential passes in ascending order -- the oracle's round() does the same, so the iterates
+    agree to the sequential tolerance after every number of rounds."""
+    from paper_1708_05357_amd import duhl, synth
+    prob = _lasso(700, 300, seed=41) if kind == "lasso" else synth.svm_csr(900, 200, 0.05, seed=42)
+    m = 40
+    for rounds in (1, 4, 9):
+        p = G.Pair(prob)
+        st = p.g.run(m, rounds, passes=passes, mode=duhl.CD_SEQUENTIAL)
+        assert st["rounds"] == rounds and st["passes"] == rounds * passes and st["converged"] == 0
+        for _ in range(rounds):
+            p.o.round(m, passes=passes)
+        a, v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+        assert np.abs(a - p.o.alpha).max() <= 1e-5 * max(np.abs(p.o.alpha).max(), 1e-30)
+        assert np.abs(v - p.o.v).max() <= 1e-5 * np.abs(p.o.v).max()
+        # the sum read back at the last check is the total gap before the last round
+        assert st["gap_memory_sum"] > 0
+        p.close()
+
+
+def test_stops_on_the_gap_and_reports_it(G):
+    from paper_1708_05357_amd import duhl
+    prob = _lasso(2000, 1500, 0.05, 0.1, seed=43)
+    p = G.Pair(prob)
+    m = 300
+    g0 = p.g.gap()
+    tol = 1e-4 * g0
+    st = p.g.run(m, 500, passes=2, mode=duhl.CD_ASYNC, gap_tol=tol, seed=7)
+    assert st["converged"] == 1 and 0 < st["rounds"] < 500
+    assert st["gap_memory_sum"] <= tol
+    assert p.g.working_set_size() == m                      # nothing left pending
+    # the state was not touched after the check: a fresh pass gives the same sum
+    assert p.g.gap() == pytest.approx(st["gap_memory_sum"], rel=1e-6)
+    # and the oracle agrees that this point is that close to optimal
+    p.sync_oracle_to_gpu_state()
+    assert p.o.gaps() == pytest.approx(st["gap_memory_sum"], rel=1e-3, abs=1e-4 * tol)
+    rng = np.random.default_rng(0)
+    for _ in range(150):
+        p.o.round(m, passes=2, rng=rng)
+    assert abs(p.g.objective() - p.o.objective()) <= max(1e-5 * abs(p.o.objective()), 2 * tol)
+    # check_every: fewer read-backs, the loop may overshoot by at most check_every - 1 rounds
+    p2 = G.Pair(prob)
+    st2 = p2.g.run(m, 500, passes=2, mode=duhl.CD_ASYNC, gap_tol=tol, seed=7, check_every=4)
+    assert st2["converged"] == 1 and st["rounds"] <= st2["rounds"] <= st["rounds"] + 3
+    assert st2["rounds"] % 4 == 0
+    p.close()
+    p2.close()
+
+
+def test_stale_gap_memory_windows_on_device_data(G):
+    """Section 4.1 on a device-resident matrix: per round only the working set and a window of
+    the sample list are refreshed.  After the run, entries are either fresh (equal to the oracle at
+    the final state, for the last working set) or stale; the problem still converges."""
+    from paper_1708_05357_amd import duhl
+    prob = _lasso(1500, 1200, 0.05, 0.1, seed=44)
+    p = G.Pair(prob)
+    n, m = prob["n"], 200
+    perm = torch.randperm(n, generator=torch.Generator().manual_seed(3)).to(torch.int32).cuda()
+    st = p.g.run(m, 120, passes=2, mode=duhl.CD_ASYNC, sample=perm, sample_per_round=n // 7, seed=1)
+    assert st["rounds"] == 120
+    full = p.g.gap()
+    assert full <= 1e-3 * G.to_np(prob["target"]).var()     # far below O(0) = ||b||^2/(2d)
+    rng = np.random.default_rng(0)
+    for _ in range(150):
+        p.o.round(m, passes=2, rng=rng)
+    assert abs(p.g.objective() - p.o.objective()) <= 1e-5 * abs(p.o.objective())
+    # stopping on the estimate alone is refused until the windows have covered the list once;
+    # with `confirm` the loop only ends on the true total gap
+    p3 = G.Pair(prob)
+    tol = 1e-4 * p3.g.gap()
+    st = p3.g.run(m, 3000, passes=2, mode=duhl.CD_ASYNC, sample=perm, sample_per_round=n // 7, gap_tol=tol,
+                  confirm=True, seed=1)
+    assert st["converged"] == 1 and st["confirmations"] >= 1 and st["rounds"] >= 7
+    assert st["gap_memory_sum"] <= tol
+    assert p3.g.gap() == pytest.approx(st["gap_memory_sum"], rel=1e-6)
+    p3.sync_oracle_to_gpu_state()
+    assert p3.o.gaps() == pytest.approx(st["gap_memory_sum"], rel=1e-3, abs=1e-4 * tol)
+    p3.close()
+    # windows wrap: a list that is not a multiple of the window, and bad arguments
+    p.g.run(m, 5, sample=perm[:1000].contiguous(), sample_per_round=300)
+    for bad in (dict(sample=perm, sample_per_round=0), dict(sample=perm, sample_per_round=n + 1),
+                dict(passes=0), dict(check_every=-1)):
+        with pytest.raises(duhl.DuhlError) as e:
+            p.g.run(m, 2, **bad)
+        assert e.value.status == duhl.EINVAL
+    with pytest.raises(duhl.DuhlError) as e:
+        p.g.run(n + 1, 2)
+    assert e.value.status == duhl.EINVAL
+    p.g.select(m)
+    with pytest.raises(duhl.DuhlError) as e:
+        p.g.run(m, 2)                                       # a selection is pending
+    assert e.value.status == duhl.ESTATE
+    p.close()
+
+
+@pytest.mark.parametrize("threads", [0, 3])
+def test_host_resident_rounds_converge_to_the_oracle(G, threads):
+    """Alg. 2 with the matrix in pinned host memory: residents refreshed from their slots, a
+    window of the others over the link (threads = 0) or by host threads while the passes run."""
+    from paper_1708_05357_amd import duhl
+    prob = _lasso(1200, 900, 0.05, 0.1, seed=45)
+    n, m = prob["n"], 120
+    p = G.Pair(prob, budget=2 * m, host_resident=True)
+    perm = torch.randperm(n, generator=torch.Generator().manual_seed(5)).to(torch.int32).cuda()
+    before = p.g.objective()
+    st = p.g.run(m, 200, passes=2, mode=duhl.CD_ASYNC, sample=perm, sample_per_round=n // 5,
+                 host_threads=threads, seed=2)
+    assert st["rounds"] == 200 and st["columns_swapped"] >= m
+    if threads:
+        assert st["host_sampled"] > 0
+    assert p.g.objective() < before
+    a, v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+    p.o.set_state(a.astype(np.float64))                     # v = A alpha - b must still hold
+    assert np.abs(v - p.o.v).max() <= 1e-4 * np.abs(G.to_np(prob["target"])).max()
+    o2 = G.Pair(prob)
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        o2.o.round(m, passes=2, rng=rng)
+    assert abs(p.g.objective() - o2.o.objective()) <= 1e-5 * abs(o2.o.objective())
+    o2.close()
+    p.close()
+    # the stopping rule with confirmation: ends on the true total gap, evaluated over the link
+    p = G.Pair(prob, budget=2 * m, host_resident=True)
+    all_idx = G.dev_i32(np.arange(n))
+    tol = 1e-4 * p.g.gap(all_idx)
+    st = p.g.run(m, 3000, passes=2, mode=duhl.CD_ASYNC, sample=perm, sample_per_round=n // 5,
+                 host_threads=threads, gap_tol=tol, confirm=True, seed=2)
+    assert st["converged"] == 1 and st["confirmations"] >= 1
+    assert p.g.gap(all_idx) == pytest.approx(st["gap_memory_sum"], rel=1e-6)
+    assert st["gap_memory_sum"] <= tol
+    p.close()
