@@ -49,6 +49,7 @@ hipError_t dev_alloc(T **p, int64_t count)
 void free_host_residency(duhl_ctx *c)
 {
     host_sampler_destroy(c);
+    csr_blocked_free(c);
     c->host_base = nullptr;
     (void)hipFree(c->slots); c->slots = nullptr;
     (void)hipFree(c->col_slot); c->col_slot = nullptr;
@@ -182,6 +183,10 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->cd_threads = env_int("DUHL_CD_THREADS", 0);
     c->copy_blocks = env_int("DUHL_COPY_BLOCKS", 8);
     if (c->copy_blocks < 1) c->copy_blocks = 1;
+    c->csr_blocked = env_int("DUHL_CSR_BLOCKED", 1);
+    c->csr_blocked_waves = env_int("DUHL_CSR_BLOCKED_WAVES", 2);
+    if (c->csr_blocked_waves < 1) c->csr_blocked_waves = 1;
+    c->csr_blocked_shape = env_int("DUHL_CSR_BLOCKED_SHAPE", 0);
 
     c->partials_cap = n / 4 + 4096;
     c->blk_cap = (n + 2047) / 2048 + 1;
@@ -287,7 +292,10 @@ duhl_status duhl_set_data_csr(duhl_ctx *c, const int64_t *rowptr, const int32_t 
     HIPCHK(c, hipMemcpy(&last, rowptr + c->n, sizeof(int64_t), hipMemcpyDeviceToHost));
     if (last < 0) return fail(c, DUHL_EINVAL, "rowptr[n] is negative");
     c->nnz = last;
-    return finish_set_data(c, target, lambda);
+    st = finish_set_data(c, target, lambda);
+    if (st != DUHL_OK) return st;
+    HIPCHK(c, csr_blocked_build(c));
+    return DUHL_OK;
 }
 
 duhl_status duhl_gap(duhl_ctx *c, const int32_t *idx, int64_t count, double *gap_sum)

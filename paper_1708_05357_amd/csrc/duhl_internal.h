@@ -177,6 +177,12 @@ struct duhl_ctx {
 
     float *score;               // scores of the non-gap selection rules (allocated on first use)
 
+    // sparse data: copy of the matrix blocked by ranges of v, for the full gap pass (cb_R == 0: none)
+    int64_t *cb_ptr;
+    uint16_t *cb_idx;
+    float *cb_val, *cb_partial;
+    int cb_R, cb_W;
+
     // private buffers of the asynchronous dense workers (allocated on first use)
     float *dv;
     int64_t dv_stride, dv_workers;
@@ -199,6 +205,9 @@ struct duhl_ctx {
     int gap_cols;      // columns per wavefront in the dense gap kernel
     int cd_threads;    // threads per coordinate in the async dense kernel (0 = by d)
     int copy_blocks;   // workgroups of the column-copy kernel
+    int csr_blocked;         // build and use the blocked copy of sparse data
+    int csr_blocked_waves;   // workgroups per compute unit launched by its pass
+    int csr_blocked_shape;   // 100*G + U to force the lanes per span and rows per span (0 = by density)
 
     std::string err;
 };
@@ -225,5 +234,8 @@ hipError_t launch_fill_i32(hipStream_t s, int32_t *p, int64_t n, int32_t value);
 hipError_t launch_fill_f32(hipStream_t s, float *p, int64_t n, float value);
 hipError_t launch_sum_partials(duhl_ctx *c, int64_t count, int scalar_slot);
 void host_sampler_destroy(duhl_ctx *c);
+hipError_t csr_blocked_build(duhl_ctx *c);
+void csr_blocked_free(duhl_ctx *c);
+hipError_t launch_gap_csr_blocked(duhl_ctx *c, int64_t *grid_out);
 
 }  // namespace duhl

@@ -274,6 +274,11 @@ hipError_t launch_gap(duhl_ctx *c, const int32_t *idx, int64_t count, bool slot_
     }
     int64_t grid = 0;
     hipError_t e;
+    if (c->sparse && c->cb_R > 0 && !idx && !slot_list && !with_norms && count == c->n) {
+        e = launch_gap_csr_blocked(c, &grid);            // full pass: from the blocked copy
+        if (e != hipSuccess) return e;
+        return launch_sum_partials(c, grid, S_GAP_SUM);
+    }
     if (c->model == DUHL_LASSO)
         e = with_norms ? launch_gap_model<DUHL_LASSO, true>(c, a, &grid)
                        : launch_gap_model<DUHL_LASSO, false>(c, a, &grid);

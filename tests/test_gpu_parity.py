@@ -88,6 +88,40 @@ def test_svm_gaps_match_oracle_dense_and_csr(G):
         p.close()
 
 
+@pytest.mark.parametrize("n,d,density", [
+    (3000, 400, 0.02),        # one range, ~8 non-zeros per row: several rows per group of lanes
+    (2000, 50000, 0.002),     # two ranges, ~50 per segment
+    (1500, 80000, 0.004),     # three ranges, ~107 per segment
+    (1200, 3000, 0.1),        # one range, ~300 per row: a wavefront per row
+    (700, 2000, 0.3),         # ~600 per row, four quads per lane
+    (900, 36865, 0.001),      # range boundary one past a multiple of the range size, d % 4 != 0
+])
+def test_sparse_full_gap_pass_from_the_blocked_copy(G, n, d, density):
+    """The full gap pass over CSR data runs from the library's range-blocked copy of the matrix;
+    every shape of that kernel must give the oracle's gaps (App. E), and the same values as the
+    plain CSR kernel that serves index lists."""
+    from paper_1708_05357_amd import duhl, synth
+    prob = synth.svm_csr(n, d, density, seed=11)
+    p = G.Pair(prob)
+    rng = np.random.default_rng(1)
+    for rnd in range(2):
+        p.g.select(n // 3)
+        p.g.commit_swap()
+        p.g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(rng.permutation(p.g.get(duhl.P)).astype(np.int32)))
+    p.sync_oracle_to_gpu_state()
+    total = p.g.gap()                                        # blocked copy
+    z_blocked = p.g.get(duhl.Z)
+    assert total == pytest.approx(p.o.gaps(), rel=1e-4)
+    G.assert_gaps_close(z_blocked, p.o.z, floor=8 * 2.0 ** -24 / n)
+    assert total == pytest.approx(float(z_blocked.astype(np.float64).sum()), rel=1e-9)
+    p.g.set(duhl.Z, np.full(n, -1.0, dtype=np.float32))
+    p.g.gap(G.dev_i32(np.arange(n)), want_sum=False)         # index list: plain CSR kernel
+    z_plain = p.g.get(duhl.Z)
+    G.assert_gaps_close(z_plain, p.o.z, floor=8 * 2.0 ** -24 / n)
+    np.testing.assert_allclose(z_blocked, z_plain, rtol=1e-4, atol=8 * 2.0 ** -24 / n)
+    p.close()
+
+
 @pytest.mark.parametrize("eta", [1.0, 0.3])
 def test_elastic_net_gaps_steps_and_objective_match_oracle(G, eta):
     """App. D elastic-net step and the gap of eq. (4) (ridge gap of App. E for eta = 1): gap vectors,
