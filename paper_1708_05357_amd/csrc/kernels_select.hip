@@ -14,7 +14,9 @@ namespace duhl {
 
 namespace {
 
-constexpr int kChunk = 2048;   // elements per workgroup in the count / scatter passes
+constexpr int kChunk = 2048;   // fewest elements per workgroup in the count / scatter passes
+constexpr int kMaxGroups = 128;   // most workgroups per selection launch: each one ends with a fence
+                                  // and a ticket, which cost more than reading 8 KB more of z
 
 __device__ __forceinline__ uint32_t zkey(float z)
 {
@@ -72,13 +74,25 @@ __global__ __launch_bounds__(256) void select_hist_kernel(const float *z, const 
     __syncthreads();
     const uint32_t prefix = st->prefix;
     double zsum = 0.0;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-        const float zi = z[i];
-        const uint32_t key = zkey(zi);
-        bool in_bucket = true;
-        if constexpr (PASS == 0) zsum += (double)zval[i];
-        else in_bucket = (key >> (kShift + kBits)) == prefix;
-        if (in_bucket) atomicAdd(&hist[(key >> kShift) & (kBins - 1)], 1u);
+    // eight independent loads per thread in flight: the pass is bound by their latency
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < n; i0 += 8 * stride) {
+        float zi[8], zv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t i = i0 + u * stride;
+            zi[u] = i < n ? z[i] : 0.0f;
+            if constexpr (PASS == 0) zv[u] = i < n ? zval[i] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            if (i0 + u * stride >= n) continue;
+            const uint32_t key = zkey(zi[u]);
+            bool in_bucket = true;
+            if constexpr (PASS == 0) zsum += (double)zv[u];
+            else in_bucket = (key >> (kShift + kBits)) == prefix;
+            if (in_bucket) atomicAdd(&hist[(key >> kShift) & (kBins - 1)], 1u);
+        }
     }
     __syncthreads();
     for (int i = threadIdx.x; i < kBins; i += 256)
@@ -129,22 +143,28 @@ __global__ __launch_bounds__(256) void select_hist_kernel(const float *z, const 
 
 // Per chunk of kChunk consecutive entries: how many lie above the threshold key and how many
 // equal it; the last workgroup turns the counts into exclusive prefixes.
-__global__ __launch_bounds__(256) void select_count_kernel(const float *z, int64_t n,
+__global__ __launch_bounds__(256) void select_count_kernel(const float *z, int64_t n, int chunk,
                                                            SelectState *st, uint32_t *blk_gt,
                                                            uint32_t *blk_eq)
 {
     __shared__ uint32_t sg[4], se[4];
     __shared__ uint32_t pg[256], pe[256];
     const uint32_t thr = st->prefix;
-    const int64_t base = (int64_t)blockIdx.x * kChunk;
+    const int64_t base = (int64_t)blockIdx.x * chunk;
     uint32_t g = 0, e = 0;
+    for (int it0 = 0; it0 < chunk / 256; it0 += 8) {     // chunk is a multiple of 8 tiles of 256
+        float zi[8];
 #pragma unroll
-    for (int it = 0; it < kChunk / 256; ++it) {
-        const int64_t i = base + it * 256 + threadIdx.x;
-        if (i < n) {
-            const uint32_t key = zkey(z[i]);
-            g += key > thr;
-            e += key == thr;
+        for (int u = 0; u < 8; ++u) {
+            const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
+            zi[u] = i < n ? z[i] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
+            const uint32_t key = zkey(zi[u]);
+            g += i < n && key > thr;
+            e += i < n && key == thr;
         }
     }
 #pragma unroll
@@ -181,7 +201,7 @@ __global__ __launch_bounds__(256) void select_count_kernel(const float *z, int64
 
 // Ordered scatter: entry i goes to position (#selected entries with a smaller index).
 __global__ __launch_bounds__(256) void select_scatter_kernel(const float *z, int64_t n, int64_t m,
-                                                             SelectState *st,
+                                                             int chunk, SelectState *st,
                                                              const uint32_t *blk_gt,
                                                              const uint32_t *blk_eq, int32_t *P,
                                                              int32_t *P_out, double *partials,
@@ -192,15 +212,21 @@ __global__ __launch_bounds__(256) void select_scatter_kernel(const float *z, int
     const uint32_t thr = st->prefix, take_eq = st->remaining;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     uint32_t gt_before = blk_gt[blockIdx.x], eq_before = blk_eq[blockIdx.x];
-    const int64_t base = (int64_t)blockIdx.x * kChunk;
+    const int64_t base = (int64_t)blockIdx.x * chunk;
     double ssel = 0.0;
-    for (int it = 0; it < kChunk / 256; ++it) {
-        const int64_t i = base + it * 256 + threadIdx.x;
-        float zi = 0.0f;
+    for (int it0 = 0; it0 < chunk / 256; it0 += 8) {     // chunk is a multiple of 8 tiles of 256
+      float zpre[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+          const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
+          zpre[u] = i < n ? z[i] : 0.0f;
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
         bool g = false, e = false;
         if (i < n) {
-            zi = z[i];
-            const uint32_t key = zkey(zi);
+            const uint32_t key = zkey(zpre[u]);
             g = key > thr;
             e = key == thr;
         }
@@ -225,6 +251,7 @@ __global__ __launch_bounds__(256) void select_scatter_kernel(const float *z, int
         gt_before += tg;
         eq_before += te;
         __syncthreads();
+      }
     }
     ssel = wave_sum(ssel);
     if (lane == 0) dsh[w] = ssel;
@@ -280,12 +307,21 @@ __global__ void mark_set_kernel(uint8_t *mark, const int32_t *list, int64_t coun
     if (k < count) mark[list[k]] = 1;
 }
 // Device residency: how many selected coordinates were not in the current set (marked).
-__global__ void count_new_kernel(const int32_t *P, int64_t m, const uint8_t *mark, SelectState *st)
+__global__ __launch_bounds__(256) void count_new_kernel(const int32_t *P, int64_t m, const uint8_t *mark,
+                                                        SelectState *st)
 {
-    const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const bool fresh = k < m && mark[P[k]] == 0;
-    const unsigned long long b = __ballot(fresh);
-    if ((threadIdx.x & 63) == 0 && b) atomicAdd(&st->n_fill, (uint32_t)__popcll(b));
+    __shared__ uint32_t part[4];
+    uint32_t mine = 0;
+    for (int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x; k < m; k += (int64_t)gridDim.x * 256)
+        mine += mark[P[k]] == 0;
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o, kWave);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = mine;
+    __syncthreads();
+    if (threadIdx.x == 0) {                      // one atomic per workgroup on the shared counter
+        const uint32_t t = part[0] + part[1] + part[2] + part[3];
+        if (t) atomicAdd(&st->n_fill, t);
+    }
 }
 // Selected columns that are in no device slot.
 __global__ void find_fill_kernel(const int32_t *P, int64_t m, const int32_t *col_slot,
@@ -378,17 +414,19 @@ hipError_t launch_select(duhl_ctx *c, int64_t m, int32_t *P_out, const float *ke
     const int64_t n = c->n;
     hipLaunchKernelGGL(select_reset_kernel, dim3(1), dim3(1024), 0, s, c->sel, (uint32_t)m);
     int64_t hgrid = (n + 2047) / 2048;
-    if (hgrid > 1024) hgrid = 1024;
+    if (hgrid > kMaxGroups) hgrid = kMaxGroups;
     hipLaunchKernelGGL(select_hist_kernel<0>, dim3(hgrid), dim3(256), 0, s, keys, c->z, n, c->sel,
                        c->partials, c->scalars);
     hipLaunchKernelGGL(select_hist_kernel<1>, dim3(hgrid), dim3(256), 0, s, keys, c->z, n, c->sel,
                        c->partials, c->scalars);
     hipLaunchKernelGGL(select_hist_kernel<2>, dim3(hgrid), dim3(256), 0, s, keys, c->z, n, c->sel,
                        c->partials, c->scalars);
-    const int64_t nb = (n + kChunk - 1) / kChunk;
-    hipLaunchKernelGGL(select_count_kernel, dim3(nb), dim3(256), 0, s, keys, n, c->sel, c->blk_gt,
+    int64_t chunk = ((n + kMaxGroups - 1) / kMaxGroups + kChunk - 1) / kChunk * kChunk;   // whole 8-tile batches
+    if (chunk < kChunk) chunk = kChunk;
+    const int64_t nb = (n + chunk - 1) / chunk;
+    hipLaunchKernelGGL(select_count_kernel, dim3(nb), dim3(256), 0, s, keys, n, (int)chunk, c->sel, c->blk_gt,
                        c->blk_eq);
-    hipLaunchKernelGGL(select_scatter_kernel, dim3(nb), dim3(256), 0, s, keys, n, m, c->sel,
+    hipLaunchKernelGGL(select_scatter_kernel, dim3(nb), dim3(256), 0, s, keys, n, m, (int)chunk, c->sel,
                        c->blk_gt, c->blk_eq, c->P_next, P_out, c->partials, c->scalars, c->z);
     return hipGetLastError();
 }
@@ -403,8 +441,9 @@ hipError_t launch_plan_swap(duhl_ctx *c, bool overlap_safe)
         if (c->m_cur > 0)
             hipLaunchKernelGGL(mark_set_kernel, dim3((c->m_cur + T - 1) / T), dim3(T), 0, s, c->mark,
                                c->P_cur, c->m_cur);
-        hipLaunchKernelGGL(count_new_kernel, dim3((m + T - 1) / T), dim3(T), 0, s, c->P_next, m,
-                           c->mark, c->sel);
+        int64_t cgrid = (m + 2047) / 2048;
+        if (cgrid > kMaxGroups) cgrid = kMaxGroups;
+        hipLaunchKernelGGL(count_new_kernel, dim3(cgrid), dim3(256), 0, s, c->P_next, m, c->mark, c->sel);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(mark_set_kernel, dim3((m + T - 1) / T), dim3(T), 0, s, c->mark, c->P_next, m);
