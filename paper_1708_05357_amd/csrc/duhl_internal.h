@@ -102,18 +102,64 @@ __device__ __forceinline__ float4 stream_load4(const float4 *p)
     return make_float4(t.x, t.y, t.z, t.w);
 }
 
-// Sum over the 64 lanes of a wavefront; every lane receives the result.
+// Cross-lane moves as DPP modifiers of ordinary vector instructions (full rate) rather than trips
+// through the LDS crossbar.  Controls: quad_perm patterns (one byte, two bits per lane of a
+// quad), row_ror:n = 0x120 + n (rotation inside a row of 16 lanes), row_half_mirror = 0x141.
+template <int CTRL>
+__device__ __forceinline__ int dpp_mov(int x)
+{
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, false);
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_add(float x)
+{
+    return x + __int_as_float(dpp_mov<CTRL>(__float_as_int(x)));
+}
+template <int CTRL>
+__device__ __forceinline__ int64_t dpp_mov64(int64_t x)
+{
+    const int lo = dpp_mov<CTRL>((int)(uint32_t)x), hi = dpp_mov<CTRL>((int)(x >> 32));
+    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
+}
+template <int CTRL>
+__device__ __forceinline__ double dpp_add(double x)
+{
+    return x + __longlong_as_double(dpp_mov64<CTRL>(__double_as_longlong(x)));
+}
+
+// Sum over the 64 lanes of a wavefront; every lane receives the result.  All lanes must be
+// active.  Rotations by 8, 4, 2, 1 give every lane the sum of its row of 16; the four row sums
+// are then read from one lane each.
+template <typename F>
+__device__ __forceinline__ F row_sum16(F x)
+{
+    x = dpp_add<0x128>(x);
+    x = dpp_add<0x124>(x);
+    x = dpp_add<0x122>(x);
+    x = dpp_add<0x121>(x);
+    return x;
+}
 __device__ __forceinline__ float wave_sum(float x)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
-    return x;
+    const int r = __float_as_int(row_sum16(x));
+    const float r0 = __int_as_float(__builtin_amdgcn_readlane(r, 0));
+    const float r1 = __int_as_float(__builtin_amdgcn_readlane(r, 16));
+    const float r2 = __int_as_float(__builtin_amdgcn_readlane(r, 32));
+    const float r3 = __int_as_float(__builtin_amdgcn_readlane(r, 48));
+    return (r0 + r1) + (r2 + r3);
 }
 __device__ __forceinline__ double wave_sum(double x)
 {
+    const int64_t r = __double_as_longlong(row_sum16(x));
+    const int lo = (int)(uint32_t)r, hi = (int)(r >> 32);
+    double part[4];
 #pragma unroll
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
-    return x;
+    for (int k = 0; k < 4; ++k) {
+        const uint32_t l = (uint32_t)__builtin_amdgcn_readlane(lo, 16 * k);
+        const uint32_t h = (uint32_t)__builtin_amdgcn_readlane(hi, 16 * k);
+        part[k] = __longlong_as_double((int64_t)(((uint64_t)h << 32) | l));
+    }
+    return (part[0] + part[1]) + (part[2] + part[3]);
 }
 // Sum over aligned groups of G lanes (G a power of two <= 64).
 template <int G>

@@ -249,6 +249,11 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
         const float *col = a.cv.col(j);
         const __amdgpu_buffer_rsrc_t rs_x =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(col), 0, vec_bytes, 0x00020000);
+        // the scalars of the step are requested before the column, so that nothing issued later
+        // (loads complete in order) stands between the reduced dot product and the update
+        const float old = a.alpha[j];
+        const float qj = a.q[j];
+        const float y = MODEL == DUHL_SVM ? a.target[j] : 0.0f;
         float4 x[CACHE_X ? NC : 1];
         float acc = 0.0f;
         if (CACHE_X) {
@@ -283,9 +288,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
         const float c = group_reduce<T>(acc, red, parity);
         parity ^= 1;
 
-        const float old = a.alpha[j];
-        const float y = MODEL == DUHL_SVM ? a.target[j] : 0.0f;
-        const float now = cd_new_alpha<MODEL>(a.mc, c, old, a.q[j], y);
+        const float now = cd_new_alpha<MODEL>(a.mc, c, old, qj, y);
         const float delta = now - old;
         if (delta != 0.0f) {
             int offu = off;

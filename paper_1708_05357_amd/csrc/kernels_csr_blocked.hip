@@ -198,26 +198,6 @@ __device__ __forceinline__ void add_batch(const float *vs, int q0, const int (&r
     }
 }
 
-// Cross-lane moves inside a group of lanes as DPP modifiers of ordinary vector instructions
-// (full rate) rather than trips through the LDS crossbar.  Controls: quad_perm patterns (one byte,
-// two bits per lane of a quad), row_ror:n = 0x120 + n, row_half_mirror = 0x141.
-template <int CTRL>
-__device__ __forceinline__ int dpp_mov(int x)
-{
-    return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, false);
-}
-template <int CTRL>
-__device__ __forceinline__ float dpp_add(float x)
-{
-    return x + __int_as_float(dpp_mov<CTRL>(__float_as_int(x)));
-}
-template <int CTRL>
-__device__ __forceinline__ int64_t dpp_mov64(int64_t x)
-{
-    const int lo = dpp_mov<CTRL>((int)(uint32_t)x), hi = dpp_mov<CTRL>((int)(x >> 32));
-    return (int64_t)(((uint64_t)(uint32_t)hi << 32) | (uint32_t)lo);
-}
-
 // Sum over the G lanes of a group; every lane gets it.
 template <int G>
 __device__ __forceinline__ float span_group_sum(float x)
