@@ -315,16 +315,18 @@ def main():
     ap.add_argument("--inflight", type=int, default=0, help="max_inflight of duhl_cd_epoch (0 = default)")
     ap.add_argument("--select-rule", default="gap", choices=["gap", "random", "block"],
                     help="working-set rule: eq. (13), or one of the paper's reference schemes")
-    ap.add_argument("--passes", type=int, default=1,
+    ap.add_argument("--passes", type=int, default=None,
                     help="CD passes per round (theta of Section 5.2); 0 with host residency: as many, "
-                         "up to 8, as fit beside the round's column copies")
+                         "up to 8, as fit beside the round's column copies; default 1, and 4 with host "
+                         "residency, where the passes are also the time unit A's sampler has per round")
     ap.add_argument("--min-passes", type=int, default=1, help="lower bound for --passes 0")
     ap.add_argument("--gap-sample", type=float, default=1.0,
                     help="device residency: refresh only the working set and this fraction of all "
                          "coordinates per round (stale gap memory, Section 4.1) instead of every gap")
-    ap.add_argument("--host-sampler-threads", type=int, default=0,
+    ap.add_argument("--host-sampler-threads", type=int, default=-1,
                     help="host residency: refresh the gap sample with this many host threads while the "
-                         "GPU runs the pass (Algorithm 2, lines 7-10) instead of over the host link")
+                         "GPU runs the pass (Algorithm 2, lines 7-10); 0: the GPU evaluates the sample "
+                         "over the host link instead; default 12 (a one-GPU share of the host's cores)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures the single-GPU hot path; this build has no multi-GPU path "
@@ -333,6 +335,10 @@ def main():
 
     if args.scale is None:
         args.scale = 0.4 if args.workload == "cfg4" else 1.0
+    if args.host_sampler_threads < 0:
+        args.host_sampler_threads = 12
+    if args.passes is None:
+        args.passes = 4 if args.workload == "cfg4" else 1
     import torch
     from paper_1708_05357_amd import duhl
     assert torch.cuda.is_available(), "bench.py needs a GPU"
@@ -422,7 +428,8 @@ def main():
                                + (f" host-resident, {budget} device slots" if prob["host_resident"] else ""),
                    "scale": args.scale, "rounds_timed": args.steps, "passes_per_round": args.passes if auto is None else passes_timed,
                    "cd_scheme": args.cd_mode, "max_inflight": args.inflight, "select_rule": args.select_rule,
-                   "gap_sample": args.gap_sample},
+                   "gap_sample": args.gap_sample,
+                   "host_sampler_threads": args.host_sampler_threads if prob["host_resident"] else None},
         "phases": {"gap_ms": avg(gap_ms), "select_ms": avg(sel_ms), "cd_ms": avg(cd_ms),
                    "gap_GBps": gap_gbps, "gap_frac_of_hbm_peak": gap_gbps / HBM_PEAK_GBPS,
                    "cd_updates_per_s": m * total_passes / args.steps / (avg(cd_ms) * 1e-3), "cd_GBps": cd_gbps,
