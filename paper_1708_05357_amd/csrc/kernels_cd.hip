@@ -214,7 +214,11 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_atomic_kernel(cons
 // touches its own LDS entries, so no barrier is needed for them).  CACHE_X keeps the column in
 // registers between the dot product and the update (one read per update); without it (very long
 // columns: the registers are needed for v) the column is read again, only when alpha_j moved.
-template <int MODEL, int T, int NR, int NL, bool CACHE_X>
+// EXT: columns longer than registers and LDS can hold a copy of v for (T*(NR+NL) float4).  The rest
+// of the worker's copy lives in its private buffer in device memory -- 400 KB or more per worker
+// that it re-reads for every coordinate, so it is served by L2 / the memory-side cache while the
+// column streams from HBM.  Each thread only touches its own rows there as well.
+template <int MODEL, int T, int NR, int NL, bool CACHE_X, bool EXT = false>
 __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
     const CdArgs a, const int64_t t_begin, const int64_t t_end, float *dv, const int64_t dv_stride,
     int32_t *dirty)
@@ -234,6 +238,18 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
     const int vec_bytes = (int)(d4 << 4);              // 16-byte part of a column; loads beyond it
     const int off = tid * 16;                          // return 0 (buffer bounds check)
     const __amdgpu_buffer_rsrc_t rs_v = __builtin_amdgcn_make_buffer_rsrc(a.v, 0, vec_bytes, 0x00020000);
+    float *const out = dv + (int64_t)w * dv_stride;    // this worker's private buffer
+    const __amdgpu_buffer_rsrc_t rs_o = __builtin_amdgcn_make_buffer_rsrc(out, 0, vec_bytes, 0x00020000);
+    const int nch = (int)((d4 + T - 1) / T);           // chunks per thread that cover a column
+    if (EXT) {                                         // rows beyond the on-chip copy: start from v
+        for (int i0 = NC; i0 < nch; i0 += 8) {
+            float4 vb[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) vb[u] = buffer_load4(rs_v, off, (i0 + u) * kStep);
+#pragma unroll
+            for (int u = 0; u < 8; ++u) buffer_store4(rs_o, off, (i0 + u) * kStep, vb[u]);
+        }
+    }
 
     float4 vr[NR > 0 ? NR : 1];                        // rows 4*(tid + i*T) .. of this worker's v
 #pragma unroll
@@ -282,6 +298,19 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
                 }
                 asm volatile("" : "+v"(offb), "+v"(acc));
             }
+            if (EXT) {
+                for (int i0 = NC; i0 < nch; i0 += KB) {
+                    float4 xb[KB], vb[KB];
+#pragma unroll
+                    for (int u = 0; u < KB; ++u) {
+                        xb[u] = buffer_stream4(rs_x, offb, (i0 + u) * kStep);
+                        vb[u] = buffer_load4(rs_o, offb, (i0 + u) * kStep);
+                    }
+#pragma unroll
+                    for (int u = 0; u < KB; ++u) acc = dot4(xb[u], vb[u], acc);
+                    asm volatile("" : "+v"(offb), "+v"(acc));
+                }
+            }
         }
         const float xt = tid < tail ? col[(d4 << 2) + tid] : 0.0f;
         acc = fmaf(xt, vt, acc);
@@ -321,14 +350,31 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
                 }
                 if (!CACHE_X) asm volatile("" : "+v"(offu), "+v"(tie));
             }
+            if (EXT) {
+                for (int i0 = NC; i0 < nch; i0 += KB) {
+                    float4 xb[KB], vb[KB];
+#pragma unroll
+                    for (int u = 0; u < KB; ++u) {
+                        xb[u] = buffer_load4(rs_x, offu, (i0 + u) * kStep);
+                        vb[u] = buffer_load4(rs_o, offu, (i0 + u) * kStep);
+                    }
+#pragma unroll
+                    for (int u = 0; u < KB; ++u) {
+                        vb[u].x = fmaf(xb[u].x, delta, vb[u].x);
+                        vb[u].y = fmaf(xb[u].y, delta, vb[u].y);
+                        vb[u].z = fmaf(xb[u].z, delta, vb[u].z);
+                        vb[u].w = fmaf(xb[u].w, delta, vb[u].w);
+                        buffer_store4(rs_o, offu, (i0 + u) * kStep, vb[u]);   // beyond the end: dropped
+                    }
+                    asm volatile("" : "+v"(offu));
+                }
+            }
             vt = fmaf(xt, delta, vt);
             moved = true;
             if (tid == 0) a.alpha[j] = now;
         }
     }
     if (moved) {                                       // this worker's change of v
-        float *out = dv + (int64_t)w * dv_stride;
-        const __amdgpu_buffer_rsrc_t rs_o = __builtin_amdgcn_make_buffer_rsrc(out, 0, vec_bytes, 0x00020000);
         int offo = off;
 #pragma unroll
         for (int i = 0; i < NC; ++i) {
@@ -338,6 +384,22 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
                           make_float4(mine.x - base.x, mine.y - base.y, mine.z - base.z,
                                       mine.w - base.w));                   // beyond the end: dropped
             if (!CACHE_X && (i & 3) == 3) asm volatile("" : "+v"(offo), "+v"(base.x));
+        }
+        if (EXT) {                                     // the copy in the buffer becomes a difference
+            for (int i0 = NC; i0 < nch; i0 += 4) {
+                float4 base[4], mine[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    base[u] = buffer_load4(rs_v, offo, (i0 + u) * kStep);
+                    mine[u] = buffer_load4(rs_o, offo, (i0 + u) * kStep);
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+                    buffer_store4(rs_o, offo, (i0 + u) * kStep,
+                                  make_float4(mine[u].x - base[u].x, mine[u].y - base[u].y,
+                                              mine[u].z - base[u].z, mine[u].w - base[u].w));
+                asm volatile("" : "+v"(offo));
+            }
         }
         if (tid < tail) out[(d4 << 2) + tid] = vt - a.v[(d4 << 2) + tid];
     }
@@ -612,7 +674,7 @@ hipError_t launch_atomic(duhl_ctx *c, const CdArgs &a, int max_inflight, bool ve
     return launch_atomic_dense_n<MODEL, 1024>(c, a, (int)inflight, vec);
 }
 
-template <int MODEL, int T, int NR, int NL, bool CACHE_X>
+template <int MODEL, int T, int NR, int NL, bool CACHE_X, bool EXT = false>
 hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
 {
     constexpr int BLOCK = T == 64 ? 256 : T;
@@ -626,7 +688,7 @@ hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
         int64_t workers = len >= 4 * (int64_t)c->num_cu ? len / 4 : (len < c->num_cu ? len : c->num_cu);
         if (workers > cap) workers = cap;
         const int64_t grid = (workers + PER - 1) / PER;
-        hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, T, NR, NL, CACHE_X>), dim3(grid), dim3(BLOCK), 0,
+        hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, T, NR, NL, CACHE_X, EXT>), dim3(grid), dim3(BLOCK), 0,
                            c->compute, a, t0, t1, c->dv, c->dv_stride, c->dirty);
         hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 63) / 64), dim3(1024), 0, c->compute, a.v,
                            c->d, c->dv, c->dv_stride, c->dirty, (int)(grid * PER));
@@ -640,7 +702,8 @@ bool launch_workers(duhl_ctx *c, const CdArgs &a, int max_inflight, bool vec, hi
 {
     const int T = threads_per_coordinate(c);
     const int64_t chunks = ((c->d >> 2) + T - 1) / T;
-    if (!vec || chunks > 25) return false;
+    // 32-bit byte offsets inside a column and a sane private-buffer size bound the extended variant
+    if (!vec || chunks > 25 * 64) return false;
     if (!c->dv) {                                   // private buffers, allocated on first use
         c->dv_stride = (c->d + 63) / 64 * 64;
         int64_t workers = (int64_t)c->num_cu * (T == 1024 ? 1 : (T == 256 ? 4 : 16));
@@ -670,7 +733,8 @@ bool launch_workers(duhl_ctx *c, const CdArgs &a, int max_inflight, bool vec, hi
         else if (chunks <= 13) DUHL_W(1024, 8, 5, true);
         else if (chunks <= 16) DUHL_W(1024, 12, 4, false);
         else if (chunks <= 20) DUHL_W(1024, 14, 6, false);
-        else DUHL_W(1024, 16, 9, false);
+        else if (chunks <= 25) DUHL_W(1024, 16, 9, false);
+        else *err = launch_workers_t<MODEL, 1024, 16, 9, false, true>(c, a, inflight);   // rest of v in the buffer
     }
 #undef DUHL_W
     return true;

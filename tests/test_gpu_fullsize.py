@@ -277,3 +277,67 @@ def test_cfg4_shape_host_resident_sampled_columns_and_swap(G):
     want = sub.T @ a2[nz].astype(np.float64) - b[rows]
     assert np.abs(v2[rows] - want).max() <= 1e-4 * np.abs(b).max()
     g.close()
+
+
+def test_paper_svm_shape_sampled_columns(G):
+    """Dense SVM dual with the shape of the paper's large experiment (Section 5.3): 40,000 samples of
+    200,704 features, 32 GB in HBM, a quarter of the samples in the working set.  Columns this long
+    exceed what registers and LDS hold of a private copy of v, so the asynchronous pass runs the
+    variant that keeps the rest of the copy in device memory."""
+    from oracle import duhl_oracle as orc
+    from paper_1708_05357_amd import duhl, synth
+    free, total = torch.cuda.mem_get_info()
+    if free < 80e9:
+        pytest.skip("needs 80 GB of free HBM")
+    prob = synth.make("fig5svm", device="cuda")
+    d, n, m = prob["d"], prob["n"], prob["m"]
+    g = duhl.Duhl(duhl.SVM, d, n, m)
+    g.set_data_dense(prob["cols"], prob["target"], prob["lam"])
+    y = prob["target"].cpu().numpy()
+    rng = np.random.default_rng(9)
+    assert g.gap() == pytest.approx(1.0, rel=1e-6)                 # App. E: z_i = 1/n at alpha = 0
+    np.testing.assert_allclose(g.get(duhl.SQNORM), 1.0, rtol=1e-5)
+
+    def oracle_on(idx):
+        cols = prob["cols"][torch.as_tensor(idx, device="cuda")].cpu().numpy()
+        full = orc.Oracle(orc.SVM, y[idx], prob["lam"] * n / idx.size, cols=cols)   # lambda*n is what enters
+        full.set_state(g.get(duhl.ALPHA)[idx].astype(np.float64), g.get(duhl.V).astype(np.float64))
+        return full
+
+    objs = [g.objective()]
+    for rnd in range(3):
+        g.select(m, want_stats=False)
+        g.commit_swap()
+        before = g.get(duhl.ALPHA)
+        g.cd_epoch(duhl.CD_ASYNC, seed=rnd)
+        objs.append(g.objective())
+        P = g.get(duhl.P)
+        moved = np.flatnonzero(g.get(duhl.ALPHA) != before)
+        assert np.all(np.isin(moved, P))
+        total = g.gap()
+        z = g.get(duhl.Z)
+        assert total == pytest.approx(float(z.astype(np.float64).sum()), rel=1e-6)
+        idx = np.unique(np.concatenate([rng.choice(P, 150, replace=False), rng.integers(0, n, 150)]))
+        o = oracle_on(idx)
+        o.gaps()
+        # the oracle was built on a subsample, so its 1/n is 1/len(idx): rescale
+        want = o.z * idx.size / n
+        assert np.abs(z[idx] - want).max() <= 1e-4 * max(want.max(), z[idx].max()) + 8 * 2.0 ** -24 / n
+    assert all(b <= a * (1 - 1e-6) for a, b in zip(objs, objs[1:]))          # the dual objective falls
+    # exact steps on sampled members of the working set, against the oracle on the same v
+    P = g.get(duhl.P)
+    step_cols = np.sort(rng.choice(P, 120, replace=False))
+    o = oracle_on(step_cols)
+    order = rng.permutation(step_cols.size).astype(np.int32)
+    g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(step_cols[order]))
+    o.cd_pass(order)
+    a2, v2 = g.get(duhl.ALPHA), g.get(duhl.V)
+    assert np.abs(a2[step_cols] - o.alpha).max() <= 1e-5 * max(np.abs(o.alpha).max(), 1e-30)
+    assert np.abs(v2 - o.v).max() <= 1e-5 * np.abs(o.v).max()
+    # v = A alpha on sampled rows
+    nz = np.flatnonzero(a2)
+    rows = torch.as_tensor(rng.integers(0, d, 32), device="cuda")
+    sub = prob["cols"][torch.as_tensor(nz, device="cuda")[:, None], rows[None, :]].double()
+    want = (sub.t() @ torch.as_tensor(a2[nz], device="cuda").double()).cpu().numpy()
+    assert np.abs(v2[rows.cpu().numpy()] - want).max() <= 1e-4 * max(np.abs(want).max(), 1e-30)
+    g.close()
