@@ -91,6 +91,22 @@ __device__ __forceinline__ float4 buffer_stream4(__amdgpu_buffer_rsrc_t rs, int 
     return make_float4(__int_as_float(raw.x), __int_as_float(raw.y), __int_as_float(raw.z),
                        __int_as_float(raw.w));
 }
+// Column data whose start is only 4-byte aligned (leading dimension not a multiple of four floats):
+// the same 16 bytes as four dword loads.  STREAM selects the non-temporal hint.
+template <bool XVEC, bool STREAM>
+__device__ __forceinline__ float4 column_load4(__amdgpu_buffer_rsrc_t rs, int voff, int soff)
+{
+    constexpr int kAux = STREAM ? 2 : 0;
+    if (XVEC) {
+        const v4i_t raw = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, kAux);
+        return make_float4(__int_as_float(raw.x), __int_as_float(raw.y), __int_as_float(raw.z),
+                           __int_as_float(raw.w));
+    }
+    return make_float4(__int_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff, kAux)),
+                       __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff + 4, kAux)),
+                       __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff + 8, kAux)),
+                       __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(rs, voff, soff + 12, kAux)));
+}
 __device__ __forceinline__ void buffer_store4(__amdgpu_buffer_rsrc_t rs, int voff, int soff, float4 x)
 {
     v4i_t raw;
@@ -218,7 +234,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_atomic_kernel(cons
 // of the worker's copy lives in its private buffer in device memory -- 400 KB or more per worker
 // that it re-reads for every coordinate, so it is served by L2 / the memory-side cache while the
 // column streams from HBM.  Each thread only touches its own rows there as well.
-template <int MODEL, int T, int NR, int NL, bool CACHE_X, bool EXT = false>
+template <int MODEL, int T, int NR, int NL, bool CACHE_X, bool EXT = false, bool XVEC = true>
 __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
     const CdArgs a, const int64_t t_begin, const int64_t t_end, float *dv, const int64_t dv_stride,
     int32_t *dirty)
@@ -274,7 +290,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
         float acc = 0.0f;
         if (CACHE_X) {
 #pragma unroll
-            for (int i = 0; i < NC; ++i) x[i] = buffer_stream4(rs_x, off, i * kStep);
+            for (int i = 0; i < NC; ++i) x[i] = column_load4<XVEC, true>(rs_x, off, i * kStep);
 #pragma unroll
             for (int i = 0; i < NR; ++i) acc = dot4(x[i], vr[i], acc);
 #pragma unroll
@@ -289,7 +305,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
                 float4 xb[KB];
 #pragma unroll
                 for (int u = 0; u < KB; ++u)
-                    if (i0 + u < NC) xb[u] = buffer_stream4(rs_x, offb, (i0 + u) * kStep);
+                    if (i0 + u < NC) xb[u] = column_load4<XVEC, true>(rs_x, offb, (i0 + u) * kStep);
 #pragma unroll
                 for (int u = 0; u < KB; ++u) {
                     const int i = i0 + u;
@@ -303,7 +319,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
                     float4 xb[KB], vb[KB];
 #pragma unroll
                     for (int u = 0; u < KB; ++u) {
-                        xb[u] = buffer_stream4(rs_x, offb, (i0 + u) * kStep);
+                        xb[u] = column_load4<XVEC, true>(rs_x, offb, (i0 + u) * kStep);
                         vb[u] = buffer_load4(rs_o, offb, (i0 + u) * kStep);
                     }
 #pragma unroll
@@ -327,7 +343,8 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
                 float4 xb[KB];
 #pragma unroll
                 for (int u = 0; u < KB; ++u)
-                    if (i0 + u < NC) xb[u] = CACHE_X ? x[CACHE_X ? i0 + u : 0] : buffer_load4(rs_x, offu, (i0 + u) * kStep);
+                    if (i0 + u < NC)
+                        xb[u] = CACHE_X ? x[CACHE_X ? i0 + u : 0] : column_load4<XVEC, false>(rs_x, offu, (i0 + u) * kStep);
 #pragma unroll
                 for (int u = 0; u < KB; ++u) {
                     const int i = i0 + u;
@@ -355,7 +372,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
                     float4 xb[KB], vb[KB];
 #pragma unroll
                     for (int u = 0; u < KB; ++u) {
-                        xb[u] = buffer_load4(rs_x, offu, (i0 + u) * kStep);
+                        xb[u] = column_load4<XVEC, false>(rs_x, offu, (i0 + u) * kStep);
                         vb[u] = buffer_load4(rs_o, offu, (i0 + u) * kStep);
                     }
 #pragma unroll
@@ -674,7 +691,7 @@ hipError_t launch_atomic(duhl_ctx *c, const CdArgs &a, int max_inflight, bool ve
     return launch_atomic_dense_n<MODEL, 1024>(c, a, (int)inflight, vec);
 }
 
-template <int MODEL, int T, int NR, int NL, bool CACHE_X, bool EXT = false>
+template <int MODEL, int T, int NR, int NL, bool CACHE_X, bool EXT, bool XVEC>
 hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
 {
     constexpr int BLOCK = T == 64 ? 256 : T;
@@ -688,7 +705,7 @@ hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
         int64_t workers = len >= 4 * (int64_t)c->num_cu ? len / 4 : (len < c->num_cu ? len : c->num_cu);
         if (workers > cap) workers = cap;
         const int64_t grid = (workers + PER - 1) / PER;
-        hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, T, NR, NL, CACHE_X, EXT>), dim3(grid), dim3(BLOCK), 0,
+        hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, T, NR, NL, CACHE_X, EXT, XVEC>), dim3(grid), dim3(BLOCK), 0,
                            c->compute, a, t0, t1, c->dv, c->dv_stride, c->dirty);
         hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 63) / 64), dim3(1024), 0, c->compute, a.v,
                            c->d, c->dv, c->dv_stride, c->dirty, (int)(grid * PER));
@@ -703,7 +720,7 @@ bool launch_workers(duhl_ctx *c, const CdArgs &a, int max_inflight, bool vec, hi
     const int T = threads_per_coordinate(c);
     const int64_t chunks = ((c->d >> 2) + T - 1) / T;
     // 32-bit byte offsets inside a column and a sane private-buffer size bound the extended variant
-    if (!vec || chunks > 25 * 64) return false;
+    if (chunks > 25 * 64) return false;
     if (!c->dv) {                                   // private buffers, allocated on first use
         c->dv_stride = (c->d + 63) / 64 * 64;
         int64_t workers = (int64_t)c->num_cu * (T == 1024 ? 1 : (T == 256 ? 4 : 16));
@@ -715,7 +732,10 @@ bool launch_workers(duhl_ctx *c, const CdArgs &a, int max_inflight, bool vec, hi
     }
     const int64_t inflight = inflight_limit(c, a.count, max_inflight);
     // (T, register chunks, LDS chunks, column cached?) by column length
-#define DUHL_W(TT, NR, NL, CX) *err = launch_workers_t<MODEL, TT, NR, NL, CX>(c, a, inflight)
+    // vec: columns start 16-byte aligned; otherwise their loads are split into dwords
+#define DUHL_W(TT, NR, NL, CX)                                                            \
+    *err = vec ? launch_workers_t<MODEL, TT, NR, NL, CX, false, true>(c, a, inflight)     \
+               : launch_workers_t<MODEL, TT, NR, NL, CX, false, false>(c, a, inflight)
     if (T == 64) {
         if (chunks <= 1) DUHL_W(64, 1, 0, true);
         else if (chunks <= 2) DUHL_W(64, 2, 0, true);
@@ -734,7 +754,9 @@ bool launch_workers(duhl_ctx *c, const CdArgs &a, int max_inflight, bool vec, hi
         else if (chunks <= 16) DUHL_W(1024, 12, 4, false);
         else if (chunks <= 20) DUHL_W(1024, 14, 6, false);
         else if (chunks <= 25) DUHL_W(1024, 16, 9, false);
-        else *err = launch_workers_t<MODEL, 1024, 16, 9, false, true>(c, a, inflight);   // rest of v in the buffer
+        else                                            // rest of the private v in the worker's buffer
+            *err = vec ? launch_workers_t<MODEL, 1024, 16, 9, false, true, true>(c, a, inflight)
+                       : launch_workers_t<MODEL, 1024, 16, 9, false, true, false>(c, a, inflight);
     }
 #undef DUHL_W
     return true;
