@@ -82,7 +82,8 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n,
 duhl_status duhl_set_eta(duhl_ctx *ctx, double eta);
 
 /* Dense data (Section 2: A in R^{d x n}, fp32 per Section 5.3).  A: column-major, column i at
- * A + i*ld, ld >= d; a device pointer for DUHL_RESIDENT_DEVICE, a pinned host pointer that the
+ * A + i*ld, ld >= d (fastest when A is 16-byte aligned and ld is a multiple of 4: the kernels
+ * then use 16-byte loads); a device pointer for DUHL_RESIDENT_DEVICE, a pinned host pointer that the
  * device can read for DUHL_RESIDENT_HOST; borrowed.  target (device, borrowed): b of length d
  * for the Lasso and the elastic net, labels y in {+1,-1} of length n for the SVM.  lambda: the lambda of the
  * objectives above, finite and > 0.  Resets alpha = 0, v = -b (Lasso) or 0 (SVM), computes the
