@@ -113,6 +113,7 @@ class Duhl:
         if st != OK:
             raise DuhlError(st, "duhl_create failed")
         self._keep = ()
+        self._empty = None
 
     def _chk(self, st):
         if st != OK:
@@ -152,10 +153,19 @@ class Duhl:
                                              residency, _dptr(target, torch.float32), float(lam)))
 
     # -- the hot path -----------------------------------------------------------------------
+    def _list(self, t):
+        """Pointer of an index list; an empty tensor (whose data pointer is NULL) still means
+        "an empty list", not "no list"."""
+        if t is not None and t.numel() == 0:
+            if self._empty is None:
+                self._empty = torch.zeros(1, dtype=torch.int32, device=self.device)
+            return C.c_void_p(self._empty.data_ptr())
+        return _dptr(t, torch.int32)
+
     def gap(self, idx=None, want_sum=True):
         out = C.c_double(0.0)
         count = 0 if idx is None else idx.numel()
-        self._chk(self.lib.duhl_gap(self._h, _dptr(idx, torch.int32), count,
+        self._chk(self.lib.duhl_gap(self._h, self._list(idx), count,
                                     C.byref(out) if want_sum else None))
         return out.value if want_sum else None
 
@@ -183,7 +193,7 @@ class Duhl:
 
     def cd_epoch(self, mode=CD_ASYNC, order=None, seed=0, max_inflight=0):
         count = 0 if order is None else order.numel()
-        self._chk(self.lib.duhl_cd_epoch(self._h, mode, _dptr(order, torch.int32), count,
+        self._chk(self.lib.duhl_cd_epoch(self._h, mode, self._list(order), count,
                                          C.c_uint64(seed), int(max_inflight)))
 
     def run(self, m, max_rounds, passes=1, mode=CD_ASYNC, gap_tol=-1.0, max_inflight=0, rule=SELECT_GAP,

@@ -587,6 +587,70 @@ def test_zero_columns_and_empty_rows(G):
     p.close()
 
 
+def test_degenerate_problems(G):
+    """What the method does at its corners: a zero target (everything is optimal at alpha = 0), a
+    regulariser at or above ||A^T b||_inf / d (alpha = 0 is optimal, every gap 0: App. E), a single
+    coordinate, m = 1 and m = n, an empty visiting order, an empty refresh list."""
+    from paper_1708_05357_amd import duhl, synth
+    from oracle import duhl_oracle as orc
+    base = lasso_problem(260, 33, 0.2, 0.1, seed=51)
+    # b = 0: v = 0, B = 0, all gaps 0, selection falls back on the index order, rho = 1, nothing moves
+    prob = dict(base)
+    prob["target"] = torch.zeros_like(base["target"])
+    p = G.Pair(prob)
+    assert p.g.gap() == 0.0 and p.g.objective() == 0.0
+    out = torch.empty(5, dtype=torch.int32, device="cuda:0")
+    nsw, rho = p.g.select(5, out)
+    np.testing.assert_array_equal(out.cpu().numpy(), np.arange(5))        # ties: smaller index first
+    assert rho == 1.0
+    p.g.commit_swap()
+    for mode in (duhl.CD_SEQUENTIAL, duhl.CD_ASYNC, duhl.CD_ATOMIC):
+        p.g.cd_epoch(mode)
+    assert not p.g.get(duhl.ALPHA).any() and not p.g.get(duhl.V).any()
+    p.close()
+    # lambda d >= ||A^T b||_inf: alpha = 0 is the optimum, every gap is exactly 0 on both sides
+    A = G.to_np(base["cols"]).astype(np.float64)
+    b = G.to_np(base["target"]).astype(np.float64)
+    prob = dict(base)
+    prob["lam"] = float(np.abs(A @ b).max() * 1.001 / base["d"])
+    p = G.Pair(prob)
+    assert p.g.gap() == 0.0 and p.o.gaps() == 0.0
+    p.g.select(base["n"])
+    p.g.commit_swap()
+    p.g.cd_epoch(duhl.CD_ASYNC)
+    assert not p.g.get(duhl.ALPHA).any()
+    assert p.g.objective() == pytest.approx(p.o.objective(), rel=1e-6)
+    p.close()
+    # one coordinate; m = 1 out of many; m = n; empty lists
+    one = lasso_problem(64, 1, 1.0, 0.1, seed=52)
+    p = G.Pair(one)
+    p.g.select(1)
+    p.g.commit_swap()
+    p.g.cd_epoch(duhl.CD_SEQUENTIAL)
+    p.o.cd_pass(np.zeros(1, dtype=np.int32))
+    np.testing.assert_allclose(p.g.get(duhl.ALPHA), p.o.alpha, rtol=1e-5)
+    p.close()
+    p = G.Pair(base)
+    z32 = p.g.get(duhl.Z)
+    out = torch.empty(1, dtype=torch.int32, device="cuda:0")
+    p.g.select(1, out)
+    assert out.item() == int(np.flatnonzero(z32 == z32.max())[0])
+    p.g.commit_swap()
+    alln = torch.empty(base["n"], dtype=torch.int32, device="cuda:0")
+    nsw, rho = p.g.select(base["n"], alln)
+    np.testing.assert_array_equal(alln.cpu().numpy(), np.arange(base["n"]))
+    assert rho == pytest.approx(1.0)
+    p.g.commit_swap()
+    before = (p.g.get(duhl.ALPHA), p.g.get(duhl.V), p.g.get(duhl.Z))
+    empty = torch.empty(0, dtype=torch.int32, device="cuda:0")
+    for mode in (duhl.CD_SEQUENTIAL, duhl.CD_ASYNC, duhl.CD_ATOMIC):
+        p.g.cd_epoch(mode, empty)
+    assert p.g.gap(empty) == 0.0                                          # nothing refreshed: sum of nothing
+    for x, y in zip(before, (p.g.get(duhl.ALPHA), p.g.get(duhl.V), p.g.get(duhl.Z))):
+        np.testing.assert_array_equal(x, y)
+    p.close()
+
+
 # ------------------------------------------------------------------------------------ reference selection rules
 def test_block_and_random_selection_rules(G):
     """The sequential-block and random reference schemes (Sections 5.1, 5.2): exact block contents
