@@ -156,3 +156,39 @@ def test_host_resident_rounds_converge_to_the_oracle(G, threads):
     assert p.g.gap(all_idx) == pytest.approx(st["gap_memory_sum"], rel=1e-6)
     assert st["gap_memory_sum"] <= tol
     p.close()
+
+
+@pytest.mark.parametrize("threads", [0, 2])
+def test_host_resident_svm_and_elastic_net_rounds(G, threads):
+    """The other two models through the host-resident path (slots, copies, unit A's sampler reads
+    the labels / the elastic-net constants): rounds converge to the oracle's objective."""
+    from paper_1708_05357_amd import duhl, synth
+    sv = synth.svm_dense(700, 260, seed=61)
+    en = dict(synth.lasso_dense(900, 500, 0.05, 0.1, seed=62))
+    en["model"], en["eta"] = "enet", 0.4
+    for prob, m, rounds in ((sv, 150, 250), (en, 80, 150)):
+        n = prob["n"]
+        p = G.Pair(prob, budget=2 * m, host_resident=True)
+        perm = torch.randperm(n, generator=torch.Generator().manual_seed(7)).to(torch.int32).cuda()
+        st = p.g.run(m, rounds, passes=2, mode=duhl.CD_ASYNC, sample=perm, sample_per_round=max(1, n // 4),
+                     host_threads=threads, seed=3)
+        assert st["rounds"] == rounds
+        if threads:
+            assert st["host_sampled"] > 0
+        ref = G.Pair(prob)
+        rng = np.random.default_rng(0)
+        for _ in range(rounds):
+            ref.o.round(m, passes=2, rng=rng)
+        og, oo = p.g.objective(), ref.o.objective()
+        assert abs(og - oo) <= (1e-5 if prob["model"] != "svm" else 1e-4) * abs(oo), (prob["model"], og, oo)
+        # the gap memory of the resident columns equals the oracle's gaps at the GPU's state
+        p.sync_oracle_to_gpu_state()
+        p.o.gaps()
+        p.g.set(duhl.Z, np.full(n, -1.0, dtype=np.float32))
+        p.g.gap(want_sum=False)
+        z = p.g.get(duhl.Z)
+        res = np.flatnonzero(z >= 0)
+        assert res.size >= m
+        np.testing.assert_allclose(z[res], p.o.z[res], rtol=1e-4, atol=1e-4 * p.o.z.max() + 1e-9)
+        ref.close()
+        p.close()
