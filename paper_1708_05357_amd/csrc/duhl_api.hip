@@ -66,7 +66,13 @@ duhl_status read_scalars(duhl_ctx *c, int first, int count)
 {
     HIPCHK(c, hipMemcpyAsync(c->h_scalars + first, c->scalars + first, sizeof(double) * count,
                              hipMemcpyDeviceToHost, c->compute));
+    HIPCHK(c, hipMemcpyAsync(c->h_u32 + 2, &c->sel->cd_abort, sizeof(uint32_t), hipMemcpyDeviceToHost,
+                             c->compute));
     HIPCHK(c, hipStreamSynchronize(c->compute));
+    if (c->h_u32[2] != 0)
+        return fail(c, DUHL_EHIP,
+                    "a coordinate-descent workgroup timed out waiting for its partner; alpha and v are "
+                    "undefined, set the data again");
     return DUHL_OK;
 }
 
@@ -79,7 +85,7 @@ duhl_status finish_set_data(duhl_ctx *c, const float *target, double lambda)
     c->cv.slots = c->slots;
     c->cv.ld_s = c->ld_s;
 
-    HIPCHK(c, launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(&c->sel->error), 1, 0));
+    HIPCHK(c, launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(&c->sel->error), 2, 0));   // and cd_abort
     HIPCHK(c, launch_validate(c));
     HIPCHK(c, hipMemcpyAsync(c->h_u32, &c->sel->error, sizeof(uint32_t), hipMemcpyDeviceToHost,
                              c->compute));
@@ -183,6 +189,7 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->cd_threads = env_int("DUHL_CD_THREADS", 0);
     c->copy_blocks = env_int("DUHL_COPY_BLOCKS", 8);
     if (c->copy_blocks < 1) c->copy_blocks = 1;
+    c->cd_units = env_int("DUHL_CD_UNITS", 0);
     c->csr_blocked = env_int("DUHL_CSR_BLOCKED", 1);
     c->csr_blocked_waves = env_int("DUHL_CSR_BLOCKED_WAVES", 2);
     if (c->csr_blocked_waves < 1) c->csr_blocked_waves = 1;
@@ -529,7 +536,7 @@ void duhl_destroy(duhl_ctx *c)
     (void)hipFree(c->P_cur); (void)hipFree(c->P_next);
     (void)hipFree(c->scalars); (void)hipFree(c->partials); (void)hipFree(c->sel);
     (void)hipFree(c->blk_gt); (void)hipFree(c->blk_eq); (void)hipFree(c->mark);
-    (void)hipFree(c->dv); (void)hipFree(c->dirty); (void)hipFree(c->score);
+    (void)hipFree(c->dv); (void)hipFree(c->dirty); (void)hipFree(c->score); (void)hipFree(c->xch);
     if (c->h_scalars) (void)hipHostFree(c->h_scalars);
     if (c->h_u32) (void)hipHostFree(c->h_u32);
     delete c;

@@ -182,7 +182,8 @@ struct SelectState {
     uint32_t n_fill;     // columns to copy (host residency)
     uint32_t n_evict;    // evictable slots found
     uint32_t error;      // validation flags
-    uint32_t pad[3];
+    uint32_t cd_abort;   // set by a coordinate-descent workgroup that gave up waiting for a partner
+    uint32_t pad[2];
 };
 
 }  // namespace duhl
@@ -233,6 +234,8 @@ struct duhl_ctx {
     float *dv;
     int64_t dv_stride, dv_workers;
     int32_t *dirty;
+    uint64_t *xch;              // exchange slots of workers that span several compute units
+    uint32_t xseq;              // next free sequence number for those slots
 
     // host residency
     const float *host_base;     // the caller's host address of the matrix
@@ -251,6 +254,7 @@ struct duhl_ctx {
     int gap_cols;      // columns per wavefront in the dense gap kernel
     int cd_threads;    // threads per coordinate in the async dense kernel (0 = by d)
     int copy_blocks;   // workgroups of the column-copy kernel
+    int cd_units;      // compute units per dense CD worker for long columns (0 = by d, 1 = never more than one)
     int csr_blocked;         // build and use the blocked copy of sparse data
     int csr_blocked_waves;   // workgroups per compute unit launched by its pass
     int csr_blocked_shape;   // 100*G + U to force the lanes per span and rows per span (0 = by density)

@@ -224,6 +224,58 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_atomic_kernel(cons
 }
 
 
+// ---- workers that span several compute units -----------------------------------------------------
+// The CUS workgroups of one worker each hold a slice of the private v and of every column; per
+// coordinate they exchange their partial dot products through a pair of 8-byte slots per
+// workgroup in device memory: (sequence number, value) written and read as one word at agent
+// scope.  Slot (seq & 1) is written for sequence number seq; a workgroup writes seq + 2 only
+// after it has read every partner's seq + 1, which a partner writes only after it has read this
+// workgroup's seq -- so two slots are enough.  The sum runs over the partners in a fixed order,
+// hence every workgroup gets the same bits.  Waiting is bounded: after kSpinLimit polls (seconds)
+// the workgroup raises the abort flag, which makes all of them leave their loops.
+constexpr int kSpinLimit = 1 << 22;
+
+template <int CUS>
+__device__ __forceinline__ float partner_sum(float mine, uint64_t *slots, int part, uint32_t seq,
+                                             uint32_t *abort_flag, float (*bcast)[2], int parity,
+                                             bool &failed)
+{
+    if (threadIdx.x == 0) {
+        uint64_t *mine_slot = slots + (seq & 1u) * CUS;
+        __hip_atomic_store(mine_slot + part, ((uint64_t)seq << 32) | __float_as_uint(mine),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        float total = 0.0f;
+        bool ok = true;
+        for (int q = 0; q < CUS; ++q) {
+            float val = mine;
+            if (q != part && ok) {
+                uint64_t got = 0;
+                int spins = 0;
+                for (;;) {
+                    got = __hip_atomic_load(mine_slot + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if ((uint32_t)(got >> 32) == seq) break;
+                    ++spins;
+                    if (spins > kSpinLimit ||
+                        ((spins & 1023) == 0 &&
+                         __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
+                        ok = false;
+                        break;
+                    }
+                    __builtin_amdgcn_s_sleep(1);
+                }
+                val = __uint_as_float((uint32_t)got);
+            }
+            total += val;
+        }
+        if (!ok) __hip_atomic_store(abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        bcast[parity][0] = total;
+        bcast[parity][1] = ok ? 0.0f : 1.0f;
+    }
+    __syncthreads();
+    failed = bcast[parity][1] != 0.0f;
+    return bcast[parity][0];
+}
+
 // ---- asynchronous, dense: workers with a private copy of v --------------------------------------
 // One sub-pass over positions [t_begin, t_end) of the visiting order.  The worker's copy of v is
 // NR 16-byte chunks per thread in registers plus NL chunks per thread in LDS (each thread only ever
@@ -234,28 +286,49 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_atomic_kernel(cons
 // of the worker's copy lives in its private buffer in device memory -- 400 KB or more per worker
 // that it re-reads for every coordinate, so it is served by L2 / the memory-side cache while the
 // column streams from HBM.  Each thread only touches its own rows there as well.
-template <int MODEL, int T, int NR, int NL, bool CACHE_X, bool EXT = false, bool XVEC = true>
+// CUS > 1: a worker is CUS workgroups, each with rows [part*S, (part+1)*S) of v and of the columns,
+// S = T*(NR+NL)*4, all of it on chip and the column cached; they meet once per coordinate in
+// partner_sum.  Workgroups 8 apart belong together: consecutive workgroups are dealt to the eight
+// dies in turn, so partners share a die and its L2 (a matter of speed only).
+template <int MODEL, int T, int NR, int NL, bool CACHE_X, bool EXT = false, bool XVEC = true, int CUS = 1>
 __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
     const CdArgs a, const int64_t t_begin, const int64_t t_end, float *dv, const int64_t dv_stride,
-    int32_t *dirty)
+    int32_t *dirty, uint64_t *xch, const uint32_t seq_base, uint32_t *abort_flag)
 {
+    static_assert(CUS == 1 || (T == 1024 && !EXT && CACHE_X), "multi-unit workers: cached, on chip");
     constexpr int BLOCK = T == 64 ? 256 : T;
     constexpr int NC = NR + NL;                        // chunks per thread that cover a column
     constexpr int kStep = T * 16;                      // bytes between a thread's chunks
     constexpr int KB = NR >= 14 ? 4 : 8;               // column chunks in flight when not cached
     __shared__ float red[2][16];
+    __shared__ float xsum[2][2];
     __shared__ float4 vs[NL > 0 ? NL * BLOCK : 1];
     const int tid = threadIdx.x % T;
     // the worker index is the same in all lanes of a wavefront: say so to the compiler
-    const int w = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (BLOCK / T) + threadIdx.x / T));
-    const int64_t nworkers = (int64_t)gridDim.x * (BLOCK / T);
+    int w = __builtin_amdgcn_readfirstlane((int)(blockIdx.x * (BLOCK / T) + threadIdx.x / T));
+    int64_t nworkers = (int64_t)gridDim.x * (BLOCK / T);
+    int part = 0;                                      // which slice of the rows this workgroup holds
+    if (CUS > 1) {
+        const int local = blockIdx.x % (8 * CUS);
+        part = local / 8;
+        w = (int)(blockIdx.x / (8 * CUS)) * 8 + local % 8;
+        nworkers = gridDim.x / CUS;
+    }
     const int64_t d4 = a.d >> 2;
-    const int tail = (int)(a.d - (d4 << 2));
-    const int vec_bytes = (int)(d4 << 4);              // 16-byte part of a column; loads beyond it
-    const int off = tid * 16;                          // return 0 (buffer bounds check)
-    const __amdgpu_buffer_rsrc_t rs_v = __builtin_amdgcn_make_buffer_rsrc(a.v, 0, vec_bytes, 0x00020000);
+    const int tail = part == CUS - 1 ? (int)(a.d - (d4 << 2)) : 0;   // ragged rows: last slice
+    const int64_t slice = (int64_t)part * NC * T * 4;  // first row of the slice
+    int vec_bytes = (int)(d4 << 4);                    // 16-byte part of a column; loads beyond it
+    if (CUS > 1) {                                     // return 0 (buffer bounds check)
+        vec_bytes -= part * NC * kStep;
+        vec_bytes = vec_bytes < 0 ? 0 : (vec_bytes > NC * kStep ? NC * kStep : vec_bytes);
+    }
+    const int off = tid * 16;
+    const __amdgpu_buffer_rsrc_t rs_v =
+        __builtin_amdgcn_make_buffer_rsrc(a.v + slice, 0, vec_bytes, 0x00020000);
     float *const out = dv + (int64_t)w * dv_stride;    // this worker's private buffer
-    const __amdgpu_buffer_rsrc_t rs_o = __builtin_amdgcn_make_buffer_rsrc(out, 0, vec_bytes, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rs_o =
+        __builtin_amdgcn_make_buffer_rsrc(out + slice, 0, vec_bytes, 0x00020000);
+    uint32_t seq = seq_base;                           // one number per coordinate of this worker
     const int nch = (int)((d4 + T - 1) / T);           // chunks per thread that cover a column
     if (EXT) {                                         // rows beyond the on-chip copy: start from v
         for (int i0 = NC; i0 < nch; i0 += 8) {
@@ -280,7 +353,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
         if (j < 0) continue;
         const float *col = a.cv.col(j);
         const __amdgpu_buffer_rsrc_t rs_x =
-            __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(col), 0, vec_bytes, 0x00020000);
+            __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(col + slice), 0, vec_bytes, 0x00020000);
         // the scalars of the step are requested before the column, so that nothing issued later
         // (loads complete in order) stands between the reduced dot product and the update
         const float old = a.alpha[j];
@@ -330,7 +403,13 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
         }
         const float xt = tid < tail ? col[(d4 << 2) + tid] : 0.0f;
         acc = fmaf(xt, vt, acc);
-        const float c = group_reduce<T>(acc, red, parity);
+        float c = group_reduce<T>(acc, red, parity);
+        if (CUS > 1) {
+            bool failed = false;
+            ++seq;
+            c = partner_sum<CUS>(c, xch + (int64_t)w * 2 * CUS, part, seq, abort_flag, xsum, parity, failed);
+            if (failed) break;                         // same decision in all threads and partners
+        }
         parity ^= 1;
 
         const float now = cd_new_alpha<MODEL>(a.mc, c, old, qj, y);
@@ -388,7 +467,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
             }
             vt = fmaf(xt, delta, vt);
             moved = true;
-            if (tid == 0) a.alpha[j] = now;
+            if (tid == 0 && part == 0) a.alpha[j] = now;
         }
     }
     if (moved) {                                       // this worker's change of v
@@ -420,7 +499,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
         }
         if (tid < tail) out[(d4 << 2) + tid] = vt - a.v[(d4 << 2) + tid];
     }
-    if (tid == 0) dirty[w] = moved ? 1 : 0;
+    if (tid == 0 && part == 0) dirty[w] = moved ? 1 : 0;
 }
 
 // v += sum over workers of their stored changes, in a fixed order (reproducible).  A workgroup
@@ -706,11 +785,40 @@ hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
         if (workers > cap) workers = cap;
         const int64_t grid = (workers + PER - 1) / PER;
         hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, T, NR, NL, CACHE_X, EXT, XVEC>), dim3(grid), dim3(BLOCK), 0,
-                           c->compute, a, t0, t1, c->dv, c->dv_stride, c->dirty);
+                           c->compute, a, t0, t1, c->dv, c->dv_stride, c->dirty, nullptr, 0u, nullptr);
         hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 63) / 64), dim3(1024), 0, c->compute, a.v,
                            c->d, c->dv, c->dv_stride, c->dirty, (int)(grid * PER));
     }
     return hipGetLastError();
+}
+
+// The same with workers of CUS workgroups each (columns too long for one compute unit to hold a
+// private v and a cached column).  All workgroups of a launch must be resident at once -- partners
+// wait for each other -- so there are at most as many as compute units, fewer by the workgroups of
+// the column copy that may be running beside the pass.
+template <int MODEL, int NR, int NL, int CUS>
+hipError_t launch_multi_t(duhl_ctx *c, const CdArgs &a, int64_t inflight, int64_t workers)
+{
+    for (int64_t t0 = 0; t0 < a.count; t0 += inflight) {
+        const int64_t t1 = t0 + inflight < a.count ? t0 + inflight : a.count;
+        const int64_t per_worker = (t1 - t0 + workers - 1) / workers;
+        hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, 1024, NR, NL, true, false, true, CUS>),
+                           dim3(workers * CUS), dim3(1024), 0, c->compute, a, t0, t1, c->dv, c->dv_stride,
+                           c->dirty, c->xch, c->xseq, &c->sel->cd_abort);
+        c->xseq += (uint32_t)per_worker + 2u;          // sequence numbers never repeat back to back
+        hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 63) / 64), dim3(1024), 0, c->compute, a.v,
+                           c->d, c->dv, c->dv_stride, c->dirty, (int)workers);
+    }
+    return hipGetLastError();
+}
+
+template <int MODEL, int CUS>
+hipError_t launch_multi(duhl_ctx *c, const CdArgs &a, int64_t inflight, int64_t workers, int64_t chunks)
+{
+    const int64_t per = (chunks + CUS - 1) / CUS;      // chunks of a column per workgroup
+    if (per <= 8) return launch_multi_t<MODEL, 8, 0, CUS>(c, a, inflight, workers);
+    if (per <= 10) return launch_multi_t<MODEL, 8, 2, CUS>(c, a, inflight, workers);
+    return launch_multi_t<MODEL, 8, 5, CUS>(c, a, inflight, workers);
 }
 
 // Dense asynchronous pass with private-v workers; false if this shape is not covered.
@@ -731,6 +839,24 @@ bool launch_workers(duhl_ctx *c, const CdArgs &a, int max_inflight, bool vec, hi
         if (*err != hipSuccess) return true;
     }
     const int64_t inflight = inflight_limit(c, a.count, max_inflight);
+    // Columns of 53,249 to 212,992 entries: two or four compute units per worker, everything on chip
+    if (T == 1024 && vec && chunks > 13 && chunks <= 52 && c->cd_units != 1) {
+        const int cus = c->cd_units == 2 || c->cd_units == 4 ? c->cd_units : (chunks <= 26 ? 2 : 4);
+        const int64_t avail = c->num_cu - (c->res == DUHL_RESIDENT_HOST ? c->copy_blocks : 0);
+        const int64_t workers = avail / (8 * cus) * 8;
+        if (workers >= 8 && workers <= c->dv_workers && chunks <= 13 * cus) {
+            if (!c->xch) {
+                *err = hipMalloc(reinterpret_cast<void **>(&c->xch), (size_t)c->dv_workers * 8 * sizeof(uint64_t));
+                if (*err == hipSuccess)
+                    *err = hipMemsetAsync(c->xch, 0, (size_t)c->dv_workers * 8 * sizeof(uint64_t), c->compute);
+                if (*err != hipSuccess) return true;
+                c->xseq = 1;
+            }
+            *err = cus == 2 ? launch_multi<MODEL, 2>(c, a, inflight, workers, chunks)
+                            : launch_multi<MODEL, 4>(c, a, inflight, workers, chunks);
+            return true;
+        }
+    }
     // (T, register chunks, LDS chunks, column cached?) by column length
     // vec: columns start 16-byte aligned; otherwise their loads are split into dwords
 #define DUHL_W(TT, NR, NL, CX)                                                            \
