@@ -255,6 +255,7 @@ struct duhl_ctx {
     int cd_threads;    // threads per coordinate in the async dense kernel (0 = by d)
     int copy_blocks;   // workgroups of the column-copy kernel
     int cd_units;      // compute units per dense CD worker for long columns (0 = by d, 1 = never more than one)
+    int cd_spin_limit; // polls a workgroup waits for a partner's partial sum before it gives up
     int csr_blocked;         // build and use the blocked copy of sparse data
     int csr_blocked_waves;   // workgroups per compute unit launched by its pass
     int csr_blocked_shape;   // 100*G + U to force the lanes per span and rows per span (0 = by density)

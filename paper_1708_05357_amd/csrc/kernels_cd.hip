@@ -231,14 +231,13 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_atomic_kernel(cons
 // scope.  Slot (seq & 1) is written for sequence number seq; a workgroup writes seq + 2 only
 // after it has read every partner's seq + 1, which a partner writes only after it has read this
 // workgroup's seq -- so two slots are enough.  The sum runs over the partners in a fixed order,
-// hence every workgroup gets the same bits.  Waiting is bounded: after kSpinLimit polls (seconds)
-// the workgroup raises the abort flag, which makes all of them leave their loops.
-constexpr int kSpinLimit = 1 << 22;
-
+// hence every workgroup gets the same bits.  Waiting is bounded: after spin_limit polls (seconds
+// with the default of 2^22) the workgroup raises the abort flag, which makes all of them leave
+// their loops.
 template <int CUS>
 __device__ __forceinline__ float partner_sum(float mine, uint64_t *slots, int part, uint32_t seq,
-                                             uint32_t *abort_flag, float (*bcast)[2], int parity,
-                                             bool &failed)
+                                             uint32_t *abort_flag, int spin_limit, float (*bcast)[2],
+                                             int parity, bool &failed)
 {
     if (threadIdx.x == 0) {
         uint64_t *mine_slot = slots + (seq & 1u) * CUS;
@@ -255,7 +254,7 @@ __device__ __forceinline__ float partner_sum(float mine, uint64_t *slots, int pa
                     got = __hip_atomic_load(mine_slot + q, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     if ((uint32_t)(got >> 32) == seq) break;
                     ++spins;
-                    if (spins > kSpinLimit ||
+                    if (spins > spin_limit ||
                         ((spins & 1023) == 0 &&
                          __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
                         ok = false;
@@ -293,7 +292,7 @@ __device__ __forceinline__ float partner_sum(float mine, uint64_t *slots, int pa
 template <int MODEL, int T, int NR, int NL, bool CACHE_X, bool EXT = false, bool XVEC = true, int CUS = 1>
 __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
     const CdArgs a, const int64_t t_begin, const int64_t t_end, float *dv, const int64_t dv_stride,
-    int32_t *dirty, uint64_t *xch, const uint32_t seq_base, uint32_t *abort_flag)
+    int32_t *dirty, uint64_t *xch, const uint32_t seq_base, uint32_t *abort_flag, const int spin_limit)
 {
     static_assert(CUS == 1 || (T == 1024 && !EXT && CACHE_X), "multi-unit workers: cached, on chip");
     constexpr int BLOCK = T == 64 ? 256 : T;
@@ -407,7 +406,8 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
         if (CUS > 1) {
             bool failed = false;
             ++seq;
-            c = partner_sum<CUS>(c, xch + (int64_t)w * 2 * CUS, part, seq, abort_flag, xsum, parity, failed);
+            c = partner_sum<CUS>(c, xch + (int64_t)w * 2 * CUS, part, seq, abort_flag, spin_limit, xsum, parity,
+                                 failed);
             if (failed) break;                         // same decision in all threads and partners
         }
         parity ^= 1;
@@ -785,7 +785,7 @@ hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
         if (workers > cap) workers = cap;
         const int64_t grid = (workers + PER - 1) / PER;
         hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, T, NR, NL, CACHE_X, EXT, XVEC>), dim3(grid), dim3(BLOCK), 0,
-                           c->compute, a, t0, t1, c->dv, c->dv_stride, c->dirty, nullptr, 0u, nullptr);
+                           c->compute, a, t0, t1, c->dv, c->dv_stride, c->dirty, nullptr, 0u, nullptr, 0);
         hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 63) / 64), dim3(1024), 0, c->compute, a.v,
                            c->d, c->dv, c->dv_stride, c->dirty, (int)(grid * PER));
     }
@@ -804,7 +804,7 @@ hipError_t launch_multi_t(duhl_ctx *c, const CdArgs &a, int64_t inflight, int64_
         const int64_t per_worker = (t1 - t0 + workers - 1) / workers;
         hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, 1024, NR, NL, true, false, true, CUS>),
                            dim3(workers * CUS), dim3(1024), 0, c->compute, a, t0, t1, c->dv, c->dv_stride,
-                           c->dirty, c->xch, c->xseq, &c->sel->cd_abort);
+                           c->dirty, c->xch, c->xseq, &c->sel->cd_abort, c->cd_spin_limit);
         c->xseq += (uint32_t)per_worker + 2u;          // sequence numbers never repeat back to back
         hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 63) / 64), dim3(1024), 0, c->compute, a.v,
                            c->d, c->dv, c->dv_stride, c->dirty, (int)workers);

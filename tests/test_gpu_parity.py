@@ -769,3 +769,34 @@ def test_stream_read_probe(G):
     with pytest.raises(duhl.DuhlError):
         g.probe_stream_read(x, reps=0)
     g.close()
+
+
+def test_partner_wait_of_multi_unit_workers_is_bounded(G, monkeypatch):
+    """Workers that span several compute units wait for each other's partial dot products.  With
+    the wait cut to a single poll (forced from the host; every kernel still ends normally) some
+    workgroup gives up, all of them leave their loops, and the next call that returns a scalar
+    reports it; setting the data again clears the condition."""
+    from paper_1708_05357_amd import duhl
+    prob = lasso_problem(120000, 300, 0.05, 0.05, seed=71)           # two compute units per worker
+    monkeypatch.setenv("DUHL_CD_SPIN_LIMIT", "0")
+    g = duhl.Duhl(duhl.LASSO, prob["d"], prob["n"], prob["n"])
+    monkeypatch.delenv("DUHL_CD_SPIN_LIMIT")
+    cols, b = prob["cols"].cuda(), prob["target"].cuda()
+    g.set_data_dense(cols, b, prob["lam"])
+    g.select(256, want_stats=False)
+    g.commit_swap()
+    for k in range(3):
+        g.cd_epoch(duhl.CD_ASYNC, seed=k)
+    with pytest.raises(duhl.DuhlError) as e:
+        g.objective()
+    assert e.value.status == duhl.EHIP and "timed out" in str(e.value)
+    g.close()
+    # the same problem with the normal limit: no error, and the pass decreases the objective
+    g = duhl.Duhl(duhl.LASSO, prob["d"], prob["n"], prob["n"])
+    g.set_data_dense(cols, b, prob["lam"])
+    before = g.objective()
+    g.select(256, want_stats=False)
+    g.commit_swap()
+    g.cd_epoch(duhl.CD_ASYNC, seed=0)
+    assert g.objective() < before
+    g.close()
