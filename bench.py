@@ -330,7 +330,7 @@ def main():
                     help="working-set rule: eq. (13), or one of the paper's reference schemes")
     ap.add_argument("--passes", type=int, default=None,
                     help="CD passes per round (theta of Section 5.2); 0 with host residency: as many, "
-                         "up to 8, as fit beside the round's column copies; default 1, and 4 with host "
+                         "up to 8, as fit beside the round's column copies; default 1, and 8 with host "
                          "residency, where the passes are also the time unit A's sampler has per round")
     ap.add_argument("--min-passes", type=int, default=1, help="lower bound for --passes 0")
     ap.add_argument("--gap-sample", type=float, default=1.0,
@@ -351,7 +351,7 @@ def main():
     if args.host_sampler_threads < 0:
         args.host_sampler_threads = 12
     if args.passes is None:
-        args.passes = 4 if args.workload == "cfg4" else 1
+        args.passes = 8 if args.workload == "cfg4" else 1
     import torch
     from paper_1708_05357_amd import duhl
     assert torch.cuda.is_available(), "bench.py needs a GPU"
