@@ -796,13 +796,13 @@ hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
 // private v and a cached column).  All workgroups of a launch must be resident at once -- partners
 // wait for each other -- so there are at most as many as compute units, fewer by the workgroups of
 // the column copy that may be running beside the pass.
-template <int MODEL, int NR, int NL, int CUS>
+template <int MODEL, int NR, int NL, int CUS, bool XVEC>
 hipError_t launch_multi_t(duhl_ctx *c, const CdArgs &a, int64_t inflight, int64_t workers)
 {
     for (int64_t t0 = 0; t0 < a.count; t0 += inflight) {
         const int64_t t1 = t0 + inflight < a.count ? t0 + inflight : a.count;
         const int64_t per_worker = (t1 - t0 + workers - 1) / workers;
-        hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, 1024, NR, NL, true, false, true, CUS>),
+        hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, 1024, NR, NL, true, false, XVEC, CUS>),
                            dim3(workers * CUS), dim3(1024), 0, c->compute, a, t0, t1, c->dv, c->dv_stride,
                            c->dirty, c->xch, c->xseq, &c->sel->cd_abort, c->cd_spin_limit);
         c->xseq += (uint32_t)per_worker + 2u;          // sequence numbers never repeat back to back
@@ -812,13 +812,13 @@ hipError_t launch_multi_t(duhl_ctx *c, const CdArgs &a, int64_t inflight, int64_
     return hipGetLastError();
 }
 
-template <int MODEL, int CUS>
+template <int MODEL, int CUS, bool XVEC>
 hipError_t launch_multi(duhl_ctx *c, const CdArgs &a, int64_t inflight, int64_t workers, int64_t chunks)
 {
     const int64_t per = (chunks + CUS - 1) / CUS;      // chunks of a column per workgroup
-    if (per <= 8) return launch_multi_t<MODEL, 8, 0, CUS>(c, a, inflight, workers);
-    if (per <= 10) return launch_multi_t<MODEL, 8, 2, CUS>(c, a, inflight, workers);
-    return launch_multi_t<MODEL, 8, 5, CUS>(c, a, inflight, workers);
+    if (per <= 8) return launch_multi_t<MODEL, 8, 0, CUS, XVEC>(c, a, inflight, workers);
+    if (per <= 10) return launch_multi_t<MODEL, 8, 2, CUS, XVEC>(c, a, inflight, workers);
+    return launch_multi_t<MODEL, 8, 5, CUS, XVEC>(c, a, inflight, workers);
 }
 
 // Dense asynchronous pass with private-v workers; false if this shape is not covered.
@@ -840,7 +840,7 @@ bool launch_workers(duhl_ctx *c, const CdArgs &a, int max_inflight, bool vec, hi
     }
     const int64_t inflight = inflight_limit(c, a.count, max_inflight);
     // Columns of 53,249 to 212,992 entries: two or four compute units per worker, everything on chip
-    if (T == 1024 && vec && chunks > 13 && chunks <= 52 && c->cd_units != 1) {
+    if (T == 1024 && chunks > 13 && chunks <= 52 && c->cd_units != 1) {
         const int cus = c->cd_units == 2 || c->cd_units == 4 ? c->cd_units : (chunks <= 26 ? 2 : 4);
         const int64_t avail = c->num_cu - (c->res == DUHL_RESIDENT_HOST ? c->copy_blocks : 0);
         const int64_t workers = avail / (8 * cus) * 8;
@@ -852,8 +852,12 @@ bool launch_workers(duhl_ctx *c, const CdArgs &a, int max_inflight, bool vec, hi
                 if (*err != hipSuccess) return true;
                 c->xseq = 1;
             }
-            *err = cus == 2 ? launch_multi<MODEL, 2>(c, a, inflight, workers, chunks)
-                            : launch_multi<MODEL, 4>(c, a, inflight, workers, chunks);
+            if (vec)
+                *err = cus == 2 ? launch_multi<MODEL, 2, true>(c, a, inflight, workers, chunks)
+                                : launch_multi<MODEL, 4, true>(c, a, inflight, workers, chunks);
+            else                                        // columns start only 4-byte aligned
+                *err = cus == 2 ? launch_multi<MODEL, 2, false>(c, a, inflight, workers, chunks)
+                                : launch_multi<MODEL, 4, false>(c, a, inflight, workers, chunks);
             return true;
         }
     }

@@ -316,8 +316,8 @@ def converge_oracle(p, m, max_rounds, passes, target_rel_gap):
 
 @pytest.mark.parametrize("scheme", ["async", "atomic"])
 @pytest.mark.parametrize("kind", ["cfg1", "lasso_mid", "lasso_ragged", "lasso_long", "lasso_longer",
-                                  "lasso_longest", "lasso_extended", "lasso_unaligned", "svm_dense",
-                                  "svm_csr"])
+                                  "lasso_longest", "lasso_extended", "lasso_unaligned",
+                                  "lasso_long_unaligned", "svm_dense", "svm_csr"])
 def test_async_cd_reaches_the_oracle_objective(G, kind, scheme):
     """The asynchronous scheme is compared on what is unique: the objective at convergence
     (1e-5 relative), and on the invariant v = A alpha (- b) that the atomic adds must keep."""
@@ -346,6 +346,9 @@ def test_async_cd_reaches_the_oracle_objective(G, kind, scheme):
     elif kind == "lasso_unaligned":
         prob = lasso_problem(50002, 300, 0.05, 0.05, seed=15)       # leading dimension = d: scalar kernels
         m = 120
+    elif kind == "lasso_long_unaligned":
+        prob = lasso_problem(90001, 200, 0.05, 0.05, seed=19)       # two units per worker, dword loads
+        m = 90
     elif kind == "svm_dense":
         prob = synth.svm_dense(2000, 300, seed=12)
         m = 500
@@ -355,7 +358,7 @@ def test_async_cd_reaches_the_oracle_objective(G, kind, scheme):
     # columns padded to a multiple of four floats take the 16-byte kernels (with a ragged tail when
     # d itself is not a multiple of four); "lasso_unaligned" keeps ld = d and the scalar ones
     ld = None
-    if "cols" in prob and kind != "lasso_unaligned" and prob["d"] % 4 != 0:
+    if "cols" in prob and "unaligned" not in kind and prob["d"] % 4 != 0:
         ld = (prob["d"] + 3) // 4 * 4
     p = G.Pair(prob, ld=ld)
     tol = 1e-7 if prob["model"] == "lasso" else 1e-6
