@@ -179,7 +179,12 @@ duhl_status duhl_commit_swap(duhl_ctx *ctx);
  *   DUHL_CD_ASYNC   dense data: the pass is cut into sub-passes of max_inflight coordinates;
  *                   workers solve their share one after the other against a private copy of v and
  *                   the changes are merged after each sub-pass (no atomics, reproducible for a
- *                   given seed).  Sparse data: same as DUHL_CD_ATOMIC.
+ *                   given seed).  Columns of more than 53,248 entries are solved by workers that
+ *                   span several compute units and wait for each other once per coordinate; that
+ *                   wait is bounded, and if it ever expires (the device shared with work that
+ *                   starves part of a worker for seconds) the pass ends early, alpha and v are
+ *                   undefined and the next call that returns a scalar fails with DUHL_EHIP until
+ *                   the data are set again.  Sparse data: same as DUHL_CD_ATOMIC.
  * In all schemes v = A alpha (- b) keeps holding up to fp32 rounding. */
 duhl_status duhl_cd_epoch(duhl_ctx *ctx, duhl_cd_mode mode, const int32_t *order,
                           int64_t n_order, uint64_t seed, int max_inflight);

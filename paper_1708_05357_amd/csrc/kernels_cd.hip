@@ -18,8 +18,12 @@
 // merge kernel adds the buffers to v in a fixed order.  Per update the only memory traffic is
 // the column itself, read once; there are no atomics and the result is reproducible.  Workers do
 // not see each other inside a sub-pass, exactly like concurrently running thread blocks that
-// read a stale v; `inflight` bounds that staleness.  Sparse data keeps the atomic scheme: its
-// scattered updates are few and spread over all of v.
+// read a stale v; `inflight` bounds that staleness.  A worker is a wavefront, a quarter of a
+// workgroup or a whole 1024-thread workgroup by column length; for columns beyond what one
+// compute unit can hold on chip (a copy of v plus the column), two or four workgroups on
+// different compute units form one worker and exchange their partial dot products per
+// coordinate.  Sparse data keeps the atomic scheme: its scattered updates are few and spread
+// over all of v.
 #include <cmath>
 
 #include "duhl_internal.h"
