@@ -803,3 +803,34 @@ def test_partner_wait_of_multi_unit_workers_is_bounded(G, monkeypatch):
     g.cd_epoch(duhl.CD_ASYNC, seed=0)
     assert g.objective() < before
     g.close()
+
+
+@pytest.mark.parametrize("name", ["lasso_identity_2x2", "svm_two_points_1d", "ridge_one_column"])
+def test_hand_worked_examples_on_the_gpu(G, name):
+    """The instances worked by hand from App. C, D and E (tests/golden/hand_worked.json): the HIP
+    path must give those numbers, which are exact in single precision, in every scheme."""
+    import json
+    from paper_1708_05357_amd import duhl
+    with open(os.path.join(os.path.dirname(__file__), "golden", "hand_worked.json")) as f:
+        case = json.load(f)[name]
+    model = {"lasso": duhl.LASSO, "svm_t": duhl.SVM, "ridge": duhl.ELASTIC_NET}[name[:5]]
+    cols = torch.tensor(case["cols"], dtype=torch.float32, device="cuda:0")
+    target = torch.tensor(case["target"], dtype=torch.float32, device="cuda:0")
+    n, d = cols.shape
+    for mode in (duhl.CD_SEQUENTIAL, duhl.CD_ASYNC, duhl.CD_ATOMIC):
+        g = duhl.Duhl(model, d, n, n)
+        if model == duhl.ELASTIC_NET:
+            g.set_eta(case["eta"])
+        g.set_data_dense(cols, target, case["lambda"])
+        assert g.objective() == pytest.approx(case["objective_at_zero"], abs=1e-7)
+        np.testing.assert_allclose(g.get(duhl.Z), case["gaps_at_zero"], rtol=1e-6, atol=1e-7)
+        assert g.gap() == pytest.approx(sum(case["gaps_at_zero"]), rel=1e-6)
+        g.select(n, want_stats=False)
+        g.commit_swap()
+        g.cd_epoch(mode, G.dev_i32(np.arange(n)), max_inflight=1)       # index order, one at a time
+        np.testing.assert_allclose(g.get(duhl.ALPHA), case["alpha_after_pass_0_1"], rtol=1e-6, atol=1e-7)
+        np.testing.assert_allclose(g.get(duhl.V), case["v_after_pass"], rtol=1e-6, atol=1e-7)
+        assert g.objective() == pytest.approx(case["objective_after_pass"], abs=1e-7)
+        g.gap(want_sum=False)
+        np.testing.assert_allclose(g.get(duhl.Z), case["gaps_after_pass"], atol=1e-7)
+        g.close()

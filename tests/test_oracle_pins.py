@@ -458,3 +458,33 @@ def test_enet_tends_to_lasso_for_small_eta():
         e.cd_pass(np.arange(6, dtype=np.int32))
         l.cd_pass(np.arange(6, dtype=np.int32))
     np.testing.assert_allclose(e.alpha, l.alpha, atol=1e-9)
+
+
+# ---------------------------------------------------------------------------------- hand-worked fixtures
+def _golden():
+    import json
+    import os
+    with open(os.path.join(os.path.dirname(__file__), "golden", "hand_worked.json")) as f:
+        return json.load(f)
+
+
+@pytest.mark.parametrize("name", ["lasso_identity_2x2", "svm_two_points_1d", "ridge_one_column"])
+def test_oracle_reproduces_the_hand_worked_examples(name):
+    """Tiny instances worked by hand from App. C, D and E (tests/golden/hand_worked.json holds the
+    derivations): objective, gaps, one pass in index order, all exact in floating point."""
+    case = _golden()[name]
+    model = {"lasso": orc.LASSO, "svm_t": orc.SVM, "ridge": orc.ENET}[name[:5]]
+    cols = np.array(case["cols"], dtype=np.float32)
+    o = orc.Oracle(model, np.array(case["target"], dtype=np.float32), case["lambda"], cols=cols,
+                   eta=case.get("eta", 1.0))
+    if "B" in case:
+        assert o.B == case["B"]
+    assert o.objective() == case["objective_at_zero"]
+    assert o.gaps() == sum(case["gaps_at_zero"])
+    np.testing.assert_array_equal(o.z, case["gaps_at_zero"])
+    o.cd_pass(np.arange(cols.shape[0], dtype=np.int32))
+    np.testing.assert_array_equal(o.alpha, case["alpha_after_pass_0_1"])
+    np.testing.assert_array_equal(o.v, case["v_after_pass"])
+    assert o.objective() == case["objective_after_pass"]
+    o.gaps()
+    np.testing.assert_array_equal(o.z, case["gaps_after_pass"])
