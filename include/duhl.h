@@ -120,7 +120,8 @@ duhl_status duhl_gap(duhl_ctx *ctx, const int32_t *idx, int64_t count, double *g
  * needs budget_cols >= |current| + m; with fewer slots the copy first waits for the compute
  * stream and duhl_cd_epoch is refused (DUHL_ESTATE) until duhl_commit_swap.
  * P_out (device, m int32, may be NULL): the set in ascending order.  n_swapped (host, may be
- * NULL): columns that have to be copied.  rho (host, may be NULL): eq. (7) evaluated on z,
+ * NULL): columns that have to be copied (device residency: members that the current set lacks;
+ * counted only when asked for).  rho (host, may be NULL): eq. (7) evaluated on z,
  * (mean of z over P)/(mean of z over all).  Non-NULL host outputs make the call wait for the
  * compute stream (not for the copies). */
 duhl_status duhl_select(duhl_ctx *ctx, int64_t m, int32_t *P_out, int64_t *n_swapped,

@@ -71,8 +71,8 @@ duhl_status read_scalars(duhl_ctx *c, int first, int count)
     HIPCHK(c, hipStreamSynchronize(c->compute));
     if (c->h_u32[2] != 0)
         return fail(c, DUHL_EHIP,
-                    "a coordinate-descent workgroup timed out waiting for its partner; alpha and v are "
-                    "undefined, set the data again");
+                    "a device-side wait between workgroups timed out (selection or coordinate descent); "
+                    "the working set, alpha and v are undefined, set the data again");
     return DUHL_OK;
 }
 
@@ -216,6 +216,10 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     ok(hipHostMalloc(reinterpret_cast<void **>(&c->h_scalars), sizeof(double) * S_COUNT, hipHostMallocDefault));
     ok(hipHostMalloc(reinterpret_cast<void **>(&c->h_u32), sizeof(uint32_t) * 4, hipHostMallocDefault));
     if (e == hipSuccess) e = hipMemset(c->sel, 0, sizeof(SelectState));
+    // working-set lists only ever hold coordinates: zero now, and a selection that ends early (a
+    // device-side wait that timed out) leaves older valid entries behind, never garbage
+    if (e == hipSuccess) e = hipMemset(c->P_cur, 0, sizeof(int32_t) * (size_t)c->budget);
+    if (e == hipSuccess) e = hipMemset(c->P_next, 0, sizeof(int32_t) * (size_t)c->budget);
     if (e != hipSuccess) {
         duhl_destroy(c);
         return e == hipErrorOutOfMemory ? DUHL_ENOMEM : DUHL_EHIP;
@@ -352,7 +356,7 @@ duhl_status duhl_select_rule_apply(duhl_ctx *c, duhl_select_rule rule, uint64_t 
     c->pending = true;
     const bool overlap_safe = c->budget >= c->m_cur + m;
     c->swap_exclusive = host && !overlap_safe;
-    HIPCHK(c, launch_plan_swap(c, host ? overlap_safe : true));
+    HIPCHK(c, launch_plan_swap(c, host ? overlap_safe : true, n_swapped != nullptr));
     if (host) {
         HIPCHK(c, hipEventRecord(c->ev_plan, c->compute));
         HIPCHK(c, hipStreamWaitEvent(c->copy, c->ev_plan, 0));

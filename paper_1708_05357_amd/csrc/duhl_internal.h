@@ -176,13 +176,13 @@ enum Scalar { S_GAP_SUM = 0, S_SUM_ALL, S_SUM_SEL, S_RHO, S_OBJ_SQ, S_OBJ_LIN, S
 // Scratch of the selection kernels (device memory, one per context).
 struct SelectState {
     uint32_t hist[3][2048];
-    uint32_t ticket[8];
+    uint32_t ticket[8];  // [0]: arrivals at the selection kernel's barriers, only ever incremented
     uint32_t prefix;     // high bits of the threshold key decided so far
     uint32_t remaining;  // how many of the current bucket are still needed
     uint32_t n_fill;     // columns to copy (host residency)
     uint32_t n_evict;    // evictable slots found
     uint32_t error;      // validation flags
-    uint32_t cd_abort;   // set by a coordinate-descent workgroup that gave up waiting for a partner
+    uint32_t cd_abort;   // set by a workgroup that gave up waiting for others (selection barrier, CD partners)
     uint32_t pad[2];
 };
 
@@ -234,6 +234,7 @@ struct duhl_ctx {
     float *dv;
     int64_t dv_stride, dv_workers;
     int32_t *dirty;
+    uint32_t sel_bar;           // value the selection kernel's barrier counter has before its next launch
     uint64_t *xch;              // exchange slots of workers that span several compute units
     uint32_t xseq;              // next free sequence number for those slots
 
@@ -270,7 +271,7 @@ hipError_t launch_gap(duhl_ctx *c, const int32_t *idx, int64_t count, bool slot_
                       bool with_norms);
 hipError_t launch_select(duhl_ctx *c, int64_t m, int32_t *P_out, const float *keys);
 hipError_t launch_score(duhl_ctx *c, int scheme, int64_t m, uint64_t arg);
-hipError_t launch_plan_swap(duhl_ctx *c, bool overlap_safe);
+hipError_t launch_plan_swap(duhl_ctx *c, bool overlap_safe, bool want_count);
 hipError_t launch_copy_columns(duhl_ctx *c);
 hipError_t launch_publish(duhl_ctx *c);
 hipError_t launch_cd(duhl_ctx *c, duhl_cd_mode mode, const int32_t *order, int64_t count,

@@ -69,7 +69,8 @@ __device__ __forceinline__ int64_t coord_at(const CdArgs &a, int64_t t)
         const int64_t j = a.order[t];
         return (uint64_t)j < (uint64_t)a.n ? j : -1;
     }
-    return a.P[a.permute ? permuted(a, t) : t];
+    const int64_t j = a.P[a.permute ? permuted(a, t) : t];
+    return (uint64_t)j < (uint64_t)a.n ? j : -1;
 }
 
 // Loads of the shared vector that must observe other workgroups' atomic adds.

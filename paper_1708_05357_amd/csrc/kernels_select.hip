@@ -4,8 +4,8 @@
 // z is turned into order-preserving 32-bit keys.  Three histogram passes (11 + 11 + 10 bits)
 // find the key of the m-th largest entry exactly; a count pass and an ordered scatter then
 // write the indices.  The work is 4n bytes per pass -- negligible next to a gap pass -- so the
-// design goal is few launches: the last workgroup to finish each pass (atomic ticket, no
-// spinning) does that pass's serial step.
+// design goal is few launches: one kernel of at most 128 small workgroups, all resident at once,
+// which meet at six device-wide barriers; serial steps are repeated by every workgroup.
 // The second half plans the column swap for host residency: which selected columns are not in
 // a device slot yet and which slots may be overwritten (Algorithm 2, "refresh memory B").
 #include "duhl_internal.h"
@@ -30,246 +30,302 @@ __device__ __forceinline__ T coherent_load(const T *p)
 {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
-
-// True in exactly one workgroup of the launch: the one that arrives last.  Everything the
-// other workgroups wrote before arriving is visible to it afterwards.
-__device__ __forceinline__ bool last_block_done(uint32_t *ticket)
+template <typename T>
+__device__ __forceinline__ void coherent_store(T *p, T x)
 {
-    __shared__ bool last;
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) last = atomicAdd(ticket, 1u) == gridDim.x - 1;
-    __syncthreads();
-    if (last) __threadfence();
-    return last;
+    __hip_atomic_store(p, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-__global__ void select_reset_kernel(SelectState *st, uint32_t m)
+// Barrier over all workgroups of the launch.  ctr only grows; `target` is its value once every
+// workgroup has arrived at this barrier (the host hands each launch a fresh range of values).
+// No cache-wide fence is paid: everything one workgroup writes for another before a barrier is
+// written with agent-scope stores or atomics (coherent_store, atomicAdd) and read after it with
+// agent-scope loads (coherent_load); the workgroup barriers around the arrival order them with
+// the counter.  The launch has at most kMaxGroups small
+// workgroups, all resident at once, so the wait is short; it is bounded all the same: after
+// spin_limit polls the workgroup reports failure, and so do all others (abort flag).
+__device__ __forceinline__ bool grid_sync(uint32_t *ctr, uint32_t target, uint32_t *abort_flag, int spin_limit)
 {
-    uint32_t *h = &st->hist[0][0];
-    for (int i = threadIdx.x; i < 3 * 2048; i += blockDim.x) h[i] = 0;
-    if (threadIdx.x < 8) st->ticket[threadIdx.x] = 0;
+    __shared__ int ok;
+    __syncthreads();                                     // this workgroup's stores have completed
     if (threadIdx.x == 0) {
-        st->prefix = 0;
-        st->remaining = m;
-        st->n_fill = 0;
-        st->n_evict = 0;
+        bool good = true;
+        __hip_atomic_fetch_add(ctr, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int spins = 0;
+        while ((int32_t)(__hip_atomic_load(ctr, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - target) < 0) {
+            ++spins;
+            if (spins > spin_limit ||
+                ((spins & 255) == 0 &&
+                 __hip_atomic_load(abort_flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u)) {
+                good = false;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(1);
+        }
+        if (!good) __hip_atomic_store(abort_flag, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        ok = good ? 1 : 0;
     }
+    __syncthreads();
+    return ok != 0;
 }
 
-// Histogram of the next digit over the entries whose higher digits equal st->prefix; the last
-// workgroup then finds the digit that holds the `remaining`-th largest entry.
+struct SelectArgs {
+    const float *keys;     // what is ranked (z, or the scores of another rule)
+    const float *zval;     // the gap memory, for the sums of eq. (7)
+    int64_t n, m;
+    int chunk;             // entries per workgroup, a multiple of 2048
+    SelectState *st;
+    uint32_t *blk_gt, *blk_eq;
+    int32_t *P, *P_out;
+    double *partials, *scalars;
+    uint32_t bar_base;     // value of st->ticket[0] before this launch
+    int spin_limit;
+};
+
+// Histogram of one digit of the keys of this workgroup's chunk (those whose higher digits equal
+// `prefix`), flushed into the device-wide histogram.
 template <int PASS>
-__global__ __launch_bounds__(256) void select_hist_kernel(const float *z, const float *zval,
-                                                          int64_t n, SelectState *st,
-                                                          double *partials, double *scalars)
+__device__ __forceinline__ void hist_pass(const SelectArgs &a, uint32_t prefix, uint32_t *hist, double *zsum)
 {
     constexpr int kBits = PASS == 2 ? 10 : 11;
     constexpr int kShift = PASS == 0 ? 21 : (PASS == 1 ? 10 : 0);
     constexpr int kBins = 1 << kBits;
-    __shared__ uint32_t hist[2048];
-    __shared__ uint32_t tsum[256];
-    __shared__ double dsh[4];
     for (int i = threadIdx.x; i < kBins; i += 256) hist[i] = 0;
     __syncthreads();
-    const uint32_t prefix = st->prefix;
-    double zsum = 0.0;
-    // eight independent loads per thread in flight: the pass is bound by their latency
-    const int64_t stride = (int64_t)gridDim.x * 256;
-    for (int64_t i0 = (int64_t)blockIdx.x * 256 + threadIdx.x; i0 < n; i0 += 8 * stride) {
-        float zi[8], zv[8];
+    const int64_t base = (int64_t)blockIdx.x * a.chunk;
+    double sum = 0.0;
+    for (int it0 = 0; it0 < a.chunk / 256; it0 += 8) {       // eight loads per thread in flight
+        float ki[8], zv[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            const int64_t i = i0 + u * stride;
-            zi[u] = i < n ? z[i] : 0.0f;
-            if constexpr (PASS == 0) zv[u] = i < n ? zval[i] : 0.0f;
+            const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
+            ki[u] = i < a.n ? a.keys[i] : 0.0f;
+            if (PASS == 0) zv[u] = i < a.n ? a.zval[i] : 0.0f;
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
-            if (i0 + u * stride >= n) continue;
-            const uint32_t key = zkey(zi[u]);
-            bool in_bucket = true;
-            if constexpr (PASS == 0) zsum += (double)zv[u];
-            else in_bucket = (key >> (kShift + kBits)) == prefix;
-            if (in_bucket) atomicAdd(&hist[(key >> kShift) & (kBins - 1)], 1u);
+            const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
+            if (i >= a.n) continue;
+            const uint32_t key = zkey(ki[u]);
+            if (PASS == 0) sum += (double)zv[u];
+            if (PASS == 0 || (key >> (kShift + kBits)) == prefix)
+                atomicAdd(&hist[(key >> kShift) & (kBins - 1)], 1u);
         }
     }
     __syncthreads();
     for (int i = threadIdx.x; i < kBins; i += 256)
-        if (hist[i]) atomicAdd(&st->hist[PASS][i], hist[i]);
-    if (PASS == 0) {
-        zsum = wave_sum(zsum);
-        if ((threadIdx.x & 63) == 0) dsh[threadIdx.x >> 6] = zsum;
-        __syncthreads();
-        if (threadIdx.x == 0) partials[blockIdx.x] = (dsh[0] + dsh[1]) + (dsh[2] + dsh[3]);
-    }
-    if (!last_block_done(&st->ticket[PASS])) return;
+        if (hist[i]) atomicAdd(&a.st->hist[PASS][i], hist[i]);
+    if (PASS == 0) *zsum = sum;
+}
 
-    // ---- serial step, one workgroup --------------------------------------------------------
+// From the complete device-wide histogram of a pass: the digit that holds the `need`-th largest
+// entry and how many entries of that bin are still needed.  Every workgroup computes this for
+// itself (same inputs, same result), which saves a second barrier per pass.
+template <int PASS>
+__device__ __forceinline__ void find_digit(const SelectArgs &a, uint32_t &prefix, uint32_t &need,
+                                           uint32_t *tsum, uint32_t *found)
+{
+    constexpr int kBits = PASS == 2 ? 10 : 11;
+    constexpr int kBins = 1 << kBits;
     constexpr int kPer = kBins / 256;                    // consecutive bins per thread
     uint32_t mine[kPer], total = 0;
 #pragma unroll
     for (int b = 0; b < kPer; ++b) {
-        mine[b] = coherent_load(&st->hist[PASS][threadIdx.x * kPer + b]);
+        mine[b] = coherent_load(&a.st->hist[PASS][threadIdx.x * kPer + b]);
         total += mine[b];
     }
     tsum[threadIdx.x] = total;
     __syncthreads();
-    // entries in bins above this thread's range (exclusive suffix sum over 256 threads)
-    uint32_t above = 0;
+    uint32_t above = 0;                                  // entries in bins above this thread's range
     for (int t = threadIdx.x + 1; t < 256; ++t) above += tsum[t];
-    const uint32_t need = st->remaining;
     if (above < need && need <= above + total) {
         uint32_t acc = above;
 #pragma unroll
         for (int b = kPer - 1; b >= 0; --b) {
             if (acc < need && need <= acc + mine[b]) {
-                st->prefix = (prefix << kBits) | (uint32_t)(threadIdx.x * kPer + b);
-                st->remaining = need - acc;      // still to take from that bin
+                found[0] = (prefix << kBits) | (uint32_t)(threadIdx.x * kPer + b);
+                found[1] = need - acc;                   // still to take from that bin
             }
             acc += mine[b];
         }
     }
-    if (PASS == 0) {
-        double s = 0.0;
-        for (int i = threadIdx.x; i < (int)gridDim.x; i += 256) s += coherent_load(&partials[i]);
-        s = wave_sum(s);
-        __syncthreads();
-        if ((threadIdx.x & 63) == 0) dsh[threadIdx.x >> 6] = s;
-        __syncthreads();
-        if (threadIdx.x == 0) scalars[S_SUM_ALL] = (dsh[0] + dsh[1]) + (dsh[2] + dsh[3]);
-    }
+    __syncthreads();
+    prefix = found[0];
+    need = found[1];
+    __syncthreads();
 }
 
-// Per chunk of kChunk consecutive entries: how many lie above the threshold key and how many
-// equal it; the last workgroup turns the counts into exclusive prefixes.
-__global__ __launch_bounds__(256) void select_count_kernel(const float *z, int64_t n, int chunk,
-                                                           SelectState *st, uint32_t *blk_gt,
-                                                           uint32_t *blk_eq)
+__device__ __forceinline__ double block_sum_partials(const double *partials, int count, double *dsh)
 {
-    __shared__ uint32_t sg[4], se[4];
-    __shared__ uint32_t pg[256], pe[256];
-    const uint32_t thr = st->prefix;
-    const int64_t base = (int64_t)blockIdx.x * chunk;
-    uint32_t g = 0, e = 0;
-    for (int it0 = 0; it0 < chunk / 256; it0 += 8) {     // chunk is a multiple of 8 tiles of 256
-        float zi[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
-            zi[u] = i < n ? z[i] : 0.0f;
-        }
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
-            const uint32_t key = zkey(zi[u]);
-            g += i < n && key > thr;
-            e += i < n && key == thr;
-        }
-    }
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) {
-        g += __shfl_xor(g, o, kWave);
-        e += __shfl_xor(e, o, kWave);
-    }
-    if ((threadIdx.x & 63) == 0) { sg[threadIdx.x >> 6] = g; se[threadIdx.x >> 6] = e; }
+    double s = 0.0;
+    for (int i = threadIdx.x; i < count; i += 256) s += coherent_load(&partials[i]);
+    s = wave_sum(s);
     __syncthreads();
-    if (threadIdx.x == 0) {
-        blk_gt[blockIdx.x] = sg[0] + sg[1] + sg[2] + sg[3];
-        blk_eq[blockIdx.x] = se[0] + se[1] + se[2] + se[3];
-    }
-    if (!last_block_done(&st->ticket[3])) return;
-
-    const int64_t nb = gridDim.x;
-    const int64_t per = (nb + 255) / 256;
-    const int64_t lo = threadIdx.x * per, hi = lo + per < nb ? lo + per : nb;
-    uint32_t tg = 0, te = 0;
-    for (int64_t b = lo; b < hi; ++b) { tg += coherent_load(&blk_gt[b]); te += coherent_load(&blk_eq[b]); }
-    pg[threadIdx.x] = tg;
-    pe[threadIdx.x] = te;
+    if ((threadIdx.x & 63) == 0) dsh[threadIdx.x >> 6] = s;
     __syncthreads();
-    uint32_t og = 0, oe = 0;
-    for (int t = 0; t < (int)threadIdx.x; ++t) { og += pg[t]; oe += pe[t]; }
-    for (int64_t b = lo; b < hi; ++b) {
-        const uint32_t cg = coherent_load(&blk_gt[b]), ce = coherent_load(&blk_eq[b]);
-        blk_gt[b] = og;
-        blk_eq[b] = oe;
-        og += cg;
-        oe += ce;
-    }
+    return (dsh[0] + dsh[1]) + (dsh[2] + dsh[3]);
 }
 
-// Ordered scatter: entry i goes to position (#selected entries with a smaller index).
-__global__ __launch_bounds__(256) void select_scatter_kernel(const float *z, int64_t n, int64_t m,
-                                                             int chunk, SelectState *st,
-                                                             const uint32_t *blk_gt,
-                                                             const uint32_t *blk_eq, int32_t *P,
-                                                             int32_t *P_out, double *partials,
-                                                             double *scalars, const float *zval)
+// The whole selection in one launch: three histogram passes find the key of the m-th largest
+// entry, then a count per chunk and an ordered scatter write the indices.  Workgroups meet at six
+// barriers; each owns one chunk of consecutive entries throughout.
+__global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
 {
+    __shared__ uint32_t hist[2048];
+    __shared__ uint32_t tsum[256];
+    __shared__ uint32_t found[2];
     __shared__ uint32_t wg[4], we[4];
     __shared__ double dsh[4];
-    const uint32_t thr = st->prefix, take_eq = st->remaining;
+    SelectState *st = a.st;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    uint32_t gt_before = blk_gt[blockIdx.x], eq_before = blk_eq[blockIdx.x];
-    const int64_t base = (int64_t)blockIdx.x * chunk;
+    const uint32_t G = gridDim.x;
+    uint32_t bar = a.bar_base;
+    uint32_t *ctr = &st->ticket[0];
+
+    // -- start from clean device-wide histograms and counters
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < 3 * 2048; i += G * 256)
+        coherent_store(&st->hist[0][0] + i, 0u);
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        st->n_fill = 0;
+        st->n_evict = 0;
+    }
+    bar += G;
+    if (!grid_sync(ctr, bar, &st->cd_abort, a.spin_limit)) return;
+
+    // -- the key of the m-th largest entry, digit by digit
+    uint32_t prefix = 0, need = (uint32_t)a.m;
+    double zsum = 0.0;
+    hist_pass<0>(a, prefix, hist, &zsum);
+    zsum = wave_sum(zsum);
+    if (lane == 0) dsh[w] = zsum;
+    __syncthreads();
+    if (threadIdx.x == 0) coherent_store(&a.partials[blockIdx.x], (dsh[0] + dsh[1]) + (dsh[2] + dsh[3]));
+    bar += G;
+    if (!grid_sync(ctr, bar, &st->cd_abort, a.spin_limit)) return;
+    find_digit<0>(a, prefix, need, tsum, found);
+    double all = 0.0;
+    if (blockIdx.x == 0) {
+        all = block_sum_partials(a.partials, (int)G, dsh);
+        if (threadIdx.x == 0) a.scalars[S_SUM_ALL] = all;
+    }
+    hist_pass<1>(a, prefix, hist, nullptr);
+    bar += G;
+    if (!grid_sync(ctr, bar, &st->cd_abort, a.spin_limit)) return;
+    find_digit<1>(a, prefix, need, tsum, found);
+    hist_pass<2>(a, prefix, hist, nullptr);
+    bar += G;
+    if (!grid_sync(ctr, bar, &st->cd_abort, a.spin_limit)) return;
+    find_digit<2>(a, prefix, need, tsum, found);
+    const uint32_t thr = prefix, take_eq = need;         // full key; entries equal to it still to take
+
+    // -- per chunk: entries above the key, entries equal to it
+    const int64_t base = (int64_t)blockIdx.x * a.chunk;
+    {
+        uint32_t g = 0, e = 0;
+        for (int it0 = 0; it0 < a.chunk / 256; it0 += 8) {
+            float ki[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
+                ki[u] = i < a.n ? a.keys[i] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
+                const uint32_t key = zkey(ki[u]);
+                g += i < a.n && key > thr;
+                e += i < a.n && key == thr;
+            }
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            g += __shfl_xor(g, o, kWave);
+            e += __shfl_xor(e, o, kWave);
+        }
+        if (lane == 0) { wg[w] = g; we[w] = e; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            coherent_store(&a.blk_gt[blockIdx.x], wg[0] + wg[1] + wg[2] + wg[3]);
+            coherent_store(&a.blk_eq[blockIdx.x], we[0] + we[1] + we[2] + we[3]);
+        }
+    }
+    bar += G;
+    if (!grid_sync(ctr, bar, &st->cd_abort, a.spin_limit)) return;
+    // entries of both kinds in the chunks before this one (G <= kMaxGroups <= 256: one per thread)
+    uint32_t gt_before = 0, eq_before = 0;
+    {
+        uint32_t g = 0, e = 0;
+        if (threadIdx.x < blockIdx.x) {
+            g = coherent_load(&a.blk_gt[threadIdx.x]);
+            e = coherent_load(&a.blk_eq[threadIdx.x]);
+        }
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) {
+            g += __shfl_xor(g, o, kWave);
+            e += __shfl_xor(e, o, kWave);
+        }
+        __syncthreads();
+        if (lane == 0) { wg[w] = g; we[w] = e; }
+        __syncthreads();
+        gt_before = wg[0] + wg[1] + wg[2] + wg[3];
+        eq_before = we[0] + we[1] + we[2] + we[3];
+        __syncthreads();
+    }
+
+    // -- ordered scatter: entry i goes to position (#selected entries with a smaller index)
     double ssel = 0.0;
-    for (int it0 = 0; it0 < chunk / 256; it0 += 8) {     // chunk is a multiple of 8 tiles of 256
-      float zpre[8];
+    for (int it0 = 0; it0 < a.chunk / 256; it0 += 8) {
+        float kpre[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-          const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
-          zpre[u] = i < n ? z[i] : 0.0f;
-      }
+        for (int u = 0; u < 8; ++u) {
+            const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
+            kpre[u] = i < a.n ? a.keys[i] : 0.0f;
+        }
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
-        bool g = false, e = false;
-        if (i < n) {
-            const uint32_t key = zkey(zpre[u]);
-            g = key > thr;
-            e = key == thr;
-        }
-        const unsigned long long mg = __ballot(g), me = __ballot(e);
-        const unsigned long long below = (1ull << lane) - 1ull;
-        if (lane == 0) { wg[w] = __popcll(mg); we[w] = __popcll(me); }
-        __syncthreads();
-        uint32_t og = gt_before + __popcll(mg & below), oe = eq_before + __popcll(me & below);
-        uint32_t tg = 0, te = 0;
+        for (int u = 0; u < 8; ++u) {
+            const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
+            bool g = false, e = false;
+            if (i < a.n) {
+                const uint32_t key = zkey(kpre[u]);
+                g = key > thr;
+                e = key == thr;
+            }
+            const unsigned long long mg = __ballot(g), me = __ballot(e);
+            const unsigned long long below = (1ull << lane) - 1ull;
+            if (lane == 0) { wg[w] = __popcll(mg); we[w] = __popcll(me); }
+            __syncthreads();
+            uint32_t og = gt_before + __popcll(mg & below), oe = eq_before + __popcll(me & below);
+            uint32_t tg = 0, te = 0;
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            if (u < w) { og += wg[u]; oe += we[u]; }
-            tg += wg[u];
-            te += we[u];
+            for (int q = 0; q < 4; ++q) {
+                if (q < w) { og += wg[q]; oe += we[q]; }
+                tg += wg[q];
+                te += we[q];
+            }
+            if (g || (e && oe < take_eq)) {
+                const uint32_t pos = og + (oe < take_eq ? oe : take_eq);
+                a.P[pos] = (int32_t)i;
+                if (a.P_out) a.P_out[pos] = (int32_t)i;
+                ssel += (double)a.zval[i];
+            }
+            gt_before += tg;
+            eq_before += te;
+            __syncthreads();
         }
-        if (g || (e && oe < take_eq)) {
-            const uint32_t pos = og + (oe < take_eq ? oe : take_eq);
-            P[pos] = (int32_t)i;
-            if (P_out) P_out[pos] = (int32_t)i;
-            ssel += (double)zval[i];
-        }
-        gt_before += tg;
-        eq_before += te;
-        __syncthreads();
-      }
     }
     ssel = wave_sum(ssel);
     if (lane == 0) dsh[w] = ssel;
     __syncthreads();
-    if (threadIdx.x == 0) partials[blockIdx.x] = (dsh[0] + dsh[1]) + (dsh[2] + dsh[3]);
-    if (!last_block_done(&st->ticket[4])) return;
-    double s = 0.0;
-    for (int i = threadIdx.x; i < (int)gridDim.x; i += 256) s += coherent_load(&partials[i]);
-    s = wave_sum(s);
-    __syncthreads();
-    if (lane == 0) dsh[w] = s;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const double sel = (dsh[0] + dsh[1]) + (dsh[2] + dsh[3]);
-        const double all = scalars[S_SUM_ALL];
-        scalars[S_SUM_SEL] = sel;
-        // eq. (7): (mean of z over P) / (mean of z over all coordinates)
-        scalars[S_RHO] = all > 0.0 ? (sel / (double)m) / (all / (double)n) : 1.0;
+    if (threadIdx.x == 0) coherent_store(&a.partials[blockIdx.x], (dsh[0] + dsh[1]) + (dsh[2] + dsh[3]));
+    bar += G;
+    if (!grid_sync(ctr, bar, &st->cd_abort, a.spin_limit)) return;
+    if (blockIdx.x == 0) {
+        const double sel = block_sum_partials(a.partials, (int)G, dsh);
+        if (threadIdx.x == 0) {
+            a.scalars[S_SUM_SEL] = sel;
+            // eq. (7): (mean of z over P) / (mean of z over all coordinates)
+            a.scalars[S_RHO] = all > 0.0 ? (sel / (double)a.m) / (all / (double)a.n) : 1.0;
+        }
     }
 }
 
@@ -410,34 +466,39 @@ hipError_t launch_score(duhl_ctx *c, int scheme, int64_t m, uint64_t arg)
 
 hipError_t launch_select(duhl_ctx *c, int64_t m, int32_t *P_out, const float *keys)
 {
-    hipStream_t s = c->compute;
     const int64_t n = c->n;
-    hipLaunchKernelGGL(select_reset_kernel, dim3(1), dim3(1024), 0, s, c->sel, (uint32_t)m);
-    int64_t hgrid = (n + 2047) / 2048;
-    if (hgrid > kMaxGroups) hgrid = kMaxGroups;
-    hipLaunchKernelGGL(select_hist_kernel<0>, dim3(hgrid), dim3(256), 0, s, keys, c->z, n, c->sel,
-                       c->partials, c->scalars);
-    hipLaunchKernelGGL(select_hist_kernel<1>, dim3(hgrid), dim3(256), 0, s, keys, c->z, n, c->sel,
-                       c->partials, c->scalars);
-    hipLaunchKernelGGL(select_hist_kernel<2>, dim3(hgrid), dim3(256), 0, s, keys, c->z, n, c->sel,
-                       c->partials, c->scalars);
     int64_t chunk = ((n + kMaxGroups - 1) / kMaxGroups + kChunk - 1) / kChunk * kChunk;   // whole 8-tile batches
     if (chunk < kChunk) chunk = kChunk;
     const int64_t nb = (n + chunk - 1) / chunk;
-    hipLaunchKernelGGL(select_count_kernel, dim3(nb), dim3(256), 0, s, keys, n, (int)chunk, c->sel, c->blk_gt,
-                       c->blk_eq);
-    hipLaunchKernelGGL(select_scatter_kernel, dim3(nb), dim3(256), 0, s, keys, n, m, (int)chunk, c->sel,
-                       c->blk_gt, c->blk_eq, c->P_next, P_out, c->partials, c->scalars, c->z);
+    SelectArgs a;
+    a.keys = keys;
+    a.zval = c->z;
+    a.n = n;
+    a.m = m;
+    a.chunk = (int)chunk;
+    a.st = c->sel;
+    a.blk_gt = c->blk_gt;
+    a.blk_eq = c->blk_eq;
+    a.P = c->P_next;
+    a.P_out = P_out;
+    a.partials = c->partials;
+    a.scalars = c->scalars;
+    a.bar_base = c->sel_bar;
+    a.spin_limit = 1 << 22;                              // seconds; the barriers take microseconds
+    c->sel_bar += 6u * (uint32_t)nb;                     // six barriers of nb arrivals each
+    hipLaunchKernelGGL(select_fused_kernel, dim3(nb), dim3(256), 0, c->compute, a);
     return hipGetLastError();
 }
 
-hipError_t launch_plan_swap(duhl_ctx *c, bool overlap_safe)
+hipError_t launch_plan_swap(duhl_ctx *c, bool overlap_safe, bool want_count)
 {
     hipStream_t s = c->compute;
     const int T = 256;
     const int64_t m = c->m_next;
+    // device residency: nothing to copy, only count what changed -- and only if someone asks
+    if (c->res != DUHL_RESIDENT_HOST && !want_count) return hipSuccess;
     hipLaunchKernelGGL(mark_clear_kernel, dim3((c->n + T - 1) / T), dim3(T), 0, s, c->mark, c->n);
-    if (c->res != DUHL_RESIDENT_HOST) {     // nothing to copy: only count what changed
+    if (c->res != DUHL_RESIDENT_HOST) {
         if (c->m_cur > 0)
             hipLaunchKernelGGL(mark_set_kernel, dim3((c->m_cur + T - 1) / T), dim3(T), 0, s, c->mark,
                                c->P_cur, c->m_cur);
