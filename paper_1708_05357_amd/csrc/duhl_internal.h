@@ -176,9 +176,8 @@ enum Scalar { S_GAP_SUM = 0, S_SUM_ALL, S_SUM_SEL, S_RHO, S_OBJ_SQ, S_OBJ_LIN, S
 // Scratch of the selection kernels (device memory, one per context).
 struct SelectState {
     uint32_t hist[3][2048];
-    uint32_t ticket[8];  // [0]: arrivals at the selection kernel's barriers, only ever incremented
-    uint32_t prefix;     // high bits of the threshold key decided so far
-    uint32_t remaining;  // how many of the current bucket are still needed
+    uint32_t barrier;    // arrivals at the selection kernel's barriers, only ever incremented
+    uint32_t reserved[9];
     uint32_t n_fill;     // columns to copy (host residency)
     uint32_t n_evict;    // evictable slots found
     uint32_t error;      // validation flags

@@ -14,9 +14,9 @@ namespace duhl {
 
 namespace {
 
-constexpr int kChunk = 2048;   // fewest elements per workgroup in the count / scatter passes
-constexpr int kMaxGroups = 128;   // most workgroups per selection launch: each one ends with a fence
-                                  // and a ticket, which cost more than reading 8 KB more of z
+constexpr int kChunk = 2048;      // granularity of a workgroup's chunk: eight tiles of 256 entries
+constexpr int kMaxGroups = 128;   // most workgroups of the selection launch: all must be resident at
+                                  // once, and a barrier costs more the more of them arrive
 
 __device__ __forceinline__ uint32_t zkey(float z)
 {
@@ -78,7 +78,7 @@ struct SelectArgs {
     uint32_t *blk_gt, *blk_eq;
     int32_t *P, *P_out;
     double *partials, *scalars;
-    uint32_t bar_base;     // value of st->ticket[0] before this launch
+    uint32_t bar_base;     // value of st->barrier before this launch
     int spin_limit;
 };
 
@@ -180,7 +180,7 @@ __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const uint32_t G = gridDim.x;
     uint32_t bar = a.bar_base;
-    uint32_t *ctr = &st->ticket[0];
+    uint32_t *ctr = &st->barrier;
 
     // -- start from clean device-wide histograms and counters
     for (int i = blockIdx.x * 256 + threadIdx.x; i < 3 * 2048; i += G * 256)
