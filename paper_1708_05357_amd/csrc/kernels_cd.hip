@@ -844,25 +844,28 @@ bool launch_workers(duhl_ctx *c, const CdArgs &a, int max_inflight, bool vec, hi
         if (*err != hipSuccess) return true;
     }
     const int64_t inflight = inflight_limit(c, a.count, max_inflight);
-    // Columns of 53,249 to 212,992 entries: two or four compute units per worker, everything on chip
-    if (T == 1024 && chunks > 13 && chunks <= 52 && c->cd_units != 1) {
-        const int cus = c->cd_units == 2 || c->cd_units == 4 ? c->cd_units : (chunks <= 26 ? 2 : 4);
+    // Columns of 53,249 to 425,984 entries: two, four or eight compute units per worker, everything on chip
+    if (T == 1024 && chunks > 13 && chunks <= 104 && c->cd_units != 1) {
+        const int cus = c->cd_units == 2 || c->cd_units == 4 || c->cd_units == 8
+                            ? c->cd_units : (chunks <= 26 ? 2 : (chunks <= 52 ? 4 : 8));
         const int64_t avail = c->num_cu - (c->res == DUHL_RESIDENT_HOST ? c->copy_blocks : 0);
         const int64_t workers = avail / (8 * cus) * 8;
         if (workers >= 8 && workers <= c->dv_workers && chunks <= 13 * cus) {
             if (!c->xch) {
-                *err = hipMalloc(reinterpret_cast<void **>(&c->xch), (size_t)c->dv_workers * 8 * sizeof(uint64_t));
+                *err = hipMalloc(reinterpret_cast<void **>(&c->xch), (size_t)c->dv_workers * 16 * sizeof(uint64_t));
                 if (*err == hipSuccess)
-                    *err = hipMemsetAsync(c->xch, 0, (size_t)c->dv_workers * 8 * sizeof(uint64_t), c->compute);
+                    *err = hipMemsetAsync(c->xch, 0, (size_t)c->dv_workers * 16 * sizeof(uint64_t), c->compute);
                 if (*err != hipSuccess) return true;
                 c->xseq = 1;
             }
             if (vec)
-                *err = cus == 2 ? launch_multi<MODEL, 2, true>(c, a, inflight, workers, chunks)
-                                : launch_multi<MODEL, 4, true>(c, a, inflight, workers, chunks);
+                *err = cus == 2   ? launch_multi<MODEL, 2, true>(c, a, inflight, workers, chunks)
+                       : cus == 4 ? launch_multi<MODEL, 4, true>(c, a, inflight, workers, chunks)
+                                  : launch_multi<MODEL, 8, true>(c, a, inflight, workers, chunks);
             else                                        // columns start only 4-byte aligned
-                *err = cus == 2 ? launch_multi<MODEL, 2, false>(c, a, inflight, workers, chunks)
-                                : launch_multi<MODEL, 4, false>(c, a, inflight, workers, chunks);
+                *err = cus == 2   ? launch_multi<MODEL, 2, false>(c, a, inflight, workers, chunks)
+                       : cus == 4 ? launch_multi<MODEL, 4, false>(c, a, inflight, workers, chunks)
+                                  : launch_multi<MODEL, 8, false>(c, a, inflight, workers, chunks);
             return true;
         }
     }

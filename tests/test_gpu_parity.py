@@ -316,7 +316,7 @@ def converge_oracle(p, m, max_rounds, passes, target_rel_gap):
 
 @pytest.mark.parametrize("scheme", ["async", "atomic"])
 @pytest.mark.parametrize("kind", ["cfg1", "lasso_mid", "lasso_ragged", "lasso_long", "lasso_longer",
-                                  "lasso_longest", "lasso_extended", "lasso_unaligned",
+                                  "lasso_longest", "lasso_extended", "lasso_eight_units", "lasso_unaligned",
                                   "lasso_long_unaligned", "svm_dense", "svm_csr"])
 def test_async_cd_reaches_the_oracle_objective(G, kind, scheme):
     """The asynchronous scheme is compared on what is unique: the objective at convergence
@@ -343,6 +343,9 @@ def test_async_cd_reaches_the_oracle_objective(G, kind, scheme):
     elif kind == "lasso_extended":
         prob = lasso_problem(150002, 160, 0.05, 0.05, seed=18)      # part of the private v in device memory
         m = 70
+    elif kind == "lasso_eight_units":
+        prob = lasso_problem(300004, 96, 0.05, 0.05, seed=20)       # eight compute units per worker
+        m = 40
     elif kind == "lasso_unaligned":
         prob = lasso_problem(50002, 300, 0.05, 0.05, seed=15)       # leading dimension = d: scalar kernels
         m = 120
