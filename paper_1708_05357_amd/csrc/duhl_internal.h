@@ -258,7 +258,8 @@ struct duhl_ctx {
     int cd_spin_limit; // polls a workgroup waits for a partner's partial sum before it gives up
     int csr_blocked;         // build and use the blocked copy of sparse data
     int csr_blocked_waves;   // workgroups per compute unit launched by its pass
-    int csr_blocked_shape;   // 100*G + U to force the lanes per span and rows per span (0 = by density)
+    int csr_blocked_shape;   // 100000*G + 1000*U + 10*K + NB to force the pass's shape (0 = by density)
+    int csr_blocked_list_min;   // shortest index list evaluated from the blocked copy (< 0: by traffic)
 
     std::string err;
 };
@@ -287,6 +288,6 @@ hipError_t launch_sum_partials(duhl_ctx *c, int64_t count, int scalar_slot);
 void host_sampler_destroy(duhl_ctx *c);
 hipError_t csr_blocked_build(duhl_ctx *c);
 void csr_blocked_free(duhl_ctx *c);
-hipError_t launch_gap_csr_blocked(duhl_ctx *c, int64_t *grid_out);
+hipError_t launch_gap_csr_blocked(duhl_ctx *c, const int32_t *idx, int64_t count, int64_t *grid_out);
 
 }  // namespace duhl

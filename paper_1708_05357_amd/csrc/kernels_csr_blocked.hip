@@ -143,8 +143,9 @@ struct BlockedArgs {
     const uint16_t *idx16;
     const float *valb;
     const float *v;
-    float *partial;          // R*n partial dot products, ordered (range, row)
-    int64_t n, d;
+    float *partial;          // R*count partial dot products, ordered (range, list position)
+    const int32_t *idx;      // the rows to evaluate (then one row per span), or nullptr for all n
+    int64_t n, d, count;     // count = n without a list
     int R, W;
 };
 
@@ -279,9 +280,9 @@ __global__ __launch_bounds__(1024) void csr_blocked_dot_kernel(const BlockedArgs
     const int64_t group = threadIdx.x / G;
     constexpr int64_t kGroups = 1024 / G;
     const int64_t *rp = a.bptr + (int64_t)r * a.n;       // boundaries of this range's rows
-    float *out = a.partial + (int64_t)r * a.n;
+    float *out = a.partial + (int64_t)r * a.count;
     // a workgroup streams its own contiguous share of the range's spans
-    const int64_t all_spans = (a.n + U - 1) / U;
+    const int64_t all_spans = (a.count + U - 1) / U;
     const int64_t share = ((all_spans + nb - 1) / nb + kGroups - 1) / kGroups * kGroups;
     const int64_t first = b * share;
     const int64_t nspans = first + share < all_spans ? first + share : all_spans;
@@ -290,6 +291,10 @@ __global__ __launch_bounds__(1024) void csr_blocked_dot_kernel(const BlockedArgs
     // the spans past the last one (all boundaries 0: an empty span at the start of the arrays)
     auto boundary = [&](int64_t s) -> int64_t {
         if (sub > U || s >= nspans) return 0;
+        if (U == 1 && a.idx) {                           // a listed row; entries that name none: empty
+            const int64_t j = a.idx[s];
+            return (uint64_t)j < (uint64_t)a.n ? rp[j + sub] : 0;
+        }
         const int64_t row = s * U + sub;
         return rp[row < a.n ? row : a.n];
     };
@@ -326,7 +331,7 @@ __global__ __launch_bounds__(1024) void csr_blocked_dot_kernel(const BlockedArgs
         for (int u = 0; u < U; ++u) {
             const float s = span_group_sum<G>(acc[u]);
             const int64_t row = span * U + u;
-            if (sub == u && row < a.n) out[row] = s;
+            if (sub == u && row < a.count) out[row] = s;
         }
     };
 
@@ -352,9 +357,10 @@ __global__ __launch_bounds__(1024) void csr_blocked_dot_kernel(const BlockedArgs
 struct FinishArgs {
     ModelConst mc;
     const float *partial, *alpha, *target;
+    const int32_t *idx;
     float *z;
     double *partials;
-    int64_t n;
+    int64_t n, count;
     int R;
 };
 
@@ -362,11 +368,12 @@ template <int MODEL>
 __global__ __launch_bounds__(256) void csr_blocked_finish_kernel(const FinishArgs a)
 {
     __shared__ double sh[4];
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t k = (int64_t)blockIdx.x * 256 + threadIdx.x;
     double wsum = 0.0;
-    if (i < a.n) {
+    const int64_t i = k < a.count ? (a.idx ? (int64_t)a.idx[k] : k) : -1;
+    if ((uint64_t)i < (uint64_t)a.n) {
         float c = 0.0f;
-        for (int r = 0; r < a.R; ++r) c += a.partial[(int64_t)r * a.n + i];
+        for (int r = 0; r < a.R; ++r) c += a.partial[(int64_t)r * a.count + k];
         const float y = (MODEL == DUHL_SVM) ? a.target[i] : 0.0f;
         const float zz = gap_value<MODEL>(a.mc, c, a.alpha[i], y);
         a.z[i] = zz;
@@ -446,8 +453,9 @@ hipError_t csr_blocked_build(duhl_ctx *c)
     return hipSuccess;
 }
 
-// Gaps of all n coordinates from the blocked copy; *grid_out = number of per-block partial sums.
-hipError_t launch_gap_csr_blocked(duhl_ctx *c, int64_t *grid_out)
+// Gaps of all n coordinates (idx == nullptr) or of the listed ones from the blocked copy;
+// *grid_out = number of per-block partial sums.
+hipError_t launch_gap_csr_blocked(duhl_ctx *c, const int32_t *idx, int64_t count, int64_t *grid_out)
 {
     BlockedArgs a;
     a.bptr = c->cb_ptr;
@@ -457,6 +465,8 @@ hipError_t launch_gap_csr_blocked(duhl_ctx *c, int64_t *grid_out)
     a.partial = c->cb_partial;
     a.n = c->n;
     a.d = c->d;
+    a.idx = idx;
+    a.count = idx ? count : c->n;
     a.R = c->cb_R;
     a.W = c->cb_W;
     // one workgroup per compute unit at a time (its LDS holds a range of v); a few rounds of
@@ -472,9 +482,11 @@ hipError_t launch_gap_csr_blocked(duhl_ctx *c, int64_t *grid_out)
         U = (shape / 1000) % 100;
         K = (shape / 10) % 100;
         NB = shape % 10;
-    } else if (quads <= 4.5) {
+    } else if (idx && quads <= 12.0) {                   // a list: one row per span, so fewer lanes
+        G = 4; U = 1; K = 3;
+    } else if (!idx && quads <= 4.5) {
         U = 6; NB = 2;
-    } else if (quads <= 9.5) {
+    } else if (!idx && quads <= 9.5) {
         U = 3;
     } else if (quads <= 28.0) {
         U = 1;
@@ -485,7 +497,8 @@ hipError_t launch_gap_csr_blocked(duhl_ctx *c, int64_t *grid_out)
     } else {
         G = 64; U = 1; K = 4; NB = 2;
     }
-    const int64_t spans = (c->n + U - 1) / U;
+    if (idx && U != 1) { G = 16; U = 1; K = 2; NB = 3; }   // (a forced shape that does not fit a list)
+    const int64_t spans = (a.count + U - 1) / U;
     const int64_t max_useful = (spans + (1024 / G) - 1) / (1024 / G);
     if (per_range > max_useful) per_range = max_useful;
     if (per_range < 1) per_range = 1;
@@ -515,11 +528,13 @@ hipError_t launch_gap_csr_blocked(duhl_ctx *c, int64_t *grid_out)
     f.partial = c->cb_partial;
     f.alpha = c->alpha;
     f.target = c->target;
+    f.idx = idx;
     f.z = c->z;
     f.partials = c->partials;
     f.n = c->n;
+    f.count = a.count;
     f.R = c->cb_R;
-    const int64_t fgrid = (c->n + 255) / 256;
+    const int64_t fgrid = (a.count + 255) / 256;
     if (c->model == DUHL_LASSO)
         hipLaunchKernelGGL(csr_blocked_finish_kernel<DUHL_LASSO>, dim3(fgrid), dim3(256), 0, c->compute, f);
     else if (c->model == DUHL_ELASTIC_NET)

@@ -154,6 +154,16 @@ def test_cfg3_full_size_sparse_svm(G):
     total = g.gap()
     assert total == pytest.approx(o.gaps(), rel=1e-4)
     G.assert_gaps_close(g.get(duhl.Z), o.z, floor=8 * 2.0 ** -24 / n)
+    # an index list long enough to be evaluated from the blocked copy, and a short one
+    for count in (300000, 3000):
+        listed = rng.permutation(n)[:count].astype(np.int32)
+        g.set(duhl.Z, np.full(n, -1.0, dtype=np.float32))
+        part = g.gap(G.dev_i32(listed))
+        z = g.get(duhl.Z)
+        G.assert_gaps_close(z[listed], o.z[listed], floor=8 * 2.0 ** -24 / n)
+        assert part == pytest.approx(float(o.z[listed].sum()), rel=1e-4)
+        assert int((z != -1.0).sum()) == count
+    g.gap(want_sum=False)
     out = torch.empty(m, dtype=torch.int32, device="cuda:0")
     g.select(m, out)
     z32 = g.get(duhl.Z)

@@ -99,7 +99,7 @@ def test_svm_gaps_match_oracle_dense_and_csr(G):
 def test_sparse_full_gap_pass_from_the_blocked_copy(G, n, d, density):
     """The full gap pass over CSR data runs from the library's range-blocked copy of the matrix;
     every shape of that kernel must give the oracle's gaps (App. E), and the same values as the
-    plain CSR kernel that serves index lists."""
+    plain CSR kernel that serves short index lists."""
     from paper_1708_05357_amd import duhl, synth
     prob = synth.svm_csr(n, d, density, seed=11)
     p = G.Pair(prob)
@@ -119,6 +119,44 @@ def test_sparse_full_gap_pass_from_the_blocked_copy(G, n, d, density):
     z_plain = p.g.get(duhl.Z)
     G.assert_gaps_close(z_plain, p.o.z, floor=8 * 2.0 ** -24 / n)
     np.testing.assert_allclose(z_blocked, z_plain, rtol=1e-4, atol=8 * 2.0 ** -24 / n)
+    p.close()
+
+
+@pytest.mark.parametrize("n,d,density", [
+    (3000, 400, 0.02),        # ~8 non-zeros per row: four lanes per row
+    (2000, 50000, 0.002),     # two ranges, ~50 per segment
+    (1200, 3000, 0.1),        # ~300 per row: a wavefront per row
+    (700, 2000, 0.3),         # ~600 per row, four quads per lane
+])
+def test_sparse_index_lists_from_the_blocked_copy(G, monkeypatch, n, d, density):
+    """Long index lists over CSR data are evaluated from the range-blocked copy too (the
+    threshold is lowered here so that short lists take that path): listed coordinates get the
+    oracle's gaps (App. E), coordinates not listed keep their old entry, entries that name no
+    coordinate are skipped, and the sum is that of the listed gaps."""
+    from paper_1708_05357_amd import duhl, synth
+    monkeypatch.setenv("DUHL_CSR_BLOCKED_LIST_MIN", "1")
+    prob = synth.svm_csr(n, d, density, seed=12)
+    p = G.Pair(prob)
+    rng = np.random.default_rng(2)
+    p.g.select(n // 3)
+    p.g.commit_swap()
+    p.g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(rng.permutation(p.g.get(duhl.P)).astype(np.int32)))
+    p.sync_oracle_to_gpu_state()
+    p.o.gaps()
+    for count in (1, 37, n // 2, n - 1):
+        listed = rng.permutation(n)[:count].astype(np.int32)
+        with_bad = listed.copy()
+        if count >= 37:
+            with_bad[5], with_bad[count - 1] = -3, n           # skipped; their rows drop out
+            listed = np.delete(listed, [5, count - 1])
+        p.g.set(duhl.Z, np.full(n, -1.0, dtype=np.float32))
+        total = p.g.gap(G.dev_i32(with_bad))
+        z = p.g.get(duhl.Z)
+        rest = np.ones(n, dtype=bool)
+        rest[listed] = False
+        assert (z[rest] == -1.0).all()
+        G.assert_gaps_close(z[listed], p.o.z[listed], floor=8 * 2.0 ** -24 / n)
+        assert total == pytest.approx(float(z[listed].astype(np.float64).sum()), rel=1e-9)
     p.close()
 
 
