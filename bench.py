@@ -307,6 +307,59 @@ def cpu_baseline(prob, m, budget_s=20.0):
             "gap_pass_threads": threads, "gap_pass_s_threads": t_par, "gap_GBps_threads": gap_bytes / t_par / 1e9}
 
 
+def cpu_time_to_gap(prob, m, target, budget_s):
+    """The paper's CPU reference point (Section 5.3: one thread of coordinate descent over all
+    coordinates) and the oracle's own DuHL rounds, each from alpha = 0 until the total gap of a
+    full pass is <= target or budget_s seconds have gone by.  Whole workload only.  Coordinate
+    descent over everything does not need gaps, so its gap passes (one per pass, the stopping
+    test) stay out of its clock; a DuHL round's gap pass drives the selection and stays in."""
+    import numpy as np
+    from oracle import duhl_oracle as orc
+    model = orc.LASSO if prob["model"] == "lasso" else orc.SVM
+    n = prob["n"]
+
+    def fresh():
+        if "cols" in prob:
+            return orc.Oracle(model, prob["target"].cpu().numpy(), prob["lam"], cols=prob["cols"].cpu().numpy())
+        return orc.Oracle(model, prob["target"].cpu().numpy(), prob["lam"],
+                          csr=(prob["rowptr"].cpu().numpy(), prob["colidx"].cpu().numpy(),
+                               prob["val"].cpu().numpy()), d=prob["d"])
+    out = {"target_total_gap": target, "cores": 1, "kind": "oracle"}
+    o = fresh()
+    rng = np.random.default_rng(0)
+    clock, rounds, gap = 0.0, 0, float("inf")
+    while clock < budget_s:
+        t0 = time.time()
+        gap = o.gaps()
+        if gap <= target:
+            clock += time.time() - t0
+            break
+        P = o.select(m)
+        o.cd_pass(P[rng.permutation(P.size)])
+        clock += time.time() - t0
+        rounds += 1
+        log(f"cpu time-to-gap: DuHL round {rounds}, {clock:.2f}s, gap before it {gap:.3e}")
+    out["duhl_rounds_of_one_pass"] = {"seconds": clock if gap <= target else None, "rounds": rounds,
+                                      "total_gap": gap}
+    log(f"cpu time-to-gap: DuHL rounds {rounds}, {clock:.2f}s, gap {gap:.3e}")
+    o = fresh()
+    rng = np.random.default_rng(0)
+    clock, passes, gap = 0.0, 0, float("inf")
+    while clock < budget_s:
+        gap = o.gaps()                              # stopping test, not part of the solver
+        if gap <= target:
+            break
+        t0 = time.time()
+        o.cd_pass(rng.permutation(n).astype(np.int32))
+        clock += time.time() - t0
+        passes += 1
+        log(f"cpu time-to-gap: CD pass {passes}, {clock:.2f}s, gap before it {gap:.3e}")
+    out["coordinate_descent_over_all"] = {"seconds": clock if gap <= target else None, "passes": passes,
+                                          "total_gap": gap}
+    log(f"cpu time-to-gap: CD over all coordinates, passes {passes}, {clock:.2f}s, gap {gap:.3e}")
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -320,6 +373,9 @@ def main():
                     help="device slots per working-set column (host residency)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-ttg", action="store_true")
+    ap.add_argument("--cpu-ttg", type=float, default=0.0,
+                    help="also time the oracle to total gap 1e-3 on one host core, for at most this many "
+                         "seconds per scheme (whole workload in host memory: cfg1-cfg3 only)")
     ap.add_argument("--copy-calibration-gib", type=float, default=0.0,
                     help="also run plain device copies of this size (GiB), as a yardstick for the "
                          "FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run")
@@ -451,7 +507,8 @@ def main():
                    # host residency: the first round's selection waits for the whole working set to
                    # arrive over the link, which dominates the mean
                    "select_ms_median": sorted(sel_ms)[len(sel_ms) // 2]},
-        "roofline": {"kernel": "gap_dense_kernel" if "cols" in prob else "gap_csr_kernel",
+        "roofline": {"kernel": "gap_dense_kernel" if "cols" in prob
+                     else "csr_blocked_dot_kernel + csr_blocked_finish_kernel",
                      "bound": "hbm", "achieved": gap_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gap_gbps / HBM_PEAK_GBPS,
                      "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload, {}).get("gap")
@@ -513,6 +570,11 @@ def main():
         out["cpu_baseline"] = cpu_baseline(prob, m)
     else:
         out["cpu_baseline"] = None
+    if args.cpu_ttg > 0:
+        if prob["host_resident"] or 4.0 * prob["n"] * prob["d"] > 8e9 and "cols" in prob:
+            log("--cpu-ttg: the workload does not fit the oracle whole; skipped")
+        else:
+            out["cpu_time_to_gap"] = cpu_time_to_gap(prob, m, 1e-3, args.cpu_ttg)
     g.close()
     if args.copy_calibration_gib > 0:
         nfl = int(args.copy_calibration_gib * (1 << 30) / 4)
