@@ -93,7 +93,7 @@ duhl_status duhl_set_data_dense(duhl_ctx *ctx, const float *A, int64_t ld, duhl_
 
 /* Sparse data: CSR over coordinates, i.e. row i lists the non-zeros of column a_i (for the SVM
  * dual: CSR of the sample matrix).  rowptr (n+1, non-decreasing, rowptr[0] = 0), colidx (each
- * in [0,d)), val: device pointers, borrowed.  Only DUHL_RESIDENT_DEVICE.  Otherwise as above. */
+ * in [0,d), strictly increasing inside a row), val: device pointers, borrowed.  Only DUHL_RESIDENT_DEVICE.  Otherwise as above. */
 duhl_status duhl_set_data_csr(duhl_ctx *ctx, const int64_t *rowptr, const int32_t *colidx,
                               const float *val, duhl_residency res, const float *target,
                               double lambda);

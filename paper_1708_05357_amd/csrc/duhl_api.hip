@@ -195,7 +195,6 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->csr_blocked = env_int("DUHL_CSR_BLOCKED", 1);
     c->csr_blocked_waves = env_int("DUHL_CSR_BLOCKED_WAVES", 2);
     if (c->csr_blocked_waves < 1) c->csr_blocked_waves = 1;
-    c->csr_blocked_shape = env_int("DUHL_CSR_BLOCKED_SHAPE", 0);
     c->csr_blocked_list_min = env_int("DUHL_CSR_BLOCKED_LIST_MIN", -1);
 
     c->partials_cap = n / 4 + 4096;

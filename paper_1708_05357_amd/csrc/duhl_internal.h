@@ -224,7 +224,9 @@ struct duhl_ctx {
     float *score;               // scores of the non-gap selection rules (allocated on first use)
 
     // sparse data: copy of the matrix blocked by ranges of v, for the full gap pass (cb_R == 0: none)
-    int64_t *cb_ptr;
+    int64_t *cb_soff;        // slice starts
+    int32_t *cb_perm;        // rows by position
+    int64_t cb_slices;       // slices per range
     uint16_t *cb_idx;
     float *cb_val, *cb_partial;
     int cb_R, cb_W;
@@ -258,8 +260,7 @@ struct duhl_ctx {
     int cd_spin_limit; // polls a workgroup waits for a partner's partial sum before it gives up
     int csr_blocked;         // build and use the blocked copy of sparse data
     int csr_blocked_waves;   // workgroups per compute unit launched by its pass
-    int csr_blocked_shape;   // 100000*G + 1000*U + 10*K + NB to force the pass's shape (0 = by density)
-    int csr_blocked_list_min;   // shortest index list evaluated from the blocked copy (< 0: by traffic)
+    int csr_blocked_list_min;   // shortest index list evaluated from the blocked copy (< 0: n/4)
 
     std::string err;
 };

@@ -274,15 +274,11 @@ hipError_t launch_gap(duhl_ctx *c, const int32_t *idx, int64_t count, bool slot_
     }
     int64_t grid = 0;
     hipError_t e;
-    // sparse data: from the blocked copy -- the full pass, and lists whose entries outweigh the
-    // copies of v's ranges that the workgroups of that pass load into LDS (shorter ones gather
-    // from L2 in the plain kernel)
+    // sparse data: from the blocked copy -- the full pass, and lists so long that the dot
+    // products of all rows from that copy cost less than those of the listed rows from the CSR
+    // arrays (the plain kernel moves about four times the bytes per row)
     int64_t list_min = c->csr_blocked_list_min;
-    if (list_min < 0) {
-        const double fill = (double)c->num_cu * c->csr_blocked_waves * (double)c->cb_W * 4.0;
-        const double per_row = 6.0 * (double)c->nnz / (double)c->n + 8.0;
-        list_min = (int64_t)(fill / per_row);
-    }
+    if (list_min < 0) list_min = c->n / 4 + 1;
     if (c->sparse && c->cb_R > 0 && !slot_list && !with_norms &&
         (idx ? count >= list_min : count == c->n)) {
         e = launch_gap_csr_blocked(c, idx, count, &grid);

@@ -160,6 +160,49 @@ def test_sparse_index_lists_from_the_blocked_copy(G, monkeypatch, n, d, density)
     p.close()
 
 
+def uneven_csr(n, d, short, long_rows, long_len, seed):
+    """SVM instance whose rows have `short` non-zeros except `long_rows` of them, which have
+    `long_len`; unit rows, labels from a random separator."""
+    rng = np.random.default_rng(seed)
+    counts = np.full(n, short, dtype=np.int64)
+    counts[rng.choice(n, size=long_rows, replace=False)] = long_len
+    rowptr = np.zeros(n + 1, dtype=np.int64)
+    rowptr[1:] = np.cumsum(counts)
+    colidx = np.concatenate([np.sort(rng.choice(d, size=k, replace=False)) for k in counts]).astype(np.int32)
+    val = rng.uniform(0.1, 1.0, size=colidx.size).astype(np.float32)
+    rows = np.repeat(np.arange(n), counts)
+    val /= np.sqrt(np.bincount(rows, weights=val.astype(np.float64) ** 2, minlength=n))[rows].astype(np.float32)
+    w = rng.standard_normal(d)
+    y = np.where(np.bincount(rows, weights=val * w[colidx], minlength=n) >= 0, 1.0, -1.0).astype(np.float32)
+    t = torch.from_numpy
+    return {"model": "svm", "d": d, "n": n, "rowptr": t(rowptr), "colidx": t(colidx), "val": t(val),
+            "target": t(y), "lam": 1.0 / n}
+
+
+@pytest.mark.parametrize("n,d,short,long_rows,long_len", [
+    (3000, 5000, 5, 5, 3000),       # a few rows 600 times longer: slices would be padding, plain pass
+    (5000, 40000, 8, 700, 400),     # a seventh of the rows 50 times longer: sorted into slices of their own
+    (1100, 70000, 3, 64, 20000),    # three ranges, one slice's worth of very long rows
+])
+def test_sparse_rows_of_uneven_length(G, n, d, short, long_rows, long_len):
+    """The sliced copy of a sparse matrix pads every 64 rows to the longest of them (after
+    sorting 1,024 at a time); with rows of very different length it is either still compact or
+    not built at all, and the gaps (App. E) are the oracle's either way."""
+    from paper_1708_05357_amd import duhl
+    prob = uneven_csr(n, d, short, long_rows, long_len, seed=21)
+    p = G.Pair(prob)
+    rng = np.random.default_rng(3)
+    assert p.g.gap() == pytest.approx(1.0, rel=1e-6)         # every z_i = 1/n at alpha = 0
+    p.g.select(n // 4)
+    p.g.commit_swap()
+    p.g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(rng.permutation(p.g.get(duhl.P)).astype(np.int32)))
+    p.sync_oracle_to_gpu_state()
+    total = p.g.gap()
+    assert total == pytest.approx(p.o.gaps(), rel=1e-4)
+    G.assert_gaps_close(p.g.get(duhl.Z), p.o.z, floor=8 * 2.0 ** -24 / n)
+    p.close()
+
+
 @pytest.mark.parametrize("eta", [1.0, 0.3])
 def test_elastic_net_gaps_steps_and_objective_match_oracle(G, eta):
     """App. D elastic-net step and the gap of eq. (4) (ridge gap of App. E for eta = 1): gap vectors,
