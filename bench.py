@@ -32,7 +32,8 @@ def log(msg):
 # HBM bytes per launch of the dominant kernel from the hardware counters (FETCH_SIZE x 2.000 KiB +
 # WRITE_SIZE x 1.000 KiB, scaled by a plain 4 GiB copy): profiles/pmc_hbm_traffic_*.txt.
 COUNTER_TRAFFIC_BYTES = {"cfg5": {"gap": 50_163_207 * 2 * 1024 + 3_103 * 1024,
-                                  "cd_pass": 4 * ((1_253_125 + 25_134) * 2 * 1024 + (50_187 + 195) * 1024)}}
+                                  "cd_pass": 4 * ((1_253_125 + 25_134) * 2 * 1024 + (50_187 + 195) * 1024)},
+                         "cfg3": {"gap": 323_719 * 2 * 1024 + 13_100 * 1024}}     # the dot kernel of the pass
 
 
 def build_problem(name, device, scale):
@@ -508,7 +509,7 @@ def main():
                    # arrive over the link, which dominates the mean
                    "select_ms_median": sorted(sel_ms)[len(sel_ms) // 2]},
         "roofline": {"kernel": "gap_dense_kernel" if "cols" in prob
-                     else "csr_blocked_dot_kernel + csr_blocked_finish_kernel",
+                     else "csr_sliced_dot_kernel + csr_blocked_finish_kernel",
                      "bound": "hbm", "achieved": gap_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gap_gbps / HBM_PEAK_GBPS,
                      "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload, {}).get("gap")
