@@ -89,16 +89,16 @@ def test_svm_gaps_match_oracle_dense_and_csr(G):
 
 
 @pytest.mark.parametrize("n,d,density", [
-    (3000, 400, 0.02),        # one range, ~8 non-zeros per row: several rows per group of lanes
-    (2000, 50000, 0.002),     # two ranges, ~50 per segment
-    (1500, 80000, 0.004),     # three ranges, ~107 per segment
-    (1200, 3000, 0.1),        # one range, ~300 per row: a wavefront per row
-    (700, 2000, 0.3),         # ~600 per row, four quads per lane
-    (900, 36865, 0.001),      # range boundary one past a multiple of the range size, d % 4 != 0
+    (3000, 400, 0.02),        # one range, ~8 non-zeros per row: two quad-rows per slice
+    (2000, 50000, 0.002),     # two ranges, ~50 per row and range
+    (1500, 80000, 0.004),     # three ranges, ~107 per row and range
+    (1200, 3000, 0.1),        # one range, ~300 per row: slices longer than a wavefront's share
+    (700, 2000, 0.3),         # ~600 per row; a last window of 700 rows, the rest of it empty
+    (900, 36865, 0.001),      # d % 4 != 0; fewer rows than one sorting window
 ])
 def test_sparse_full_gap_pass_from_the_blocked_copy(G, n, d, density):
-    """The full gap pass over CSR data runs from the library's range-blocked copy of the matrix;
-    every shape of that kernel must give the oracle's gaps (App. E), and the same values as the
+    """The full gap pass over CSR data runs from the library's range-blocked, sliced copy of the
+    matrix; at every density it must give the oracle's gaps (App. E), and the same values as the
     plain CSR kernel that serves short index lists."""
     from paper_1708_05357_amd import duhl, synth
     prob = synth.svm_csr(n, d, density, seed=11)
@@ -123,14 +123,15 @@ def test_sparse_full_gap_pass_from_the_blocked_copy(G, n, d, density):
 
 
 @pytest.mark.parametrize("n,d,density", [
-    (3000, 400, 0.02),        # ~8 non-zeros per row: four lanes per row
-    (2000, 50000, 0.002),     # two ranges, ~50 per segment
-    (1200, 3000, 0.1),        # ~300 per row: a wavefront per row
-    (700, 2000, 0.3),         # ~600 per row, four quads per lane
+    (3000, 400, 0.02),        # ~8 non-zeros per row
+    (2000, 50000, 0.002),     # two ranges, ~50 per row and range
+    (1200, 3000, 0.1),        # ~300 per row
+    (700, 2000, 0.3),         # ~600 per row
 ])
 def test_sparse_index_lists_from_the_blocked_copy(G, monkeypatch, n, d, density):
-    """Long index lists over CSR data are evaluated from the range-blocked copy too (the
-    threshold is lowered here so that short lists take that path): listed coordinates get the
+    """Long index lists over CSR data are evaluated from the range-blocked copy too -- the dot
+    products of all rows, then the gap formula for the listed ones (the threshold is lowered here
+    so that short lists take that path): listed coordinates get the
     oracle's gaps (App. E), coordinates not listed keep their old entry, entries that name no
     coordinate are skipped, and the sum is that of the listed gaps."""
     from paper_1708_05357_amd import duhl, synth
