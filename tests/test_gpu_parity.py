@@ -95,6 +95,8 @@ def test_svm_gaps_match_oracle_dense_and_csr(G):
     (1200, 3000, 0.1),        # one range, ~300 per row: slices longer than a wavefront's share
     (700, 2000, 0.3),         # ~600 per row; a last window of 700 rows, the rest of it empty
     (900, 36865, 0.001),      # d % 4 != 0; fewer rows than one sorting window
+    (65, 3, 0.7),             # two slices, the second with one row; columns shorter than a quad
+    (1, 5, 1.0),              # a single row
 ])
 def test_sparse_full_gap_pass_from_the_blocked_copy(G, n, d, density):
     """The full gap pass over CSR data runs from the library's range-blocked, sliced copy of the
@@ -105,7 +107,7 @@ def test_sparse_full_gap_pass_from_the_blocked_copy(G, n, d, density):
     p = G.Pair(prob)
     rng = np.random.default_rng(1)
     for rnd in range(2):
-        p.g.select(n // 3)
+        p.g.select(max(1, n // 3))
         p.g.commit_swap()
         p.g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(rng.permutation(p.g.get(duhl.P)).astype(np.int32)))
     p.sync_oracle_to_gpu_state()
