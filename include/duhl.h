@@ -267,6 +267,12 @@ duhl_status duhl_device_ptr(duhl_ctx *ctx, duhl_what what, void **ptr);
 duhl_status duhl_probe_stream_read(duhl_ctx *ctx, const void *dev, int64_t bytes, int reps,
                                    double *best_ms);
 
+/* The threshold of the last selection (eq. (13)): the smallest score among the selected
+ * coordinates -- for DUHL_SELECT_GAP the m-th largest entry of the gap memory z as the selection
+ * saw it (entries equal to it are taken in index order until m are chosen).  threshold: host.
+ * Waits.  DUHL_ESTATE before the first selection. */
+duhl_status duhl_selection_threshold(duhl_ctx *ctx, float *threshold);
+
 /* Size of the current working set (0 before the first commit). */
 int64_t duhl_working_set_size(const duhl_ctx *ctx);
 

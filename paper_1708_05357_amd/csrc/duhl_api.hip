@@ -4,6 +4,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
+#include <cstring>
 #include <new>
 
 #include "duhl_internal.h"
@@ -528,6 +529,24 @@ duhl_status duhl_device_ptr(duhl_ctx *c, duhl_what what, void **ptr)
 }
 
 int64_t duhl_working_set_size(const duhl_ctx *c) { return c ? c->m_cur : 0; }
+
+duhl_status duhl_selection_threshold(duhl_ctx *c, float *threshold)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!threshold) return fail(c, DUHL_EINVAL, "threshold is NULL");
+    if (!c->have_data || (!c->pending && c->m_cur == 0)) return fail(c, DUHL_ESTATE, "no selection yet");
+    HIPCHK(c, hipSetDevice(c->device));
+    uint32_t key = 0;
+    HIPCHK(c, hipMemcpyAsync(&key, &c->sel->thr_key, sizeof(key), hipMemcpyDeviceToHost, c->compute));
+    HIPCHK(c, hipStreamSynchronize(c->compute));
+    // keys order floats as unsigned integers: sign bit set for non-negative values, all bits
+    // inverted for negative ones
+    const uint32_t bits = (key & 0x80000000u) ? (key & 0x7fffffffu) : ~key;
+    float out;
+    memcpy(&out, &bits, sizeof(out));
+    *threshold = out;
+    return DUHL_OK;
+}
 
 const char *duhl_last_error(const duhl_ctx *c) { return c ? c->err.c_str() : "null context"; }
 

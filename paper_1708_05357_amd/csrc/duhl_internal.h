@@ -177,7 +177,8 @@ enum Scalar { S_GAP_SUM = 0, S_SUM_ALL, S_SUM_SEL, S_RHO, S_OBJ_SQ, S_OBJ_LIN, S
 struct SelectState {
     uint32_t hist[3][2048];
     uint32_t barrier;    // arrivals at the selection kernel's barriers, only ever incremented
-    uint32_t reserved[9];
+    uint32_t thr_key;    // key of the smallest selected entry of the last selection
+    uint32_t reserved[8];
     uint32_t n_fill;     // columns to copy (host residency)
     uint32_t n_evict;    // evictable slots found
     uint32_t error;      // validation flags

@@ -217,6 +217,7 @@ __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
     if (!grid_sync(ctr, bar, &st->cd_abort, a.spin_limit)) return;
     find_digit<2>(a, prefix, need, tsum, found);
     const uint32_t thr = prefix, take_eq = need;         // full key; entries equal to it still to take
+    if (blockIdx.x == 0 && threadIdx.x == 0) st->thr_key = thr;
 
     // -- per chunk: entries above the key, entries equal to it
     const int64_t base = (int64_t)blockIdx.x * a.chunk;

@@ -24,7 +24,8 @@ OK, EINVAL, ENOMEM, EHIP, ESTATE, EBUDGET = 0, -1, -2, -3, -4, -5
 EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_data_dense", "duhl_set_data_csr", "duhl_gap", "duhl_select",
            "duhl_select_rule_apply", "duhl_host_sample_begin", "duhl_host_sample_end",
            "duhl_commit_swap", "duhl_cd_epoch", "duhl_run", "duhl_objective", "duhl_recompute_v", "duhl_get",
-           "duhl_set", "duhl_device_ptr", "duhl_probe_stream_read", "duhl_working_set_size", "duhl_last_error",
+           "duhl_set", "duhl_device_ptr", "duhl_probe_stream_read", "duhl_selection_threshold",
+           "duhl_working_set_size", "duhl_last_error",
            "duhl_destroy"]
 
 _lib = None
@@ -75,6 +76,7 @@ def load():
     lib.duhl_get.argtypes = [p, i32, p, i64]
     lib.duhl_set.argtypes = [p, i32, p, i64]
     lib.duhl_device_ptr.argtypes = [p, i32, C.POINTER(p)]
+    lib.duhl_selection_threshold.argtypes = [p, C.POINTER(C.c_float)]
     lib.duhl_working_set_size.argtypes = [p]
     lib.duhl_working_set_size.restype = i64
     lib.duhl_last_error.argtypes = [p]
@@ -83,7 +85,7 @@ def load():
     lib.duhl_destroy.restype = None
     lib.duhl_probe_stream_read.argtypes = [p, p, i64, i32, C.POINTER(dbl)]
     lib.duhl_run.argtypes = [p, C.POINTER(RunOpts), C.POINTER(RunStats)]
-    for name in EXPORTS[:18]:
+    for name in EXPORTS[:19]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -233,6 +235,12 @@ class Duhl:
         self._chk(self.lib.duhl_probe_stream_read(self._h, C.c_void_p(tensor.data_ptr()), nbytes, int(reps),
                                                   C.byref(ms)))
         return ms.value
+
+    def selection_threshold(self):
+        """Smallest score of the last selection: the m-th largest entry of z it saw (eq. (13))."""
+        out = C.c_float(0.0)
+        self._chk(self.lib.duhl_selection_threshold(self._h, C.byref(out)))
+        return out.value
 
     # -- state ------------------------------------------------------------------------------
     def working_set_size(self):

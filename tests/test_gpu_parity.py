@@ -249,7 +249,7 @@ def test_elastic_net_gaps_steps_and_objective_match_oracle(G, eta):
 @pytest.mark.parametrize("n", [7, 500, 2048, 2049, 70001])
 def test_selection_is_bit_exact_on_the_same_z(G, n):
     """eq. (13): same fp32 z into both selectors -> identical sets (ascending), incl. heavy ties,
-    m = 1, m = n, and rho of eq. (7)."""
+    m = 1, m = n, the threshold (the m-th largest entry) and rho of eq. (7)."""
     from oracle import duhl_oracle as orc
     from paper_1708_05357_amd import duhl
     p = G.Pair(lasso_problem(16, n, 0.1, 0.1, seed=n))
@@ -268,6 +268,7 @@ def test_selection_is_bit_exact_on_the_same_z(G, n):
             nsw, rho = p.g.select(m, out)
             want = orc.select_topm(z.astype(np.float64), m)
             np.testing.assert_array_equal(out.cpu().numpy(), want, err_msg=f"{name} m={m}")
+            assert p.g.selection_threshold() == np.sort(z)[n - m], (name, m)   # the m-th largest, exactly
             if z.sum() > 0:
                 assert rho == pytest.approx(orc.rho(z.astype(np.float64), want), rel=1e-12), (name, m)
             else:
@@ -568,6 +569,9 @@ def test_error_paths(G):
     assert e.value.status == duhl.EINVAL
     with pytest.raises(duhl.DuhlError) as e:
         g.commit_swap()
+    assert e.value.status == duhl.ESTATE
+    with pytest.raises(duhl.DuhlError) as e:
+        g.selection_threshold()
     assert e.value.status == duhl.ESTATE
     g.select(3)
     g.commit_swap()
