@@ -45,7 +45,7 @@ class Pair:
             self.g.set_data_csr(self.rowptr, self.colidx, self.val, self.target, prob["lam"])
             self.o = orc.Oracle(model, to_np(prob["target"]), prob["lam"],
                                 csr=(to_np(prob["rowptr"]), to_np(prob["colidx"]), to_np(prob["val"])),
-                                d=d)
+                                d=d, eta=eta)
 
     def sync_oracle_to_gpu_state(self):
         """Put the GPU's (alpha, v) into the oracle so both evaluate at the same point."""

@@ -206,6 +206,69 @@ def test_sparse_rows_of_uneven_length(G, n, d, short, long_rows, long_len):
     p.close()
 
 
+def sparse_regression(n, d, density, model, eta, seed):
+    """Lasso / elastic-net instance with sparse columns, as CSR over coordinates: unit columns with
+    ~density*d non-zeros, b = A alpha* + noise for a sparse alpha*, lambda d = 0.1 ||A^T b||_inf."""
+    from paper_1708_05357_amd import synth
+    base = synth.svm_csr(n, d, density, seed=seed)           # the sparsity pattern and unit rows
+    rng = np.random.default_rng(seed)
+    rowptr, colidx = base["rowptr"].numpy(), base["colidx"].numpy()
+    val = (base["val"].numpy() * rng.choice([-1.0, 1.0], size=colidx.size)).astype(np.float32)
+    rows = np.repeat(np.arange(n), np.diff(rowptr))
+    alpha = np.where(rng.random(n) < 0.1, rng.standard_normal(n), 0.0)
+    b = np.bincount(colidx, weights=val * alpha[rows], minlength=d) + 0.01 * rng.standard_normal(d)
+    b = b.astype(np.float32)
+    corr = np.abs(np.bincount(rows, weights=val.astype(np.float64) * b[colidx], minlength=n)).max()
+    t = torch.from_numpy
+    return {"model": model, "eta": eta, "d": d, "n": n, "rowptr": t(rowptr), "colidx": t(colidx),
+            "val": t(val), "target": t(b), "lam": 0.1 * corr / d}
+
+
+@pytest.mark.parametrize("model,eta", [("lasso", 1.0), ("enet", 0.4)])
+def test_sparse_lasso_and_elastic_net(G, model, eta):
+    """The regression models on CSR data (rows = coordinates = sparse columns of A): gaps of the
+    full pass and of a list (App. E, eq. (4)), sequential iterates (App. D), and the objective the
+    concurrent scheme reaches, against the oracle."""
+    from paper_1708_05357_amd import duhl
+    n, d, m = 2500, 40000, 500
+    prob = sparse_regression(n, d, 0.002, model, eta, seed=17)
+    p = G.Pair(prob)
+    floor_of = G.lasso_gap_floor if model == "lasso" else G.enet_gap_floor
+    np.testing.assert_allclose(p.g.get(duhl.SQNORM), p.o.q, rtol=2e-6)
+    assert p.g.gap() == pytest.approx(p.o.gaps(), rel=1e-4)
+    G.assert_gaps_close(p.g.get(duhl.Z), p.o.z, floor=floor_of(p))
+    rng = np.random.default_rng(5)
+    for rnd in range(4):
+        p.g.gap(want_sum=False)
+        p.g.select(m, want_stats=False)
+        p.g.commit_swap()
+        order = rng.permutation(p.g.get(duhl.P)).astype(np.int32)
+        p.g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(order))
+        p.o.cd_pass(order)
+        a, v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+        assert np.abs(a - p.o.alpha).max() <= 1e-5 * np.abs(p.o.alpha).max()
+        assert np.abs(v - p.o.v).max() <= 1e-5 * np.abs(p.o.v).max()
+        p.sync_oracle_to_gpu_state()
+        assert p.g.gap() == pytest.approx(p.o.gaps(), rel=1e-4, abs=n * floor_of(p))
+        G.assert_gaps_close(p.g.get(duhl.Z), p.o.z, floor=floor_of(p))
+        listed = rng.permutation(n)[:n // 5].astype(np.int32)
+        p.g.set(duhl.Z, np.zeros(n, dtype=np.float32))
+        p.g.gap(G.dev_i32(listed), want_sum=False)
+        G.assert_gaps_close(p.g.get(duhl.Z)[listed], p.o.z[listed], floor=floor_of(p))
+    # concurrent scheme: rounds until both have converged, then the objectives agree
+    for rnd in range(150):
+        p.g.gap(want_sum=False)
+        p.g.select(m, want_stats=False)
+        p.g.commit_swap()
+        p.g.cd_epoch(duhl.CD_ASYNC, seed=rnd)
+    rng2 = np.random.default_rng(0)
+    for rnd in range(150):
+        p.o.round(m, passes=1, rng=rng2)
+    og, oo = p.g.objective(), p.o.objective()
+    assert abs(og - oo) <= 1e-5 * abs(oo), (og, oo)
+    p.close()
+
+
 @pytest.mark.parametrize("eta", [1.0, 0.3])
 def test_elastic_net_gaps_steps_and_objective_match_oracle(G, eta):
     """App. D elastic-net step and the gap of eq. (4) (ridge gap of App. E for eta = 1): gap vectors,
