@@ -193,6 +193,7 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->cd_units = env_int("DUHL_CD_UNITS", 0);
     c->cd_spin_limit = env_int("DUHL_CD_SPIN_LIMIT", 1 << 22);
     if (c->cd_spin_limit < 0) c->cd_spin_limit = 0;
+    c->select_groups = env_int("DUHL_SELECT_GROUPS", 0);
     c->csr_blocked = env_int("DUHL_CSR_BLOCKED", 1);
     c->csr_blocked_waves = env_int("DUHL_CSR_BLOCKED_WAVES", 2);
     if (c->csr_blocked_waves < 1) c->csr_blocked_waves = 1;

@@ -259,6 +259,7 @@ struct duhl_ctx {
     int copy_blocks;   // workgroups of the column-copy kernel
     int cd_units;      // compute units per dense CD worker for long columns (0 = by d, 1 = never more than one)
     int cd_spin_limit; // polls a workgroup waits for a partner's partial sum before it gives up
+    int select_groups;       // most workgroups of the selection kernel (0: the kernel's own limit)
     int csr_blocked;         // build and use the blocked copy of sparse data
     int csr_blocked_waves;   // workgroups per compute unit launched by its pass
     int csr_blocked_list_min;   // shortest index list evaluated from the blocked copy (< 0: n/4)

@@ -468,7 +468,8 @@ hipError_t launch_score(duhl_ctx *c, int scheme, int64_t m, uint64_t arg)
 hipError_t launch_select(duhl_ctx *c, int64_t m, int32_t *P_out, const float *keys)
 {
     const int64_t n = c->n;
-    int64_t chunk = ((n + kMaxGroups - 1) / kMaxGroups + kChunk - 1) / kChunk * kChunk;   // whole 8-tile batches
+    int64_t groups = c->select_groups > 0 && c->select_groups < kMaxGroups ? c->select_groups : kMaxGroups;
+    int64_t chunk = ((n + groups - 1) / groups + kChunk - 1) / kChunk * kChunk;   // whole 8-tile batches
     if (chunk < kChunk) chunk = kChunk;
     const int64_t nb = (n + chunk - 1) / chunk;
     SelectArgs a;
