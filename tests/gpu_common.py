@@ -91,5 +91,18 @@ def enet_gap_floor(pair):
     return float((8 * eps * terms + dot_err * (amax + cmax / (Lam * o.eta))) / o.d)
 
 
+def svm_gap_floor_csr(rowptr, colidx, val, v, alpha, lam):
+    """Rounding floor of the fp32 SVM gap on sparse data.  The dot product a_i^T v is summed in
+    fp32 (per lane and range one after the other, then the ranges): its error is a small multiple
+    of eps * S_i, S_i = sum_k |x_ik v_k|, which enters z_i through s_i = a_i^T v / (lambda n)
+    multiplied by (1 + |alpha_i|) / n; the formula itself adds a few eps / n."""
+    n = rowptr.size - 1
+    rows = np.repeat(np.arange(n), np.diff(rowptr))
+    S = np.bincount(rows, weights=np.abs(val.astype(np.float64) * np.asarray(v, dtype=np.float64)[colidx]),
+                    minlength=n)
+    eps = 2.0 ** -24
+    return float(4 * eps / n * (1.0 + (1.0 + np.abs(alpha).max()) * S.max() / (lam * n)))
+
+
 def dev_i32(a):
     return torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32), device="cuda:0")

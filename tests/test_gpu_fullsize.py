@@ -153,14 +153,18 @@ def test_cfg3_full_size_sparse_svm(G):
     o.set_state(g.get(duhl.ALPHA).astype(np.float64), g.get(duhl.V).astype(np.float64))
     total = g.gap()
     assert total == pytest.approx(o.gaps(), rel=1e-4)
-    G.assert_gaps_close(g.get(duhl.Z), o.z, floor=8 * 2.0 ** -24 / n)
+    # (the state differs from run to run -- the passes above are concurrent -- and so does how
+    # close the comparison comes to the floor: measured errors reach an eighth of it)
+    floor = G.svm_gap_floor_csr(host["rowptr"].numpy(), host["colidx"].numpy(), host["val"].numpy(),
+                                o.v, o.alpha, prob["lam"])
+    G.assert_gaps_close(g.get(duhl.Z), o.z, floor=floor)
     # an index list long enough to be evaluated from the blocked copy, and a short one
     for count in (300000, 3000):
         listed = rng.permutation(n)[:count].astype(np.int32)
         g.set(duhl.Z, np.full(n, -1.0, dtype=np.float32))
         part = g.gap(G.dev_i32(listed))
         z = g.get(duhl.Z)
-        G.assert_gaps_close(z[listed], o.z[listed], floor=8 * 2.0 ** -24 / n)
+        G.assert_gaps_close(z[listed], o.z[listed], floor=floor)
         assert part == pytest.approx(float(o.z[listed].sum()), rel=1e-4)
         assert int((z != -1.0).sum()) == count
     g.gap(want_sum=False)
