@@ -505,6 +505,7 @@ def main():
                    "cd_updates_per_s": m * total_passes / args.steps / (avg(cd_ms) * 1e-3), "cd_GBps": cd_gbps,
                    "cd_frac_of_hbm_peak": cd_gbps / HBM_PEAK_GBPS,
                    "gap_ms_min": min(gap_ms), "cd_ms_min": min(cd_ms), "cd_ms_max": max(cd_ms),
+                   "gap_ms_median": sorted(gap_ms)[len(gap_ms) // 2], "cd_ms_median": sorted(cd_ms)[len(cd_ms) // 2],
                    # host residency: the first round's selection waits for the whole working set to
                    # arrive over the link, which dominates the mean
                    "select_ms_median": sorted(sel_ms)[len(sel_ms) // 2]},
