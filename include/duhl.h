@@ -185,7 +185,10 @@ duhl_status duhl_commit_swap(duhl_ctx *ctx);
  *                   wait is bounded, and if it ever expires (the device shared with work that
  *                   starves part of a worker for seconds) the pass ends early, alpha and v are
  *                   undefined and the next call that returns a scalar fails with DUHL_EHIP until
- *                   the data are set again.  Sparse data: same as DUHL_CD_ATOMIC.
+ *                   the data are set again.
+ *                   Sparse data: sub-passes of max_inflight coordinates, one kernel launch each;
+ *                   the steps of a sub-pass run concurrently, read v as the sub-passes before it
+ *                   left it (or fresher) and add to it with fp32 atomics; iterates depend on timing.
  * In all schemes v = A alpha (- b) keeps holding up to fp32 rounding. */
 duhl_status duhl_cd_epoch(duhl_ctx *ctx, duhl_cd_mode mode, const int32_t *order,
                           int64_t n_order, uint64_t seed, int max_inflight);

@@ -541,44 +541,66 @@ __global__ __launch_bounds__(1024) void merge_workers_kernel(float *v, int64_t d
     }
 }
 
-// ---- asynchronous, sparse: G lanes per coordinate -------------------------------------------------
-template <int MODEL, int G>
-__global__ __launch_bounds__(256) void cd_csr_async_kernel(const CdArgs a)
+// ---- concurrent, sparse: G lanes per coordinate ---------------------------------------------------
+// Positions [t_begin, t_end) of the visiting order.  LIVE: the gathers of v observe the atomic
+// adds of steps that finished before them (device-scope loads, served past the per-die L2); one
+// launch covers the pass and a.groups bounds how many steps run without seeing each other.
+// !LIVE: plain, cached gathers -- a step may miss every update made since the launch began, so
+// the caller launches one sub-pass of that many coordinates at a time (kernel boundaries are what
+// make the adds visible to plain loads).  Device-scope loads are the slower kind: 2e7 of them take
+// longer than the 2e7 atomic adds of the same pass.
+template <int MODEL, int G, bool LIVE>
+__global__ __launch_bounds__(256) void cd_csr_async_kernel(const CdArgs a, const int64_t t_begin, const int64_t t_end)
 {
     const int sub = threadIdx.x % G;
     const int64_t ngroups = a.groups;              // idle groups of the last workgroup leave at once
     const int64_t first = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
     if (first >= ngroups) return;
-    for (int64_t t = first; t < a.count; t += ngroups) {
+    for (int64_t t = t_begin + first; t < t_end; t += ngroups) {
         const int64_t j = coord_at(a, t);
         if (j < 0) continue;
         const int64_t beg = a.cv.rowptr[j], end = a.cv.rowptr[j + 1];
+        // the scalars of the step are requested now, not after the dot product: one round trip
+        // to memory less in the chain order -> row -> entries -> v -> step
+        const float old = a.alpha[j];
+        const float qj = a.q[j];
+        const float y = MODEL == DUHL_SVM ? a.target[j] : 0.0f;
         float acc = 0.0f;
         // index/value loads of a batch first, then the gathers that depend on them: K gathers
         // of v in flight per lane
         constexpr int K = 8;
+        int32_t ci[K];                                 // (the row's first batch stays in registers)
+        float xv[K];
         for (int64_t e0 = beg + sub; e0 < end; e0 += (int64_t)G * K) {
-            int32_t ci[K];
-            float xv[K], vv[K];
+            int32_t cj[K];
+            float xj[K], vv[K];
 #pragma unroll
             for (int u = 0; u < K; ++u) {
                 const int64_t e = e0 + (int64_t)u * G;
                 const bool in = e < end;
-                ci[u] = in ? a.cv.colidx[e] : 0;
-                xv[u] = in ? a.cv.val[e] : 0.0f;
+                cj[u] = in ? a.cv.colidx[e] : 0;
+                xj[u] = in ? a.cv.val[e] : 0.0f;
             }
 #pragma unroll
-            for (int u = 0; u < K; ++u) vv[u] = live_load(a.v + ci[u]);
+            for (int u = 0; u < K; ++u) vv[u] = LIVE ? live_load(a.v + cj[u]) : a.v[cj[u]];
 #pragma unroll
-            for (int u = 0; u < K; ++u) acc = fmaf(xv[u], vv[u], acc);
+            for (int u = 0; u < K; ++u) acc = fmaf(xj[u], vv[u], acc);
+            if (e0 == beg + sub) {
+#pragma unroll
+                for (int u = 0; u < K; ++u) {
+                    ci[u] = cj[u];
+                    xv[u] = xj[u];
+                }
+            }
         }
         const float c = group_sum<G>(acc);
-        const float old = a.alpha[j];
-        const float y = MODEL == DUHL_SVM ? a.target[j] : 0.0f;
-        const float now = cd_new_alpha<MODEL>(a.mc, c, old, a.q[j], y);
+        const float now = cd_new_alpha<MODEL>(a.mc, c, old, qj, y);
         const float delta = now - old;
         if (delta != 0.0f) {
-            for (int64_t e = beg + sub; e < end; e += G)
+#pragma unroll
+            for (int u = 0; u < K; ++u)                 // padding of the batch has value 0: skipped
+                if (beg + sub + (int64_t)u * G < end) live_add(a.v + ci[u], xv[u] * delta);
+            for (int64_t e = beg + sub + (int64_t)G * K; e < end; e += G)
                 live_add(a.v + a.cv.colidx[e], a.cv.val[e] * delta);
             if (sub == 0) a.alpha[j] = now;
         }
@@ -761,9 +783,11 @@ hipError_t launch_atomic(duhl_ctx *c, const CdArgs &a, int max_inflight, bool ve
         CdArgs b = a;
         b.groups = inflight;
         if (G == 64)
-            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 64>), dim3(grid), dim3(256), 0, c->compute, b);
+            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 64, true>), dim3(grid), dim3(256), 0, c->compute, b,
+                               (int64_t)0, a.count);
         else
-            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 16>), dim3(grid), dim3(256), 0, c->compute, b);
+            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 16, true>), dim3(grid), dim3(256), 0, c->compute, b,
+                               (int64_t)0, a.count);
         return hipGetLastError();
     }
     const int T = threads_per_coordinate(c);
@@ -773,6 +797,28 @@ hipError_t launch_atomic(duhl_ctx *c, const CdArgs &a, int max_inflight, bool ve
     if (T == 64) return launch_atomic_dense_n<MODEL, 64>(c, a, (int)inflight, vec);
     if (T == 256) return launch_atomic_dense_n<MODEL, 256>(c, a, (int)inflight, vec);
     return launch_atomic_dense_n<MODEL, 1024>(c, a, (int)inflight, vec);
+}
+
+// Sparse data, mode ASYNC: sub-passes of `inflight` coordinates, one launch each, all of a
+// sub-pass's steps concurrent and reading v as the previous sub-passes left it (or fresher).
+template <int MODEL>
+hipError_t launch_csr_subpasses(duhl_ctx *c, const CdArgs &a, int max_inflight)
+{
+    const int64_t avg = c->n > 0 ? c->nnz / c->n : 0;
+    const int G = avg > 256 ? 64 : 16;
+    const int64_t inflight = inflight_limit(c, a.count, max_inflight);
+    const int64_t cap = (int64_t)c->num_cu * 8 * (256 / G);      // groups that fit the device at once
+    CdArgs b = a;
+    b.groups = inflight < cap ? inflight : cap;
+    const int64_t grid = (b.groups + 256 / G - 1) / (256 / G);
+    for (int64_t t0 = 0; t0 < a.count; t0 += inflight) {
+        const int64_t t1 = t0 + inflight < a.count ? t0 + inflight : a.count;
+        if (G == 64)
+            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 64, false>), dim3(grid), dim3(256), 0, c->compute, b, t0, t1);
+        else
+            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 16, false>), dim3(grid), dim3(256), 0, c->compute, b, t0, t1);
+    }
+    return hipGetLastError();
 }
 
 template <int MODEL, int T, int NR, int NL, bool CACHE_X, bool EXT, bool XVEC>
@@ -914,7 +960,8 @@ hipError_t launch_cd_model(duhl_ctx *c, duhl_cd_mode mode, const CdArgs &a, int 
             hipLaunchKernelGGL((cd_dense_seq_kernel<MODEL, false>), dim3(1), dim3(1024), 0, c->compute, a);
         return hipGetLastError();
     }
-    if (mode == DUHL_CD_ASYNC && !c->sparse) {
+    if (mode == DUHL_CD_ASYNC && c->sparse) return launch_csr_subpasses<MODEL>(c, a, max_inflight);
+    if (mode == DUHL_CD_ASYNC) {
         hipError_t err = hipSuccess;
         if (launch_workers<MODEL>(c, a, max_inflight, vec, &err)) return err;
     }
