@@ -563,6 +563,7 @@ void duhl_destroy(duhl_ctx *c)
     (void)hipFree(c->scalars); (void)hipFree(c->partials); (void)hipFree(c->sel);
     (void)hipFree(c->blk_gt); (void)hipFree(c->blk_eq); (void)hipFree(c->mark);
     (void)hipFree(c->dv); (void)hipFree(c->dirty); (void)hipFree(c->score); (void)hipFree(c->xch);
+    (void)hipFree(c->cd_plan);
     if (c->h_scalars) (void)hipHostFree(c->h_scalars);
     if (c->h_u32) (void)hipHostFree(c->h_u32);
     delete c;

@@ -238,6 +238,8 @@ struct duhl_ctx {
     int32_t *dirty;
     uint32_t sel_bar;           // value the selection kernel's barrier counter has before its next launch
     uint64_t *xch;              // exchange slots of workers that span several compute units
+    void *cd_plan;              // sparse sub-passes: one record per position of the visiting order
+    int64_t cd_plan_cap;
     uint32_t xseq;              // next free sequence number for those slots
 
     // host residency

@@ -32,6 +32,15 @@ namespace duhl {
 
 namespace {
 
+// What a sparse step needs to know before it can fetch its row, gathered once per pass for every
+// position of the visiting order (32 bytes, read with two 16-byte loads).
+struct CdPlan {
+    int64_t beg;            // first entry of the row
+    int32_t j, len;         // coordinate (-1: skip) and its number of entries
+    float alpha, q, y, pad;
+};
+static_assert(sizeof(CdPlan) == 32, "two 16-byte loads");
+
 struct CdArgs {
     ColView cv;
     ModelConst mc;
@@ -43,6 +52,7 @@ struct CdArgs {
     uint32_t pbits, pmul[3], padd[3];
     float *alpha, *v;
     const float *q, *target;
+    CdPlan *plan;           // sparse sub-passes only
 };
 
 // Bijection on [0, count): multiply-add and xor-shift steps are each invertible on pbits bits;
@@ -549,6 +559,25 @@ __global__ __launch_bounds__(1024) void merge_workers_kernel(float *v, int64_t d
 // the caller launches one sub-pass of that many coordinates at a time (kernel boundaries are what
 // make the adds visible to plain loads).  Device-scope loads are the slower kind: 2e7 of them take
 // longer than the 2e7 atomic adds of the same pass.
+// For the sub-passes the chain of dependent round trips to memory -- order -> row -> entries -> v ->
+// adds -- is cut by one: cd_csr_plan_kernel resolves order and row for the whole pass beforehand.
+template <int MODEL>
+__global__ __launch_bounds__(256) void cd_csr_plan_kernel(const CdArgs a)
+{
+    const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= a.count) return;
+    const int64_t j = coord_at(a, t);
+    CdPlan p;
+    p.j = (int32_t)j;
+    p.beg = j < 0 ? 0 : a.cv.rowptr[j];
+    p.len = j < 0 ? 0 : (int32_t)(a.cv.rowptr[j + 1] - p.beg);
+    p.alpha = j < 0 ? 0.0f : a.alpha[j];            // a pass visits a coordinate once: still current then
+    p.q = j < 0 ? 0.0f : a.q[j];
+    p.y = (MODEL == DUHL_SVM && j >= 0) ? a.target[j] : 0.0f;
+    p.pad = 0.0f;
+    a.plan[t] = p;
+}
+
 template <int MODEL, int G, bool LIVE>
 __global__ __launch_bounds__(256) void cd_csr_async_kernel(const CdArgs a, const int64_t t_begin, const int64_t t_end)
 {
@@ -557,14 +586,28 @@ __global__ __launch_bounds__(256) void cd_csr_async_kernel(const CdArgs a, const
     const int64_t first = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
     if (first >= ngroups) return;
     for (int64_t t = t_begin + first; t < t_end; t += ngroups) {
-        const int64_t j = coord_at(a, t);
-        if (j < 0) continue;
-        const int64_t beg = a.cv.rowptr[j], end = a.cv.rowptr[j + 1];
-        // the scalars of the step are requested now, not after the dot product: one round trip
-        // to memory less in the chain order -> row -> entries -> v -> step
-        const float old = a.alpha[j];
-        const float qj = a.q[j];
-        const float y = MODEL == DUHL_SVM ? a.target[j] : 0.0f;
+        int64_t j, beg, end;
+        float old, qj, y;
+        if (LIVE) {
+            j = coord_at(a, t);
+            if (j < 0) continue;
+            beg = a.cv.rowptr[j];
+            end = a.cv.rowptr[j + 1];
+            // the scalars of the step are requested now, not after the dot product: one round
+            // trip to memory less
+            old = a.alpha[j];
+            qj = a.q[j];
+            y = MODEL == DUHL_SVM ? a.target[j] : 0.0f;
+        } else {
+            const CdPlan p = a.plan[t];
+            j = p.j;
+            if (j < 0) continue;
+            beg = p.beg;
+            end = p.beg + p.len;
+            old = p.alpha;
+            qj = p.q;
+            y = p.y;
+        }
         float acc = 0.0f;
         // index/value loads of a batch first, then the gathers that depend on them: K gathers
         // of v in flight per lane
@@ -808,7 +851,17 @@ hipError_t launch_csr_subpasses(duhl_ctx *c, const CdArgs &a, int max_inflight)
     const int G = avg > 256 ? 64 : 16;
     const int64_t inflight = inflight_limit(c, a.count, max_inflight);
     const int64_t cap = (int64_t)c->num_cu * 8 * (256 / G);      // groups that fit the device at once
+    if (a.count > c->cd_plan_cap) {
+        (void)hipFree(c->cd_plan);
+        c->cd_plan = nullptr;
+        c->cd_plan_cap = 0;
+        const hipError_t e = hipMalloc(&c->cd_plan, (size_t)a.count * sizeof(CdPlan));
+        if (e != hipSuccess) return e;
+        c->cd_plan_cap = a.count;
+    }
     CdArgs b = a;
+    b.plan = static_cast<CdPlan *>(c->cd_plan);
+    hipLaunchKernelGGL(cd_csr_plan_kernel<MODEL>, dim3((a.count + 255) / 256), dim3(256), 0, c->compute, b);
     b.groups = inflight < cap ? inflight : cap;
     const int64_t grid = (b.groups + 256 / G - 1) / (256 / G);
     for (int64_t t0 = 0; t0 < a.count; t0 += inflight) {
@@ -987,6 +1040,7 @@ hipError_t launch_cd(duhl_ctx *c, duhl_cd_mode mode, const int32_t *order, int64
     a.v = c->v;
     a.q = c->q;
     a.target = c->target;
+    a.plan = nullptr;
     a.pbits = 1;
     while ((1ll << a.pbits) < a.count) ++a.pbits;
     uint64_t s = seed ^ (0xD1B54A32D192ED03ull * (c->pass_counter + 1));
