@@ -578,6 +578,73 @@ __global__ __launch_bounds__(256) void cd_csr_plan_kernel(const CdArgs a)
     a.plan[t] = p;
 }
 
+// One exact step on the coordinate at position t of the visiting order, by a group of G lanes.
+template <int MODEL, int G, bool LIVE>
+__device__ __forceinline__ void csr_step(const CdArgs &a, int64_t t, int sub)
+{
+    int64_t j, beg, end;
+    float old, qj, y;
+    if (LIVE) {
+        j = coord_at(a, t);
+        if (j < 0) return;
+        beg = a.cv.rowptr[j];
+        end = a.cv.rowptr[j + 1];
+        // the scalars of the step are requested now, not after the dot product: one round
+        // trip to memory less
+        old = a.alpha[j];
+        qj = a.q[j];
+        y = MODEL == DUHL_SVM ? a.target[j] : 0.0f;
+    } else {
+        const CdPlan p = a.plan[t];
+        j = p.j;
+        if (j < 0) return;
+        beg = p.beg;
+        end = p.beg + p.len;
+        old = p.alpha;
+        qj = p.q;
+        y = p.y;
+    }
+    float acc = 0.0f;
+    // index/value loads of a batch first, then the gathers that depend on them: K gathers
+    // of v in flight per lane
+    constexpr int K = 8;
+    int32_t ci[K];                                     // (the row's first batch stays in registers)
+    float xv[K];
+    for (int64_t e0 = beg + sub; e0 < end; e0 += (int64_t)G * K) {
+        int32_t cj[K];
+        float xj[K], vv[K];
+#pragma unroll
+        for (int u = 0; u < K; ++u) {
+            const int64_t e = e0 + (int64_t)u * G;
+            const bool in = e < end;
+            cj[u] = in ? a.cv.colidx[e] : 0;
+            xj[u] = in ? a.cv.val[e] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < K; ++u) vv[u] = LIVE ? live_load(a.v + cj[u]) : a.v[cj[u]];
+#pragma unroll
+        for (int u = 0; u < K; ++u) acc = fmaf(xj[u], vv[u], acc);
+        if (e0 == beg + sub) {
+#pragma unroll
+            for (int u = 0; u < K; ++u) {
+                ci[u] = cj[u];
+                xv[u] = xj[u];
+            }
+        }
+    }
+    const float c = group_sum<G>(acc);
+    const float now = cd_new_alpha<MODEL>(a.mc, c, old, qj, y);
+    const float delta = now - old;
+    if (delta != 0.0f) {
+#pragma unroll
+        for (int u = 0; u < K; ++u)                     // padding of the batch has value 0: skipped
+            if (beg + sub + (int64_t)u * G < end) live_add(a.v + ci[u], xv[u] * delta);
+        for (int64_t e = beg + sub + (int64_t)G * K; e < end; e += G)
+            live_add(a.v + a.cv.colidx[e], a.cv.val[e] * delta);
+        if (sub == 0) a.alpha[j] = now;
+    }
+}
+
 template <int MODEL, int G, bool LIVE>
 __global__ __launch_bounds__(256) void cd_csr_async_kernel(const CdArgs a, const int64_t t_begin, const int64_t t_end)
 {
@@ -585,69 +652,7 @@ __global__ __launch_bounds__(256) void cd_csr_async_kernel(const CdArgs a, const
     const int64_t ngroups = a.groups;              // idle groups of the last workgroup leave at once
     const int64_t first = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
     if (first >= ngroups) return;
-    for (int64_t t = t_begin + first; t < t_end; t += ngroups) {
-        int64_t j, beg, end;
-        float old, qj, y;
-        if (LIVE) {
-            j = coord_at(a, t);
-            if (j < 0) continue;
-            beg = a.cv.rowptr[j];
-            end = a.cv.rowptr[j + 1];
-            // the scalars of the step are requested now, not after the dot product: one round
-            // trip to memory less
-            old = a.alpha[j];
-            qj = a.q[j];
-            y = MODEL == DUHL_SVM ? a.target[j] : 0.0f;
-        } else {
-            const CdPlan p = a.plan[t];
-            j = p.j;
-            if (j < 0) continue;
-            beg = p.beg;
-            end = p.beg + p.len;
-            old = p.alpha;
-            qj = p.q;
-            y = p.y;
-        }
-        float acc = 0.0f;
-        // index/value loads of a batch first, then the gathers that depend on them: K gathers
-        // of v in flight per lane
-        constexpr int K = 8;
-        int32_t ci[K];                                 // (the row's first batch stays in registers)
-        float xv[K];
-        for (int64_t e0 = beg + sub; e0 < end; e0 += (int64_t)G * K) {
-            int32_t cj[K];
-            float xj[K], vv[K];
-#pragma unroll
-            for (int u = 0; u < K; ++u) {
-                const int64_t e = e0 + (int64_t)u * G;
-                const bool in = e < end;
-                cj[u] = in ? a.cv.colidx[e] : 0;
-                xj[u] = in ? a.cv.val[e] : 0.0f;
-            }
-#pragma unroll
-            for (int u = 0; u < K; ++u) vv[u] = LIVE ? live_load(a.v + cj[u]) : a.v[cj[u]];
-#pragma unroll
-            for (int u = 0; u < K; ++u) acc = fmaf(xj[u], vv[u], acc);
-            if (e0 == beg + sub) {
-#pragma unroll
-                for (int u = 0; u < K; ++u) {
-                    ci[u] = cj[u];
-                    xv[u] = xj[u];
-                }
-            }
-        }
-        const float c = group_sum<G>(acc);
-        const float now = cd_new_alpha<MODEL>(a.mc, c, old, qj, y);
-        const float delta = now - old;
-        if (delta != 0.0f) {
-#pragma unroll
-            for (int u = 0; u < K; ++u)                 // padding of the batch has value 0: skipped
-                if (beg + sub + (int64_t)u * G < end) live_add(a.v + ci[u], xv[u] * delta);
-            for (int64_t e = beg + sub + (int64_t)G * K; e < end; e += G)
-                live_add(a.v + a.cv.colidx[e], a.cv.val[e] * delta);
-            if (sub == 0) a.alpha[j] = now;
-        }
-    }
+    for (int64_t t = t_begin + first; t < t_end; t += ngroups) csr_step<MODEL, G, LIVE>(a, t, sub);
 }
 
 // ---- sequential ----------------------------------------------------------------------------------
