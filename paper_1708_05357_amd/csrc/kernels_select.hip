@@ -134,10 +134,19 @@ __device__ __forceinline__ void find_digit(const SelectArgs &a, uint32_t &prefix
         mine[b] = coherent_load(&a.st->hist[PASS][threadIdx.x * kPer + b]);
         total += mine[b];
     }
-    tsum[threadIdx.x] = total;
+    // entries in bins above this thread's range: a suffix sum over the 256 threads, inside each
+    // wavefront by shuffles, across the four wavefronts through tsum[0..3]
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t incl = total;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t y = __shfl_down(incl, o, kWave);
+        if (lane + o < 64) incl += y;
+    }
+    if (lane == 0) tsum[w] = incl;
     __syncthreads();
-    uint32_t above = 0;                                  // entries in bins above this thread's range
-    for (int t = threadIdx.x + 1; t < 256; ++t) above += tsum[t];
+    uint32_t above = incl - total;
+    for (int q = w + 1; q < 4; ++q) above += tsum[q];
     if (above < need && need <= above + total) {
         uint32_t acc = above;
 #pragma unroll
