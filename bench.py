@@ -98,7 +98,8 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
         g.gap(want_sum=False)
     if sample_idx is not None and not on_host:
         g.gap(sample_idx[step % len(sample_idx)], want_sum=False)
-        refreshed += sample_idx[step % len(sample_idx)].numel()
+        if not prob["host_resident"]:           # (host residency: the sample crosses the link and is
+            refreshed += sample_idx[step % len(sample_idx)].numel()   # not part of the HBM figure)
     if ev:
         ev[1].record()
     stats = g.select(m, want_stats=swap_log is not None or passes == 0, rule=rule, arg=step)
@@ -138,7 +139,7 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
         g.commit_swap()
     if swap_log is not None:
         swap_log.append({"columns": stats[0], "rho": stats[1], "overlapped": bool(overlapped)})
-    return refreshed                            # gaps evaluated by the GPU in this round
+    return refreshed                            # gaps evaluated by the GPU from HBM in this round
 
 
 def time_to_gap(g, set_data, prob, m, target, max_rounds, mode=1, inflight=0, sample_idx=None,
@@ -474,7 +475,11 @@ def main():
     avg = lambda x: sum(x) / len(x)
     gap_bytes, cd_bytes = algorithmic_bytes(prob, m)
     if prob["host_resident"]:
-        gap_bytes = 4.0 * prob["d"] * budget     # resident part only; the sample is link-bound
+        # A lower bound: the pass refreshes every column held in a device slot -- the working set
+        # and whatever earlier members have not been evicted yet -- and only the working set is
+        # counted here (the library does not report how many slots are in use).  The sample of the
+        # other columns is link- or host-bound and not part of this figure.
+        gap_bytes = 4.0 * prob["d"] * refreshed / args.steps
     elif sample_idx is not None:
         gap_bytes *= refreshed / args.steps / prob["n"]        # working set + sample, as refreshed
     gap_gbps = gap_bytes / (avg(gap_ms) * 1e-3) / 1e9
