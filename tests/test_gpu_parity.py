@@ -465,7 +465,7 @@ def converge_oracle(p, m, max_rounds, passes, target_rel_gap):
 @pytest.mark.parametrize("scheme", ["async", "atomic"])
 @pytest.mark.parametrize("kind", ["cfg1", "lasso_mid", "lasso_ragged", "lasso_long", "lasso_longer",
                                   "lasso_longest", "lasso_extended", "lasso_eight_units", "lasso_unaligned",
-                                  "lasso_long_unaligned", "svm_dense", "svm_csr"])
+                                  "lasso_long_unaligned", "svm_dense", "svm_csr", "svm_csr_long_rows"])
 def test_async_cd_reaches_the_oracle_objective(G, kind, scheme):
     """The asynchronous scheme is compared on what is unique: the objective at convergence
     (1e-5 relative), and on the invariant v = A alpha (- b) that the atomic adds must keep."""
@@ -503,6 +503,9 @@ def test_async_cd_reaches_the_oracle_objective(G, kind, scheme):
     elif kind == "svm_dense":
         prob = synth.svm_dense(2000, 300, seed=12)
         m = 500
+    elif kind == "svm_csr_long_rows":
+        prob = synth.svm_csr(3000, 6000, 0.06, seed=21)             # ~360 non-zeros per row: a wavefront per row
+        m = 600
     else:
         prob = synth.svm_csr(20000, 2000, 0.01, seed=13)
         m = 4000
