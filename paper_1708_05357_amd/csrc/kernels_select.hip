@@ -82,34 +82,63 @@ struct SelectArgs {
     int spin_limit;
 };
 
+// f(i, key value) for every position of this workgroup's chunk, the same number of calls in
+// every thread (positions past n included; f checks).  KPT > 0: the chunk is KPT entries per
+// thread and they are in registers (kreg), read once for all passes of the kernel; KPT == 0: a
+// chunk of any length, read again each time, eight loads per thread in flight.
+template <int KPT, typename F>
+__device__ __forceinline__ void for_each_key(const SelectArgs &a, const float (&kreg)[KPT > 0 ? KPT : 1], F &&f)
+{
+    const int64_t base = (int64_t)blockIdx.x * a.chunk;
+    if (KPT > 0) {
+#pragma unroll
+        for (int q = 0; q < KPT; ++q) f(base + q * 256 + threadIdx.x, kreg[q]);
+    } else {
+        for (int it0 = 0; it0 < a.chunk / 256; it0 += 8) {
+            float ki[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
+                ki[u] = i < a.n ? a.keys[i] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) f(base + (it0 + u) * 256 + threadIdx.x, ki[u]);
+        }
+    }
+}
+
 // Histogram of one digit of the keys of this workgroup's chunk (those whose higher digits equal
-// `prefix`), flushed into the device-wide histogram.
-template <int PASS>
-__device__ __forceinline__ void hist_pass(const SelectArgs &a, uint32_t prefix, uint32_t *hist, double *zsum)
+// `prefix`), flushed into the device-wide histogram.  Pass 0 also adds up the gap memory over the
+// chunk (the keys themselves when the gaps are what is ranked).
+template <int PASS, int KPT>
+__device__ __forceinline__ void hist_pass(const SelectArgs &a, const float (&kreg)[KPT > 0 ? KPT : 1],
+                                          uint32_t prefix, uint32_t *hist, double *zsum)
 {
     constexpr int kBits = PASS == 2 ? 10 : 11;
     constexpr int kShift = PASS == 0 ? 21 : (PASS == 1 ? 10 : 0);
     constexpr int kBins = 1 << kBits;
     for (int i = threadIdx.x; i < kBins; i += 256) hist[i] = 0;
     __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * a.chunk;
+    const bool own = a.zval == a.keys;
     double sum = 0.0;
-    for (int it0 = 0; it0 < a.chunk / 256; it0 += 8) {       // eight loads per thread in flight
-        float ki[8], zv[8];
+    for_each_key<KPT>(a, kreg, [&](int64_t i, float kf) {
+        if (i >= a.n) return;
+        const uint32_t key = zkey(kf);
+        if (PASS == 0 && own) sum += (double)kf;
+        if (PASS == 0 || (key >> (kShift + kBits)) == prefix)
+            atomicAdd(&hist[(key >> kShift) & (kBins - 1)], 1u);
+    });
+    if (PASS == 0 && !own) {                             // another rule's scores are ranked
+        const int64_t base = (int64_t)blockIdx.x * a.chunk;
+        for (int it0 = 0; it0 < a.chunk / 256; it0 += 8) {
+            float zv[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
-            ki[u] = i < a.n ? a.keys[i] : 0.0f;
-            if (PASS == 0) zv[u] = i < a.n ? a.zval[i] : 0.0f;
-        }
+            for (int u = 0; u < 8; ++u) {
+                const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
+                zv[u] = i < a.n ? a.zval[i] : 0.0f;
+            }
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
-            if (i >= a.n) continue;
-            const uint32_t key = zkey(ki[u]);
-            if (PASS == 0) sum += (double)zv[u];
-            if (PASS == 0 || (key >> (kShift + kBits)) == prefix)
-                atomicAdd(&hist[(key >> kShift) & (kBins - 1)], 1u);
+            for (int u = 0; u < 8; ++u) sum += (double)zv[u];
         }
     }
     __syncthreads();
@@ -178,6 +207,7 @@ __device__ __forceinline__ double block_sum_partials(const double *partials, int
 // The whole selection in one launch: three histogram passes find the key of the m-th largest
 // entry, then a count per chunk and an ordered scatter write the indices.  Workgroups meet at six
 // barriers; each owns one chunk of consecutive entries throughout.
+template <int KPT>
 __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
 {
     __shared__ uint32_t hist[2048];
@@ -190,6 +220,15 @@ __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
     const uint32_t G = gridDim.x;
     uint32_t bar = a.bar_base;
     uint32_t *ctr = &st->barrier;
+    // the chunk's keys, requested before anything else (they arrive during the first barrier)
+    float kreg[KPT > 0 ? KPT : 1];
+    if (KPT > 0) {
+#pragma unroll
+        for (int q = 0; q < KPT; ++q) {
+            const int64_t i = (int64_t)blockIdx.x * a.chunk + q * 256 + threadIdx.x;
+            kreg[q] = i < a.n ? a.keys[i] : 0.0f;
+        }
+    }
 
     // -- start from clean device-wide histograms and counters
     for (int i = blockIdx.x * 256 + threadIdx.x; i < 3 * 2048; i += G * 256)
@@ -204,7 +243,7 @@ __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
     // -- the key of the m-th largest entry, digit by digit
     uint32_t prefix = 0, need = (uint32_t)a.m;
     double zsum = 0.0;
-    hist_pass<0>(a, prefix, hist, &zsum);
+    hist_pass<0, KPT>(a, kreg, prefix, hist, &zsum);
     zsum = wave_sum(zsum);
     if (lane == 0) dsh[w] = zsum;
     __syncthreads();
@@ -217,11 +256,11 @@ __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
         all = block_sum_partials(a.partials, (int)G, dsh);
         if (threadIdx.x == 0) a.scalars[S_SUM_ALL] = all;
     }
-    hist_pass<1>(a, prefix, hist, nullptr);
+    hist_pass<1, KPT>(a, kreg, prefix, hist, nullptr);
     bar += G;
     if (!grid_sync(ctr, bar, &st->cd_abort, a.spin_limit)) return;
     find_digit<1>(a, prefix, need, tsum, found);
-    hist_pass<2>(a, prefix, hist, nullptr);
+    hist_pass<2, KPT>(a, kreg, prefix, hist, nullptr);
     bar += G;
     if (!grid_sync(ctr, bar, &st->cd_abort, a.spin_limit)) return;
     find_digit<2>(a, prefix, need, tsum, found);
@@ -229,24 +268,13 @@ __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
     if (blockIdx.x == 0 && threadIdx.x == 0) st->thr_key = thr;
 
     // -- per chunk: entries above the key, entries equal to it
-    const int64_t base = (int64_t)blockIdx.x * a.chunk;
     {
         uint32_t g = 0, e = 0;
-        for (int it0 = 0; it0 < a.chunk / 256; it0 += 8) {
-            float ki[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
-                ki[u] = i < a.n ? a.keys[i] : 0.0f;
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
-                const uint32_t key = zkey(ki[u]);
-                g += i < a.n && key > thr;
-                e += i < a.n && key == thr;
-            }
-        }
+        for_each_key<KPT>(a, kreg, [&](int64_t i, float kf) {
+            const uint32_t key = zkey(kf);
+            g += i < a.n && key > thr;
+            e += i < a.n && key == thr;
+        });
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) {
             g += __shfl_xor(g, o, kWave);
@@ -284,45 +312,36 @@ __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
 
     // -- ordered scatter: entry i goes to position (#selected entries with a smaller index)
     double ssel = 0.0;
-    for (int it0 = 0; it0 < a.chunk / 256; it0 += 8) {
-        float kpre[8];
-#pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
-            kpre[u] = i < a.n ? a.keys[i] : 0.0f;
+    const bool own = a.zval == a.keys;
+    for_each_key<KPT>(a, kreg, [&](int64_t i, float kf) {
+        bool g = false, e = false;
+        if (i < a.n) {
+            const uint32_t key = zkey(kf);
+            g = key > thr;
+            e = key == thr;
         }
+        const unsigned long long mg = __ballot(g), me = __ballot(e);
+        const unsigned long long below = (1ull << lane) - 1ull;
+        if (lane == 0) { wg[w] = __popcll(mg); we[w] = __popcll(me); }
+        __syncthreads();
+        uint32_t og = gt_before + __popcll(mg & below), oe = eq_before + __popcll(me & below);
+        uint32_t tg = 0, te = 0;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) {
-            const int64_t i = base + (it0 + u) * 256 + threadIdx.x;
-            bool g = false, e = false;
-            if (i < a.n) {
-                const uint32_t key = zkey(kpre[u]);
-                g = key > thr;
-                e = key == thr;
-            }
-            const unsigned long long mg = __ballot(g), me = __ballot(e);
-            const unsigned long long below = (1ull << lane) - 1ull;
-            if (lane == 0) { wg[w] = __popcll(mg); we[w] = __popcll(me); }
-            __syncthreads();
-            uint32_t og = gt_before + __popcll(mg & below), oe = eq_before + __popcll(me & below);
-            uint32_t tg = 0, te = 0;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                if (q < w) { og += wg[q]; oe += we[q]; }
-                tg += wg[q];
-                te += we[q];
-            }
-            if (g || (e && oe < take_eq)) {
-                const uint32_t pos = og + (oe < take_eq ? oe : take_eq);
-                a.P[pos] = (int32_t)i;
-                if (a.P_out) a.P_out[pos] = (int32_t)i;
-                ssel += (double)a.zval[i];
-            }
-            gt_before += tg;
-            eq_before += te;
-            __syncthreads();
+        for (int q = 0; q < 4; ++q) {
+            if (q < w) { og += wg[q]; oe += we[q]; }
+            tg += wg[q];
+            te += we[q];
         }
-    }
+        if (g || (e && oe < take_eq)) {
+            const uint32_t pos = og + (oe < take_eq ? oe : take_eq);
+            a.P[pos] = (int32_t)i;
+            if (a.P_out) a.P_out[pos] = (int32_t)i;
+            ssel += own ? (double)kf : (double)a.zval[i];
+        }
+        gt_before += tg;
+        eq_before += te;
+        __syncthreads();
+    });
     ssel = wave_sum(ssel);
     if (lane == 0) dsh[w] = ssel;
     __syncthreads();
@@ -497,7 +516,14 @@ hipError_t launch_select(duhl_ctx *c, int64_t m, int32_t *P_out, const float *ke
     a.bar_base = c->sel_bar;
     a.spin_limit = 1 << 22;                              // seconds; the barriers take microseconds
     c->sel_bar += 6u * (uint32_t)nb;                     // six barriers of nb arrivals each
-    hipLaunchKernelGGL(select_fused_kernel, dim3(nb), dim3(256), 0, c->compute, a);
+    // chunks of up to 8,192 entries stay in registers for the whole kernel
+    switch (chunk / 256) {
+    case 8: hipLaunchKernelGGL(select_fused_kernel<8>, dim3(nb), dim3(256), 0, c->compute, a); break;
+    case 16: hipLaunchKernelGGL(select_fused_kernel<16>, dim3(nb), dim3(256), 0, c->compute, a); break;
+    case 24: hipLaunchKernelGGL(select_fused_kernel<24>, dim3(nb), dim3(256), 0, c->compute, a); break;
+    case 32: hipLaunchKernelGGL(select_fused_kernel<32>, dim3(nb), dim3(256), 0, c->compute, a); break;
+    default: hipLaunchKernelGGL(select_fused_kernel<0>, dim3(nb), dim3(256), 0, c->compute, a); break;
+    }
     return hipGetLastError();
 }
 
