@@ -518,36 +518,45 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
 }
 
 // v += sum over workers of their stored changes, in a fixed order (reproducible).  A workgroup
-// owns 64 consecutive elements of v; each of its 16 wavefronts adds up every 16th worker's buffer
-// (eight independent 256-byte loads in flight), then the 16 partial sums are added in wavefront
-// order.  dirty[] is uniform, so skipping a clean worker is a scalar branch.
+// owns 256 consecutive elements of v as 64 chunks of 16 bytes; each of its 16 wavefronts adds up
+// every 16th worker's buffer for those chunks (eight independent 1 KB loads in flight), then the
+// 16 partial sums are added in wavefront order.  dirty[] is uniform, so skipping a clean worker is
+// a scalar branch.  The buffers' rows are dv_stride (a multiple of 64) floats apart and hold
+// nothing meaningful past d, so the last chunk is cut to d when it is added.
 __global__ __launch_bounds__(1024) void merge_workers_kernel(float *v, int64_t d, const float *dv,
                                                              int64_t dv_stride, const int32_t *dirty,
                                                              int nworkers)
 {
-    __shared__ float part[16][64];
+    __shared__ float4 part[16][64];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int64_t k = (int64_t)blockIdx.x * 64 + lane;
-    const bool in = k < d;
-    const float *p = dv + (in ? k : 0);
-    float s = 0.0f;
+    const int64_t k4 = (int64_t)blockIdx.x * 64 + lane;            // chunk of four elements
+    const bool in = 4 * k4 < d;
+    const float4 *p = reinterpret_cast<const float4 *>(dv) + (in ? k4 : 0);
+    const int64_t stride4 = dv_stride >> 2;
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
+    auto add = [](float4 &x, const float4 y) { x.x += y.x; x.y += y.y; x.z += y.z; x.w += y.w; };
     int g = w;
     for (; g + 16 * 7 < nworkers; g += 16 * 8) {
-        float t[8];
+        float4 t[8];
 #pragma unroll
-        for (int u = 0; u < 8; ++u) t[u] = dirty[g + 16 * u] ? p[(int64_t)(g + 16 * u) * dv_stride] : 0.0f;
+        for (int u = 0; u < 8; ++u)
+            t[u] = dirty[g + 16 * u] ? p[(int64_t)(g + 16 * u) * stride4] : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int u = 0; u < 8; ++u) s += t[u];
+        for (int u = 0; u < 8; ++u) add(s, t[u]);
     }
     for (; g < nworkers; g += 16)
-        if (dirty[g]) s += p[(int64_t)g * dv_stride];
+        if (dirty[g]) add(s, p[(int64_t)g * stride4]);
     part[w][lane] = s;
     __syncthreads();
     if (w == 0 && in) {
-        float t = 0.0f;
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int u = 0; u < 16; ++u) t += part[u][lane];
-        if (t != 0.0f) v[k] += t;
+        for (int u = 0; u < 16; ++u) add(t, part[u][lane]);
+        const int64_t k = 4 * k4;
+        if (t.x != 0.0f) v[k] += t.x;
+        if (k + 1 < d && t.y != 0.0f) v[k + 1] += t.y;
+        if (k + 2 < d && t.z != 0.0f) v[k + 2] += t.z;
+        if (k + 3 < d && t.w != 0.0f) v[k + 3] += t.w;
     }
 }
 
@@ -895,7 +904,7 @@ hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
         const int64_t grid = (workers + PER - 1) / PER;
         hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, T, NR, NL, CACHE_X, EXT, XVEC>), dim3(grid), dim3(BLOCK), 0,
                            c->compute, a, t0, t1, c->dv, c->dv_stride, c->dirty, nullptr, 0u, nullptr, 0);
-        hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 63) / 64), dim3(1024), 0, c->compute, a.v,
+        hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 255) / 256), dim3(1024), 0, c->compute, a.v,
                            c->d, c->dv, c->dv_stride, c->dirty, (int)(grid * PER));
     }
     return hipGetLastError();
@@ -915,7 +924,7 @@ hipError_t launch_multi_t(duhl_ctx *c, const CdArgs &a, int64_t inflight, int64_
                            dim3(workers * CUS), dim3(1024), 0, c->compute, a, t0, t1, c->dv, c->dv_stride,
                            c->dirty, c->xch, c->xseq, &c->sel->cd_abort, c->cd_spin_limit);
         c->xseq += (uint32_t)per_worker + 2u;          // sequence numbers never repeat back to back
-        hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 63) / 64), dim3(1024), 0, c->compute, a.v,
+        hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 255) / 256), dim3(1024), 0, c->compute, a.v,
                            c->d, c->dv, c->dv_stride, c->dirty, (int)workers);
     }
     return hipGetLastError();
