@@ -475,11 +475,12 @@ def main():
     avg = lambda x: sum(x) / len(x)
     gap_bytes, cd_bytes = algorithmic_bytes(prob, m)
     if prob["host_resident"]:
-        # A lower bound: the pass refreshes every column held in a device slot -- the working set
-        # and whatever earlier members have not been evicted yet -- and only the working set is
-        # counted here (the library does not report how many slots are in use).  The sample of the
-        # other columns is link- or host-bound and not part of this figure.
-        gap_bytes = 4.0 * prob["d"] * refreshed / args.steps
+        # The pass refreshes every column held in a device slot: the working set and whatever
+        # earlier members have not been evicted yet, counted after the timed rounds (the number
+        # settles once the slots are full).  The sample of the other columns is link- or
+        # host-bound and not part of this figure.
+        resident = g.resident_columns()
+        gap_bytes = 4.0 * prob["d"] * resident
     elif sample_idx is not None:
         gap_bytes *= refreshed / args.steps / prob["n"]        # working set + sample, as refreshed
     gap_gbps = gap_bytes / (avg(gap_ms) * 1e-3) / 1e9
@@ -504,7 +505,8 @@ def main():
                    "scale": args.scale, "rounds_timed": args.steps, "passes_per_round": args.passes if auto is None else passes_timed,
                    "cd_scheme": args.cd_mode, "max_inflight": args.inflight, "select_rule": args.select_rule,
                    "gap_sample": args.gap_sample,
-                   "host_sampler_threads": args.host_sampler_threads if prob["host_resident"] else None},
+                   "host_sampler_threads": args.host_sampler_threads if prob["host_resident"] else None,
+                   "resident_columns": g.resident_columns() if prob["host_resident"] else None},
         "phases": {"gap_ms": avg(gap_ms), "select_ms": avg(sel_ms), "cd_ms": avg(cd_ms),
                    "gap_GBps": gap_gbps, "gap_frac_of_hbm_peak": gap_gbps / HBM_PEAK_GBPS,
                    "cd_updates_per_s": m * total_passes / args.steps / (avg(cd_ms) * 1e-3), "cd_GBps": cd_gbps,

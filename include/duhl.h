@@ -276,6 +276,11 @@ duhl_status duhl_probe_stream_read(duhl_ctx *ctx, const void *dev, int64_t bytes
  * Waits.  DUHL_ESTATE before the first selection. */
 duhl_status duhl_selection_threshold(duhl_ctx *ctx, float *threshold);
 
+/* Columns that duhl_gap(NULL) refreshes at the speed of device memory: with host residency the
+ * number of device slots in use (the working set, and earlier members that have not been evicted
+ * yet); n with device residency.  count: host.  Waits; meant for reports, not for the round loop. */
+duhl_status duhl_resident_columns(duhl_ctx *ctx, int64_t *count);
+
 /* Size of the current working set (0 before the first commit). */
 int64_t duhl_working_set_size(const duhl_ctx *ctx);
 

@@ -531,6 +531,28 @@ duhl_status duhl_device_ptr(duhl_ctx *c, duhl_what what, void **ptr)
 
 int64_t duhl_working_set_size(const duhl_ctx *c) { return c ? c->m_cur : 0; }
 
+duhl_status duhl_resident_columns(duhl_ctx *c, int64_t *count)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!count) return fail(c, DUHL_EINVAL, "count is NULL");
+    if (!c->have_data) return fail(c, DUHL_ESTATE, "no data");
+    if (c->res != DUHL_RESIDENT_HOST) {
+        *count = c->n;
+        return DUHL_OK;
+    }
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, hipStreamSynchronize(c->compute));
+    int32_t *host = static_cast<int32_t *>(malloc((size_t)c->budget * sizeof(int32_t)));
+    if (!host) return fail(c, DUHL_ENOMEM, "host allocation failed");
+    const hipError_t e = hipMemcpy(host, c->slot_col, (size_t)c->budget * sizeof(int32_t), hipMemcpyDeviceToHost);
+    int64_t used = 0;
+    for (int64_t s = 0; e == hipSuccess && s < c->budget; ++s) used += host[s] >= 0;
+    free(host);
+    HIPCHK(c, e);
+    *count = used;
+    return DUHL_OK;
+}
+
 duhl_status duhl_selection_threshold(duhl_ctx *c, float *threshold)
 {
     if (!c) return DUHL_EINVAL;

@@ -25,6 +25,7 @@ EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_data_dense", "duhl_set_data_
            "duhl_select_rule_apply", "duhl_host_sample_begin", "duhl_host_sample_end",
            "duhl_commit_swap", "duhl_cd_epoch", "duhl_run", "duhl_objective", "duhl_recompute_v", "duhl_get",
            "duhl_set", "duhl_device_ptr", "duhl_probe_stream_read", "duhl_selection_threshold",
+           "duhl_resident_columns",
            "duhl_working_set_size", "duhl_last_error",
            "duhl_destroy"]
 
@@ -77,6 +78,7 @@ def load():
     lib.duhl_set.argtypes = [p, i32, p, i64]
     lib.duhl_device_ptr.argtypes = [p, i32, C.POINTER(p)]
     lib.duhl_selection_threshold.argtypes = [p, C.POINTER(C.c_float)]
+    lib.duhl_resident_columns.argtypes = [p, C.POINTER(i64)]
     lib.duhl_working_set_size.argtypes = [p]
     lib.duhl_working_set_size.restype = i64
     lib.duhl_last_error.argtypes = [p]
@@ -85,7 +87,7 @@ def load():
     lib.duhl_destroy.restype = None
     lib.duhl_probe_stream_read.argtypes = [p, p, i64, i32, C.POINTER(dbl)]
     lib.duhl_run.argtypes = [p, C.POINTER(RunOpts), C.POINTER(RunStats)]
-    for name in EXPORTS[:19]:
+    for name in EXPORTS[:20]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -240,6 +242,12 @@ class Duhl:
         """Smallest score of the last selection: the m-th largest entry of z it saw (eq. (13))."""
         out = C.c_float(0.0)
         self._chk(self.lib.duhl_selection_threshold(self._h, C.byref(out)))
+        return out.value
+
+    def resident_columns(self):
+        """Columns held in device memory (host residency: device slots in use)."""
+        out = C.c_int64(0)
+        self._chk(self.lib.duhl_resident_columns(self._h, C.byref(out)))
         return out.value
 
     # -- state ------------------------------------------------------------------------------

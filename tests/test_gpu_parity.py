@@ -533,6 +533,28 @@ def test_async_cd_reaches_the_oracle_objective(G, kind, scheme):
 
 
 # ------------------------------------------------------------------------------------ host residency
+def test_resident_columns_counts_device_slots(G):
+    """Host residency: the slots in use are the working set after the first commit, and never
+    more than the budget; device residency: every column."""
+    from paper_1708_05357_amd import duhl
+    prob = lasso_problem(600, 90, 0.1, 0.05, seed=61)
+    p = G.Pair(prob)
+    assert p.g.resident_columns() == 90
+    p.close()
+    p = G.Pair(prob, budget=40, host_resident=True)
+    assert p.g.resident_columns() == 0
+    p.g.select(20)
+    p.g.commit_swap()
+    assert p.g.resident_columns() == 20
+    for rnd in range(3):
+        p.g.cd_epoch(duhl.CD_ASYNC, seed=rnd)
+        p.g.gap(want_sum=False)
+        p.g.select(20)
+        p.g.commit_swap()
+        assert 20 <= p.g.resident_columns() <= 40
+    p.close()
+
+
 def test_host_resident_swap_matches_oracle(G):
     """Alg. 2 with the matrix in pinned host memory and fewer device slots than columns: the
     copies run on the side stream while the previous set is being worked on; iterates must still
