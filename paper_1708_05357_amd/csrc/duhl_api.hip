@@ -87,6 +87,8 @@ duhl_status finish_set_data(duhl_ctx *c, const float *target, double lambda)
     c->cv.ld_s = c->ld_s;
 
     HIPCHK(c, launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(&c->sel->error), 2, 0));   // and cd_abort
+    // the selection kernel expects clean histograms and leaves them clean, unless a barrier failed
+    HIPCHK(c, launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(&c->sel->hist[0][0]), 3 * 2048, 0));
     HIPCHK(c, launch_validate(c));
     HIPCHK(c, hipMemcpyAsync(c->h_u32, &c->sel->error, sizeof(uint32_t), hipMemcpyDeviceToHost,
                              c->compute));

@@ -5,7 +5,7 @@
 // find the key of the m-th largest entry exactly; a count pass and an ordered scatter then
 // write the indices.  The work is 4n bytes per pass -- negligible next to a gap pass -- so the
 // design goal is few launches: one kernel of at most 128 small workgroups, all resident at once,
-// which meet at six device-wide barriers; serial steps are repeated by every workgroup.
+// which meet at five device-wide barriers; serial steps are repeated by every workgroup.
 // The second half plans the column swap for host residency: which selected columns are not in
 // a device slot yet and which slots may be overwritten (Algorithm 2, "refresh memory B").
 #include "duhl_internal.h"
@@ -205,7 +205,7 @@ __device__ __forceinline__ double block_sum_partials(const double *partials, int
 }
 
 // The whole selection in one launch: three histogram passes find the key of the m-th largest
-// entry, then a count per chunk and an ordered scatter write the indices.  Workgroups meet at six
+// entry, then a count per chunk and an ordered scatter write the indices.  Workgroups meet at five
 // barriers; each owns one chunk of consecutive entries throughout.
 template <int KPT>
 __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
@@ -230,15 +230,11 @@ __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
         }
     }
 
-    // -- start from clean device-wide histograms and counters
-    for (int i = blockIdx.x * 256 + threadIdx.x; i < 3 * 2048; i += G * 256)
-        coherent_store(&st->hist[0][0] + i, 0u);
-    if (blockIdx.x == 0 && threadIdx.x == 0) {
+    // -- the device-wide histograms are clean: the previous launch left them so (see below)
+    if (blockIdx.x == 0 && threadIdx.x == 0) {           // (read by the kernels after this one)
         st->n_fill = 0;
         st->n_evict = 0;
     }
-    bar += G;
-    if (!grid_sync(ctr, bar, &st->cd_abort, a.spin_limit)) return;
 
     // -- the key of the m-th largest entry, digit by digit
     uint32_t prefix = 0, need = (uint32_t)a.m;
@@ -289,6 +285,10 @@ __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
     }
     bar += G;
     if (!grid_sync(ctr, bar, &st->cd_abort, a.spin_limit)) return;
+    // every workgroup is through with the histograms: clean them for the next launch (which
+    // saves it a barrier; the data are set with clean ones, and set again after a failed barrier)
+    for (int i = blockIdx.x * 256 + threadIdx.x; i < 3 * 2048; i += G * 256)
+        coherent_store(&st->hist[0][0] + i, 0u);
     // entries of both kinds in the chunks before this one (G <= kMaxGroups <= 256: one per thread)
     uint32_t gt_before = 0, eq_before = 0;
     {
@@ -515,7 +515,7 @@ hipError_t launch_select(duhl_ctx *c, int64_t m, int32_t *P_out, const float *ke
     a.scalars = c->scalars;
     a.bar_base = c->sel_bar;
     a.spin_limit = 1 << 22;                              // seconds; the barriers take microseconds
-    c->sel_bar += 6u * (uint32_t)nb;                     // six barriers of nb arrivals each
+    c->sel_bar += 5u * (uint32_t)nb;                     // five barriers of nb arrivals each
     // chunks of up to 8,192 entries stay in registers for the whole kernel
     switch (chunk / 256) {
     case 8: hipLaunchKernelGGL(select_fused_kernel<8>, dim3(nb), dim3(256), 0, c->compute, a); break;
