@@ -214,6 +214,7 @@ __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
     __shared__ uint32_t tsum[256];
     __shared__ uint32_t found[2];
     __shared__ uint32_t wg[4], we[4];
+    __shared__ uint32_t tg2[2][4], te2[2][4];            // the scatter's per-tile counts, two tiles deep
     __shared__ double dsh[4];
     SelectState *st = a.st;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
@@ -311,9 +312,14 @@ __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
     }
 
     // -- ordered scatter: entry i goes to position (#selected entries with a smaller index)
+    // (the counts of consecutive tiles alternate between two buffers, so one barrier per tile
+    // is enough: a buffer is rewritten two tiles later, with the next tile's barrier in between)
     double ssel = 0.0;
     const bool own = a.zval == a.keys;
+    int tile = 0;
     for_each_key<KPT>(a, kreg, [&](int64_t i, float kf) {
+        uint32_t *cg = tg2[tile & 1], *ce = te2[tile & 1];
+        ++tile;
         bool g = false, e = false;
         if (i < a.n) {
             const uint32_t key = zkey(kf);
@@ -322,15 +328,15 @@ __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
         }
         const unsigned long long mg = __ballot(g), me = __ballot(e);
         const unsigned long long below = (1ull << lane) - 1ull;
-        if (lane == 0) { wg[w] = __popcll(mg); we[w] = __popcll(me); }
+        if (lane == 0) { cg[w] = __popcll(mg); ce[w] = __popcll(me); }
         __syncthreads();
         uint32_t og = gt_before + __popcll(mg & below), oe = eq_before + __popcll(me & below);
         uint32_t tg = 0, te = 0;
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            if (q < w) { og += wg[q]; oe += we[q]; }
-            tg += wg[q];
-            te += we[q];
+            if (q < w) { og += cg[q]; oe += ce[q]; }
+            tg += cg[q];
+            te += ce[q];
         }
         if (g || (e && oe < take_eq)) {
             const uint32_t pos = og + (oe < take_eq ? oe : take_eq);
@@ -340,7 +346,6 @@ __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
         }
         gt_before += tg;
         eq_before += te;
-        __syncthreads();
     });
     ssel = wave_sum(ssel);
     if (lane == 0) dsh[w] = ssel;
