@@ -78,10 +78,10 @@ float host_gap_value(const ModelConst &mc, float c, float alpha, float y)
     return z > 0.0f ? z : 0.0f;
 }
 
-void sampler_thread(duhl_ctx *c, duhl_host_sampler *hs, int tid, int nthreads)
+// `seen`: the round counter at the time the thread was created; it works on later rounds only.
+void sampler_thread(duhl_ctx *c, duhl_host_sampler *hs, int tid, int nthreads, int seen)
 {
     (void)hipSetDevice(c->device);
-    int seen = 0;
     for (;;) {
         {
             std::unique_lock<std::mutex> lk(hs->mu);
@@ -198,12 +198,20 @@ extern "C" duhl_status duhl_host_sample_begin(duhl_ctx *c, const int32_t *idx_ho
         if (!hs) return DUHL_ENOMEM;
         c->sampler = hs;
         hs->list = new std::vector<int32_t>();
-        HS_CHK(c, hipEventCreateWithFlags(&hs->snap, hipEventDisableTiming));
-        HS_CHK(c, hipHostMalloc(reinterpret_cast<void **>(&hs->h_alpha), sizeof(float) * c->n, hipHostMallocDefault));
-        HS_CHK(c, hipHostMalloc(reinterpret_cast<void **>(&hs->h_v), sizeof(float) * c->d, hipHostMallocDefault));
-        if (c->model == DUHL_SVM) {
-            HS_CHK(c, hipHostMalloc(reinterpret_cast<void **>(&hs->h_target), sizeof(float) * c->n, hipHostMallocDefault));
-            HS_CHK(c, hipMemcpy(hs->h_target, c->target, sizeof(float) * c->n, hipMemcpyDeviceToHost));
+        hipError_t e = hipEventCreateWithFlags(&hs->snap, hipEventDisableTiming);
+        if (e == hipSuccess)
+            e = hipHostMalloc(reinterpret_cast<void **>(&hs->h_alpha), sizeof(float) * c->n, hipHostMallocDefault);
+        if (e == hipSuccess)
+            e = hipHostMalloc(reinterpret_cast<void **>(&hs->h_v), sizeof(float) * c->d, hipHostMallocDefault);
+        if (e == hipSuccess && c->model == DUHL_SVM) {
+            e = hipHostMalloc(reinterpret_cast<void **>(&hs->h_target), sizeof(float) * c->n, hipHostMallocDefault);
+            if (e == hipSuccess)
+                e = hipMemcpy(hs->h_target, c->target, sizeof(float) * c->n, hipMemcpyDeviceToHost);
+        }
+        if (e != hipSuccess) {                       // leave no half-built sampler behind
+            host_sampler_destroy(c);
+            c->err = std::string("host sampler set-up: ") + hipGetErrorString(e);
+            return e == hipErrorOutOfMemory ? DUHL_ENOMEM : DUHL_EHIP;
         }
     }
     if (hs->host_A != c->host_base) {
@@ -232,7 +240,8 @@ extern "C" duhl_status duhl_host_sample_begin(duhl_ctx *c, const int32_t *idx_ho
     hs->stop.store(0);
     if ((int)hs->threads.size() != nthreads) {                    // (re)build the pool
         stop_pool(hs);
-        for (int t = 0; t < nthreads; ++t) hs->threads.emplace_back(sampler_thread, c, hs, t, nthreads);
+        for (int t = 0; t < nthreads; ++t)
+            hs->threads.emplace_back(sampler_thread, c, hs, t, nthreads, hs->generation);
     }
     {
         std::lock_guard<std::mutex> lk(hs->mu);

@@ -931,6 +931,13 @@ def test_host_gap_sampler_matches_oracle(G):
     with pytest.raises(duhl.DuhlError) as e:
         p.g.host_sample_end()
     assert e.value.status == duhl.ESTATE
+    # a pool of another size, built in the middle of the context's life, does one round's work once
+    for threads in (3, 5):
+        p.g.set(duhl.Z, np.full(prob["n"], -3.0, dtype=np.float32))
+        p.g.host_sample_begin(idx, nthreads=threads)
+        assert p.g.host_sample_end(wait_all=True) == idx.size
+        np.testing.assert_allclose(p.g.get(duhl.Z), p.o.z, rtol=1e-4,
+                                   atol=1e-4 * p.o.z.max() + G.lasso_gap_floor(p))
     p.close()
     q = G.Pair(lasso_problem(64, 40, 0.1, 0.1, seed=1))           # device residency: not applicable
     with pytest.raises(duhl.DuhlError) as e:
