@@ -36,14 +36,18 @@ COUNTER_TRAFFIC_BYTES = {"cfg5": {"gap": 50_163_074 * 2 * 1024 + 3_106 * 1024,
                          "cfg3": {"gap": 323_719 * 2 * 1024 + 13_100 * 1024}}     # the dot kernel of the pass
 
 
-def build_problem(name, device, scale):
+def build_problem(name, device, scale, piece_gib=8.0):
     import torch
     from paper_1708_05357_amd import synth
     cfg = synth.CONFIGS[name]
     out = None
     if cfg.get("host_resident"):
+        # unit A's memory: pinned host memory in pieces of at most piece_gib (one pinned allocation
+        # of more than about 32 GB fails on the test machines)
         n = max(8, int(cfg["n"] * scale)) if scale != 1.0 else cfg["n"]
-        out = torch.empty((n, cfg["d"]), dtype=torch.float32, pin_memory=True)
+        per = max(1, min(n, int(piece_gib * (1 << 30)) // (4 * cfg["d"])))
+        out = [torch.empty((min(per, n - first), cfg["d"]), dtype=torch.float32, pin_memory=True)
+               for first in range(0, n, per)]
     t0 = time.time()
     prob = synth.make(name, seed=0, device=device, scale=scale, out=out)
     torch.cuda.synchronize()
@@ -58,7 +62,9 @@ def make_ctx(prob, budget):
     g = duhl.Duhl(model, prob["d"], prob["n"], budget)
 
     def set_data():
-        if "cols" in prob:
+        if "cols" in prob and isinstance(prob["cols"], list):
+            g.set_data_dense_chunks(prob["cols"], prob["target"], prob["lam"])
+        elif "cols" in prob:
             g.set_data_dense(prob["cols"], prob["target"], prob["lam"],
                              duhl.RESIDENT_HOST if prob["host_resident"] else duhl.RESIDENT_DEVICE)
         else:
@@ -260,7 +266,12 @@ def cpu_baseline(prob, m, budget_s=20.0):
         if bytes_total > 8e9:                       # too large for the host: column subsample
             frac = 8e9 / bytes_total
         ns = int(n * frac)
-        cols = prob["cols"][:ns].cpu().numpy()
+        if isinstance(prob["cols"], list):          # host matrix in pieces: the first ns columns
+            import torch
+            cols = torch.cat([t[:max(0, ns - k * prob["cols"][0].shape[0])] for k, t in enumerate(prob["cols"])
+                              if ns > k * prob["cols"][0].shape[0]]).numpy()
+        else:
+            cols = prob["cols"][:ns].cpu().numpy()
         o = orc.Oracle(model, prob["target"].cpu().numpy(), prob["lam"], cols=cols)
     else:
         ns = n
@@ -369,8 +380,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "fig5svm"])
     ap.add_argument("--scale", type=float, default=None,
-                    help="shrink n (and m) at fixed d; default 1.0, but 0.4 for cfg4: one pinned host "
-                         "allocation is limited to about 32 GB on the test machines")
+                    help="shrink n (and m) at fixed d; default 1.0, but 0.8 for cfg4: the test machines "
+                         "pin at most 64 GiB of host memory")
     ap.add_argument("--budget-factor", type=float, default=2.0,
                     help="device slots per working-set column (host residency)")
     ap.add_argument("--no-cpu", action="store_true")
@@ -405,7 +416,7 @@ def main():
         sys.exit(2)
 
     if args.scale is None:
-        args.scale = 0.4 if args.workload == "cfg4" else 1.0
+        args.scale = 0.8 if args.workload == "cfg4" else 1.0
     if args.host_sampler_threads < 0:
         args.host_sampler_threads = 12
     if args.passes is None:

@@ -91,6 +91,17 @@ duhl_status duhl_set_eta(duhl_ctx *ctx, double eta);
 duhl_status duhl_set_data_dense(duhl_ctx *ctx, const float *A, int64_t ld, duhl_residency res,
                                 const float *target, double lambda);
 
+/* The same for a host-resident matrix (unit A's memory, Section 3) handed over in pieces, for
+ * machines that limit the size of one pinned allocation: piece k holds the columns
+ * [k*cols_per_chunk, min(n, (k+1)*cols_per_chunk)), column i of them at
+ * chunks[k] + (i - k*cols_per_chunk)*ld.  chunks: host array of n_chunks pointers, read during the
+ * call only; n_chunks == ceil(n / cols_per_chunk).  Each piece: pinned host memory that the device can
+ * read, borrowed like A above.  Residency is DUHL_RESIDENT_HOST; everything else as for
+ * duhl_set_data_dense.  DUHL_EINVAL for a NULL piece, a piece the device cannot read, or counts that do not fit n. */
+duhl_status duhl_set_data_dense_chunks(duhl_ctx *ctx, const float *const *chunks, int64_t n_chunks,
+                                       int64_t cols_per_chunk, int64_t ld, const float *target,
+                                       double lambda);
+
 /* Sparse data: CSR over coordinates, i.e. row i lists the non-zeros of column a_i (for the SVM
  * dual: CSR of the sample matrix).  rowptr (n+1, non-decreasing, rowptr[0] = 0), colidx (each
  * in [0,d), strictly increasing inside a row), val: device pointers, borrowed.  Only DUHL_RESIDENT_DEVICE.  Otherwise as above. */

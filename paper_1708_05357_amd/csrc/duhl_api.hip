@@ -6,6 +6,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <new>
+#include <vector>
 
 #include "duhl_internal.h"
 
@@ -51,7 +52,8 @@ void free_host_residency(duhl_ctx *c)
 {
     host_sampler_destroy(c);
     csr_blocked_free(c);
-    c->host_base = nullptr;
+    c->host_chunks.clear();
+    (void)hipFree(c->chunk_tab); c->chunk_tab = nullptr;
     (void)hipFree(c->slots); c->slots = nullptr;
     (void)hipFree(c->col_slot); c->col_slot = nullptr;
     (void)hipFree(c->slot_col); c->slot_col = nullptr;
@@ -161,6 +163,62 @@ duhl_status check_common(duhl_ctx *c, const void *target, double lambda)
     return DUHL_OK;
 }
 
+// Dense data: one piece in device or host memory, or several pieces in host memory.
+duhl_status set_data_dense_pieces(duhl_ctx *c, const float *const *pieces, int64_t n_pieces,
+                                         int64_t piece_cols, int64_t ld, duhl_residency res,
+                                         const float *target, double lambda)
+{
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, hipStreamSynchronize(c->compute));
+    HIPCHK(c, hipStreamSynchronize(c->copy));       // column copies of a pending selection
+    c->have_data = false;
+    free_host_residency(c);
+    c->sparse = false;
+    c->res = res;
+    c->nnz = c->d * c->n;
+    c->cv = ColView{};
+    c->cv.ld = ld;
+    c->chunk_cols = piece_cols;
+    c->a_aligned16 = true;
+    for (int64_t k = 0; k < n_pieces; ++k)
+        c->a_aligned16 = c->a_aligned16 && (reinterpret_cast<uintptr_t>(pieces[k]) & 15) == 0;
+    if (res == DUHL_RESIDENT_DEVICE) {
+        c->cv.base = pieces[0];
+        c->ld_s = 0;
+    } else {
+        std::vector<const float *> dev(n_pieces);
+        for (int64_t k = 0; k < n_pieces; ++k) {
+            void *dptr = nullptr;
+            if (hipHostGetDevicePointer(&dptr, const_cast<float *>(pieces[k]), 0) != hipSuccess || !dptr) {
+                (void)hipGetLastError();
+                return fail(c, DUHL_EINVAL, "host-resident A must be pinned, device-mapped host memory");
+            }
+            dev[k] = static_cast<const float *>(dptr);
+            c->a_aligned16 = c->a_aligned16 && (reinterpret_cast<uintptr_t>(dptr) & 15) == 0;
+        }
+        c->cv.base = dev[0];
+        c->host_chunks.assign(pieces, pieces + n_pieces);
+        if (n_pieces > 1) {
+            HIPCHK(c, dev_alloc(&c->chunk_tab, n_pieces));
+            HIPCHK(c, hipMemcpy(c->chunk_tab, dev.data(), sizeof(float *) * (size_t)n_pieces, hipMemcpyHostToDevice));
+            c->cv.chunk = c->chunk_tab;
+            c->cv.chunk_cols = (uint32_t)piece_cols;
+        }
+        c->ld_s = (c->d + 63) / 64 * 64;
+        HIPCHK(c, dev_alloc(&c->slots, c->budget * c->ld_s));
+        HIPCHK(c, dev_alloc(&c->col_slot, c->n));
+        HIPCHK(c, dev_alloc(&c->slot_col, c->budget));
+        HIPCHK(c, dev_alloc(&c->fill_col, c->budget));
+        HIPCHK(c, dev_alloc(&c->fill_slot, c->budget));
+        HIPCHK(c, dev_alloc(&c->evict_slot, c->budget));
+        HIPCHK(c, hipEventCreateWithFlags(&c->ev_plan, hipEventDisableTiming));
+        HIPCHK(c, hipEventCreateWithFlags(&c->ev_copy, hipEventDisableTiming));
+        HIPCHK(c, launch_fill_i32(c->compute, c->col_slot, c->n, -1));
+        HIPCHK(c, launch_fill_i32(c->compute, c->slot_col, c->budget, -1));
+    }
+    return finish_set_data(c, target, lambda);
+}
+
 }  // namespace
 
 extern "C" {
@@ -249,40 +307,22 @@ duhl_status duhl_set_data_dense(duhl_ctx *c, const float *A, int64_t ld, duhl_re
     if (!A) return fail(c, DUHL_EINVAL, "A is NULL");
     if (ld < c->d) return fail(c, DUHL_EINVAL, "ld (%lld) < d (%lld)", (long long)ld, (long long)c->d);
     if (res != DUHL_RESIDENT_DEVICE && res != DUHL_RESIDENT_HOST) return fail(c, DUHL_EINVAL, "bad residency");
-    HIPCHK(c, hipSetDevice(c->device));
-    HIPCHK(c, hipStreamSynchronize(c->compute));
-    HIPCHK(c, hipStreamSynchronize(c->copy));       // column copies of a pending selection
-    c->have_data = false;
-    free_host_residency(c);
-    c->sparse = false;
-    c->res = res;
-    c->nnz = c->d * c->n;
-    c->cv = ColView{};
-    c->cv.ld = ld;
-    if (res == DUHL_RESIDENT_DEVICE) {
-        c->cv.base = A;
-        c->ld_s = 0;
-    } else {
-        void *dptr = nullptr;
-        if (hipHostGetDevicePointer(&dptr, const_cast<float *>(A), 0) != hipSuccess || !dptr) {
-            (void)hipGetLastError();
-            return fail(c, DUHL_EINVAL, "host-resident A must be pinned, device-mapped host memory");
-        }
-        c->cv.base = static_cast<const float *>(dptr);
-        c->host_base = A;
-        c->ld_s = (c->d + 63) / 64 * 64;
-        HIPCHK(c, dev_alloc(&c->slots, c->budget * c->ld_s));
-        HIPCHK(c, dev_alloc(&c->col_slot, c->n));
-        HIPCHK(c, dev_alloc(&c->slot_col, c->budget));
-        HIPCHK(c, dev_alloc(&c->fill_col, c->budget));
-        HIPCHK(c, dev_alloc(&c->fill_slot, c->budget));
-        HIPCHK(c, dev_alloc(&c->evict_slot, c->budget));
-        HIPCHK(c, hipEventCreateWithFlags(&c->ev_plan, hipEventDisableTiming));
-        HIPCHK(c, hipEventCreateWithFlags(&c->ev_copy, hipEventDisableTiming));
-        HIPCHK(c, launch_fill_i32(c->compute, c->col_slot, c->n, -1));
-        HIPCHK(c, launch_fill_i32(c->compute, c->slot_col, c->budget, -1));
-    }
-    return finish_set_data(c, target, lambda);
+    return set_data_dense_pieces(c, &A, 1, c->n, ld, res, target, lambda);
+}
+
+duhl_status duhl_set_data_dense_chunks(duhl_ctx *c, const float *const *chunks, int64_t n_chunks,
+                                       int64_t cols_per_chunk, int64_t ld, const float *target,
+                                       double lambda)
+{
+    duhl_status st = check_common(c, target, lambda);
+    if (st != DUHL_OK) return st;
+    if (!chunks) return fail(c, DUHL_EINVAL, "chunks is NULL");
+    if (ld < c->d) return fail(c, DUHL_EINVAL, "ld (%lld) < d (%lld)", (long long)ld, (long long)c->d);
+    if (cols_per_chunk < 1 || n_chunks < 1 || n_chunks != (c->n + cols_per_chunk - 1) / cols_per_chunk)
+        return fail(c, DUHL_EINVAL, "need cols_per_chunk >= 1 and n_chunks == ceil(n / cols_per_chunk)");
+    for (int64_t k = 0; k < n_chunks; ++k)
+        if (!chunks[k]) return fail(c, DUHL_EINVAL, "chunk %lld is NULL", (long long)k);
+    return set_data_dense_pieces(c, chunks, n_chunks, cols_per_chunk, ld, DUHL_RESIDENT_HOST, target, lambda);
 }
 
 duhl_status duhl_set_data_csr(duhl_ctx *c, const int64_t *rowptr, const int32_t *colidx,

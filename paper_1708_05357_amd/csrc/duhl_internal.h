@@ -3,6 +3,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 #include <string>
+#include <vector>
 
 #include "duhl.h"
 
@@ -17,6 +18,10 @@ struct ColView {
     // dense
     const float *base;        // column j at base + j*ld (device memory, or device-mapped host memory)
     int64_t ld;
+    // host matrix given in pieces: column j in piece j / chunk_cols, at chunk[..] + (j % chunk_cols)*ld;
+    // base is then the first piece (non-null marks dense data)
+    const float *const *chunk;
+    uint32_t chunk_cols;
     const int32_t *col_slot;  // host residency: device slot holding column j, or -1; else nullptr
     const float *slots;       // slot s at slots + s*ld_s
     int64_t ld_s;
@@ -30,6 +35,10 @@ struct ColView {
         if (col_slot) {
             const int32_t s = col_slot[j];
             if (s >= 0) return slots + (int64_t)s * ld_s;
+        }
+        if (chunk) {
+            const uint32_t k = (uint32_t)j / chunk_cols;
+            return chunk[k] + (int64_t)((uint32_t)j - k * chunk_cols) * ld;
         }
         return base + j * ld;
     }
@@ -243,7 +252,10 @@ struct duhl_ctx {
     uint32_t xseq;              // next free sequence number for those slots
 
     // host residency
-    const float *host_base;     // the caller's host address of the matrix
+    std::vector<const float *> host_chunks;   // the caller's host addresses of the matrix: its pieces, or one entry
+    int64_t chunk_cols;         // columns per piece (n when the matrix is one piece)
+    const float **chunk_tab;    // device table of the pieces' device addresses (nullptr: one piece)
+    bool a_aligned16;           // every piece (or the matrix) starts on a 16-byte boundary
     duhl_host_sampler *sampler; // unit A's gap sampler, created on first use
     float *slots;
     int64_t ld_s;
@@ -270,6 +282,13 @@ struct duhl_ctx {
 };
 
 namespace duhl {
+
+// Host address of column j of a host-resident dense matrix.
+inline const float *host_col(const duhl_ctx *c, int64_t j)
+{
+    const int64_t k = j / c->chunk_cols;
+    return c->host_chunks[(size_t)k] + (j - k * c->chunk_cols) * c->cv.ld;
+}
 
 // ---- launchers (each enqueues on the given stream and returns the launch status) ----------
 hipError_t launch_gap(duhl_ctx *c, const int32_t *idx, int64_t count, bool slot_list,

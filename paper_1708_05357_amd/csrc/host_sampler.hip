@@ -33,7 +33,7 @@ struct duhl_host_sampler {
     int32_t *d_idx = nullptr;
     int64_t cap = 0, count = 0;
     bool active = false;
-    const float *host_A = nullptr;   // host address of the matrix (the device sees a mapped alias)
+    std::vector<const float *> touched;   // host pieces of the matrix whose pages were touched once
     std::vector<int32_t> *list = nullptr;   // coordinates of the running round
 };
 
@@ -90,12 +90,12 @@ void sampler_thread(duhl_ctx *c, duhl_host_sampler *hs, int tid, int nthreads, i
             seen = hs->generation;
         }
         if (hipEventSynchronize(hs->snap) == hipSuccess) {        // snapshots are in host memory now
-            const int64_t d = c->d, ld = c->cv.ld;
+            const int64_t d = c->d;
             const std::vector<int32_t> &list = *hs->list;
             for (int64_t k = tid; k < hs->count; k += nthreads) {
                 if (hs->stop.load(std::memory_order_relaxed)) break;
                 const int32_t j = list[k];
-                const float cj = host_dot(hs->host_A + (int64_t)j * ld, hs->h_v, d);
+                const float cj = host_dot(host_col(c, j), hs->h_v, d);
                 const float y = c->model == DUHL_SVM ? hs->h_target[j] : 0.0f;
                 hs->h_z[k] = host_gap_value(c->mc, cj, hs->h_alpha[j], y);
                 hs->h_idx[k] = j;                                 // marks the entry as refreshed
@@ -214,9 +214,13 @@ extern "C" duhl_status duhl_host_sample_begin(duhl_ctx *c, const int32_t *idx_ho
             return e == hipErrorOutOfMemory ? DUHL_ENOMEM : DUHL_EHIP;
         }
     }
-    if (hs->host_A != c->host_base) {
-        hs->host_A = c->host_base;
-        prefault(hs->host_A, c->cv.ld * (c->n - 1) + c->d, nthreads);
+    if (hs->touched != c->host_chunks) {
+        hs->touched = c->host_chunks;
+        for (size_t k = 0; k < hs->touched.size(); ++k) {
+            const int64_t first = (int64_t)k * c->chunk_cols;
+            const int64_t cols = c->n - first < c->chunk_cols ? c->n - first : c->chunk_cols;
+            prefault(hs->touched[k], c->cv.ld * (cols - 1) + c->d, nthreads);
+        }
     }
     if (count > hs->cap) {
         if (hs->h_z) (void)hipHostFree(hs->h_z);

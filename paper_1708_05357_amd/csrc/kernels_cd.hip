@@ -1016,7 +1016,7 @@ bool launch_workers(duhl_ctx *c, const CdArgs &a, int max_inflight, bool vec, hi
 template <int MODEL>
 hipError_t launch_cd_model(duhl_ctx *c, duhl_cd_mode mode, const CdArgs &a, int max_inflight)
 {
-    const bool vec = !c->sparse && aligned16(a.cv.base) && (a.cv.ld % 4 == 0) && aligned16(a.v) &&
+    const bool vec = !c->sparse && c->a_aligned16 && (a.cv.ld % 4 == 0) && aligned16(a.v) &&
                      (!a.cv.col_slot || (aligned16(a.cv.slots) && a.cv.ld_s % 4 == 0));
     if (mode == DUHL_CD_SEQUENTIAL) {
         if (c->sparse)

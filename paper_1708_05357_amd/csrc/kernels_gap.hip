@@ -226,7 +226,7 @@ static hipError_t launch_gap_model(duhl_ctx *c, const GapArgs &a, int64_t *grid_
                                c->compute, a);
         }
     } else {
-        const bool vec = aligned16(a.cv.base) && (a.cv.ld % 4 == 0) && aligned16(a.v) &&
+        const bool vec = c->a_aligned16 && (a.cv.ld % 4 == 0) && aligned16(a.v) &&
                          (!a.cv.col_slot || (aligned16(a.cv.slots) && a.cv.ld_s % 4 == 0));
         // Short columns: more columns per wavefront to keep enough bytes in flight.
         const int cols = c->gap_cols;

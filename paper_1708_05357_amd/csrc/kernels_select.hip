@@ -457,15 +457,18 @@ __global__ void publish_kernel(const SelectState *st, const int32_t *fill_col,
 // Eight workgroups (64 KB of reads in flight each) already saturate the host link (56 GB/s
 // measured); more of them only slow the concurrent coordinate-descent pass down (5x with 32).
 template <bool VEC4>
-__global__ __launch_bounds__(256) void copy_columns_kernel(const float *src, int64_t ld, float *slots,
-                                                           int64_t ld_s, int64_t d,
+__global__ __launch_bounds__(256) void copy_columns_kernel(const float *src, int64_t ld,
+                                                           const float *const *chunk, uint32_t chunk_cols,
+                                                           float *slots, int64_t ld_s, int64_t d,
                                                            const SelectState *st,
                                                            const int32_t *fill_col,
                                                            const int32_t *fill_slot)
 {
     const int64_t count = st->n_fill;
     for (int64_t k = blockIdx.x; k < count; k += gridDim.x) {
-        const float *s = src + (int64_t)fill_col[k] * ld;
+        const uint32_t j = (uint32_t)fill_col[k];
+        const uint32_t piece = chunk ? j / chunk_cols : 0u;          // the matrix may come in pieces
+        const float *s = (chunk ? chunk[piece] : src) + (int64_t)(j - piece * chunk_cols) * ld;
         float *t = slots + (int64_t)fill_slot[k] * ld_s;
         int64_t done = 0;
         if (VEC4) {
@@ -564,15 +567,15 @@ hipError_t launch_plan_swap(duhl_ctx *c, bool overlap_safe, bool want_count)
 
 hipError_t launch_copy_columns(duhl_ctx *c)
 {
-    const bool vec = ((reinterpret_cast<uintptr_t>(c->cv.base) & 15) == 0) && (c->cv.ld % 4 == 0);
+    const bool vec = c->a_aligned16 && (c->cv.ld % 4 == 0);
     if (vec)
         hipLaunchKernelGGL(copy_columns_kernel<true>, dim3(c->copy_blocks), dim3(256), 0, c->copy,
-                           c->cv.base, c->cv.ld, c->slots, c->ld_s, c->d, c->sel, c->fill_col,
-                           c->fill_slot);
+                           c->cv.base, c->cv.ld, c->cv.chunk, c->cv.chunk_cols, c->slots, c->ld_s, c->d,
+                           c->sel, c->fill_col, c->fill_slot);
     else
         hipLaunchKernelGGL(copy_columns_kernel<false>, dim3(c->copy_blocks), dim3(256), 0, c->copy,
-                           c->cv.base, c->cv.ld, c->slots, c->ld_s, c->d, c->sel, c->fill_col,
-                           c->fill_slot);
+                           c->cv.base, c->cv.ld, c->cv.chunk, c->cv.chunk_cols, c->slots, c->ld_s, c->d,
+                           c->sel, c->fill_col, c->fill_slot);
     return hipGetLastError();
 }
 

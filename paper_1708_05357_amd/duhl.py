@@ -21,7 +21,7 @@ CD_SEQUENTIAL, CD_ASYNC, CD_ATOMIC = 0, 1, 2
 SELECT_GAP, SELECT_RANDOM, SELECT_BLOCK = 0, 1, 2
 OK, EINVAL, ENOMEM, EHIP, ESTATE, EBUDGET = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_data_dense", "duhl_set_data_csr", "duhl_gap", "duhl_select",
+EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_data_dense", "duhl_set_data_dense_chunks", "duhl_set_data_csr", "duhl_gap", "duhl_select",
            "duhl_select_rule_apply", "duhl_host_sample_begin", "duhl_host_sample_end",
            "duhl_commit_swap", "duhl_cd_epoch", "duhl_run", "duhl_objective", "duhl_recompute_v", "duhl_get",
            "duhl_set", "duhl_device_ptr", "duhl_probe_stream_read", "duhl_selection_threshold",
@@ -64,6 +64,7 @@ def load():
     lib.duhl_create.argtypes = [C.POINTER(p), i32, i64, i64, i64, i32, p, p]
     lib.duhl_set_eta.argtypes = [p, dbl]
     lib.duhl_set_data_dense.argtypes = [p, p, i64, i32, p, dbl]
+    lib.duhl_set_data_dense_chunks.argtypes = [p, p, i64, i64, i64, p, dbl]
     lib.duhl_set_data_csr.argtypes = [p, p, p, p, i32, p, dbl]
     lib.duhl_gap.argtypes = [p, p, i64, C.POINTER(dbl)]
     lib.duhl_select.argtypes = [p, i64, p, C.POINTER(i64), C.POINTER(dbl)]
@@ -87,7 +88,7 @@ def load():
     lib.duhl_destroy.restype = None
     lib.duhl_probe_stream_read.argtypes = [p, p, i64, i32, C.POINTER(dbl)]
     lib.duhl_run.argtypes = [p, C.POINTER(RunOpts), C.POINTER(RunStats)]
-    for name in EXPORTS[:20]:
+    for name in EXPORTS[:21]:
         getattr(lib, name).restype = i32
     _lib = lib
     return lib
@@ -149,6 +150,20 @@ class Duhl:
         self._keep = (cols, target)
         self._chk(self.lib.duhl_set_data_dense(self._h, C.c_void_p(cols.data_ptr()), cols.stride(0),
                                                residency, _dptr(target, torch.float32), float(lam)))
+
+    def set_data_dense_chunks(self, chunks, target, lam):
+        """chunks: list of pinned float32 (cols_k, d) host tensors that together hold the n columns in
+        order; all but the last have the same number of rows, and all the same row stride."""
+        cpc = chunks[0].shape[0]
+        for k, t in enumerate(chunks):
+            assert t.dtype == torch.float32 and t.dim() == 2 and t.stride(1) == 1 and t.shape[1] == self.d
+            assert t.device.type == "cpu" and t.is_pinned() and t.stride(0) == chunks[0].stride(0)
+            assert t.shape[0] == (cpc if k + 1 < len(chunks) else self.n - cpc * (len(chunks) - 1))
+        self._keep = (list(chunks), target)
+        ptrs = (C.c_void_p * len(chunks))(*[t.data_ptr() for t in chunks])
+        self._chk(self.lib.duhl_set_data_dense_chunks(self._h, ptrs, len(chunks), int(cpc),
+                                                      chunks[0].stride(0), _dptr(target, torch.float32),
+                                                      float(lam)))
 
     def set_data_csr(self, rowptr, colidx, val, target, lam, residency=RESIDENT_DEVICE):
         self._keep = (rowptr, colidx, val, target)

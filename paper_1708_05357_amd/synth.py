@@ -22,6 +22,20 @@ def _gen(seed, device):
     return g
 
 
+def _segments(out, j0, j1):
+    """The rows [j0, j1) of a matrix stored as one (n, d) tensor or as a list of (rows_k, d) pieces
+    (all of the same height but the last): (tensor slice, first row, end row) per piece touched."""
+    if isinstance(out, torch.Tensor):
+        yield out[j0:j1], j0, j1
+        return
+    per = out[0].shape[0]
+    while j0 < j1:
+        k, a = divmod(j0, per)
+        b = min(out[k].shape[0], a + (j1 - j0))
+        yield out[k][a:b], j0, j0 + (b - a)
+        j0 += b - a
+
+
 def lasso_dense(d, n, support_frac, c_lambda, seed=0, device="cpu", out=None, block_cols=None,
                 noise=0.01):
     """Dense Lasso instance.
@@ -32,13 +46,18 @@ def lasso_dense(d, n, support_frac, c_lambda, seed=0, device="cpu", out=None, bl
     returned ``lam`` is the lambda of the paper's objective ||A alpha - b||^2/(2d) + lambda||alpha||_1.
 
     ``out`` (optional) is a preallocated float32 (n, d) tensor to fill -- on the device, or in
-    pinned host memory for the out-of-budget case; blocks are generated on ``device`` and copied.
+    pinned host memory for the out-of-budget case --, or a list of such tensors that hold the
+    columns in order, piece by piece; blocks are generated on ``device`` and copied.
     """
     dev = torch.device(device)
     g = _gen(seed, dev)
     if out is None:
         out = torch.empty((n, d), dtype=torch.float32, device=dev)
-    assert out.shape == (n, d) and out.dtype == torch.float32
+    if isinstance(out, torch.Tensor):
+        assert out.shape == (n, d) and out.dtype == torch.float32
+    else:
+        assert sum(t.shape[0] for t in out) == n and all(t.shape[1] == d and t.dtype == torch.float32 for t in out)
+        assert all(t.shape[0] == out[0].shape[0] for t in out[:-1]) and out[-1].shape[0] <= out[0].shape[0]
     if block_cols is None:
         block_cols = max(1, min(n, (256 << 20) // (4 * d)))
     k = int(math.floor(support_frac * n))
@@ -52,13 +71,15 @@ def lasso_dense(d, n, support_frac, c_lambda, seed=0, device="cpu", out=None, bl
         x = torch.randn((j1 - j0, d), generator=g, device=dev, dtype=torch.float32)
         x /= x.norm(dim=1, keepdim=True)
         b += x.t() @ alpha_star[j0:j1]
-        out[j0:j1].copy_(x)
+        for piece, a, e in _segments(out, j0, j1):
+            piece.copy_(x[a - j0:e - j0])
     b += noise * torch.randn(d, generator=g, device=dev, dtype=torch.float32)
     atb_inf = 0.0
     for j0 in range(0, n, block_cols):
         j1 = min(n, j0 + block_cols)
-        x = out[j0:j1].to(dev, non_blocking=False)
-        atb_inf = max(atb_inf, float((x @ b).abs().max()))
+        for piece, a, e in _segments(out, j0, j1):
+            x = piece.to(dev, non_blocking=False)
+            atb_inf = max(atb_inf, float((x @ b).abs().max()))
     lam = c_lambda * atb_inf / d
     return {"model": "lasso", "d": d, "n": n, "cols": out, "target": b, "lam": lam,
             "alpha_star": alpha_star}

@@ -13,7 +13,7 @@ def to_np(t):
 class Pair:
     """The same seeded problem in the HIP library (self.g) and in the CPU oracle (self.o)."""
 
-    def __init__(self, prob, budget=None, host_resident=False, ld=None):
+    def __init__(self, prob, budget=None, host_resident=False, ld=None, chunk_cols=None):
         self.prob = prob
         model = {"lasso": duhl.LASSO, "svm": duhl.SVM, "enet": duhl.ELASTIC_NET}[prob["model"]]
         self.model = model
@@ -26,16 +26,27 @@ class Pair:
             self.g.set_eta(eta)
         if "cols" in prob:
             ld_eff = ld if ld is not None else d
-            if host_resident:
-                store = torch.empty((n, ld_eff), dtype=torch.float32, pin_memory=True)
+            if chunk_cols is not None:
+                # the host matrix in separately pinned pieces of chunk_cols columns (the last one shorter)
+                assert host_resident
+                self.pieces = []
+                for first in range(0, n, chunk_cols):
+                    rows = min(chunk_cols, n - first)
+                    piece = torch.full((rows, ld_eff), float("nan"), dtype=torch.float32).pin_memory()
+                    piece[:, :d].copy_(prob["cols"][first:first + rows])
+                    self.pieces.append(piece[:, :d])
+                self.g.set_data_dense_chunks(self.pieces, self.target, prob["lam"])
             else:
-                store = torch.empty((n, ld_eff), dtype=torch.float32, device=dev)
-            if ld_eff > d:
-                store.fill_(float("nan"))                      # padding must never be read
-            store[:, :d].copy_(prob["cols"])
-            self.cols = store[:, :d]
-            self.g.set_data_dense(self.cols, self.target, prob["lam"],
-                                  duhl.RESIDENT_HOST if host_resident else duhl.RESIDENT_DEVICE)
+                if host_resident:
+                    store = torch.empty((n, ld_eff), dtype=torch.float32, pin_memory=True)
+                else:
+                    store = torch.empty((n, ld_eff), dtype=torch.float32, device=dev)
+                if ld_eff > d:
+                    store.fill_(float("nan"))                      # padding must never be read
+                store[:, :d].copy_(prob["cols"])
+                self.cols = store[:, :d]
+                self.g.set_data_dense(self.cols, self.target, prob["lam"],
+                                      duhl.RESIDENT_HOST if host_resident else duhl.RESIDENT_DEVICE)
             self.o = orc.Oracle(model, to_np(prob["target"]), prob["lam"],
                                 cols=np.ascontiguousarray(to_np(prob["cols"])), eta=eta)
         else:

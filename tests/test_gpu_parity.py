@@ -569,10 +569,19 @@ def test_host_resident_swap_long_columns(G):
     run_host_resident(G, lasso_problem(100000, 160, 0.1, 0.1, seed=22), 30, rounds=4)
 
 
-def run_host_resident(G, prob, m, rounds=10):
+def test_host_resident_matrix_in_pieces(G):
+    """The host matrix handed over as separately pinned pieces (a short last one; padded leading
+    dimension): same iterates, slots and gaps as from one allocation."""
+    prob = lasso_problem(1028, 400, 0.1, 0.1, seed=23)
+    run_host_resident(G, prob, 60, rounds=6, chunk_cols=130, ld=1040)
+    run_host_resident(G, prob, 60, rounds=3, chunk_cols=1)        # a piece per column
+    run_host_resident(G, prob, 60, rounds=3, chunk_cols=400)      # one piece through the table
+
+
+def run_host_resident(G, prob, m, rounds=10, chunk_cols=None, ld=None):
     from paper_1708_05357_amd import duhl
     for budget in (2 * m, m + 7):                  # overlapping copies / in-place replacement
-        p = G.Pair(prob, budget=budget, host_resident=True)
+        p = G.Pair(prob, budget=budget, host_resident=True, chunk_cols=chunk_cols, ld=ld)
         p.o.gaps()
         G.assert_gaps_close(p.g.get(duhl.Z), p.o.z)
         rng = np.random.default_rng(2)
@@ -664,6 +673,25 @@ def test_error_paths(G):
     g.select(3)
     g.commit_swap()
     g.cd_epoch()
+    # a host matrix in pieces: the counts must fit n, and every piece must be readable by the device
+    import ctypes as C
+    pieces = [torch.randn(4, 8).pin_memory(), torch.randn(2, 8).pin_memory()]
+    ptrs = (C.c_void_p * 2)(*[t.data_ptr() for t in pieces])
+    bp = C.c_void_p(b.data_ptr())
+    for n_chunks, per in ((3, 3), (2, 2), (1, 4), (2, 0), (0, 6)):
+        assert g.lib.duhl_set_data_dense_chunks(g._h, ptrs, n_chunks, per, 8, bp, 0.1) == duhl.EINVAL
+    assert g.lib.duhl_set_data_dense_chunks(g._h, None, 2, 4, 8, bp, 0.1) == duhl.EINVAL
+    assert g.lib.duhl_set_data_dense_chunks(g._h, ptrs, 2, 4, 7, bp, 0.1) == duhl.EINVAL       # ld < d
+    null_piece = (C.c_void_p * 2)(pieces[0].data_ptr(), None)
+    assert g.lib.duhl_set_data_dense_chunks(g._h, null_piece, 2, 4, 8, bp, 0.1) == duhl.EINVAL
+    pageable = torch.randn(2, 8)
+    not_pinned = (C.c_void_p * 2)(pieces[0].data_ptr(), pageable.data_ptr())
+    assert g.lib.duhl_set_data_dense_chunks(g._h, not_pinned, 2, 4, 8, bp, 0.1) == duhl.EINVAL
+    with pytest.raises(duhl.DuhlError) as e:
+        g.gap()                                                  # the failed call left no data behind
+    assert e.value.status == duhl.ESTATE
+    g.set_data_dense_chunks(pieces, b, 0.1)
+    assert g.gap() >= 0.0
     g.close()
     with pytest.raises(duhl.DuhlError) as e:
         duhl.Duhl(duhl.LASSO, 8, 6, 3).set_eta(0.5)              # eta belongs to the elastic net
@@ -883,14 +911,15 @@ def test_block_and_random_selection_rules(G):
 
 
 # ------------------------------------------------------------------------------------ unit A's gap sampler
-def test_host_gap_sampler_matches_oracle(G):
+@pytest.mark.parametrize("chunk_cols", [None, 170])
+def test_host_gap_sampler_matches_oracle(G, chunk_cols):
     """Alg. 2, lines 7-10: host threads refresh z_j := gap_j(alpha^(t)) from the host matrix while
     the GPU runs the pass on the current block.  The refreshed entries must equal the oracle's gaps
     at the snapshot alpha^(t) (not at the state after the pass); other entries stay untouched."""
     from paper_1708_05357_amd import duhl
     prob = lasso_problem(2051, 600, 0.1, 0.1, seed=61)
     m = 90
-    p = G.Pair(prob, budget=2 * m, host_resident=True)
+    p = G.Pair(prob, budget=2 * m, host_resident=True, chunk_cols=chunk_cols)   # one allocation, or pieces
     rng = np.random.default_rng(7)
     p.g.select(m)
     p.g.commit_swap()
