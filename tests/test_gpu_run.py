@@ -168,7 +168,8 @@ def test_host_resident_svm_and_elastic_net_rounds(G, threads):
     en["model"], en["eta"] = "enet", 0.4
     for prob, m, rounds in ((sv, 150, 250), (en, 80, 150)):
         n = prob["n"]
-        p = G.Pair(prob, budget=2 * m, host_resident=True)
+        # with host threads the matrix comes in pinned pieces of 97 columns, otherwise in one
+        p = G.Pair(prob, budget=2 * m, host_resident=True, chunk_cols=97 if threads else None)
         perm = torch.randperm(n, generator=torch.Generator().manual_seed(7)).to(torch.int32).cuda()
         st = p.g.run(m, rounds, passes=2, mode=duhl.CD_ASYNC, sample=perm, sample_per_round=max(1, n // 4),
                      host_threads=threads, seed=3)
