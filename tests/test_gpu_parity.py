@@ -1049,3 +1049,64 @@ def test_hand_worked_examples_on_the_gpu(G, name):
         g.gap(want_sum=False)
         np.testing.assert_allclose(g.get(duhl.Z), case["gaps_after_pass"], atol=1e-7)
         g.close()
+
+
+def test_context_reused_for_other_data(G):
+    """duhl_set_data_* may be called again on a context, with another matrix, storage or residency:
+    everything the previous data left behind (slots, the sparse copy, worker buffers, selection
+    state) must be rebuilt or reset, so the rounds that follow equal those of a fresh context."""
+    from paper_1708_05357_amd import duhl, synth
+    dev = "cuda:0"
+    n, d, m = 900, 2600, 200
+    dense = [synth.svm_dense(n, d, seed=s) for s in (71, 72)]
+    sparse = synth.svm_csr(n, d, 0.02, seed=73)
+
+    def rounds(g, reproducible):
+        out = []
+        for rnd in range(4):
+            g.gap(want_sum=False)
+            g.select(m, want_stats=False)
+            g.commit_swap()
+            g.cd_epoch(duhl.CD_ASYNC if reproducible else duhl.CD_SEQUENTIAL, seed=rnd)
+        out.append(g.get(duhl.ALPHA))
+        out.append(g.get(duhl.V))
+        out.append(np.float32(g.gap()))
+        out.append(g.get(duhl.P))
+        return out
+
+    def load(g, kind, prob, keep):
+        y = prob["target"].to(dev)
+        if kind == "device":
+            cols = prob["cols"].to(dev)
+            keep += [cols, y]
+            g.set_data_dense(cols, y, prob["lam"])
+        elif kind == "host":
+            cols = prob["cols"].pin_memory()
+            keep += [cols, y]
+            g.set_data_dense(cols, y, prob["lam"], duhl.RESIDENT_HOST)
+        elif kind == "pieces":
+            pieces = [prob["cols"][a:a + 350].clone().pin_memory() for a in range(0, n, 350)]
+            keep += pieces + [y]
+            g.set_data_dense_chunks(pieces, y, prob["lam"])
+        else:
+            arrs = [prob[k].to(dev) for k in ("rowptr", "colidx", "val")]
+            keep += arrs + [y]
+            g.set_data_csr(*arrs, y, prob["lam"])
+
+    plan = [("device", dense[0]), ("csr", sparse), ("host", dense[1]), ("pieces", dense[0]),
+            ("csr", sparse), ("device", dense[1])]
+    keep = []
+    reused = duhl.Duhl(duhl.SVM, d, n, 2 * m)
+    for kind, prob in plan:
+        # dense workers are reproducible for a seed; sparse concurrent passes are not, so the
+        # sparse data are compared on sequential passes
+        reproducible = kind != "csr"
+        load(reused, kind, prob, keep)
+        got = rounds(reused, reproducible)
+        fresh = duhl.Duhl(duhl.SVM, d, n, 2 * m)
+        load(fresh, kind, prob, keep)
+        want = rounds(fresh, reproducible)
+        fresh.close()
+        for a, b in zip(got, want):
+            assert np.array_equal(a, b), kind
+    reused.close()
