@@ -251,6 +251,22 @@ def time_to_gap_native(g, set_data, prob, m, target, mode, inflight, rule, passe
     return out
 
 
+def host_description():
+    """CPU model, logical CPUs and memory of the machine the baseline ran on."""
+    model, mem_gb = "unknown", None
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+        with open("/proc/meminfo") as f:
+            mem_gb = round(int(f.readline().split()[1]) / 1e6)
+    except OSError:
+        pass
+    return {"cpu": model, "logical_cpus": os.cpu_count(), "memory_GB": mem_gb}
+
+
 def cpu_baseline(prob, m, budget_s=20.0):
     """The oracle as it stands, single thread, on the same inputs: rounds of full gap pass,
     selection and one CD pass from alpha = 0, for about budget_s seconds (at least one round;
@@ -317,7 +333,8 @@ def cpu_baseline(prob, m, budget_s=20.0):
             "gap_pass_s": t_gap / rounds, "cd_pass_s": t_cd / rounds,
             "gap_GBps": gap_bytes / (t_gap / rounds) / 1e9,
             "cd_updates_per_s": ms / (t_cd / rounds),
-            "gap_pass_threads": threads, "gap_pass_s_threads": t_par, "gap_GBps_threads": gap_bytes / t_par / 1e9}
+            "gap_pass_threads": threads, "gap_pass_s_threads": t_par, "gap_GBps_threads": gap_bytes / t_par / 1e9,
+            "host": host_description()}
 
 
 def cpu_time_to_gap(prob, m, target, budget_s):
