@@ -245,8 +245,12 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->copy = reinterpret_cast<hipStream_t>(copy_stream);
     c->num_cu = 256;
     (void)hipDeviceGetAttribute(&c->num_cu, hipDeviceAttributeMultiprocessorCount, device);
-    c->gap_cols = env_int("DUHL_GAP_COLS", d < 4096 ? 8 : 4);
-    if (c->gap_cols != 1 && c->gap_cols != 2 && c->gap_cols != 4 && c->gap_cols != 8) c->gap_cols = 4;
+    // columns per wavefront of the dense gap pass: several amortise the reads of v, but a problem
+    // of few columns needs one wavefront per column to put enough of them on every compute unit
+    int gap_cols = d < 4096 ? 8 : 4;
+    while (gap_cols > 1 && n / gap_cols < 8 * (int64_t)c->num_cu) gap_cols /= 2;
+    c->gap_cols = env_int("DUHL_GAP_COLS", gap_cols);
+    if (c->gap_cols != 1 && c->gap_cols != 2 && c->gap_cols != 4 && c->gap_cols != 8) c->gap_cols = gap_cols;
     c->cd_threads = env_int("DUHL_CD_THREADS", 0);
     c->copy_blocks = env_int("DUHL_COPY_BLOCKS", 8);
     if (c->copy_blocks < 1) c->copy_blocks = 1;

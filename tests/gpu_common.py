@@ -117,3 +117,21 @@ def svm_gap_floor_csr(rowptr, colidx, val, v, alpha, lam):
 
 def dev_i32(a):
     return torch.as_tensor(np.ascontiguousarray(a, dtype=np.int32), device="cuda:0")
+
+
+def v_accumulation_floor(pair, alpha):
+    """Rounding floor of v = A alpha (- b) (App. D) accumulated in fp32 in any order.  Each of the
+    N = nnz(alpha) additions rounds a partial sum that is at most S_i = sum_j |a_ij alpha_j| (+ |b_i|)
+    in size, by at most u = 2^-24 of it; N such errors add up like a random walk, sqrt(N) u S_i
+    (worst case N u S_i).  A fixed 8 u S_i covers short sums."""
+    prob = pair.prob
+    a = np.abs(np.asarray(alpha, dtype=np.float64))
+    if "cols" in prob:
+        mag = np.abs(to_np(prob["cols"]).astype(np.float64)).T @ a
+    else:
+        rowptr, colidx, val = (to_np(prob[k]) for k in ("rowptr", "colidx", "val"))
+        rows = np.repeat(np.arange(prob["n"]), np.diff(rowptr))
+        mag = np.bincount(colidx, weights=np.abs(val.astype(np.float64)) * a[rows], minlength=prob["d"])
+    if prob["model"] != "svm":
+        mag = mag + np.abs(to_np(prob["target"]).astype(np.float64))
+    return (8.0 + np.sqrt(np.count_nonzero(a))) * 2.0 ** -24 * float(mag.max())
