@@ -166,6 +166,10 @@ CONFIGS = {
     # the shape of the paper's large-scale SVM experiment (Section 5.3: 40,000 samples with 200,704
     # dense single-precision features, 30 GB, a quarter of them on the accelerator)
     "fig5svm": dict(kind="svm_dense", n=40_000, d=200_704, m=10_000, rounds=20),
+    # the shape of the paper's convergence experiments (Section 5.1: a dense dataset of 400,000
+    # samples and 2,000 features, a quarter of the coordinates on the accelerator, Lasso support ~12 %)
+    "sec51lasso": dict(kind="lasso_dense", d=400_000, n=2_000, support_frac=0.12, c_lambda=0.1,
+                       m=500, rounds=20),
 }
 
 

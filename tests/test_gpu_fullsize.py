@@ -367,3 +367,46 @@ def test_paper_svm_shape_sampled_columns(G):
     want = (sub.t() @ torch.as_tensor(a2[nz], device="cuda").double()).cpu().numpy()
     assert np.abs(v2[rows.cpu().numpy()] - want).max() <= 1e-4 * max(np.abs(want).max(), 1e-30)
     g.close()
+
+
+@pytest.mark.parametrize("model", ["lasso", "ridge"])
+def test_paper_convergence_shape_few_long_columns(G, model):
+    """The shape of the paper's convergence experiments (Section 5.1): 400,000 samples and 2,000
+    features, a quarter of the coordinates in the working set, Lasso and ridge regression.  Few,
+    very long columns: one wavefront per column in the gap pass, workers of eight compute units in
+    the pass.  The whole problem still fits the oracle, so everything is compared in full."""
+    from paper_1708_05357_amd import duhl, synth
+    prob = dict(synth.make("sec51lasso", device="cuda"))
+    if model == "ridge":
+        prob["model"], prob["eta"] = "enet", 1.0                   # eta = 1: App. C (a)
+    m = prob["m"]
+    host = {k: (v.cpu() if isinstance(v, torch.Tensor) else v) for k, v in prob.items()}
+    del prob
+    p = G.Pair(host)
+    floor = (lambda: G.lasso_gap_floor(p)) if model == "lasso" else (lambda: G.enet_gap_floor(p))
+    p.o.gaps()
+    G.assert_gaps_close(p.g.get(duhl.Z), p.o.z, floor=floor())
+    rng = np.random.default_rng(0)
+    for rnd in range(12):
+        p.g.gap(want_sum=False)
+        p.g.select(m, want_stats=False)
+        p.g.commit_swap()
+        p.g.cd_epoch(duhl.CD_ASYNC, seed=rnd)
+        p.o.round(m, passes=1, rng=rng)
+    og, oo = p.g.objective(), p.o.objective()
+    print(f"{model}: objective gpu {og:.9e} oracle {oo:.9e}", flush=True)
+    assert abs(og - oo) <= 1e-5 * abs(oo)
+    a, v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+    p.o.set_state(a.astype(np.float64))                            # v = A alpha - b (App. D)
+    assert np.abs(v - p.o.v).max() <= 2e-5 * max(np.abs(p.o.v).max(), np.abs(G.to_np(host["target"])).max())
+    p.o.set_state(a.astype(np.float64), v.astype(np.float64))
+    p.o.gaps()
+    p.g.gap(want_sum=False)
+    G.assert_gaps_close(p.g.get(duhl.Z), np.maximum(p.o.z, 0.0), floor=floor())
+    order = rng.permutation(p.g.get(duhl.P))[:40].astype(np.int32)
+    p.g.cd_epoch(duhl.CD_SEQUENTIAL, G.dev_i32(order))
+    p.o.cd_pass(order)
+    a2, v2 = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+    assert np.abs(a2 - p.o.alpha).max() <= 1e-5 * max(np.abs(p.o.alpha).max(), 1e-30)
+    assert np.abs(v2 - p.o.v).max() <= 1e-5 * np.abs(p.o.v).max()
+    p.close()
