@@ -170,6 +170,8 @@ CONFIGS = {
     # samples and 2,000 features, a quarter of the coordinates on the accelerator, Lasso support ~12 %)
     "sec51lasso": dict(kind="lasso_dense", d=400_000, n=2_000, support_frac=0.12, c_lambda=0.1,
                        m=500, rounds=20),
+    # the same dataset shape for the SVM dual, where the coordinates are the samples
+    "sec51svm": dict(kind="svm_dense", n=400_000, d=2_000, m=100_000, rounds=20),
 }
 
 
