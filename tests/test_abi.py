@@ -60,3 +60,17 @@ def test_product_path_does_not_reach_for_the_oracle():
             if f.endswith((".py", ".hip", ".h")):
                 text = open(os.path.join(dirpath, f)).read()
                 assert not re.search(r"import\s+oracle|from\s+oracle|duhl_oracle|oracle/", text), f
+
+
+def test_header_is_plain_c_and_a_c_client_links():
+    """include/duhl.h compiles as pedantic C99 with all warnings as errors, inside a client written
+    in C that links against the library (gcc; no GPU needed to build)."""
+    import importlib.util
+    spec = importlib.util.spec_from_file_location(
+        "build_client", os.path.join(ROOT, "tests", "c_client", "build_client.py"))
+    mod = importlib.util.module_from_spec(spec)
+    spec.loader.exec_module(mod)
+    from paper_1708_05357_amd import duhl
+    duhl.load()                                              # the library the client links against
+    lib = ctypes.CDLL(mod.build())
+    assert hasattr(lib, "duhl_c_client_rounds")

@@ -1110,3 +1110,48 @@ def test_context_reused_for_other_data(G):
         for a, b in zip(got, want):
             assert np.array_equal(a, b), kind
     reused.close()
+
+
+def test_plain_c_client_matches_oracle(G):
+    """The library driven by a client written in C (HIP runtime C interface, default stream, no
+    torch objects): rounds of Algorithm 1 with sequential passes give the oracle's iterates (1e-5),
+    gaps (1e-4) and working set."""
+    import ctypes as C
+    from oracle import duhl_oracle as orc
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    path = os.path.join(root, "tests", "c_client", "libduhl_c_client.so")
+    assert os.path.exists(path), "build it with __graft_entry__.build()"
+    lib = C.CDLL(path)
+    d, n, ld, m, rounds = 1003, 260, 1004, 60, 5
+    prob = lasso_problem(d, n, 0.1, 0.1, seed=81)
+    A = np.full((n, ld), np.nan, dtype=np.float32)             # padding must never be read
+    A[:, :d] = prob["cols"].numpy()
+    b = prob["target"].numpy().astype(np.float32)
+    alpha, v, z = np.empty(n, np.float32), np.empty(d, np.float32), np.empty(n, np.float32)
+    P = np.empty(m, np.int32)
+    obj, gap = C.c_double(0.0), C.c_double(0.0)
+    fp, ip = C.POINTER(C.c_float), C.POINTER(C.c_int32)
+    lib.duhl_c_client_rounds.argtypes = [fp, fp, C.c_int64, C.c_int64, C.c_int64, C.c_double, C.c_int64, C.c_int,
+                                         fp, fp, fp, ip, C.POINTER(C.c_double), C.POINTER(C.c_double)]
+    rc = lib.duhl_c_client_rounds(A.ctypes.data_as(fp), b.ctypes.data_as(fp), d, n, ld, prob["lam"], m, rounds,
+                                  alpha.ctypes.data_as(fp), v.ctypes.data_as(fp), z.ctypes.data_as(fp),
+                                  P.ctypes.data_as(ip), C.byref(obj), C.byref(gap))
+    assert rc == 0, rc
+    o = orc.Oracle(orc.LASSO, b, prob["lam"], cols=np.ascontiguousarray(A[:, :d]))
+    for _ in range(rounds):
+        o.gaps()
+        Po = o.select(m)
+        o.cd_pass(np.sort(Po).astype(np.int32))
+    total = o.gaps()
+    assert np.array_equal(np.sort(P), np.sort(Po))
+    assert np.abs(alpha - o.alpha).max() <= 1e-5 * np.abs(o.alpha).max()
+    assert np.abs(v - o.v).max() <= 1e-5 * np.abs(o.v).max()
+    assert obj.value == pytest.approx(o.objective(), rel=1e-5)
+
+    class _P:
+        pass
+    pp = _P()
+    pp.o = o
+    floor = G.lasso_gap_floor(pp)
+    G.assert_gaps_close(z, o.z, floor=floor)
+    assert gap.value == pytest.approx(total, rel=1e-4, abs=n * floor)
