@@ -184,8 +184,10 @@ duhl_status duhl_commit_swap(duhl_ctx *ctx);
  * sigma(L), an estimate of the largest eigenvalue of an L-column Gram block made from the block
  * shape and the mean correlation of a column sample taken by duhl_set_data_*: the largest L with
  * sigma(L) <= 2 (concurrent exact steps still contract), or 2*count/sigma(count) capped at count/4
- * if that is more.  Strongly correlated columns tolerate fewer concurrent steps; lower
- * max_inflight if the objective stops decreasing.
+ * if that is more.  Strongly correlated columns tolerate fewer concurrent steps -- in particular
+ * groups of near-duplicate columns that a selection by gap gathers, which the mean correlation does
+ * not show: lower max_inflight if the objective rises (duhl_run does so by itself, see
+ * adapt_inflight).
  *   DUHL_CD_ATOMIC  each step reads the live v and adds a_j*delta to it with fp32 atomics;
  *                   iterates depend on timing.
  *   DUHL_CD_ASYNC   dense data: the pass is cut into sub-passes of max_inflight coordinates;
@@ -241,6 +243,10 @@ typedef struct duhl_run_opts {
     int confirm;                /* != 0 with a sample list: when the estimate passes gap_tol, refresh
                                    all n gaps (host residency: one pass over the host link), test
                                    their sum -- the true total gap -- and go on if it fails       */
+    int adapt_inflight;         /* != 0 (concurrent modes): on every checked round read the objective;
+                                   exact steps never raise it, so if it rose the concurrent steps
+                                   collided -- alpha and v go back to the last checked round that was
+                                   fine and max_inflight is halved for the rest of the run        */
 } duhl_run_opts;
 
 typedef struct duhl_run_stats {
@@ -253,6 +259,8 @@ typedef struct duhl_run_stats {
     int64_t columns_swapped;    /* columns copied into slots, summed over the checked rounds     */
     int64_t host_sampled;       /* gap-memory entries refreshed by host threads                  */
     double seconds;             /* wall time of the call                                         */
+    int inflight_halvings;      /* times adapt_inflight went back and halved the bound           */
+    int inflight_last;          /* max_inflight in force at the end (0: the library's own bound) */
 } duhl_run_stats;
 
 duhl_status duhl_run(duhl_ctx *ctx, const duhl_run_opts *opts, duhl_run_stats *stats);

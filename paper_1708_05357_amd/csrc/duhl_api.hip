@@ -632,6 +632,7 @@ void duhl_destroy(duhl_ctx *c)
     (void)hipFree(c->blk_gt); (void)hipFree(c->blk_eq); (void)hipFree(c->mark);
     (void)hipFree(c->dv); (void)hipFree(c->dirty); (void)hipFree(c->score); (void)hipFree(c->xch);
     (void)hipFree(c->cd_plan);
+    (void)hipFree(c->snap_alpha); (void)hipFree(c->snap_v);
     if (c->h_scalars) (void)hipHostFree(c->h_scalars);
     if (c->h_u32) (void)hipHostFree(c->h_u32);
     delete c;

@@ -247,6 +247,7 @@ struct duhl_ctx {
     int32_t *dirty;
     uint32_t sel_bar;           // value the selection kernel's barrier counter has before its next launch
     uint64_t *xch;              // exchange slots of workers that span several compute units
+    float *snap_alpha, *snap_v; // duhl_run's last good iterate (allocated on first use)
     void *cd_plan;              // sparse sub-passes: one record per position of the visiting order
     int64_t cd_plan_cap;
     uint32_t xseq;              // next free sequence number for those slots
@@ -300,6 +301,7 @@ hipError_t launch_copy_columns(duhl_ctx *c);
 hipError_t launch_publish(duhl_ctx *c);
 hipError_t launch_cd(duhl_ctx *c, duhl_cd_mode mode, const int32_t *order, int64_t count,
                      uint64_t seed, int max_inflight);
+int64_t default_inflight(const duhl_ctx *c, int64_t count);
 hipError_t launch_objective(duhl_ctx *c);
 hipError_t launch_init_v(duhl_ctx *c);
 hipError_t launch_accumulate_v(duhl_ctx *c);

@@ -29,6 +29,22 @@ duhl_status refresh_all(duhl_ctx *c, double *total)
     return DUHL_OK;
 }
 
+// Keep (restore == false) or bring back (restore == true) the iterate: alpha and v, on the compute stream.
+duhl_status snapshot(duhl_ctx *c, bool restore)
+{
+    hipError_t e = hipSuccess;
+    if (!c->snap_alpha) e = hipMalloc(reinterpret_cast<void **>(&c->snap_alpha), sizeof(float) * (size_t)c->n);
+    if (e == hipSuccess && !c->snap_v) e = hipMalloc(reinterpret_cast<void **>(&c->snap_v), sizeof(float) * (size_t)c->d);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(restore ? c->alpha : c->snap_alpha, restore ? c->snap_alpha : c->alpha,
+                           sizeof(float) * (size_t)c->n, hipMemcpyDeviceToDevice, c->compute);
+    if (e == hipSuccess)
+        e = hipMemcpyAsync(restore ? c->v : c->snap_v, restore ? c->snap_v : c->v, sizeof(float) * (size_t)c->d,
+                           hipMemcpyDeviceToDevice, c->compute);
+    if (e != hipSuccess) return set_error(c, e == hipErrorOutOfMemory ? DUHL_ENOMEM : DUHL_EHIP, hipGetErrorString(e));
+    return DUHL_OK;
+}
+
 // Entries [start, start + len) of a list of `total` entries, wrapping at the end: at most two runs.
 template <typename F>
 duhl_status for_window(int64_t total, int64_t start, int64_t len, F &&f)
@@ -66,7 +82,32 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
     duhl_status st = DUHL_OK;
     int64_t cursor = 0;                                     // where the next sample window starts
     int64_t swept = 0;                                      // list entries refreshed since the last full refresh
+    int inflight = o->max_inflight;                         // 0: the library's own bound
+    double good_objective = 0.0;
+    bool have_good = false;
     for (int64_t rnd = 0; rnd < o->max_rounds; ++rnd) {
+        // -- guard of the concurrent passes ----------------------------------------------------
+        // Exact coordinate steps never raise the objective; steps taken concurrently can, when the
+        // columns worked on at once are more alike than the bound on their number assumed (e.g. a
+        // selection that gathers near-duplicate columns).  So the objective is looked at on every
+        // checked round: if it rose, the iterate goes back to the last good one and the bound is halved.
+        if (o->adapt_inflight && o->mode != DUHL_CD_SEQUENTIAL && rnd % check_every == 0) {
+            double obj = 0.0;
+            st = duhl_objective(c, &obj);
+            if (st != DUHL_OK) return st;
+            const bool fine = !have_good || (std::isfinite(obj) && obj <= good_objective + 1e-6 * std::fabs(good_objective) + 1e-30);
+            if (fine) {
+                st = snapshot(c, false);
+                good_objective = obj;
+                have_good = true;
+            } else {
+                st = snapshot(c, true);
+                const int64_t now = inflight > 0 ? inflight : duhl::default_inflight(c, o->m);
+                inflight = (int)(now / 2 > 1 ? now / 2 : 1);
+                s.inflight_halvings++;
+            }
+            if (st != DUHL_OK) return st;
+        }
         // -- refresh the gap memory (Section 4.1) --------------------------------------------
         if (!host && !sampled) {
             st = duhl_gap(c, nullptr, 0, nullptr);          // every coordinate: eq. (11) exactly
@@ -138,7 +179,7 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
             if (st != DUHL_OK) return st;
         }
         for (int k = 0; k < o->passes && st == DUHL_OK; ++k)
-            st = duhl_cd_epoch(c, o->mode, nullptr, 0, o->seed + (uint64_t)(rnd * o->passes + k), o->max_inflight);
+            st = duhl_cd_epoch(c, o->mode, nullptr, 0, o->seed + (uint64_t)(rnd * o->passes + k), inflight);
         if (threads) {
             // "while B not finished": the threads sample until the passes and the copies are done
             if (st == DUHL_OK && hipStreamSynchronize(c->compute) != hipSuccess) st = DUHL_EHIP;
@@ -164,6 +205,7 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
         s.passes += o->passes;
     }
     if (hipStreamSynchronize(c->compute) != hipSuccess) return set_error(c, DUHL_EHIP, "stream synchronisation failed");
+    s.inflight_last = inflight;
     s.seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
     *out = s;
     return DUHL_OK;

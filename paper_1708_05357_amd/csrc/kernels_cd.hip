@@ -1037,6 +1037,9 @@ hipError_t launch_cd_model(duhl_ctx *c, duhl_cd_mode mode, const CdArgs &a, int 
 
 }  // namespace
 
+// The library's own bound on concurrent steps for a pass over `count` coordinates.
+int64_t default_inflight(const duhl_ctx *c, int64_t count) { return inflight_limit(c, count, 0); }
+
 hipError_t launch_cd(duhl_ctx *c, duhl_cd_mode mode, const int32_t *order, int64_t count,
                      uint64_t seed, int max_inflight)
 {

@@ -85,6 +85,25 @@ def lasso_dense(d, n, support_frac, c_lambda, seed=0, device="cpu", out=None, bl
             "alpha_star": alpha_star}
 
 
+def lasso_clustered(d, n, clusters, spread, support_frac=0.05, c_lambda=0.1, seed=0, noise=0.01):
+    """Dense Lasso instance whose columns come in `clusters` groups of near-duplicates: column j is
+    the centre of group j mod clusters plus `spread` times N(0,1) noise, scaled to unit norm (cosine
+    within a group about 1/(1+spread^2), between groups about 0).  Features of real datasets are
+    often this alike; a working set chosen by gap then gathers whole groups.  alpha*, b and lambda
+    as in lasso_dense.  CPU tensors."""
+    g = _gen(seed, "cpu")
+    centres = torch.randn((clusters, d), generator=g, dtype=torch.float32)
+    cols = centres[torch.arange(n) % clusters] + spread * torch.randn((n, d), generator=g, dtype=torch.float32)
+    cols /= cols.norm(dim=1, keepdim=True)
+    k = int(math.floor(support_frac * n))
+    alpha_star = torch.zeros(n, dtype=torch.float32)
+    alpha_star[torch.randperm(n, generator=g)[:k]] = torch.randn(k, generator=g, dtype=torch.float32)
+    b = cols.t() @ alpha_star + noise * torch.randn(d, generator=g, dtype=torch.float32)
+    lam = c_lambda * float((cols @ b).abs().max()) / d
+    return {"model": "lasso", "d": d, "n": n, "cols": cols.contiguous(), "target": b, "lam": lam,
+            "alpha_star": alpha_star}
+
+
 def orthonormal_lasso(d, n, seed=0):
     """Lasso instance whose columns are exactly orthonormal (n <= d); used for closed forms."""
     g = _gen(seed, "cpu")

@@ -193,3 +193,35 @@ def test_host_resident_svm_and_elastic_net_rounds(G, threads):
         np.testing.assert_allclose(z[res], p.o.z[res], rtol=1e-4, atol=1e-4 * p.o.z.max() + 1e-9)
         ref.close()
         p.close()
+
+
+@pytest.mark.parametrize("clusters,spread", [(50, 0.3), (10, 0.3)])
+def test_guard_of_concurrent_passes_on_near_duplicate_columns(G, clusters, spread):
+    """Columns in groups of near-duplicates, and a selection by gap that gathers whole groups: more
+    alike than the library's bound on concurrent steps assumes from the mean correlation, so the
+    concurrent passes overshoot.  duhl_run's guard (adapt_inflight) notices the objective rising --
+    exact steps never raise it (App. D) --, returns to the last good iterate and halves the bound
+    until the passes descend again; the run then reaches the oracle's objective."""
+    from paper_1708_05357_amd import duhl, synth
+    prob = synth.lasso_clustered(3000, 2000, clusters, spread, seed=1)
+    m = 200
+    p = G.Pair(prob)
+    start = p.g.objective()
+    st = p.g.run(m, 150, passes=1, mode=duhl.CD_ASYNC, seed=3, adapt_inflight=True)
+    assert st["rounds"] == 150
+    assert st["inflight_halvings"] >= 1 and st["inflight_last"] >= 1
+    og = p.g.objective()
+    assert np.isfinite(og) and og < start
+    a, v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+    p.o.set_state(a.astype(np.float64))                     # v = A alpha - b still holds (App. D)
+    assert np.abs(v - p.o.v).max() <= 1e-4 * np.abs(G.to_np(prob["target"])).max()
+    ref = G.Pair(prob)
+    rng = np.random.default_rng(0)
+    for _ in range(150):
+        ref.o.round(m, passes=1, rng=rng)
+    oo = ref.o.objective()
+    print(f"clusters {clusters}: halvings {st['inflight_halvings']} in flight at the end {st['inflight_last']} "
+          f"objective gpu {og:.9e} oracle {oo:.9e}")
+    assert abs(og - oo) <= 1e-5 * abs(oo)
+    ref.close()
+    p.close()
