@@ -225,3 +225,30 @@ def test_guard_of_concurrent_passes_on_near_duplicate_columns(G, clusters, sprea
     assert abs(og - oo) <= 1e-5 * abs(oo)
     ref.close()
     p.close()
+
+
+@pytest.mark.parametrize("model,rep", [("lasso", 40), ("svm", 40), ("svm", 8)])
+def test_guard_on_exact_duplicates(G, model, rep):
+    """Every column `rep` times over (duplicated samples are common in real data; for the Lasso the
+    minimiser is then not unique, the objective is): duplicates have equal gaps, are selected
+    together and collide when solved at once.  With the guard the rounds reach the oracle's
+    objective (1e-5)."""
+    from paper_1708_05357_amd import duhl, synth
+    base_n = 2000 // rep
+    prob = dict(synth.lasso_dense(3000, base_n, 0.1, 0.1, seed=4) if model == "lasso"
+                else synth.svm_dense(base_n, 3000, seed=4))
+    prob["cols"] = prob["cols"].repeat_interleave(rep, dim=0).contiguous()
+    prob["n"] = base_n * rep
+    if model == "svm":
+        prob["target"] = prob["target"].repeat_interleave(rep)
+        prob["lam"] = 1.0 / prob["n"]
+    m = prob["n"] // 5
+    p = G.Pair(prob)
+    st = p.g.run(m, 120, passes=1, mode=duhl.CD_ASYNC, seed=3, adapt_inflight=True)
+    rng = np.random.default_rng(0)
+    for _ in range(120):
+        p.o.round(m, passes=1, rng=rng)
+    og, oo = p.g.objective(), p.o.objective()
+    print(f"{model} x{rep}: halvings {st['inflight_halvings']} objective gpu {og:.9e} oracle {oo:.9e}")
+    assert abs(og - oo) <= 1e-5 * abs(oo)
+    p.close()
