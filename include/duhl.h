@@ -87,7 +87,9 @@ duhl_status duhl_set_eta(duhl_ctx *ctx, double eta);
  * device can read for DUHL_RESIDENT_HOST; borrowed.  target (device, borrowed): b of length d
  * for the Lasso and the elastic net, labels y in {+1,-1} of length n for the SVM.  lambda: the lambda of the
  * objectives above, finite and > 0.  Resets alpha = 0, v = -b (Lasso) or 0 (SVM), computes the
- * column norms and a first full gap pass into z (one read of A).  Waits for completion. */
+ * column norms and a first full gap pass into z (one read of A).  Waits for completion.
+ * DUHL_EINVAL for a NaN or an infinity in the target vector or the matrix, labels other than +-1,
+ * a lambda that is not finite and positive; the context then holds no data. */
 duhl_status duhl_set_data_dense(duhl_ctx *ctx, const float *A, int64_t ld, duhl_residency res,
                                 const float *target, double lambda);
 

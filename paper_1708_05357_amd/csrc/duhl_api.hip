@@ -135,6 +135,14 @@ duhl_status finish_set_data(duhl_ctx *c, const float *target, double lambda)
     c->have_data = true;
     // column norms and a first full gap pass in one read of the matrix
     HIPCHK(c, launch_gap(c, nullptr, c->n, false, true));
+    // a NaN or an infinity anywhere in the matrix shows in its column's norm
+    HIPCHK(c, launch_check_norms(c));
+    HIPCHK(c, hipMemcpyAsync(c->h_u32, &c->sel->error, sizeof(uint32_t), hipMemcpyDeviceToHost, c->compute));
+    HIPCHK(c, hipStreamSynchronize(c->compute));
+    if (c->h_u32[0] & 16u) {
+        c->have_data = false;
+        return fail(c, DUHL_EINVAL, "the matrix holds a non-finite value (a column norm is not finite)");
+    }
     // how strongly the columns share a direction, from up to 1024 evenly spaced columns; it sets
     // the default bound on concurrent coordinate steps
     c->mean_corr = 0.0;

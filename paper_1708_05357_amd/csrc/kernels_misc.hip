@@ -148,6 +148,14 @@ __global__ void validate_kernel(int model, int64_t d, int64_t n, const float *ta
     if (f) atomicOr(flags, f);
 }
 
+// Bit 16 of *flags: a column norm that is not finite, i.e. a NaN or an infinity (or an overflow of
+// the sum of squares) somewhere in that column of the matrix.
+__global__ void check_norms_kernel(const float *q, int64_t n, uint32_t *flags)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n && !isfinite(q[i])) atomicOr(flags, 16u);
+}
+
 __global__ void fill_i32_kernel(int32_t *p, int64_t n, int32_t value)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -239,6 +247,13 @@ hipError_t launch_validate(duhl_ctx *c)
     const int64_t len = c->d > c->n ? c->d : c->n;
     hipLaunchKernelGGL(validate_kernel, dim3((len + 255) / 256), dim3(256), 0, c->compute, (int)c->model,
                        c->d, c->n, c->target, c->cv.rowptr, c->cv.colidx, &c->sel->error);
+    return hipGetLastError();
+}
+
+hipError_t launch_check_norms(duhl_ctx *c)
+{
+    hipLaunchKernelGGL(check_norms_kernel, dim3((c->n + 255) / 256), dim3(256), 0, c->compute, c->q, c->n,
+                       &c->sel->error);
     return hipGetLastError();
 }
 

@@ -654,6 +654,15 @@ def test_error_paths(G):
     with pytest.raises(duhl.DuhlError) as e:
         g.set_data_dense(cols, torch.full((8,), float("nan"), device=dev), 0.1)
     assert e.value.status == duhl.EINVAL
+    for bad in (float("nan"), float("inf")):                      # a non-finite entry of the matrix
+        spoiled = cols.clone()
+        spoiled[4, 3] = bad
+        with pytest.raises(duhl.DuhlError) as e:
+            g.set_data_dense(spoiled, b, 0.1)
+        assert e.value.status == duhl.EINVAL
+        with pytest.raises(duhl.DuhlError) as e:
+            g.gap()
+        assert e.value.status == duhl.ESTATE
     g.set_data_dense(cols, b, 0.1)
     with pytest.raises(duhl.DuhlError) as e:
         g.cd_epoch()
