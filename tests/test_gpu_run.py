@@ -252,3 +252,37 @@ def test_guard_on_exact_duplicates(G, model, rep):
     print(f"{model} x{rep}: halvings {st['inflight_halvings']} objective gpu {og:.9e} oracle {oo:.9e}")
     assert abs(og - oo) <= 1e-5 * abs(oo)
     p.close()
+
+
+def test_guard_on_duplicated_sparse_rows(G):
+    """The same for CSR data, whose concurrent passes add to v with atomics: every sample 16 times
+    over.  The guard brings the rounds to the oracle's objective."""
+    from paper_1708_05357_amd import duhl, synth
+    rep = 16
+    base = synth.svm_csr(400, 3000, 0.02, seed=9)
+    rowptr, colidx, val = (base[k].numpy() for k in ("rowptr", "colidx", "val"))
+    lens = np.repeat(np.diff(rowptr), rep)
+    new_ptr = np.concatenate([[0], np.cumsum(lens)]).astype(np.int64)
+    pieces_c, pieces_v = [], []
+    for i in range(400):
+        for _ in range(rep):
+            pieces_c.append(colidx[rowptr[i]:rowptr[i + 1]])
+            pieces_v.append(val[rowptr[i]:rowptr[i + 1]])
+    n = 400 * rep
+    prob = {"model": "svm", "n": n, "d": 3000, "rowptr": torch.from_numpy(new_ptr),
+            "colidx": torch.from_numpy(np.concatenate(pieces_c).astype(np.int32)),
+            "val": torch.from_numpy(np.concatenate(pieces_v).astype(np.float32)),
+            "target": base["target"].repeat_interleave(rep), "lam": 1.0 / n}
+    m = n // 5
+    p = G.Pair(prob)
+    st = p.g.run(m, 150, passes=1, mode=duhl.CD_ASYNC, seed=3, adapt_inflight=True)
+    rng = np.random.default_rng(0)
+    for _ in range(150):
+        p.o.round(m, passes=1, rng=rng)
+    og, oo = p.g.objective(), p.o.objective()
+    print(f"sparse x{rep}: halvings {st['inflight_halvings']} in flight {st['inflight_last']} gpu {og:.9e} oracle {oo:.9e}")
+    assert abs(og - oo) <= 1e-5 * abs(oo)
+    a, v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+    p.o.set_state(a.astype(np.float64))
+    assert np.abs(v - p.o.v).max() <= 1e-4 * max(np.abs(p.o.v).max(), 1e-30)
+    p.close()
