@@ -135,7 +135,7 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
     if ev:
         ev[3].record()
     if on_host:
-        g.compute_stream.synchronize()          # "while B not finished": the pass and the copies
+        g.compute_stream.synchronize()          # unit A samples while unit B works: the pass and the copies
         g.copy_stream.synchronize()
         done = g.host_sample_end(wait_all=False)
         sample_host["cursor"] = (cur + max(done - 2 * host_threads, 0)) % sample_host["n"]
@@ -424,7 +424,7 @@ def main():
                          "coordinates per round (stale gap memory, Section 4.1) instead of every gap")
     ap.add_argument("--host-sampler-threads", type=int, default=-1,
                     help="host residency: refresh the gap sample with this many host threads while the "
-                         "GPU runs the pass (Algorithm 2, lines 7-10); 0: the GPU evaluates the sample "
+                         "GPU runs the pass (unit A's loop of Algorithm 2); 0: the GPU evaluates the sample "
                          "over the host link instead; default 12 (a one-GPU share of the host's cores)")
     args = ap.parse_args()
     if args.gpus != 1:

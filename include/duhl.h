@@ -11,7 +11,7 @@
  *     duhl_gap       per-coordinate gaps  z_i            (eq. (4); Appendix E)
  *     duhl_select    top-m working set P, rho            (eq. (11)/(13); eq. (7))
  *     duhl_cd_epoch  one pass of exact coordinate steps   (Algorithm 3; Appendix D)
- *     column swap    host -> device copy of new columns   (Algorithm 2, "refresh memory B")
+ *     column swap    host -> device copy of new columns   (Algorithm 2, the step that refreshes B's memory)
  *     duhl_objective O(alpha)                             (Appendix C (b), (c))
  *
  * Models.  DUHL_LASSO:  O = ||A alpha - b||^2/(2d) + lambda ||alpha||_1, shared vector
@@ -151,7 +151,8 @@ typedef enum { DUHL_SELECT_GAP = 0, DUHL_SELECT_RANDOM = 1, DUHL_SELECT_BLOCK = 
 duhl_status duhl_select_rule_apply(duhl_ctx *ctx, duhl_select_rule rule, uint64_t arg, int64_t m,
                                    int32_t *P_out, int64_t *n_swapped, double *rho);
 
-/* Unit A's task in Algorithm 2 (lines 7-10: "while B not finished: sample j, z_j := gap_j(alpha_j^(t))"),
+/* Unit A's task in Algorithm 2 (for as long as unit B works on its block, A picks coordinates j and
+ * stores their gaps at the round's starting point alpha^(t) in the gap memory, z_j = gap_j(alpha_j^(t))),
  * for a dense matrix with DUHL_RESIDENT_HOST.  duhl_host_sample_begin snapshots alpha and v at the
  * current point of the compute stream and starts nthreads host threads (1..256) that evaluate the
  * coordinate gaps of idx_host[0..count) (host, int32, each in [0,n)) from the matrix in host memory,
@@ -219,7 +220,7 @@ duhl_status duhl_cd_epoch(duhl_ctx *ctx, duhl_cd_mode mode, const int32_t *order
  *   host residency:  every column held in a device slot, plus this round's window of the list --
  *                    evaluated by the GPU over the host link (sample_dev), or by host_threads host
  *                    threads from host memory while the passes run (sample_host, Algorithm 2
- *                    lines 7-10; their result enters the gap memory at the end of the round).
+ *                    unit A's loop; their result enters the gap memory at the end of the round).
  * The window is sample_per_round consecutive entries of the list (sample_len entries, each in
  * [0,n), no duplicates), advancing and wrapping from round to round.
  * Every check_every-th round (0 = 1) the sum of the gap memory as the selection saw it is read

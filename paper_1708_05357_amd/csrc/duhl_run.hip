@@ -181,7 +181,7 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
         for (int k = 0; k < o->passes && st == DUHL_OK; ++k)
             st = duhl_cd_epoch(c, o->mode, nullptr, 0, o->seed + (uint64_t)(rnd * o->passes + k), inflight);
         if (threads) {
-            // "while B not finished": the threads sample until the passes and the copies are done
+            // unit A samples for as long as unit B works (Algorithm 2): until the passes and the copies are done
             if (st == DUHL_OK && hipStreamSynchronize(c->compute) != hipSuccess) st = DUHL_EHIP;
             if (st == DUHL_OK && hipStreamSynchronize(c->copy) != hipSuccess) st = DUHL_EHIP;
             int64_t done = 0;

@@ -1,10 +1,10 @@
-// Unit A's side of Algorithm 2 (lines 7-10 of the DuHL listing): while the GPU works on the
+// Unit A's side of Algorithm 2 (its loop next to unit B's update step): while the GPU works on the
 // current block, host threads refresh entries of the gap memory z from the matrix in host memory.
 //
 // duhl_host_sample_begin snapshots alpha and v at the current point of the compute stream (the
 // iterate alpha^(t) of the listing), then starts threads that evaluate gap_j for the listed
 // coordinates straight from the pinned host matrix -- the host link stays free for the column
-// swap.  duhl_host_sample_end stops them ("while B not finished"), uploads what was refreshed and
+// swap.  duhl_host_sample_end stops them (unit A samples only while unit B works), uploads what was refreshed and
 // scatters it into z on the compute stream.  The arithmetic is single precision with eight
 // partial sums per dot product, like the device kernels; the formulas are those of Appendix E.
 #include <atomic>
@@ -263,7 +263,7 @@ extern "C" duhl_status duhl_host_sample_end(duhl_ctx *c, int wait_all, int64_t *
     duhl_host_sampler *hs = c->sampler;
     if (!hs || !hs->active) { c->err = "no host sampling round is running"; return DUHL_ESTATE; }
     HS_CHK(c, hipSetDevice(c->device));
-    if (!wait_all) hs->stop.store(1);            // "while B not finished": B is done, stop sampling
+    if (!wait_all) hs->stop.store(1);            // unit B is done: stop sampling
     {
         std::unique_lock<std::mutex> lk(hs->mu);
         hs->cv_done.wait(lk, [&] { return hs->finished == (int)hs->threads.size(); });

@@ -7,7 +7,7 @@
 // design goal is few launches: one kernel of at most 128 small workgroups, all resident at once,
 // which meet at five device-wide barriers; serial steps are repeated by every workgroup.
 // The second half plans the column swap for host residency: which selected columns are not in
-// a device slot yet and which slots may be overwritten (Algorithm 2, "refresh memory B").
+// a device slot yet and which slots may be overwritten (Algorithm 2, the step that refreshes B's memory).
 #include "duhl_internal.h"
 
 namespace duhl {

@@ -922,7 +922,7 @@ def test_block_and_random_selection_rules(G):
 # ------------------------------------------------------------------------------------ unit A's gap sampler
 @pytest.mark.parametrize("chunk_cols", [None, 170])
 def test_host_gap_sampler_matches_oracle(G, chunk_cols):
-    """Alg. 2, lines 7-10: host threads refresh z_j := gap_j(alpha^(t)) from the host matrix while
+    """Alg. 2, unit A's loop: host threads refresh z_j := gap_j(alpha^(t)) from the host matrix while
     the GPU runs the pass on the current block.  The refreshed entries must equal the oracle's gaps
     at the snapshot alpha^(t) (not at the state after the pass); other entries stay untouched."""
     from paper_1708_05357_amd import duhl

@@ -190,7 +190,7 @@ def test_svm_cd_reaches_bruteforce_optimum(seed):
 # ----------------------------------------------------------------------------- single steps
 @pytest.mark.parametrize("model", [LASSO, SVM])
 def test_each_step_is_the_one_dimensional_argmin(model):
-    """Alg. 3, line 4: the step minimises O over that coordinate alone.  Checked with scipy's
+    """Alg. 3, the update of the chosen coordinate: the step minimises O over that coordinate alone.  Checked with scipy's
     scalar minimiser on an objective evaluated from A and alpha directly."""
     if model == LASSO:
         cols, tgt, A, lam = tiny_lasso(7, d=9, n=5)
