@@ -565,7 +565,7 @@ def main():
         "gen_s": prob["gen_s"],
     }
     if host:
-        # column swap (Algorithm 2, "refresh memory B"): copies start after the selection and run
+        # column swap (Algorithm 2, the step that refreshes the memory of unit B): copies start after the selection and run
         # on the side stream; how much of them the concurrent pass hides
         rows = []
         sampled = [x["host_sampled"] for x in swap_log if "host_sampled" in x]
