@@ -126,6 +126,32 @@ duhl_status duhl_set_data_csr(duhl_ctx *ctx, const int64_t *rowptr, const int32_
  * written, the total gap when all were asked for; non-NULL makes the call wait. */
 duhl_status duhl_gap(duhl_ctx *ctx, const int32_t *idx, int64_t count, double *gap_sum);
 
+/* duhl_gap for callers that cannot allocate device memory -- code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  No context: the caller passes every input and
+ * output, and the per-workgroup partial sums of the pass (the only memory duhl_gap needs beyond
+ * them) live in a static device array of DUHL_GAP_STATIC_MAX_GROUPS doubles (512 KB) that every GPU
+ * the library runs on holds until the process ends.  The call allocates and frees nothing, waits
+ * for nothing, and only enqueues kernels on `stream` (hipStream_t, NULL = the default stream).
+ * Dense matrix in device memory only: A, ld, v (d floats), alpha (n floats), target (the labels y,
+ * n floats, for DUHL_SVM; unused otherwise), idx / count as for duhl_gap (idx == NULL: all n).
+ * lambda, eta (DUHL_ELASTIC_NET) as for duhl_set_data_dense / duhl_set_eta; bound: the Lasso's
+ * B = ||b||^2 / (2 lambda d).  Outputs (device): z (n floats; entries not listed keep their values),
+ * gap_sum (one double, may be NULL): the sum of the entries written.  All pointers are borrowed
+ * for the duration of the enqueued work.
+ * Limit: the pass may have at most DUHL_GAP_STATIC_MAX_GROUPS workgroups; a workgroup takes 4 to 32
+ * coordinates (4 wavefronts of 1, 2, 4 or 8 columns each, by the rule duhl_create uses), so lists
+ * of up to 262,144 coordinates always fit and up to 2,097,152 may; longer ones are refused with
+ * DUHL_EINVAL.  err (host, err_len bytes, may be NULL) receives the text of an error.
+ * Every call on a GPU uses that GPU's one array: calls that overlap on the same GPU (two streams,
+ * two threads) race on it and their gap_sum is undefined; z is not affected.  The first call on a
+ * device looks up the array's address (hipGetSymbolAddress): make it outside a graph capture. */
+#define DUHL_GAP_STATIC_MAX_GROUPS 65536
+duhl_status duhl_gap_dense_static(duhl_model model, int64_t d, int64_t n, const float *A, int64_t ld,
+                                  const float *v, const float *alpha, const float *target,
+                                  double lambda, double eta, double bound, const int32_t *idx,
+                                  int64_t count, float *z, double *gap_sum, int device, void *stream,
+                                  char *err, int64_t err_len);
+
 /* Working-set selection (eq. (13)): the m coordinates with the largest z, ties to the smaller
  * index; 1 <= m <= min(n, budget_cols).  The set becomes the *pending* working set; with host
  * residency the columns it lacks are copied into free device slots on the copy stream while

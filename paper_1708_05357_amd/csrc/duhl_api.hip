@@ -107,27 +107,15 @@ duhl_status finish_set_data(duhl_ctx *c, const float *target, double lambda)
     HIPCHK(c, launch_fill_f32(c->compute, c->z, c->n, 0.0f));
     HIPCHK(c, launch_init_v(c));
 
-    ModelConst mc{};
-    mc.model = c->model;
-    const double d = (double)c->d, n = (double)c->n;
+    double bound = 0.0;
     if (c->model == DUHL_LASSO) {
         duhl_status st = read_scalars(c, S_BSQ, 1);
         if (st != DUHL_OK) return st;
-        mc.Lam = (float)(lambda * d);
-        mc.B = (float)(c->h_scalars[S_BSQ] / (2.0 * lambda * d));   // Appendix E: ||b||^2/(2 lambda d)
-        mc.inv_d = (float)(1.0 / d);
+        bound = c->h_scalars[S_BSQ] / (2.0 * lambda * (double)c->d);   // Appendix E: ||b||^2/(2 lambda d)
     } else if (c->model == DUHL_ELASTIC_NET) {
         c->eta_active = c->eta;
-        mc.Lam = (float)(lambda * d);
-        mc.lam_eta = (float)(lambda * d * c->eta);
-        mc.lam_l1 = (float)(lambda * d * (1.0 - c->eta));
-        mc.inv_2lam_eta = (float)(1.0 / (2.0 * lambda * d * c->eta));
-        mc.inv_d = (float)(1.0 / d);
-    } else {
-        mc.lam_n = (float)(lambda * n);
-        mc.inv_lam_n = (float)(1.0 / (lambda * n));
-        mc.inv_n = (float)(1.0 / n);
     }
+    const ModelConst mc = model_constants(c->model, c->d, c->n, lambda, c->eta, bound);
     c->mc = mc;
     c->m_cur = c->m_next = 0;
     c->pending = c->swap_exclusive = false;
@@ -253,10 +241,7 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->copy = reinterpret_cast<hipStream_t>(copy_stream);
     c->num_cu = 256;
     (void)hipDeviceGetAttribute(&c->num_cu, hipDeviceAttributeMultiprocessorCount, device);
-    // columns per wavefront of the dense gap pass: several amortise the reads of v, but a problem
-    // of few columns needs one wavefront per column to put enough of them on every compute unit
-    int gap_cols = d < 4096 ? 8 : 4;
-    while (gap_cols > 1 && n / gap_cols < 8 * (int64_t)c->num_cu) gap_cols /= 2;
+    const int gap_cols = default_gap_cols(d, n, c->num_cu);
     c->gap_cols = env_int("DUHL_GAP_COLS", gap_cols);
     if (c->gap_cols != 1 && c->gap_cols != 2 && c->gap_cols != 4 && c->gap_cols != 8) c->gap_cols = gap_cols;
     c->cd_threads = env_int("DUHL_CD_THREADS", 0);

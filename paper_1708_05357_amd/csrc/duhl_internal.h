@@ -58,6 +58,40 @@ struct ModelConst {
     float inv_2lam_eta;  // elastic net: 1 / (2 lambda d eta)
 };
 
+// The constants from the problem's sizes and parameters; B is the Lipschitzing bound of the Lasso
+// (Appendix E: ||b||^2 / (2 lambda d)), eta the elastic-net mix.
+inline ModelConst model_constants(int model, int64_t d_, int64_t n_, double lambda, double eta, double B)
+{
+    ModelConst mc{};
+    mc.model = model;
+    const double d = (double)d_, n = (double)n_;
+    if (model == DUHL_LASSO) {
+        mc.Lam = (float)(lambda * d);
+        mc.B = (float)B;
+        mc.inv_d = (float)(1.0 / d);
+    } else if (model == DUHL_ELASTIC_NET) {
+        mc.Lam = (float)(lambda * d);
+        mc.lam_eta = (float)(lambda * d * eta);
+        mc.lam_l1 = (float)(lambda * d * (1.0 - eta));
+        mc.inv_2lam_eta = (float)(1.0 / (2.0 * lambda * d * eta));
+        mc.inv_d = (float)(1.0 / d);
+    } else {
+        mc.lam_n = (float)(lambda * n);
+        mc.inv_lam_n = (float)(1.0 / (lambda * n));
+        mc.inv_n = (float)(1.0 / n);
+    }
+    return mc;
+}
+
+// Columns per wavefront of the dense gap pass: several amortise the reads of v, but a problem of
+// few columns needs one wavefront per column to put enough of them on every compute unit.
+inline int default_gap_cols(int64_t d, int64_t n, int num_cu)
+{
+    int cols = d < 4096 ? 8 : 4;
+    while (cols > 1 && n / cols < 8 * (int64_t)num_cu) cols /= 2;
+    return cols;
+}
+
 // Coordinate gap from c = a_i^T v (Appendix E), clamped at 0 (Section 2: the gap is non-negative).
 template <int MODEL>
 __device__ __forceinline__ float gap_value(const ModelConst &mc, float c, float alpha, float y)

@@ -8,6 +8,10 @@
 // groups: the hardware dispatcher balances the tail.
 // Sparse: one group of G lanes per CSR row (rows of the paper's workloads have ~100 non-zeros,
 // far fewer than a wavefront would need), gathers of v served by L2.
+#include <cmath>
+#include <cstdio>
+#include <mutex>
+
 #include "duhl_internal.h"
 
 namespace duhl {
@@ -210,31 +214,40 @@ hipError_t launch_sum_partials(duhl_ctx *c, int64_t count, int scalar_slot)
 
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
 
-template <int MODEL, bool NORMS>
-static hipError_t launch_gap_model(duhl_ctx *c, const GapArgs &a, int64_t *grid_out)
+// What a launch of the gap kernels needs to know beyond GapArgs.
+struct GapLaunch {
+    bool sparse;
+    int64_t avg_nnz;      // sparse: mean non-zeros per row
+    bool a_aligned16;     // dense: the matrix (every piece of it) starts on a 16-byte boundary
+    int cols;             // dense: columns per wavefront (1, 2, 4 or 8)
+    hipStream_t stream;
+};
+
+// Workgroups the launch of the gap kernels has for `count` list entries (= partial sums written).
+static int64_t gap_grid(const GapLaunch &L, int64_t count)
 {
-    int64_t grid;
-    if (c->sparse) {
-        const int64_t avg = c->n > 0 ? c->nnz / c->n : 0;
-        if (avg > 256) {
-            grid = (a.count + 3) / 4;
-            hipLaunchKernelGGL((gap_csr_kernel<MODEL, 64, NORMS>), dim3(grid), dim3(256), 0,
-                               c->compute, a);
-        } else {
-            grid = (a.count + 15) / 16;
-            hipLaunchKernelGGL((gap_csr_kernel<MODEL, 16, NORMS>), dim3(grid), dim3(256), 0,
-                               c->compute, a);
-        }
+    if (L.sparse) return L.avg_nnz > 256 ? (count + 3) / 4 : (count + 15) / 16;
+    const int64_t groups = (count + L.cols - 1) / L.cols;
+    return (groups + 3) / 4;
+}
+
+template <int MODEL, bool NORMS>
+static hipError_t launch_gap_model(const GapLaunch &L, const GapArgs &a, int64_t *grid_out)
+{
+    const int64_t grid = gap_grid(L, a.count);
+    if (L.sparse) {
+        if (L.avg_nnz > 256)
+            hipLaunchKernelGGL((gap_csr_kernel<MODEL, 64, NORMS>), dim3(grid), dim3(256), 0, L.stream, a);
+        else
+            hipLaunchKernelGGL((gap_csr_kernel<MODEL, 16, NORMS>), dim3(grid), dim3(256), 0, L.stream, a);
     } else {
-        const bool vec = c->a_aligned16 && (a.cv.ld % 4 == 0) && aligned16(a.v) &&
+        const bool vec = L.a_aligned16 && (a.cv.ld % 4 == 0) && aligned16(a.v) &&
                          (!a.cv.col_slot || (aligned16(a.cv.slots) && a.cv.ld_s % 4 == 0));
         // Short columns: more columns per wavefront to keep enough bytes in flight.
-        const int cols = c->gap_cols;
-        const int64_t groups = (a.count + cols - 1) / cols;
-        grid = (groups + 3) / 4;
+        const int cols = L.cols;
 #define DUHL_GAP_LAUNCH(COLS, VEC)                                                              \
     hipLaunchKernelGGL((gap_dense_kernel<MODEL, COLS, VEC, NORMS>), dim3(grid), dim3(256), 0, \
-                       c->compute, a)
+                       L.stream, a)
         if (vec) {
             if (cols == 8) DUHL_GAP_LAUNCH(8, true);
             else if (cols == 4) DUHL_GAP_LAUNCH(4, true);
@@ -250,6 +263,18 @@ static hipError_t launch_gap_model(duhl_ctx *c, const GapArgs &a, int64_t *grid_
     }
     *grid_out = grid;
     return hipGetLastError();
+}
+
+static hipError_t launch_gap_any(const GapLaunch &L, const GapArgs &a, bool with_norms, int64_t *grid)
+{
+    if (a.mc.model == DUHL_LASSO)
+        return with_norms ? launch_gap_model<DUHL_LASSO, true>(L, a, grid)
+                          : launch_gap_model<DUHL_LASSO, false>(L, a, grid);
+    if (a.mc.model == DUHL_ELASTIC_NET)
+        return with_norms ? launch_gap_model<DUHL_ELASTIC_NET, true>(L, a, grid)
+                          : launch_gap_model<DUHL_ELASTIC_NET, false>(L, a, grid);
+    return with_norms ? launch_gap_model<DUHL_SVM, true>(L, a, grid)
+                      : launch_gap_model<DUHL_SVM, false>(L, a, grid);
 }
 
 hipError_t launch_gap(duhl_ctx *c, const int32_t *idx, int64_t count, bool slot_list,
@@ -285,17 +310,120 @@ hipError_t launch_gap(duhl_ctx *c, const int32_t *idx, int64_t count, bool slot_
         if (e != hipSuccess) return e;
         return launch_sum_partials(c, grid, S_GAP_SUM);
     }
-    if (c->model == DUHL_LASSO)
-        e = with_norms ? launch_gap_model<DUHL_LASSO, true>(c, a, &grid)
-                       : launch_gap_model<DUHL_LASSO, false>(c, a, &grid);
-    else if (c->model == DUHL_ELASTIC_NET)
-        e = with_norms ? launch_gap_model<DUHL_ELASTIC_NET, true>(c, a, &grid)
-                       : launch_gap_model<DUHL_ELASTIC_NET, false>(c, a, &grid);
-    else
-        e = with_norms ? launch_gap_model<DUHL_SVM, true>(c, a, &grid)
-                       : launch_gap_model<DUHL_SVM, false>(c, a, &grid);
+    GapLaunch L;
+    L.sparse = c->sparse;
+    L.avg_nnz = c->n > 0 ? c->nnz / c->n : 0;
+    L.a_aligned16 = c->a_aligned16;
+    L.cols = c->gap_cols;
+    L.stream = c->compute;
+    e = launch_gap_any(L, a, with_norms, &grid);
     if (e != hipSuccess) return e;
     return launch_sum_partials(c, grid, S_GAP_SUM);
 }
 
+// ---- the gap pass for callers that cannot allocate ------------------------------------------------
+// The per-workgroup partial sums of duhl_gap_dense_static live in this array instead of a buffer
+// from hipMalloc.  Every device the library runs on holds its own copy until the process ends.  The
+// name below is only a host-side handle: the device address is asked for once per device
+// (static_partials) and that pointer is what the kernels receive.
+constexpr int64_t kStaticGroups = DUHL_GAP_STATIC_MAX_GROUPS;
+static __device__ __align__(256) double scratch[kStaticGroups];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_static_mu;
+static double *g_static_ptr[kMaxDevices];
+
+// Device address of `scratch` on `device` (which must be current); nullptr and *e set on failure.
+static double *static_partials(int device, hipError_t *e)
+{
+    std::lock_guard<std::mutex> lk(g_static_mu);
+    if (!g_static_ptr[device]) {
+        double *ptr = nullptr;
+        *e = hipGetSymbolAddress(reinterpret_cast<void **>(&ptr), HIP_SYMBOL(scratch));
+        if (*e != hipSuccess) return nullptr;
+        g_static_ptr[device] = ptr;
+    }
+    return g_static_ptr[device];
+}
+
 }  // namespace duhl
+
+using namespace duhl;
+
+static duhl_status static_fail(char *err, int64_t err_len, duhl_status st, const char *fmt, long long a = 0,
+                               long long b = 0)
+{
+    if (err && err_len > 0) snprintf(err, (size_t)err_len, fmt, a, b);
+    return st;
+}
+
+extern "C" duhl_status duhl_gap_dense_static(duhl_model model, int64_t d, int64_t n, const float *A,
+                                             int64_t ld, const float *v, const float *alpha,
+                                             const float *target, double lambda, double eta, double bound,
+                                             const int32_t *idx, int64_t count, float *z, double *gap_sum,
+                                             int device, void *stream, char *err, int64_t err_len)
+{
+    if (model != DUHL_LASSO && model != DUHL_SVM && model != DUHL_ELASTIC_NET)
+        return static_fail(err, err_len, DUHL_EINVAL, "unknown model");
+    if (d <= 0 || n <= 0 || n > 0x7fffffffll || d >= (1ll << 29))
+        return static_fail(err, err_len, DUHL_EINVAL, "need 1 <= d < 2^29 and 1 <= n < 2^31");
+    if (!A || !v || !alpha || !z) return static_fail(err, err_len, DUHL_EINVAL, "A, v, alpha or z is NULL");
+    if (model == DUHL_SVM && !target) return static_fail(err, err_len, DUHL_EINVAL, "the SVM needs its labels");
+    if (ld < d) return static_fail(err, err_len, DUHL_EINVAL, "ld (%lld) < d (%lld)", ld, d);
+    if (!(lambda > 0.0) || !std::isfinite(lambda))
+        return static_fail(err, err_len, DUHL_EINVAL, "lambda must be finite and > 0");
+    if (model == DUHL_ELASTIC_NET && (!(eta > 0.0) || !(eta <= 1.0)))
+        return static_fail(err, err_len, DUHL_EINVAL, "eta must be in (0, 1]");
+    if (model == DUHL_LASSO && (!(bound >= 0.0) || !std::isfinite(bound)))
+        return static_fail(err, err_len, DUHL_EINVAL, "the Lasso needs its bound B = ||b||^2/(2 lambda d) >= 0");
+    if (idx ? (count < 0 || count > n) : false)
+        return static_fail(err, err_len, DUHL_EINVAL, "count (%lld) must be in [0, n = %lld]", count, n);
+    if (device < 0 || device >= kMaxDevices) return static_fail(err, err_len, DUHL_EINVAL, "bad device ordinal");
+    if (hipSetDevice(device) != hipSuccess) return static_fail(err, err_len, DUHL_EHIP, "hipSetDevice failed");
+
+    const int64_t entries = idx ? count : n;
+    int num_cu = 256;
+    (void)hipDeviceGetAttribute(&num_cu, hipDeviceAttributeMultiprocessorCount, device);
+    GapLaunch L;
+    L.sparse = false;
+    L.avg_nnz = 0;
+    L.a_aligned16 = (reinterpret_cast<uintptr_t>(A) & 15) == 0;
+    L.cols = default_gap_cols(d, n, num_cu);
+    L.stream = reinterpret_cast<hipStream_t>(stream);
+    const int64_t grid = gap_grid(L, entries);
+    if (grid > kStaticGroups)
+        return static_fail(err, err_len, DUHL_EINVAL,
+                           "%lld coordinates need %lld workgroups, more than the static scratch array holds; "
+                           "use duhl_gap, or split the list",
+                           entries, grid);
+    hipError_t e = hipSuccess;
+    double *partials = static_partials(device, &e);
+    if (!partials) return static_fail(err, err_len, DUHL_EHIP, "hipGetSymbolAddress failed for the scratch array");
+
+    GapArgs a{};
+    a.cv.base = A;
+    a.cv.ld = ld;
+    a.mc = model_constants(model, d, n, lambda, eta, bound);
+    a.d = d;
+    a.n = n;
+    a.count = entries;
+    a.idx = idx;
+    a.slot_col = nullptr;
+    a.v = v;
+    a.alpha = alpha;
+    a.target = target;
+    a.z = z;
+    a.q = nullptr;
+    a.partials = partials;
+    int64_t launched = 0;
+    if (entries > 0) {
+        e = launch_gap_any(L, a, false, &launched);
+        if (e != hipSuccess) return static_fail(err, err_len, DUHL_EHIP, "a kernel launch failed (HIP error %lld)", (long long)e);
+    }
+    if (gap_sum) {
+        hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(1024), 0, L.stream, partials, launched, gap_sum);
+        e = hipGetLastError();
+        if (e != hipSuccess) return static_fail(err, err_len, DUHL_EHIP, "a kernel launch failed (HIP error %lld)", (long long)e);
+    }
+    return DUHL_OK;
+}

@@ -22,6 +22,7 @@ SELECT_GAP, SELECT_RANDOM, SELECT_BLOCK = 0, 1, 2
 OK, EINVAL, ENOMEM, EHIP, ESTATE, EBUDGET = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_data_dense", "duhl_set_data_dense_chunks", "duhl_set_data_csr", "duhl_gap", "duhl_select",
+           "duhl_gap_dense_static",
            "duhl_select_rule_apply", "duhl_host_sample_begin", "duhl_host_sample_end",
            "duhl_commit_swap", "duhl_cd_epoch", "duhl_run", "duhl_objective", "duhl_recompute_v", "duhl_get",
            "duhl_set", "duhl_device_ptr", "duhl_probe_stream_read", "duhl_selection_threshold",
@@ -89,8 +90,11 @@ def load():
     lib.duhl_destroy.restype = None
     lib.duhl_probe_stream_read.argtypes = [p, p, i64, i32, C.POINTER(dbl)]
     lib.duhl_run.argtypes = [p, C.POINTER(RunOpts), C.POINTER(RunStats)]
-    for name in EXPORTS[:21]:
-        getattr(lib, name).restype = i32
+    lib.duhl_gap_dense_static.argtypes = [i32, i64, i64, p, i64, p, p, p, dbl, dbl, dbl, p, i64, p, p, i32, p,
+                                          C.c_char_p, i64]
+    for name in EXPORTS:
+        if name not in ("duhl_working_set_size", "duhl_last_error", "duhl_destroy"):
+            getattr(lib, name).restype = i32
     _lib = lib
     return lib
 
@@ -100,6 +104,28 @@ def _dptr(t, dtype):
         return None
     assert isinstance(t, torch.Tensor) and t.dtype == dtype and t.is_contiguous(), (t.dtype, dtype)
     return C.c_void_p(t.data_ptr())
+
+
+def gap_dense_static(model, cols, v, alpha, z, lam, target=None, eta=1.0, bound=0.0, idx=None,
+                     gap_sum=None, device=0, stream=None):
+    """duhl_gap_dense_static: the gap pass without a context and without any allocation.  cols:
+    float32 (n, d) device tensor, row i = column a_i; v, alpha, z, target: float32 device tensors;
+    idx: int32 device tensor or None; gap_sum: float64 device tensor of one element or None.  Only
+    enqueues on `stream` (default: torch's current stream)."""
+    lib = load()
+    assert cols.dtype == torch.float32 and cols.dim() == 2 and cols.stride(1) == 1 and cols.is_cuda
+    n, d = cols.shape
+    if stream is None:
+        stream = torch.cuda.current_stream(device)
+    err = C.create_string_buffer(256)
+    st = lib.duhl_gap_dense_static(model, d, n, C.c_void_p(cols.data_ptr()), cols.stride(0),
+                                   _dptr(v, torch.float32), _dptr(alpha, torch.float32),
+                                   _dptr(target, torch.float32), float(lam), float(eta), float(bound),
+                                   _dptr(idx, torch.int32), 0 if idx is None else idx.numel(),
+                                   _dptr(z, torch.float32), _dptr(gap_sum, torch.float64), device,
+                                   C.c_void_p(stream.cuda_stream), err, len(err))
+    if st != OK:
+        raise DuhlError(st, err.value.decode())
 
 
 class Duhl:
