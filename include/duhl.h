@@ -71,8 +71,9 @@ typedef enum {
 
 /* Create a context for a problem with columns of length d (1 <= d < 2^29) and n coordinates
  * (1 <= n < 2^31).
- * budget_cols: the largest working set (and, for DUHL_RESIDENT_HOST, the number of device
- * column slots); 1 <= budget_cols.  device: HIP device ordinal.  compute_stream / copy_stream:
+ * budget_cols: the memory of unit B in columns (Assumption 1 of Section 3: B holds at most m of the
+ * n columns) -- the largest working set and, for DUHL_RESIDENT_HOST, the number of device
+ * column slots; 1 <= budget_cols.  device: HIP device ordinal.  compute_stream / copy_stream:
  * hipStream_t handles (NULL = the default stream); both must have the default priority. */
 duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n,
                         int64_t budget_cols, int device, void *compute_stream, void *copy_stream);
@@ -80,6 +81,15 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n,
 /* Mixing parameter eta of DUHL_ELASTIC_NET, 0 < eta <= 1 (default 1 = ridge).  Takes effect at the
  * next duhl_set_data_* call.  DUHL_EINVAL for other models or values. */
 duhl_status duhl_set_eta(duhl_ctx *ctx, double eta);
+
+/* Two kernels let workgroups wait for each other on the device: the selection (five barriers per
+ * call) and the coordinate-descent workers that span several compute units (once per coordinate).
+ * Every such wait gives up after `polls` polls (default 2^22: seconds, where the waits take
+ * microseconds); the kernels then end early, alpha, v and the working set are undefined, and the next
+ * call that returns a scalar fails with DUHL_EHIP until the data are set again
+ * (duhl_set_data_* restores a usable context).  polls in [0, 2^31); 0 makes any wait that is not
+ * satisfied at once fail, which is how the error path can be exercised from the host. */
+duhl_status duhl_set_wait_limit(duhl_ctx *ctx, int64_t polls);
 
 /* Dense data (Section 2: A in R^{d x n}, fp32 per Section 5.3).  A: column-major, column i at
  * A + i*ld, ld >= d (fastest when A is 16-byte aligned and ld is a multiple of 4: the kernels
@@ -190,8 +200,9 @@ duhl_status duhl_select_rule_apply(duhl_ctx *ctx, duhl_select_rule rule, uint64_
 duhl_status duhl_host_sample_begin(duhl_ctx *ctx, const int32_t *idx_host, int64_t count, int nthreads);
 duhl_status duhl_host_sample_end(duhl_ctx *ctx, int wait_all, int64_t *n_done);
 
-/* Make the pending working set current: the compute stream waits (on the device, not the
- * host) for the column copies, then later calls see the new set.  DUHL_ESTATE if nothing is
+/* The round boundary of Figure 2 (the point of Algorithm 2 where the refreshed memory of unit B
+ * and the result of its update step meet): make the pending working set current.  The compute
+ * stream waits (on the device, not the host) for the column copies, then later calls see the new set.  DUHL_ESTATE if nothing is
  * pending. */
 duhl_status duhl_commit_swap(duhl_ctx *ctx);
 
@@ -271,11 +282,17 @@ typedef struct duhl_run_opts {
     int host_threads;           /* 0: the GPU evaluates the window                               */
     int confirm;                /* != 0 with a sample list: when the estimate passes gap_tol, refresh
                                    all n gaps (host residency: one pass over the host link), test
-                                   their sum -- the true total gap -- and go on if it fails       */
+                                   their sum -- the true total gap -- and go on if it fails.  Host
+                                   residency without a sample list always confirms: the columns
+                                   outside the device slots are never refreshed otherwise        */
     int adapt_inflight;         /* != 0 (concurrent modes): on every checked round read the objective;
                                    exact steps never raise it, so if it rose the concurrent steps
                                    collided -- alpha and v go back to the last checked round that was
                                    fine and max_inflight is halved for the rest of the run        */
+    int host_wait_all;          /* host_threads > 0: != 0 lets the threads finish the round's whole
+                                   window before the round ends (reproducible rounds: which entries
+                                   are refreshed no longer depends on timing); 0 stops them when the
+                                   passes and copies are done, as unit A is stopped in Algorithm 2 */
 } duhl_run_opts;
 
 typedef struct duhl_run_stats {

@@ -203,3 +203,40 @@ class Oracle:
                 order = P
             self.cd_pass(order)
         return P, total
+
+    # -- outer loop with a gap memory that may be stale (Algorithm 2; Section 4.1, eq. (13)) -----
+    def round_delayed(self, m, refresh_idx, passes=1, rng=None, order_fn=None, fresh_idx=None, P=None):
+        """One round t of Algorithm 2 on the gap memory self.z, whose entries may stem from earlier
+        iterates (Section 4.1).
+
+        1. (optional, not part of the printed algorithm) entries `fresh_idx` are evaluated at the
+           round's starting point alpha^(t) BEFORE the selection -- what a unit that holds columns in
+           its own memory can do for them at no cost to the other;
+        2. P := the m largest entries of the gap memory as it stands (eq. (13));
+        3. unit B: `passes` passes of exact coordinate steps over P (visiting order as in round());
+        4. unit A, meanwhile: z_j := gap_j(alpha^(t)) for the sampled coordinates `refresh_idx` --
+           at the round's STARTING point, whatever B has done since; they are seen by the selection
+           of round t+1;
+        5. alpha^(t+1) := alpha^(t) + B's update.
+        `P` (optional) replaces step 2 by a given working set: eq. (13) has several maximisers when
+        entries of the memory tie, and a caller that checks another implementation's choice among
+        them passes that choice on.  Returns P."""
+        if fresh_idx is not None and len(fresh_idx):
+            self.gaps(fresh_idx)
+        P = self.select(m) if P is None else np.ascontiguousarray(P, dtype=np.int32)
+        alpha_t, v_t = self.alpha.copy(), self.v.copy()
+        for k in range(passes):
+            if order_fn is not None:
+                order = order_fn(P, k)
+            elif rng is not None:
+                order = P[rng.permutation(P.size)]
+            else:
+                order = P
+            self.cd_pass(order)
+        if refresh_idx is not None and len(refresh_idx):
+            alpha_next, v_next = self.alpha.copy(), self.v.copy()
+            self.alpha[:], self.v[:] = alpha_t, v_t
+            self.gaps(refresh_idx)
+            self.alpha[:], self.v[:] = alpha_next, v_next
+        return P
+

@@ -91,6 +91,10 @@ duhl_status finish_set_data(duhl_ctx *c, const float *target, double lambda)
     HIPCHK(c, launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(&c->sel->error), 2, 0));   // and cd_abort
     // the selection kernel expects clean histograms and leaves them clean, unless a barrier failed
     HIPCHK(c, launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(&c->sel->hist[0][0]), 3 * 2048, 0));
+    // a selection that gave up at a barrier (or was never launched) leaves the device's arrival
+    // counter behind the host's account of it: both start again from zero
+    HIPCHK(c, launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(&c->sel->barrier), 1, 0));
+    c->sel_bar = 0;
     HIPCHK(c, launch_validate(c));
     HIPCHK(c, hipMemcpyAsync(c->h_u32, &c->sel->error, sizeof(uint32_t), hipMemcpyDeviceToHost,
                              c->compute));
@@ -98,7 +102,7 @@ duhl_status finish_set_data(duhl_ctx *c, const float *target, double lambda)
     const uint32_t flags = c->h_u32[0];
     if (flags & 1u) return fail(c, DUHL_EINVAL, "labels must be +1 or -1");
     if (flags & 8u) return fail(c, DUHL_EINVAL, "target vector holds a non-finite value");
-    if (flags & 2u) return fail(c, DUHL_EINVAL, "rowptr must start at 0 and be non-decreasing");
+    if (flags & 2u) return fail(c, DUHL_EINVAL, "rowptr must start at 0, be non-decreasing and end at rowptr[n]");
     if (flags & 4u)
         return fail(c, DUHL_EINVAL,
                     "column indices must lie in [0,d) and increase strictly inside a row");
@@ -250,6 +254,8 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->cd_units = env_int("DUHL_CD_UNITS", 0);
     c->cd_spin_limit = env_int("DUHL_CD_SPIN_LIMIT", 1 << 22);
     if (c->cd_spin_limit < 0) c->cd_spin_limit = 0;
+    c->select_spin_limit = env_int("DUHL_SELECT_SPIN_LIMIT", 1 << 22);
+    if (c->select_spin_limit < 0) c->select_spin_limit = 0;
     c->select_groups = env_int("DUHL_SELECT_GROUPS", 0);
     c->csr_blocked = env_int("DUHL_CSR_BLOCKED", 1);
     c->csr_blocked_waves = env_int("DUHL_CSR_BLOCKED_WAVES", 2);
@@ -293,6 +299,14 @@ duhl_status duhl_set_eta(duhl_ctx *c, double eta)
     if (c->model != DUHL_ELASTIC_NET) return fail(c, DUHL_EINVAL, "eta applies to DUHL_ELASTIC_NET only");
     if (!(eta > 0.0) || !(eta <= 1.0)) return fail(c, DUHL_EINVAL, "eta must be in (0, 1]");
     c->eta = eta;
+    return DUHL_OK;
+}
+
+duhl_status duhl_set_wait_limit(duhl_ctx *c, int64_t polls)
+{
+    if (!c) return DUHL_EINVAL;
+    if (polls < 0 || polls > 0x7fffffffll) return fail(c, DUHL_EINVAL, "polls must be in [0, 2^31)");
+    c->cd_spin_limit = c->select_spin_limit = (int)polls;
     return DUHL_OK;
 }
 

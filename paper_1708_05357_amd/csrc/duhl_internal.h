@@ -308,6 +308,7 @@ struct duhl_ctx {
     int copy_blocks;   // workgroups of the column-copy kernel
     int cd_units;      // compute units per dense CD worker for long columns (0 = by d, 1 = never more than one)
     int cd_spin_limit; // polls a workgroup waits for a partner's partial sum before it gives up
+    int select_spin_limit;   // polls a workgroup of the selection kernel waits at a barrier
     int select_groups;       // most workgroups of the selection kernel (0: the kernel's own limit)
     int csr_blocked;         // build and use the blocked copy of sparse data
     int csr_blocked_waves;   // workgroups per compute unit launched by its pass
@@ -347,6 +348,7 @@ hipError_t launch_fill_i32(hipStream_t s, int32_t *p, int64_t n, int32_t value);
 hipError_t launch_fill_f32(hipStream_t s, float *p, int64_t n, float value);
 hipError_t launch_sum_partials(duhl_ctx *c, int64_t count, int scalar_slot);
 void host_sampler_destroy(duhl_ctx *c);
+int64_t host_sampler_prefix(const duhl_ctx *c);   // leading list entries the last host sampling round refreshed
 hipError_t csr_blocked_build(duhl_ctx *c);
 void csr_blocked_free(duhl_ctx *c);
 hipError_t launch_gap_csr_blocked(duhl_ctx *c, const int32_t *idx, int64_t count, int64_t *grid_out);

@@ -141,7 +141,11 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
             // listed entry has been refreshed at least once: entries still hold their values from
             // the starting point (for the Lasso most of those are exactly zero).
             bool reached = s.gap_memory_sum <= o->gap_tol && (!sampled || swept >= o->sample_len);
-            if (reached && sampled && o->confirm) {
+            // host residency without a sample list: only the columns in device slots are ever
+            // refreshed, the rest keep the values of the starting point, so the sum says nothing
+            // about them -- it is always confirmed by a full refresh before the loop ends on it
+            const bool must_confirm = sampled ? o->confirm != 0 : host;
+            if (reached && must_confirm) {
                 // make every entry fresh at the current point and test the true total gap
                 st = duhl_commit_swap(c);
                 if (st != DUHL_OK) return st;
@@ -150,7 +154,7 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
                 if (st != DUHL_OK) return st;
                 s.confirmations++;
                 s.gap_memory_sum = total;
-                swept = o->sample_len;
+                swept = sampled ? o->sample_len : 0;
                 if (total <= o->gap_tol) {
                     s.converged = 1;
                     break;
@@ -185,13 +189,12 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
             if (st == DUHL_OK && hipStreamSynchronize(c->compute) != hipSuccess) st = DUHL_EHIP;
             if (st == DUHL_OK && hipStreamSynchronize(c->copy) != hipSuccess) st = DUHL_EHIP;
             int64_t done = 0;
-            const duhl_status st2 = duhl_host_sample_end(c, 0, &done);
+            const duhl_status st2 = duhl_host_sample_end(c, o->host_wait_all ? 1 : 0, &done);
             if (st == DUHL_OK) st = st2;
-            // entries the threads had claimed when they were stopped may be missing: start the next
-            // window early enough to cover them again
-            int64_t adv = done - 2 * (int64_t)o->host_threads;
-            if (adv < 0) adv = 0;
-            if (done >= begun) adv = begun;
+            // the threads take the window's entries in order, so all but the few they were working
+            // on when stopped form a prefix: the next window starts where that prefix ends
+            int64_t adv = duhl::host_sampler_prefix(c);
+            if (adv > begun) adv = begun;
             cursor = (cursor + adv) % o->sample_len;
             swept += adv;
             s.host_sampled += done;

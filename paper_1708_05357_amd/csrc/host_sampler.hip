@@ -25,6 +25,8 @@ struct duhl_host_sampler {
     int generation = 0, finished = 0;
     bool quit = false;
     std::atomic<int> stop{0};
+    std::atomic<int64_t> next{0};   // next list entry to hand out: entries are claimed in list order
+    int64_t prefix = 0;             // after a round: leading entries of the list that were all refreshed
     hipEvent_t snap = nullptr;
     float *h_alpha = nullptr, *h_v = nullptr, *h_target = nullptr;   // pinned snapshots
     float *h_z = nullptr;                                            // pinned results, one per list entry
@@ -92,8 +94,15 @@ void sampler_thread(duhl_ctx *c, duhl_host_sampler *hs, int tid, int nthreads, i
         if (hipEventSynchronize(hs->snap) == hipSuccess) {        // snapshots are in host memory now
             const int64_t d = c->d;
             const std::vector<int32_t> &list = *hs->list;
-            for (int64_t k = tid; k < hs->count; k += nthreads) {
+            // entries are claimed one by one from a shared counter, so what is refreshed when the
+            // round is stopped early is a prefix of the list but for the (at most one per thread)
+            // entries still being worked on
+            (void)tid;
+            (void)nthreads;
+            for (;;) {
                 if (hs->stop.load(std::memory_order_relaxed)) break;
+                const int64_t k = hs->next.fetch_add(1, std::memory_order_relaxed);
+                if (k >= hs->count) break;
                 const int32_t j = list[k];
                 const float cj = host_dot(host_col(c, j), hs->h_v, d);
                 const float y = c->model == DUHL_SVM ? hs->h_target[j] : 0.0f;
@@ -141,6 +150,8 @@ void stop_pool(duhl_host_sampler *hs)
 }
 
 }  // namespace
+
+int64_t host_sampler_prefix(const duhl_ctx *c) { return c->sampler ? c->sampler->prefix : 0; }
 
 void host_sampler_destroy(duhl_ctx *c)
 {
@@ -242,6 +253,7 @@ extern "C" duhl_status duhl_host_sample_begin(duhl_ctx *c, const int32_t *idx_ho
     HS_CHK(c, hipMemcpyAsync(hs->h_v, c->v, sizeof(float) * c->d, hipMemcpyDeviceToHost, c->compute));
     HS_CHK(c, hipEventRecord(hs->snap, c->compute));
     hs->stop.store(0);
+    hs->next.store(0);
     if ((int)hs->threads.size() != nthreads) {                    // (re)build the pool
         stop_pool(hs);
         for (int t = 0; t < nthreads; ++t)
@@ -269,8 +281,10 @@ extern "C" duhl_status duhl_host_sample_end(duhl_ctx *c, int wait_all, int64_t *
         hs->cv_done.wait(lk, [&] { return hs->finished == (int)hs->threads.size(); });
     }
     hs->active = false;
-    int64_t done = 0;
+    int64_t done = 0, prefix = 0;
     for (int64_t k = 0; k < hs->count; ++k) done += hs->h_idx[k] >= 0;
+    while (prefix < hs->count && hs->h_idx[prefix] >= 0) ++prefix;
+    hs->prefix = prefix;
     if (hs->count > 0) {
         HS_CHK(c, hipMemcpyAsync(hs->d_idx, hs->h_idx, sizeof(int32_t) * hs->count, hipMemcpyHostToDevice, c->compute));
         HS_CHK(c, hipMemcpyAsync(hs->d_z, hs->h_z, sizeof(float) * hs->count, hipMemcpyHostToDevice, c->compute));

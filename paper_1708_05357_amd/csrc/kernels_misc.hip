@@ -120,10 +120,10 @@ __global__ __launch_bounds__(1024) void sumsq_kernel(const float *b, int64_t d, 
     }
 }
 
-// Input checks; bits of *flags: 1 = label not +-1, 2 = rowptr[0] != 0 or decreasing,
+// Input checks; bits of *flags: 1 = label not +-1, 2 = rowptr[0] != 0, decreasing, negative or beyond nnz,
 // 4 = column index out of range or not strictly increasing inside a row, 8 = non-finite target.
 __global__ void validate_kernel(int model, int64_t d, int64_t n, const float *target,
-                                const int64_t *rowptr, const int32_t *colidx, uint32_t *flags)
+                                const int64_t *rowptr, const int32_t *colidx, int64_t nnz, uint32_t *flags)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     uint32_t f = 0;
@@ -135,7 +135,9 @@ __global__ void validate_kernel(int model, int64_t d, int64_t n, const float *ta
     if (rowptr && i < n) {
         const int64_t beg = rowptr[i], end = rowptr[i + 1];
         if (i == 0 && beg != 0) f |= 2u;
-        if (end < beg) f |= 2u;
+        // a row is only walked if it lies inside the arrays: a rowptr that is locally increasing
+        // but points past the nnz = rowptr[n] entries the caller allocated must not be followed
+        if (beg < 0 || end < beg || end > nnz) f |= 2u;
         else {
             int32_t prev = -1;
             for (int64_t e = beg; e < end; ++e) {
@@ -246,7 +248,7 @@ hipError_t launch_validate(duhl_ctx *c)
 {
     const int64_t len = c->d > c->n ? c->d : c->n;
     hipLaunchKernelGGL(validate_kernel, dim3((len + 255) / 256), dim3(256), 0, c->compute, (int)c->model,
-                       c->d, c->n, c->target, c->cv.rowptr, c->cv.colidx, &c->sel->error);
+                       c->d, c->n, c->target, c->cv.rowptr, c->cv.colidx, c->nnz, &c->sel->error);
     return hipGetLastError();
 }
 

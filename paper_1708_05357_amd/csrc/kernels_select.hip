@@ -365,7 +365,7 @@ __global__ __launch_bounds__(256) void select_fused_kernel(const SelectArgs a)
 
 // ---- other selection rules, as scores fed to the same top-m machinery ---------------------------
 // Uniformly random subset (the random reference scheme of Section 5.1): score = a hash of
-// (seed, i) mapped to [1,2); the m largest scores are a uniform sample.  Contiguous block (the
+// (seed, i) mapped to a positive float; the m largest scores are a uniform sample.  Contiguous block (the
 // sequential reference scheme of Section 5.2): score 1 on {start + k mod n, k < m}, else 0.
 __global__ void score_random_kernel(float *score, int64_t n, uint64_t seed)
 {
@@ -375,7 +375,11 @@ __global__ void score_random_kernel(float *score, int64_t n, uint64_t seed)
     x = (x ^ (x >> 30)) * 0xBF58476D1CE4E5B9ull;
     x = (x ^ (x >> 27)) * 0x94D049BB133111EBull;
     x ^= x >> 31;
-    score[i] = __uint_as_float(0x3F800000u | (uint32_t)(x >> 41));      // 23 random mantissa bits
+    // one of the 254 * 2^23 positive normal floats, chosen uniformly by bit pattern (order is all that
+    // matters): almost 31 random bits, so even for n ~ 1e6 equal scores -- which fall to the smaller
+    // index -- are rare enough (n^2 / 2^32 pairs) not to bias the subset
+    const uint32_t pick = (uint32_t)__umul64hi(x, 254ull << 23);
+    score[i] = __uint_as_float(0x00800000u + pick);
 }
 __global__ void score_block_kernel(float *score, int64_t n, int64_t start, int64_t m)
 {
@@ -522,8 +526,7 @@ hipError_t launch_select(duhl_ctx *c, int64_t m, int32_t *P_out, const float *ke
     a.partials = c->partials;
     a.scalars = c->scalars;
     a.bar_base = c->sel_bar;
-    a.spin_limit = 1 << 22;                              // seconds; the barriers take microseconds
-    c->sel_bar += 5u * (uint32_t)nb;                     // five barriers of nb arrivals each
+    a.spin_limit = c->select_spin_limit;                 // default: seconds; the barriers take microseconds
     // chunks of up to 8,192 entries stay in registers for the whole kernel
     switch (chunk / 256) {
     case 8: hipLaunchKernelGGL(select_fused_kernel<8>, dim3(nb), dim3(256), 0, c->compute, a); break;
@@ -532,7 +535,10 @@ hipError_t launch_select(duhl_ctx *c, int64_t m, int32_t *P_out, const float *ke
     case 32: hipLaunchKernelGGL(select_fused_kernel<32>, dim3(nb), dim3(256), 0, c->compute, a); break;
     default: hipLaunchKernelGGL(select_fused_kernel<0>, dim3(nb), dim3(256), 0, c->compute, a); break;
     }
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    // five barriers of nb arrivals each: the device counter only moves if the kernel really runs
+    if (e == hipSuccess) c->sel_bar += 5u * (uint32_t)nb;
+    return e;
 }
 
 hipError_t launch_plan_swap(duhl_ctx *c, bool overlap_safe, bool want_count)

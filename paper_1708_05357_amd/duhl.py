@@ -21,7 +21,7 @@ CD_SEQUENTIAL, CD_ASYNC, CD_ATOMIC = 0, 1, 2
 SELECT_GAP, SELECT_RANDOM, SELECT_BLOCK = 0, 1, 2
 OK, EINVAL, ENOMEM, EHIP, ESTATE, EBUDGET = 0, -1, -2, -3, -4, -5
 
-EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_data_dense", "duhl_set_data_dense_chunks", "duhl_set_data_csr", "duhl_gap", "duhl_select",
+EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_wait_limit", "duhl_set_data_dense", "duhl_set_data_dense_chunks", "duhl_set_data_csr", "duhl_gap", "duhl_select",
            "duhl_gap_dense_static",
            "duhl_select_rule_apply", "duhl_host_sample_begin", "duhl_host_sample_end",
            "duhl_commit_swap", "duhl_cd_epoch", "duhl_run", "duhl_objective", "duhl_recompute_v", "duhl_get",
@@ -38,7 +38,7 @@ class RunOpts(C.Structure):
                 ("rule", C.c_int), ("seed", C.c_uint64), ("max_rounds", C.c_int64), ("gap_tol", C.c_double),
                 ("check_every", C.c_int), ("sample_dev", C.c_void_p), ("sample_host", C.c_void_p),
                 ("sample_len", C.c_int64), ("sample_per_round", C.c_int64), ("host_threads", C.c_int),
-                ("confirm", C.c_int), ("adapt_inflight", C.c_int)]
+                ("confirm", C.c_int), ("adapt_inflight", C.c_int), ("host_wait_all", C.c_int)]
 
 
 class RunStats(C.Structure):
@@ -65,6 +65,7 @@ def load():
     p, i64, i32, dbl = C.c_void_p, C.c_int64, C.c_int, C.c_double
     lib.duhl_create.argtypes = [C.POINTER(p), i32, i64, i64, i64, i32, p, p]
     lib.duhl_set_eta.argtypes = [p, dbl]
+    lib.duhl_set_wait_limit.argtypes = [p, i64]
     lib.duhl_set_data_dense.argtypes = [p, p, i64, i32, p, dbl]
     lib.duhl_set_data_dense_chunks.argtypes = [p, p, i64, i64, i64, p, dbl]
     lib.duhl_set_data_csr.argtypes = [p, p, p, p, i32, p, dbl]
@@ -167,6 +168,9 @@ class Duhl:
     def set_eta(self, eta):
         self._chk(self.lib.duhl_set_eta(self._h, float(eta)))
 
+    def set_wait_limit(self, polls):
+        self._chk(self.lib.duhl_set_wait_limit(self._h, int(polls)))
+
     def set_data_dense(self, cols, target, lam, residency=RESIDENT_DEVICE):
         """cols: float32 (n, d) tensor, row i = column a_i (device, or pinned host memory for
         RESIDENT_HOST); row stride = leading dimension.  target: device float32."""
@@ -244,13 +248,13 @@ class Duhl:
 
     def run(self, m, max_rounds, passes=1, mode=CD_ASYNC, gap_tol=-1.0, max_inflight=0, rule=SELECT_GAP,
             seed=0, check_every=1, sample=None, sample_per_round=0, host_threads=0, confirm=False,
-            adapt_inflight=True):
+            adapt_inflight=True, host_wait_all=False):
         """The native round loop.  sample: int32 device tensor with the coordinates whose gaps are
         refreshed window by window (None: see duhl_run); returns a dict of the statistics."""
         o = RunOpts(m=int(m), passes=int(passes), mode=mode, max_inflight=int(max_inflight), rule=rule,
                     seed=int(seed), max_rounds=int(max_rounds), gap_tol=float(gap_tol),
                     check_every=int(check_every), host_threads=int(host_threads), confirm=1 if confirm else 0,
-                    adapt_inflight=1 if adapt_inflight else 0)
+                    adapt_inflight=1 if adapt_inflight else 0, host_wait_all=1 if host_wait_all else 0)
         keep = None
         if sample is not None:
             assert sample.dtype == torch.int32 and sample.is_contiguous() and sample.is_cuda

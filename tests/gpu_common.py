@@ -7,7 +7,7 @@ from paper_1708_05357_amd import duhl, synth
 
 
 def to_np(t):
-    return t.detach().cpu().numpy()
+    return t if isinstance(t, np.ndarray) else t.detach().cpu().numpy()
 
 
 class Pair:
@@ -66,53 +66,118 @@ class Pair:
         self.g.close()
 
 
-def assert_gaps_close(z_gpu, z_or, tol=1e-4, floor=0.0):
-    """Normwise 1e-4 relative on the whole vector, entrywise 1e-4 relative on the entries that
-    matter (>= 1e-3 of the largest).  `floor` is the absolute rounding floor of the formula."""
-    zmax = float(np.max(z_or))
-    err = np.abs(z_gpu.astype(np.float64) - z_or)
-    assert err.max() <= tol * zmax + floor, (err.max(), zmax, floor)
+# ---- tolerance of the gap vectors -------------------------------------------------------------------
+# The bar is 1e-4 relative.  The kernels compute in single precision, so an entry whose terms cancel
+# (near the optimum alpha_i c_i = -Lambda |alpha_i|) cannot be better than the rounding of those
+# terms.  That resolution is modelled PER ENTRY from the entry's own terms (gap_floor below) and is
+# only granted to an entry where it exceeds the 1e-4 bar; everywhere else the bare bar applies.
+EPS = 2.0 ** -24          # unit roundoff of fp32
+DOT_SIGMAS = 8.0          # multiples of the modelled standard deviation of a dot product's rounding error
+FORM_ULPS = 4.0           # roundings of a term of the gap formula, in units of EPS times the term
+
+MARGINS = {}              # label -> worst observed err / floor (written out at the end of the session)
+
+
+def dot_rounding(sumsq_prod, length, partials):
+    """Modelled standard deviation of the rounding error of an fp32 dot product whose `length`
+    terms a_k v_k (sumsq_prod = sum_k (a_k v_k)^2) are accumulated with fused multiply-adds into
+    `partials` running sums which are then added pairwise: every rounding is independent,
+    uniform within half an ulp of the running sum, and the running sum of random-sign terms grows
+    like a random walk.  The variance is EPS^2 * sumsq_prod * (length/(6 partials) + log2(partials)/3 + 1/3)."""
+    partials = max(1.0, min(float(partials), float(length)))
+    return EPS * np.sqrt(sumsq_prod) * np.sqrt(length / (6.0 * partials) + np.log2(partials) / 3.0 + 1.0 / 3.0)
+
+
+def column_stats(pair, idx=None):
+    """c_i = a_i^T v in double and sum_k (a_ik v_k)^2, at the oracle's v, for all or the listed columns."""
+    prob, v = pair.prob, pair.o.v
+    if "cols" in prob:
+        cols = to_np(prob["cols"])
+        if idx is not None:
+            cols = cols[idx]
+        cols = cols.astype(np.float64)
+        return cols @ v, (cols * cols) @ (v * v), float(prob["d"])
+    import scipy.sparse as sp
+    rowptr, colidx, val = (to_np(prob[k]) for k in ("rowptr", "colidx", "val"))
+    X = sp.csr_matrix((val.astype(np.float64), colidx, rowptr), shape=(prob["n"], prob["d"]))
+    if idx is not None:
+        X = X[idx]
+    length = float(np.diff(X.indptr).max()) if X.shape[0] else 1.0
+    return X @ v, X.multiply(X) @ (v * v), length
+
+
+def gap_floor(pair, idx=None, partials=128):
+    """Per-entry resolution of the fp32 gap at the oracle's current (alpha, v): DOT_SIGMAS modelled
+    standard deviations of the dot product's rounding error, carried through the formula's derivative
+    with respect to c_i, plus FORM_ULPS roundings of each term of the formula (App. E / eq. (4)).
+    `partials`: running sums of the kernel's dot product (dense gap kernel: 64 lanes x 2; one per lane
+    and a tree of 16 for sparse rows; 8 for the host sampler)."""
+    o = pair.o
+    c, sumsq, length = column_stats(pair, idx)
+    signed = o.alpha if idx is None else o.alpha[idx]
+    alpha = np.abs(signed)
+    dot = DOT_SIGMAS * dot_rounding(sumsq, length, partials)
+    if pair.prob["model"] == "svm":
+        y = o.target.astype(np.float64) if idx is None else o.target[idx].astype(np.float64)
+        lam_n = o.lam * o.n
+        s = c / lam_n
+        active = (1.0 - y * s) > -dot / lam_n                 # the hinge term is, or may round to, non-zero
+        hinge = np.maximum(1.0 - y * s, 0.0)
+        form = FORM_ULPS * EPS * (alpha * np.abs(s) * 2 + hinge + active * (1.0 + np.abs(s)) + alpha)
+        return (dot / lam_n * (alpha + active) + form) / o.n
+    Lam = o.lam * o.d
+    if pair.prob["model"] == "lasso":
+        active = np.abs(c) > Lam - dot                         # [|c| - Lambda]_+ is, or may round to, non-zero
+        over = np.maximum(np.abs(c) - Lam, 0.0)
+        form = FORM_ULPS * EPS * (alpha * np.abs(c) + Lam * alpha + o.B * over + active * o.B * Lam)
+        return (dot * (alpha + active * o.B) + form) / o.d
+    eta = o.eta
+    l1, l2 = Lam * (1.0 - eta), Lam * eta
+    active = np.abs(c) > l1 - dot
+    over = np.maximum(np.abs(c) - l1, 0.0)
+    form = FORM_ULPS * EPS * (alpha * np.abs(c) + l2 * alpha * alpha + l1 * alpha + over * over / l2
+                              + active * over * l1 / l2)
+    # dz/dc = alpha_i + sign(c_i) [|c_i| - l1]_+ / l2, which vanishes at the optimum of an active
+    # coordinate: the dot product's error then enters through the second-order term only
+    slope = np.abs(signed + np.sign(c) * over / l2)
+    return (dot * slope + active * dot * dot / (2.0 * l2) + form) / o.d
+
+
+def assert_gaps_close(z_gpu, z_or, tol=1e-4, floor=None, label=None):
+    """The 1e-4 bar on a gap vector: normwise, |z_i - zhat_i| <= tol * max zhat for every entry, and
+    entrywise, <= tol * zhat_i on the entries that matter (zhat_i >= 1e-3 of the largest).  `floor`
+    (per entry, or one number) is the fp32 resolution of the entry; it is added to a bound only where
+    it exceeds that bound, i.e. where single precision cannot do better -- never in the first
+    rounds, where the bare rule must hold.  Records the worst err/floor under `label`."""
+    z_or = np.maximum(np.asarray(z_or, dtype=np.float64), 0.0)      # the device clamps at 0
+    zmax = float(np.max(z_or)) if z_or.size else 0.0
+    err = np.abs(np.asarray(z_gpu, dtype=np.float64) - z_or)
+    fl = np.zeros_like(err) if floor is None else np.broadcast_to(np.asarray(floor, dtype=np.float64), err.shape)
+    bound = tol * zmax + np.where(fl > tol * zmax, fl, 0.0)
+    bad = err > bound
+    assert not bad.any(), ("normwise", int(bad.sum()), float(err[bad].max()), zmax, float(fl[bad].max()))
     big = z_or >= 1e-3 * zmax
     if zmax > 0 and big.any():
-        rel = err[big] / z_or[big]
-        assert rel.max() <= tol + floor / max(zmax * 1e-3, 1e-300), rel.max()
+        bound_e = tol * z_or[big] + np.where(fl[big] > tol * z_or[big], fl[big], 0.0)
+        bad = err[big] > bound_e
+        assert not bad.any(), ("entrywise", int(bad.sum()), float((err[big] / z_or[big])[bad].max()))
+    if label is not None and floor is not None and (fl > 0).any():
+        pos = fl > 0
+        worst = float((err[pos] / fl[pos]).max())
+        needed = int((fl > tol * zmax).sum())
+        prev = MARGINS.get(label, (0.0, 0, 0))
+        MARGINS[label] = (max(prev[0], worst), max(prev[1], needed), prev[2] + 1)
+        print(f"[gap tolerance] {label}: worst err/floor {worst:.3f}, entries that needed the floor {needed}/{err.size}, "
+              f"max err/zmax {err.max() / max(zmax, 1e-300):.2e}")
 
 
 def lasso_gap_floor(pair):
-    """Rounding floor of the fp32 Lasso gap: the terms alpha_i c_i and Lambda |alpha_i| cancel
-    near the optimum, leaving an absolute error of a few ulps of Lambda |alpha_i| / d, plus the
-    error of the fp32 dot product scaled by |alpha_i| + B."""
-    o = pair.o
-    Lam = o.lam * o.d
-    eps = 2.0 ** -24
-    dot_err = 8 * eps * np.sqrt(o.d) * np.linalg.norm(o.v) * np.sqrt(o.q.max())
-    return float((4 * eps * Lam * np.abs(o.alpha).max() + dot_err * (np.abs(o.alpha).max() + o.B)) / o.d)
+    """Largest per-entry resolution of the Lasso gap (for bands around selection thresholds)."""
+    return float(gap_floor(pair).max())
 
 
 def enet_gap_floor(pair):
-    """Rounding floor of the fp32 elastic-net gap: the three terms cancel to ~0 at the optimum, each
-    carrying a few ulps of its own size, plus the fp32 dot error times |alpha_i| + |c_i|/(Lambda eta)."""
-    o = pair.o
-    Lam = o.lam * o.d
-    eps = 2.0 ** -24
-    amax = np.abs(o.alpha).max()
-    dot_err = 8 * eps * np.sqrt(o.d) * np.linalg.norm(o.v) * np.sqrt(o.q.max())
-    cmax = np.linalg.norm(o.v) * np.sqrt(o.q.max())
-    terms = amax * cmax + Lam * (o.eta * amax * amax + amax) + cmax * cmax / (Lam * o.eta)
-    return float((8 * eps * terms + dot_err * (amax + cmax / (Lam * o.eta))) / o.d)
-
-
-def svm_gap_floor_csr(rowptr, colidx, val, v, alpha, lam):
-    """Rounding floor of the fp32 SVM gap on sparse data.  The dot product a_i^T v is summed in
-    fp32 (per lane and range one after the other, then the ranges): its error is a small multiple
-    of eps * S_i, S_i = sum_k |x_ik v_k|, which enters z_i through s_i = a_i^T v / (lambda n)
-    multiplied by (1 + |alpha_i|) / n; the formula itself adds a few eps / n."""
-    n = rowptr.size - 1
-    rows = np.repeat(np.arange(n), np.diff(rowptr))
-    S = np.bincount(rows, weights=np.abs(val.astype(np.float64) * np.asarray(v, dtype=np.float64)[colidx]),
-                    minlength=n)
-    eps = 2.0 ** -24
-    return float(4 * eps / n * (1.0 + (1.0 + np.abs(alpha).max()) * S.max() / (lam * n)))
+    return float(gap_floor(pair).max())
 
 
 def dev_i32(a):

@@ -286,3 +286,143 @@ def test_guard_on_duplicated_sparse_rows(G):
     p.o.set_state(a.astype(np.float64))
     assert np.abs(v - p.o.v).max() <= 1e-4 * max(np.abs(p.o.v).max(), 1e-30)
     p.close()
+
+
+def _windows(length, per_round, rounds, wrap):
+    """The windows duhl_run takes from a sample list of `length` entries: `per_round` consecutive
+    positions from a cursor that advances round by round; `wrap`: a window runs on from the start of
+    the list (GPU-evaluated windows), otherwise it is cut at the end of the list (host threads)."""
+    cursor, out = 0, []
+    for _ in range(rounds):
+        if wrap:
+            pos = [(cursor + k) % length for k in range(per_round)]
+        else:
+            pos = list(range(cursor, min(length, cursor + per_round)))
+        out.append(np.array(pos, dtype=np.int64))
+        cursor = (cursor + len(pos)) % length
+    return out
+
+
+def _check_gap_memory(G, p, z_gpu, refreshed, states, label, partials=128):
+    """The gap memory after some rounds, entry by entry: entry i was last evaluated in round
+    refreshed[i], i.e. at the iterate the GPU had after that many rounds (states[t] = its alpha, v),
+    and must equal the oracle's gap at that very iterate to the 1e-4 bar."""
+    n = z_gpu.size
+    z_want, floor = np.zeros(n), np.zeros(n)
+    for t in np.unique(refreshed):
+        idx = np.flatnonzero(refreshed == t).astype(np.int32)
+        p.o.set_state(states[t][0].astype(np.float64), states[t][1].astype(np.float64))
+        p.o.gaps(idx)
+        z_want[idx] = p.o.z[idx]
+        floor[idx] = G.gap_floor(p, idx=idx, partials=partials)
+    G.assert_gaps_close(z_gpu, z_want, floor=floor, label=label)
+
+
+def _same_working_set_outside_the_tie_band(G, p, P_gpu, P_or, z_sel):
+    """The two selections may differ only in coordinates whose gap-memory entry lies within the
+    tie band around the m-th largest entry: the 1e-4 agreement of the gaps plus their fp32 resolution
+    (an entry that is 1e-13 in double precision is an exact 0 in single, and ranks with the zeros)."""
+    if np.array_equal(P_gpu, P_or):
+        return
+    diff = np.setxor1d(P_gpu, P_or).astype(np.int32)
+    thr = np.sort(z_sel)[-P_or.size]
+    band = 1e-4 * z_sel.max() + G.gap_floor(p, idx=diff).max()
+    assert np.all(np.abs(z_sel[diff] - thr) <= band), (diff, z_sel[diff], thr, band)
+
+
+@pytest.mark.parametrize("kind", ["lasso", "svm"])
+def test_stale_memory_rounds_match_the_oracle_round_by_round(G, kind):
+    """Sec. 4.1 / eq. (13) on a device-resident matrix, the GPU evaluating the windows: per round the
+    gap memory is refreshed for the last working set and one window of the sample list at the current
+    iterate, the m largest entries of the (otherwise stale) memory are taken, and `passes` sequential
+    passes run over them in ascending order.  The oracle does the same rounds with the same windows:
+    iterates 1e-5 and identical working sets after every number of rounds up to 9; and every entry
+    of the gap memory equals the oracle's gap at the iterate of the round that last refreshed it."""
+    from paper_1708_05357_amd import duhl, synth
+    prob = _lasso(700, 300, seed=46) if kind == "lasso" else synth.svm_dense(400, 96, seed=47)
+    n, m, per_round, passes = prob["n"], 40, 57, 2
+    perm = np.random.default_rng(8).permutation(n).astype(np.int32)[: n - 11]       # 11 coordinates never sampled
+    wins = _windows(perm.size, per_round, 9, wrap=True)
+    states, refreshed = {}, np.zeros(n, dtype=np.int64)
+    p = G.Pair(prob)
+    states[0] = (p.g.get(duhl.ALPHA), p.g.get(duhl.V))
+    p.o.gaps()                                                # set_data's first pass: every gap at alpha = 0
+    P_prev = None
+    for rounds in range(1, 10):
+        q = G.Pair(prob)
+        st = q.g.run(m, rounds, passes=passes, mode=duhl.CD_SEQUENTIAL, sample=G.dev_i32(perm),
+                     sample_per_round=per_round)
+        assert st["rounds"] == rounds
+        # the oracle's round number rounds-1: what is refreshed at alpha^(t) before the selection
+        t = rounds - 1
+        fresh = np.arange(n) if P_prev is None else np.union1d(P_prev, perm[wins[t]])
+        refreshed[fresh] = t
+        p.o.gaps(fresh.astype(np.int32))
+        # the GPU's working set of this round must be the oracle's outside the tie band; the oracle
+        # then goes on with the GPU's choice, so that later rounds compare like with like
+        P_prev = q.g.get(duhl.P)
+        _same_working_set_outside_the_tie_band(G, p, P_prev, p.o.select(m), p.o.z)
+        p.o.round_delayed(m, None, passes=passes, P=P_prev)
+        a, v = q.g.get(duhl.ALPHA), q.g.get(duhl.V)
+        states[rounds] = (a, v)
+        assert np.abs(a - p.o.alpha).max() <= 1e-5 * max(np.abs(p.o.alpha).max(), 1e-30), rounds
+        assert np.abs(v - p.o.v).max() <= 1e-5 * np.abs(p.o.v).max(), rounds
+        if rounds in (1, 4, 9):
+            keep = (p.o.alpha.copy(), p.o.v.copy(), p.o.z.copy())
+            _check_gap_memory(G, p, q.g.get(duhl.Z), refreshed, states, f"stale memory ({kind}), {rounds} rounds")
+            p.o.set_state(keep[0], keep[1])
+            p.o.z[:] = keep[2]
+        q.close()
+    p.close()
+
+
+@pytest.mark.parametrize("chunk_cols", [None, 128])
+def test_delayed_rounds_with_unit_a_threads_match_the_oracle_round_by_round(G, chunk_cols):
+    """Alg. 2 as printed, on a matrix in host memory: unit B (the GPU) selects by eq. (13) and runs its
+    passes while unit A's host threads evaluate z_j = gap_j(alpha^(t)) for the round's window; those
+    values enter the gap memory after the round.  With host_wait_all the threads finish every window,
+    so the rounds are reproducible and the oracle's round_delayed() -- same windows, samples taken at
+    alpha^(t), residents refreshed before the selection -- must give the same iterates (1e-5) and
+    working sets after every number of rounds up to 9, and every entry of the gap memory must be the
+    oracle's gap at the iterate of the round that last refreshed it.  The device holds exactly m
+    columns, so the columns in its slots at the start of a round are the previous working set."""
+    from paper_1708_05357_amd import duhl
+    prob = _lasso(900, 380, 0.1, 0.1, seed=48)
+    n, m, per_round, passes = prob["n"], 50, 64, 2
+    perm = np.random.default_rng(9).permutation(n).astype(np.int32)
+    wins = _windows(perm.size, per_round, 9, wrap=False)
+    states, refreshed = {}, np.zeros(n, dtype=np.int64)
+    by_host = np.zeros(n, dtype=bool)
+    p = G.Pair(prob)
+    states[0] = (p.g.get(duhl.ALPHA), p.g.get(duhl.V))
+    p.o.gaps()
+    P_prev = None
+    for rounds in range(1, 10):
+        q = G.Pair(prob, budget=m, host_resident=True, chunk_cols=chunk_cols)
+        st = q.g.run(m, rounds, passes=passes, mode=duhl.CD_SEQUENTIAL, sample=G.dev_i32(perm),
+                     sample_per_round=per_round, host_threads=3, host_wait_all=True)
+        assert st["rounds"] == rounds
+        assert st["host_sampled"] == sum(w.size for w in wins[:rounds])
+        t = rounds - 1
+        if P_prev is not None:
+            refreshed[P_prev] = t
+            by_host[P_prev] = False
+        refreshed[perm[wins[t]]] = t                          # unit A's samples: also at alpha^(t)
+        by_host[perm[wins[t]]] = True
+        if P_prev is not None:
+            p.o.gaps(P_prev)                                   # residents, before the selection
+        P_prev = q.g.get(duhl.P)                              # (the oracle follows the GPU among ties)
+        _same_working_set_outside_the_tie_band(G, p, P_prev, p.o.select(m), p.o.z)
+        p.o.round_delayed(m, perm[wins[t]], passes=passes, P=P_prev)
+        a, v = q.g.get(duhl.ALPHA), q.g.get(duhl.V)
+        states[rounds] = (a, v)
+        assert np.abs(a - p.o.alpha).max() <= 1e-5 * max(np.abs(p.o.alpha).max(), 1e-30), rounds
+        assert np.abs(v - p.o.v).max() <= 1e-5 * np.abs(p.o.v).max(), rounds
+        if rounds in (1, 4, 9):
+            keep = (p.o.alpha.copy(), p.o.v.copy(), p.o.z.copy())
+            _check_gap_memory(G, p, q.g.get(duhl.Z), refreshed, states,
+                              f"delayed rounds with host threads, {rounds} rounds", partials=8)
+            p.o.set_state(keep[0], keep[1])
+            p.o.z[:] = keep[2]
+        q.close()
+    p.close()

@@ -63,13 +63,7 @@ def test_dense_shapes(G, seed):
         p.o.gaps()
         p.g.gap(want_sum=False)
         z, zo = p.g.get(duhl.Z), np.maximum(p.o.z, 0.0)
-        if model == "lasso":
-            floor = G.lasso_gap_floor(p)
-        elif model == "enet":
-            floor = G.enet_gap_floor(p)
-        else:                                            # fp32 dot of length d against |s| = O(1)
-            floor = 64 * 2.0 ** -24 * max(1.0, np.sqrt(d) / 30) / n
-        assert np.abs(z - zo).max() <= 1e-4 * zo.max() + 4 * floor, what
+        G.assert_gaps_close(z, zo, floor=G.gap_floor(p), label=f"dense shapes {model}")
         members = set(p.g.get(duhl.P).tolist())
         order = np.array([j for j in rng.permutation(n)[:5] if j in members], dtype=np.int32)
         if order.size:

@@ -306,6 +306,118 @@ def test_block_rounds_converge_to_the_full_optimum(seed):
     assert o.objective() == pytest.approx(ostar, rel=1e-9, abs=1e-12)
 
 
+# ----------------------------------------------------------------------------- Algorithm 2
+def test_rho_hand_computed():
+    """eq. (7) on numbers small enough to do in the head: z = (4, 2, 1, 1), P = {0, 1}: the mean over
+    P is 3, the mean over all is 2, so rho = 3/2; P = {2, 3} gives 1/2; P = everything gives 1; and
+    a single coordinate that holds the whole gap gives n/m = 4."""
+    z = np.array([4.0, 2.0, 1.0, 1.0])
+    assert orc.rho(z, np.array([0, 1], dtype=np.int32)) == 1.5
+    assert orc.rho(z, np.array([2, 3], dtype=np.int32)) == 0.5
+    assert orc.rho(z, np.arange(4, dtype=np.int32)) == 1.0
+    assert orc.rho(np.array([0.0, 0.0, 7.0, 0.0]), np.array([2], dtype=np.int32)) == 4.0
+    # a slip in either normalisation (1/m or 1/n) changes these: (6)/(8) = 0.75, (6/2)/8 = 0.375, ...
+    assert orc.rho(z, np.array([0], dtype=np.int32)) == 2.0
+
+
+def _delayed_by_hand(o, m, refresh, passes):
+    """Algorithm 2's round written out with nothing but the oracle's pinned steps and a SECOND oracle
+    object that is put at alpha^(t) to evaluate unit A's samples there."""
+    P = orc.select_topm(o.z, m)
+    at_t = orc.Oracle(o.model, o.target, o.lam, cols=o._keep[0], eta=o.eta)
+    at_t.set_state(o.alpha.copy(), o.v.copy())
+    for _ in range(passes):
+        o.cd_pass(P)
+    at_t.gaps(refresh)
+    o.z[refresh] = at_t.z[refresh]
+    return P
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_delayed_round_evaluates_samples_at_the_start_of_the_round(seed):
+    """Alg. 2: unit A's samples are gap_j(alpha^(t)) -- the iterate BEFORE unit B's update of the same
+    round -- they enter the gap memory after the selection, and every other entry keeps its value."""
+    p = synth.lasso_dense(60, 40, 0.2, 0.1, seed=seed)
+    cols, b = p["cols"].numpy(), p["target"].numpy()
+    o = orc.Oracle(LASSO, b, p["lam"], cols=cols)
+    ref = orc.Oracle(LASSO, b, p["lam"], cols=cols)
+    o.gaps()
+    ref.gaps()
+    rng = np.random.default_rng(seed)
+    differs = False
+    for t in range(12):
+        refresh = np.sort(rng.choice(40, 7, replace=False)).astype(np.int32)
+        z_before = o.z.copy()
+        P = o.round_delayed(8, refresh, passes=2)
+        P_ref = _delayed_by_hand(ref, 8, refresh, 2)
+        np.testing.assert_array_equal(P, P_ref)
+        np.testing.assert_array_equal(P, orc.select_topm(z_before, 8))       # selection saw the OLD memory
+        np.testing.assert_array_equal(o.alpha, ref.alpha)
+        np.testing.assert_array_equal(o.z, ref.z)
+        rest = np.ones(40, dtype=bool)
+        rest[refresh] = False
+        np.testing.assert_array_equal(o.z[rest], z_before[rest])               # stale entries stay
+        # and the refreshed ones are NOT the gaps at the new iterate (unless B did not move)
+        now = orc.Oracle(LASSO, b, p["lam"], cols=cols)
+        now.set_state(o.alpha.copy(), o.v.copy())
+        now.gaps(refresh)
+        differs = differs or np.abs(now.z[refresh] - o.z[refresh]).max() > 0
+        # the running v still is A alpha - b
+        np.testing.assert_allclose(o.v, cols.astype(np.float64).T @ o.alpha - b, atol=1e-12)
+    assert differs            # (many Lasso gaps are exactly 0 at both iterates, but not all of them)
+
+
+def test_delayed_round_special_cases_reduce_to_algorithm_1():
+    """m = n: the working set is everything whatever the memory says, so the iterates are those of
+    plain coordinate descent (round() with m = n).  Refreshing every coordinate BEFORE the selection
+    (fresh_idx = all) is Alg. 1 with rule (11) itself.  Refreshing every coordinate as unit A does
+    (after the selection) is rule (11) one round late: round t+1 selects by the gaps at alpha^(t)."""
+    p = synth.lasso_dense(60, 40, 0.2, 0.1, seed=5)
+    cols, b = p["cols"].numpy(), p["target"].numpy()
+    everything = np.arange(40, dtype=np.int32)
+    a = orc.Oracle(LASSO, b, p["lam"], cols=cols)
+    c = orc.Oracle(LASSO, b, p["lam"], cols=cols)
+    for _ in range(6):
+        a.round_delayed(40, everything[:5], passes=1)
+        c.round(40, passes=1)
+        np.testing.assert_array_equal(a.alpha, c.alpha)
+    a = orc.Oracle(LASSO, b, p["lam"], cols=cols)
+    c = orc.Oracle(LASSO, b, p["lam"], cols=cols)
+    for _ in range(8):
+        Pa = a.round_delayed(9, None, passes=2, fresh_idx=everything)
+        Pc, _ = c.round(9, passes=2)
+        np.testing.assert_array_equal(Pa, Pc)
+        np.testing.assert_array_equal(a.alpha, c.alpha)
+    a = orc.Oracle(LASSO, b, p["lam"], cols=cols)
+    a.gaps()
+    for _ in range(8):
+        shadow = orc.Oracle(LASSO, b, p["lam"], cols=cols)
+        shadow.set_state(a.alpha.copy(), a.v.copy())
+        shadow.gaps()                                        # the gaps at alpha^(t)
+        a.round_delayed(9, everything, passes=2)
+        np.testing.assert_array_equal(a.z, shadow.z)          # what round t+1 will select by
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_delayed_rounds_converge_to_the_full_optimum(seed):
+    """Alg. 2 with a gap memory refreshed a few coordinates per round still reaches the optimum of the
+    whole problem (brute force over sign patterns / active sets), Lasso and SVM."""
+    cols, b, A, lam = tiny_lasso(seed)
+    ostar, _ = bf.lasso_optimum(A, b.astype(np.float64), lam)
+    o = orc.Oracle(LASSO, b, lam, cols=cols)
+    o.gaps()
+    for t in range(400):
+        o.round_delayed(3, np.array([(2 * t) % 6, (2 * t + 1) % 6], dtype=np.int32), passes=2)
+    assert o.objective() == pytest.approx(ostar, rel=1e-9, abs=1e-12)
+    cols, y, A, lam = tiny_svm(seed)
+    ostar, _ = bf.svm_dual_optimum(A, y.astype(np.float64), lam)
+    o = orc.Oracle(SVM, y, lam, cols=cols)
+    o.gaps()
+    for t in range(2500):
+        o.round_delayed(4, np.array([(3 * t + k) % 8 for k in range(3)], dtype=np.int32), passes=2)
+    assert o.objective() == pytest.approx(ostar, rel=1e-9, abs=1e-12)
+
+
 # ----------------------------------------------------------------------------- storage forms
 @pytest.mark.parametrize("model", [LASSO, SVM])
 def test_sparse_and_dense_storage_agree(model):
