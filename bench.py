@@ -36,23 +36,29 @@ COUNTER_TRAFFIC_BYTES = {"cfg5": {"gap": 50_163_074 * 2 * 1024 + 3_106 * 1024,
                          "cfg3": {"gap": 323_719 * 2 * 1024 + 13_100 * 1024}}     # the dot kernel of the pass
 
 
-def build_problem(name, device, scale, piece_gib=8.0):
+def build_problem(name, device, scale, piece_gib=8.0, host_memory="pageable"):
     import torch
     from paper_1708_05357_amd import synth
     cfg = synth.CONFIGS[name]
     out = None
     if cfg.get("host_resident"):
-        # unit A's memory: pinned host memory in pieces of at most piece_gib (one pinned allocation
-        # of more than about 32 GB fails on the test machines)
         n = max(8, int(cfg["n"] * scale)) if scale != 1.0 else cfg["n"]
-        per = max(1, min(n, int(piece_gib * (1 << 30)) // (4 * cfg["d"])))
-        out = [torch.empty((min(per, n - first), cfg["d"]), dtype=torch.float32, pin_memory=True)
-               for first in range(0, n, per)]
+        if host_memory == "pageable":
+            # unit A's memory: ordinary host memory, as large as the workload says (80 GB); the
+            # library stages what crosses the link through its own pinned buffers
+            out = torch.empty((n, cfg["d"]), dtype=torch.float32)
+        else:
+            # pinned, device-readable host memory in pieces of at most piece_gib (the test machines
+            # pin at most 64 GiB in all and about 32 GB in one allocation)
+            per = max(1, min(n, int(piece_gib * (1 << 30)) // (4 * cfg["d"])))
+            out = [torch.empty((min(per, n - first), cfg["d"]), dtype=torch.float32, pin_memory=True)
+                   for first in range(0, n, per)]
     t0 = time.time()
     prob = synth.make(name, seed=0, device=device, scale=scale, out=out)
     torch.cuda.synchronize()
     prob["gen_s"] = time.time() - t0
     prob["host_resident"] = bool(cfg.get("host_resident"))
+    prob["pageable"] = prob["host_resident"] and host_memory == "pageable"
     return prob
 
 
@@ -66,7 +72,8 @@ def make_ctx(prob, budget):
             g.set_data_dense_chunks(prob["cols"], prob["target"], prob["lam"])
         elif "cols" in prob:
             g.set_data_dense(prob["cols"], prob["target"], prob["lam"],
-                             duhl.RESIDENT_HOST if prob["host_resident"] else duhl.RESIDENT_DEVICE)
+                             (duhl.RESIDENT_HOST_PAGEABLE if prob["pageable"] else duhl.RESIDENT_HOST)
+                             if prob["host_resident"] else duhl.RESIDENT_DEVICE)
         else:
             g.set_data_csr(prob["rowptr"], prob["colidx"], prob["val"], prob["target"], prob["lam"])
     set_data()
@@ -123,8 +130,6 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
         g.commit_swap()
     if ev:
         ev[2].record()
-        if len(ev) > 4:
-            ev[4].record(g.copy_stream)             # completes when the column copies are done
     if on_host:                                 # unit A samples gaps while unit B runs the pass
         # the list continues where the previous round was stopped, so that every column is
         # refreshed once per sweep of the permutation however long the rounds are
@@ -144,7 +149,8 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
     if overlapped:
         g.commit_swap()
     if swap_log is not None:
-        swap_log.append({"columns": stats[0], "rho": stats[1], "overlapped": bool(overlapped)})
+        copy_ms = g.swap_stats()[1] if prob["host_resident"] else 0.0    # the library's own clock of the copies
+        swap_log.append({"columns": stats[0], "rho": stats[1], "overlapped": bool(overlapped), "copy_ms": copy_ms})
     return refreshed                            # gaps evaluated by the GPU from HBM in this round
 
 
@@ -396,9 +402,11 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "fig5svm", "sec51lasso", "sec51svm"])
-    ap.add_argument("--scale", type=float, default=None,
-                    help="shrink n (and m) at fixed d; default 1.0, but 0.8 for cfg4: the test machines "
-                         "pin at most 64 GiB of host memory")
+    ap.add_argument("--scale", type=float, default=1.0, help="shrink n (and m) at fixed d")
+    ap.add_argument("--host-memory", default="pageable", choices=["pageable", "pinned"],
+                    help="host residency (cfg4): the matrix in ordinary host memory, staged by the library "
+                         "through pinned buffers (any size), or in pinned device-readable memory (the test "
+                         "machines pin at most 64 GiB: --scale 0.8 or less)")
     ap.add_argument("--budget-factor", type=float, default=2.0,
                     help="device slots per working-set column (host residency)")
     ap.add_argument("--no-cpu", action="store_true")
@@ -432,8 +440,6 @@ def main():
               "(--gpus must be 1)", file=sys.stderr)
         sys.exit(2)
 
-    if args.scale is None:
-        args.scale = 0.8 if args.workload == "cfg4" else 1.0
     if args.host_sampler_threads < 0:
         args.host_sampler_threads = 12
     if args.passes is None:
@@ -443,7 +449,7 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     log(f"generating {args.workload} (scale {args.scale})")
-    prob = build_problem(args.workload, "cuda", args.scale)
+    prob = build_problem(args.workload, "cuda", args.scale, host_memory=args.host_memory)
     log(f"generated in {prob['gen_s']:.1f}s; setting data")
     m = prob["m"]
     budget = int(m * args.budget_factor) if prob["host_resident"] else m
@@ -483,7 +489,7 @@ def main():
     torch.cuda.synchronize()
 
     host = prob["host_resident"]
-    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(5 if host else 4)] for _ in range(args.steps)]
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(args.steps)]
     swap_log = [] if host else None
     torch.cuda.synchronize()
     t0 = time.time()
@@ -529,7 +535,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{args.workload}: {prob['model']} d={prob['d']} n={prob['n']} m={m}"
-                               + (f" host-resident, {budget} device slots" if prob["host_resident"] else ""),
+                               + (f" host-resident ({args.host_memory} memory), {budget} device slots"
+                                  if prob["host_resident"] else ""),
                    "scale": args.scale, "rounds_timed": args.steps, "passes_per_round": args.passes if auto is None else passes_timed,
                    "cd_scheme": args.cd_mode, "max_inflight": args.inflight, "select_rule": args.select_rule,
                    "gap_sample": args.gap_sample,
@@ -571,7 +578,7 @@ def main():
         sampled = [x["host_sampled"] for x in swap_log if "host_sampled" in x]
         swap_log = [x for x in swap_log if "columns" in x]
         for e, sw in zip(evs, swap_log):
-            copy_ms = e[2].elapsed_time(e[4])
+            copy_ms = sw["copy_ms"]
             cd = e[2].elapsed_time(e[3])
             rows.append({"columns": sw["columns"], "copy_ms": copy_ms, "cd_ms": cd,
                          "overlapped": sw["overlapped"], "rho": sw["rho"],

@@ -55,8 +55,13 @@ typedef enum {
 /* Where the matrix lives (Assumption 1: unit A holds everything, unit B a subset). */
 typedef enum {
     DUHL_RESIDENT_DEVICE = 0, /* whole matrix in HBM; the working set is an index list        */
-    DUHL_RESIDENT_HOST = 1    /* matrix in pinned, device-mapped host memory; the library
+    DUHL_RESIDENT_HOST = 1,   /* matrix in pinned, device-mapped host memory; the library
                                  keeps budget_cols columns in device slots and swaps          */
+    DUHL_RESIDENT_HOST_PAGEABLE = 2 /* matrix in ordinary host memory that the device cannot read (for
+                                 machines that cannot pin all of it): as DUHL_RESIDENT_HOST, but
+                                 every column that crosses the host link is first copied by host
+                                 threads into pinned staging buffers (3 x 64 MB for the gap passes,
+                                 3 x 64 MB for the column swap, owned by the library)           */
 } duhl_residency;
 
 typedef enum { DUHL_ALPHA = 0, DUHL_V = 1, DUHL_Z = 2, DUHL_P = 3, DUHL_SQNORM = 4 } duhl_what;
@@ -94,7 +99,10 @@ duhl_status duhl_set_wait_limit(duhl_ctx *ctx, int64_t polls);
 /* Dense data (Section 2: A in R^{d x n}, fp32 per Section 5.3).  A: column-major, column i at
  * A + i*ld, ld >= d (fastest when A is 16-byte aligned and ld is a multiple of 4: the kernels
  * then use 16-byte loads); a device pointer for DUHL_RESIDENT_DEVICE, a pinned host pointer that the
- * device can read for DUHL_RESIDENT_HOST; borrowed.  target (device, borrowed): b of length d
+ * device can read for DUHL_RESIDENT_HOST, any host pointer for DUHL_RESIDENT_HOST_PAGEABLE; borrowed.
+ * With DUHL_RESIDENT_HOST_PAGEABLE duhl_select reads the swap plan back (it waits for the compute
+ * stream) and a library thread stages and copies the columns until duhl_commit_swap; duhl_gap over
+ * an index list reads every listed column from host memory.  target (device, borrowed): b of length d
  * for the Lasso and the elastic net, labels y in {+1,-1} of length n for the SVM.  lambda: the lambda of the
  * objectives above, finite and > 0.  Resets alpha = 0, v = -b (Lasso) or 0 (SVM), computes the
  * column norms and a first full gap pass into z (one read of A).  Waits for completion.
@@ -345,6 +353,14 @@ duhl_status duhl_selection_threshold(duhl_ctx *ctx, float *threshold);
  * number of device slots in use (the working set, and earlier members that have not been evicted
  * yet); n with device residency.  count: host.  Waits; meant for reports, not for the round loop. */
 duhl_status duhl_resident_columns(duhl_ctx *ctx, int64_t *count);
+
+/* The column swap of the last committed selection (host residency): how many columns were copied into
+ * device slots and how long the copy stream took over them, from the moment it could start (the
+ * plan was made, and in-place replacement had waited for the passes) to the last copy -- with
+ * DUHL_RESIDENT_HOST_PAGEABLE this includes the host threads' staging.  columns, copy_ms: host.
+ * Waits for both streams; meant for reports.  DUHL_ESTATE while a selection is pending or before
+ * the first one. */
+duhl_status duhl_swap_stats(duhl_ctx *ctx, int64_t *columns, double *copy_ms);
 
 /* Size of the current working set (0 before the first commit). */
 int64_t duhl_working_set_size(const duhl_ctx *ctx);

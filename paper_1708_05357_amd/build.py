@@ -9,7 +9,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libduhl.so")
 SOURCES = ["duhl_api.hip", "kernels_gap.hip", "kernels_select.hip", "kernels_cd.hip", "kernels_misc.hip",
-           "host_sampler.hip", "duhl_run.hip",
+           "host_sampler.hip", "host_stage.hip", "duhl_run.hip",
            "kernels_csr_blocked.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-munsafe-fp-atomics",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -51,6 +51,8 @@ hipError_t dev_alloc(T **p, int64_t count)
 void free_host_residency(duhl_ctx *c)
 {
     host_sampler_destroy(c);
+    stager_destroy(c);
+    c->pageable = false;
     csr_blocked_free(c);
     c->host_chunks.clear();
     (void)hipFree(c->chunk_tab); c->chunk_tab = nullptr;
@@ -62,6 +64,8 @@ void free_host_residency(duhl_ctx *c)
     (void)hipFree(c->evict_slot); c->evict_slot = nullptr;
     if (c->ev_plan) { (void)hipEventDestroy(c->ev_plan); c->ev_plan = nullptr; }
     if (c->ev_copy) { (void)hipEventDestroy(c->ev_copy); c->ev_copy = nullptr; }
+    if (c->ev_copy_begin) { (void)hipEventDestroy(c->ev_copy_begin); c->ev_copy_begin = nullptr; }
+    c->swap_timed = false;
 }
 
 // Read `count` doubles of the device scalar block after the compute stream has drained.
@@ -174,10 +178,14 @@ duhl_status set_data_dense_pieces(duhl_ctx *c, const float *const *pieces, int64
     c->have_data = false;
     free_host_residency(c);
     c->sparse = false;
+    const bool pageable = res == DUHL_RESIDENT_HOST_PAGEABLE;
+    if (pageable) res = DUHL_RESIDENT_HOST;         // host residency in every other respect
+    c->pageable = pageable;
     c->res = res;
     c->nnz = c->d * c->n;
     c->cv = ColView{};
     c->cv.ld = ld;
+    c->host_ld = ld;
     c->chunk_cols = piece_cols;
     c->a_aligned16 = true;
     for (int64_t k = 0; k < n_pieces; ++k)
@@ -187,7 +195,7 @@ duhl_status set_data_dense_pieces(duhl_ctx *c, const float *const *pieces, int64
         c->ld_s = 0;
     } else {
         std::vector<const float *> dev(n_pieces);
-        for (int64_t k = 0; k < n_pieces; ++k) {
+        for (int64_t k = 0; k < n_pieces && !pageable; ++k) {
             void *dptr = nullptr;
             if (hipHostGetDevicePointer(&dptr, const_cast<float *>(pieces[k]), 0) != hipSuccess || !dptr) {
                 (void)hipGetLastError();
@@ -198,7 +206,7 @@ duhl_status set_data_dense_pieces(duhl_ctx *c, const float *const *pieces, int64
         }
         c->cv.base = dev[0];
         c->host_chunks.assign(pieces, pieces + n_pieces);
-        if (n_pieces > 1) {
+        if (n_pieces > 1 && !pageable) {
             HIPCHK(c, dev_alloc(&c->chunk_tab, n_pieces));
             HIPCHK(c, hipMemcpy(c->chunk_tab, dev.data(), sizeof(float *) * (size_t)n_pieces, hipMemcpyHostToDevice));
             c->cv.chunk = c->chunk_tab;
@@ -212,9 +220,19 @@ duhl_status set_data_dense_pieces(duhl_ctx *c, const float *const *pieces, int64
         HIPCHK(c, dev_alloc(&c->fill_slot, c->budget));
         HIPCHK(c, dev_alloc(&c->evict_slot, c->budget));
         HIPCHK(c, hipEventCreateWithFlags(&c->ev_plan, hipEventDisableTiming));
-        HIPCHK(c, hipEventCreateWithFlags(&c->ev_copy, hipEventDisableTiming));
+        HIPCHK(c, hipEventCreate(&c->ev_copy));             // these two also time the copies
+        HIPCHK(c, hipEventCreate(&c->ev_copy_begin));
         HIPCHK(c, launch_fill_i32(c->compute, c->col_slot, c->n, -1));
         HIPCHK(c, launch_fill_i32(c->compute, c->slot_col, c->budget, -1));
+        if (pageable) {
+            // no kernel may follow a host address: a column that is in no slot is only ever read from
+            // a staging buffer.  The view keeps a harmless device address for coordinates without a
+            // slot (slot 0, stride 0), so that a caller's list that names one reads valid memory.
+            c->cv.base = c->slots;
+            c->cv.ld = 0;
+            c->a_aligned16 = true;
+            HIPCHK(c, stager_create(c));
+        }
     }
     return finish_set_data(c, target, lambda);
 }
@@ -317,7 +335,8 @@ duhl_status duhl_set_data_dense(duhl_ctx *c, const float *A, int64_t ld, duhl_re
     if (st != DUHL_OK) return st;
     if (!A) return fail(c, DUHL_EINVAL, "A is NULL");
     if (ld < c->d) return fail(c, DUHL_EINVAL, "ld (%lld) < d (%lld)", (long long)ld, (long long)c->d);
-    if (res != DUHL_RESIDENT_DEVICE && res != DUHL_RESIDENT_HOST) return fail(c, DUHL_EINVAL, "bad residency");
+    if (res != DUHL_RESIDENT_DEVICE && res != DUHL_RESIDENT_HOST && res != DUHL_RESIDENT_HOST_PAGEABLE)
+        return fail(c, DUHL_EINVAL, "bad residency");
     return set_data_dense_pieces(c, &A, 1, c->n, ld, res, target, lambda);
 }
 
@@ -415,8 +434,16 @@ duhl_status duhl_select_rule_apply(duhl_ctx *c, duhl_select_rule rule, uint64_t 
     if (host) {
         HIPCHK(c, hipEventRecord(c->ev_plan, c->compute));
         HIPCHK(c, hipStreamWaitEvent(c->copy, c->ev_plan, 0));
-        HIPCHK(c, launch_copy_columns(c));
-        HIPCHK(c, hipEventRecord(c->ev_copy, c->copy));
+        HIPCHK(c, hipEventRecord(c->ev_copy_begin, c->copy));
+        c->swap_timed = true;
+        if (c->pageable) {
+            // the host must gather the columns: the plan comes back (this waits for the compute
+            // stream), then a background thread stages them and enqueues the copies
+            HIPCHK(c, stager_swap_begin(c));
+        } else {
+            HIPCHK(c, launch_copy_columns(c));
+            HIPCHK(c, hipEventRecord(c->ev_copy, c->copy));
+        }
     }
     if (n_swapped || rho) {
         HIPCHK(c, hipMemcpyAsync(c->h_u32, &c->sel->n_fill, sizeof(uint32_t), hipMemcpyDeviceToHost,
@@ -441,6 +468,7 @@ duhl_status duhl_commit_swap(duhl_ctx *c)
     if (!c->pending) return fail(c, DUHL_ESTATE, "no selection is pending");
     HIPCHK(c, hipSetDevice(c->device));
     if (c->res == DUHL_RESIDENT_HOST) {
+        if (c->pageable) HIPCHK(c, stager_swap_join(c));   // every copy is enqueued, ev_copy recorded
         HIPCHK(c, hipStreamWaitEvent(c->compute, c->ev_copy, 0));
         HIPCHK(c, launch_publish(c));
     }
@@ -583,6 +611,25 @@ duhl_status duhl_device_ptr(duhl_ctx *c, duhl_what what, void **ptr)
 }
 
 int64_t duhl_working_set_size(const duhl_ctx *c) { return c ? c->m_cur : 0; }
+
+duhl_status duhl_swap_stats(duhl_ctx *c, int64_t *columns, double *copy_ms)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!columns || !copy_ms) return fail(c, DUHL_EINVAL, "columns or copy_ms is NULL");
+    if (!c->have_data || c->res != DUHL_RESIDENT_HOST) return fail(c, DUHL_ESTATE, "no host-resident data");
+    if (c->pending) return fail(c, DUHL_ESTATE, "a selection is pending: call duhl_commit_swap first");
+    if (!c->swap_timed) return fail(c, DUHL_ESTATE, "no selection yet");
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, hipStreamSynchronize(c->copy));
+    uint32_t n_fill = 0;
+    HIPCHK(c, hipMemcpyAsync(&n_fill, &c->sel->n_fill, sizeof(n_fill), hipMemcpyDeviceToHost, c->compute));
+    HIPCHK(c, hipStreamSynchronize(c->compute));
+    float ms = 0.0f;
+    HIPCHK(c, hipEventElapsedTime(&ms, c->ev_copy_begin, c->ev_copy));
+    *columns = (int64_t)n_fill;
+    *copy_ms = (double)ms;
+    return DUHL_OK;
+}
 
 duhl_status duhl_resident_columns(duhl_ctx *c, int64_t *count)
 {

@@ -8,6 +8,7 @@
 #include "duhl.h"
 
 struct duhl_host_sampler;   // host-thread gap sampler (host_sampler.hip)
+struct duhl_stager;         // pinned staging of a matrix in pageable host memory (host_stage.hip)
 
 namespace duhl {
 
@@ -289,15 +290,21 @@ struct duhl_ctx {
     // host residency
     std::vector<const float *> host_chunks;   // the caller's host addresses of the matrix: its pieces, or one entry
     int64_t chunk_cols;         // columns per piece (n when the matrix is one piece)
+    int64_t host_ld;            // floats between the columns of the host matrix
     const float **chunk_tab;    // device table of the pieces' device addresses (nullptr: one piece)
     bool a_aligned16;           // every piece (or the matrix) starts on a 16-byte boundary
     duhl_host_sampler *sampler; // unit A's gap sampler, created on first use
+    bool pageable;              // the host matrix is in ordinary memory that the device cannot read:
+                                // every column crosses the link through pinned staging buffers
+    duhl_stager *stager;        // those buffers, their copy threads and the background swap job
     float *slots;
     int64_t ld_s;
     int32_t *col_slot, *slot_col;
     uint8_t *mark;
     int32_t *fill_col, *fill_slot, *evict_slot;
     hipEvent_t ev_plan, ev_copy;
+    hipEvent_t ev_copy_begin;   // on the copy stream, before the first column copy of a selection (timing)
+    bool swap_timed;            // ev_copy_begin / ev_copy bracket a finished or running swap
 
     double *h_scalars;          // pinned staging for scalar read-back
     uint32_t *h_u32;
@@ -323,7 +330,7 @@ namespace duhl {
 inline const float *host_col(const duhl_ctx *c, int64_t j)
 {
     const int64_t k = j / c->chunk_cols;
-    return c->host_chunks[(size_t)k] + (j - k * c->chunk_cols) * c->cv.ld;
+    return c->host_chunks[(size_t)k] + (j - k * c->chunk_cols) * c->host_ld;
 }
 
 // ---- launchers (each enqueues on the given stream and returns the launch status) ----------
@@ -349,6 +356,32 @@ hipError_t launch_fill_f32(hipStream_t s, float *p, int64_t n, float value);
 hipError_t launch_sum_partials(duhl_ctx *c, int64_t count, int scalar_slot);
 void host_sampler_destroy(duhl_ctx *c);
 int64_t host_sampler_prefix(const duhl_ctx *c);   // leading list entries the last host sampling round refreshed
+// ---- pageable host matrix (host_stage.hip) -------------------------------------------------------
+// One batch of staged columns: column k of the batch is at stage + k*lds (device-readable pinned
+// memory, 16-byte aligned columns); it is list entry k0 + k of the pass.
+struct StageBatch {
+    const float *stage;
+    int64_t lds, k0, count;
+};
+hipError_t stager_create(duhl_ctx *c);
+void stager_destroy(duhl_ctx *c);
+// The gap pass over columns read from host memory: the listed coordinates (device list idx of `count`
+// entries), or first .. first+count-1 when idx == nullptr.  Waits for the compute stream.
+hipError_t staged_gap(duhl_ctx *c, const int32_t *idx, int64_t first, int64_t count, bool with_norms);
+hipError_t staged_corr_sample(duhl_ctx *c, float *u, int samples);
+hipError_t staged_accumulate_v(duhl_ctx *c);
+// Column swap: reads the plan back, then a background thread stages the missing columns and
+// enqueues their copies into the slots on the copy stream; stager_swap_join waits until all of them
+// are enqueued and ev_copy is recorded.
+hipError_t stager_swap_begin(duhl_ctx *c);
+hipError_t stager_swap_join(duhl_ctx *c);
+// kernels of other files that the staged passes launch
+hipError_t launch_gap_batch(duhl_ctx *c, const StageBatch &b, const int32_t *idx, int64_t first, bool with_norms,
+                            bool first_batch);
+hipError_t launch_corr_batch(duhl_ctx *c, const StageBatch &b, const int32_t *idx, float *u);
+hipError_t launch_accumulate_batch(duhl_ctx *c, const StageBatch &b, const int32_t *idx);
+hipError_t launch_copy_batch(duhl_ctx *c, const StageBatch &b);
+
 hipError_t csr_blocked_build(duhl_ctx *c);
 void csr_blocked_free(duhl_ctx *c);
 hipError_t launch_gap_csr_blocked(duhl_ctx *c, const int32_t *idx, int64_t count, int64_t *grid_out);

@@ -230,7 +230,7 @@ extern "C" duhl_status duhl_host_sample_begin(duhl_ctx *c, const int32_t *idx_ho
         for (size_t k = 0; k < hs->touched.size(); ++k) {
             const int64_t first = (int64_t)k * c->chunk_cols;
             const int64_t cols = c->n - first < c->chunk_cols ? c->n - first : c->chunk_cols;
-            prefault(hs->touched[k], c->cv.ld * (cols - 1) + c->d, nthreads);
+            prefault(hs->touched[k], c->host_ld * (cols - 1) + c->d, nthreads);
         }
     }
     if (count > hs->cap) {

@@ -25,6 +25,9 @@ struct GapArgs {
     const float *v, *alpha, *target;
     float *z, *q;
     double *partials;
+    int64_t first;            // idx == nullptr: list entry k stands for coordinate first + k
+    const float *stage;       // non-null: the column of list entry k is at stage + k*stage_ld (a batch of
+    int64_t stage_ld;         // columns staged from host memory) instead of where cv finds coordinate j
 };
 
 // Which coordinate does list entry k stand for (-1: nothing to do).
@@ -35,7 +38,7 @@ __device__ __forceinline__ int64_t list_entry(const GapArgs &a, int64_t k)
         const int32_t j = a.slot_col[k];
         return (j >= 0 && a.cv.col_slot[j] == (int32_t)k) ? j : -1;   // skip empty / unpublished
     }
-    if (!a.idx) return k;
+    if (!a.idx) return k + a.first;
     const int64_t j = a.idx[k];
     return (uint64_t)j < (uint64_t)a.n ? j : -1;        // entries that name no coordinate are skipped
 }
@@ -75,11 +78,14 @@ __global__ __launch_bounds__(256) void gap_dense_kernel(const GapArgs a)
     double wsum = 0.0;
     if (any) {
         int64_t jany = 0;
+        int cany = 0;
 #pragma unroll
         for (int c = 0; c < COLS; ++c)
-            if (j[c] >= 0) jany = j[c];
+            if (j[c] >= 0) { jany = j[c]; cany = c; }
 #pragma unroll
-        for (int c = 0; c < COLS; ++c) p[c] = a.cv.col(j[c] >= 0 ? j[c] : jany);
+        for (int c = 0; c < COLS; ++c)
+            p[c] = a.stage ? a.stage + (group * COLS + (j[c] >= 0 ? c : cany)) * a.stage_ld
+                           : a.cv.col(j[c] >= 0 ? j[c] : jany);
 
         float acc0[COLS], acc1[COLS], nq[COLS];
 #pragma unroll
@@ -190,7 +196,7 @@ __global__ __launch_bounds__(256) void gap_csr_kernel(const GapArgs a)
 
 // Sum of `count` per-block partials in a fixed order -> scalars[slot].
 __global__ __launch_bounds__(1024) void sum_partials_kernel(const double *partials, int64_t count,
-                                                            double *out)
+                                                            double *out, bool accumulate = false)
 {
     __shared__ double sh[16];
     double s = 0.0;
@@ -201,14 +207,14 @@ __global__ __launch_bounds__(1024) void sum_partials_kernel(const double *partia
     if (threadIdx.x == 0) {
         double t = 0.0;
         for (int w = 0; w < 16; ++w) t += sh[w];
-        *out = t;
+        *out = accumulate ? *out + t : t;
     }
 }
 
 hipError_t launch_sum_partials(duhl_ctx *c, int64_t count, int scalar_slot)
 {
     hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(1024), 0, c->compute, c->partials, count,
-                       c->scalars + scalar_slot);
+                       c->scalars + scalar_slot, false);
     return hipGetLastError();
 }
 
@@ -241,8 +247,9 @@ static hipError_t launch_gap_model(const GapLaunch &L, const GapArgs &a, int64_t
         else
             hipLaunchKernelGGL((gap_csr_kernel<MODEL, 16, NORMS>), dim3(grid), dim3(256), 0, L.stream, a);
     } else {
-        const bool vec = L.a_aligned16 && (a.cv.ld % 4 == 0) && aligned16(a.v) &&
-                         (!a.cv.col_slot || (aligned16(a.cv.slots) && a.cv.ld_s % 4 == 0));
+        const bool vec = a.stage ? (aligned16(a.stage) && a.stage_ld % 4 == 0 && aligned16(a.v))
+                                 : L.a_aligned16 && (a.cv.ld % 4 == 0) && aligned16(a.v) &&
+                                       (!a.cv.col_slot || (aligned16(a.cv.slots) && a.cv.ld_s % 4 == 0));
         // Short columns: more columns per wavefront to keep enough bytes in flight.
         const int cols = L.cols;
 #define DUHL_GAP_LAUNCH(COLS, VEC)                                                              \
@@ -294,9 +301,14 @@ hipError_t launch_gap(duhl_ctx *c, const int32_t *idx, int64_t count, bool slot_
     a.z = c->z;
     a.q = c->q;
     a.partials = c->partials;
+    a.first = 0;
+    a.stage = nullptr;
+    a.stage_ld = 0;
     if (count <= 0) {
         return launch_sum_partials(c, 0, S_GAP_SUM);
     }
+    // a matrix in pageable host memory: whatever is not asked for by slot crosses the link in batches
+    if (c->pageable && !slot_list) return staged_gap(c, idx, 0, count, with_norms);
     int64_t grid = 0;
     hipError_t e;
     // sparse data: from the blocked copy -- the full pass, and lists so long that the dot
@@ -319,6 +331,41 @@ hipError_t launch_gap(duhl_ctx *c, const int32_t *idx, int64_t count, bool slot_
     e = launch_gap_any(L, a, with_norms, &grid);
     if (e != hipSuccess) return e;
     return launch_sum_partials(c, grid, S_GAP_SUM);
+}
+
+// One batch of a gap pass over columns staged from host memory.
+hipError_t launch_gap_batch(duhl_ctx *c, const StageBatch &b, const int32_t *idx, int64_t first, bool with_norms,
+                            bool first_batch)
+{
+    GapArgs a{};
+    a.cv = c->cv;
+    a.mc = c->mc;
+    a.d = c->d;
+    a.n = c->n;
+    a.count = b.count;
+    a.idx = idx ? idx + b.k0 : nullptr;
+    a.slot_col = nullptr;
+    a.v = c->v;
+    a.alpha = c->alpha;
+    a.target = c->target;
+    a.z = c->z;
+    a.q = c->q;
+    a.partials = c->partials;
+    a.first = first + b.k0;
+    a.stage = b.stage;
+    a.stage_ld = b.lds;
+    GapLaunch L;
+    L.sparse = false;
+    L.avg_nnz = 0;
+    L.a_aligned16 = true;
+    L.cols = c->gap_cols;
+    L.stream = c->compute;
+    int64_t grid = 0;
+    hipError_t e = launch_gap_any(L, a, with_norms, &grid);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(1024), 0, c->compute, c->partials, grid,
+                       c->scalars + S_GAP_SUM, !first_batch);
+    return hipGetLastError();
 }
 
 // ---- the gap pass for callers that cannot allocate ------------------------------------------------
@@ -421,7 +468,7 @@ extern "C" duhl_status duhl_gap_dense_static(duhl_model model, int64_t d, int64_
         if (e != hipSuccess) return static_fail(err, err_len, DUHL_EHIP, "a kernel launch failed (HIP error %lld)", (long long)e);
     }
     if (gap_sum) {
-        hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(1024), 0, L.stream, partials, launched, gap_sum);
+        hipLaunchKernelGGL(sum_partials_kernel, dim3(1), dim3(1024), 0, L.stream, partials, launched, gap_sum, false);
         e = hipGetLastError();
         if (e != hipSuccess) return static_fail(err, err_len, DUHL_EHIP, "a kernel launch failed (HIP error %lld)", (long long)e);
     }

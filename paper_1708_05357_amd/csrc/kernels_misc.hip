@@ -104,6 +104,36 @@ __global__ __launch_bounds__(256) void corr_sample_kernel(const ColView cv, int6
     }
 }
 
+// The same two passes over a batch of columns staged from host memory: column s of the batch holds
+// coordinate idx[s].
+__global__ __launch_bounds__(256) void accumulate_v_staged_kernel(const float *stage, int64_t lds, int64_t d,
+                                                                  const int32_t *idx, int64_t count,
+                                                                  const float *alpha, float *v)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t s = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (s >= count) return;
+    const float aj = alpha[idx[s]];
+    if (aj == 0.0f) return;
+    const float *col = stage + s * lds;
+    for (int64_t r = lane; r < d; r += 64)
+        (void)__hip_atomic_fetch_add(v + r, col[r] * aj, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__global__ __launch_bounds__(256) void corr_sample_staged_kernel(const float *stage, int64_t lds, int64_t d,
+                                                                 const int32_t *idx, int64_t count,
+                                                                 const float *q, float *u)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t s = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (s >= count) return;
+    const float qj = q[idx[s]];
+    if (!(qj > 0.0f)) return;
+    const float w = rsqrtf(qj);
+    const float *col = stage + s * lds;
+    for (int64_t r = lane; r < d; r += 64)
+        (void)__hip_atomic_fetch_add(u + r, col[r] * w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // ||b||^2 in double (for the Lipschitzing bound of Appendix E).
 __global__ __launch_bounds__(1024) void sumsq_kernel(const float *b, int64_t d, double *out)
 {
@@ -202,16 +232,36 @@ hipError_t launch_init_v(duhl_ctx *c)
 
 hipError_t launch_accumulate_v(duhl_ctx *c)
 {
+    if (c->pageable) return staged_accumulate_v(c);
     hipLaunchKernelGGL(accumulate_v_kernel, dim3((c->n + 3) / 4), dim3(256), 0, c->compute, c->cv, c->d,
                        c->n, c->alpha, c->v);
+    return hipGetLastError();
+}
+
+hipError_t launch_corr_batch(duhl_ctx *c, const StageBatch &b, const int32_t *idx, float *u)
+{
+    hipLaunchKernelGGL(corr_sample_staged_kernel, dim3((b.count + 3) / 4), dim3(256), 0, c->compute, b.stage,
+                       b.lds, c->d, idx + b.k0, b.count, c->q, u);
+    return hipGetLastError();
+}
+
+hipError_t launch_accumulate_batch(duhl_ctx *c, const StageBatch &b, const int32_t *idx)
+{
+    hipLaunchKernelGGL(accumulate_v_staged_kernel, dim3((b.count + 3) / 4), dim3(256), 0, c->compute, b.stage,
+                       b.lds, c->d, idx + b.k0, b.count, c->alpha, c->v);
     return hipGetLastError();
 }
 
 hipError_t launch_corr_sample(duhl_ctx *c, float *u, int samples)
 {
     hipLaunchKernelGGL(fill_f32_kernel, dim3((c->d + 255) / 256), dim3(256), 0, c->compute, u, c->d, 0.0f);
-    hipLaunchKernelGGL(corr_sample_kernel, dim3((samples + 3) / 4), dim3(256), 0, c->compute, c->cv, c->d,
-                       c->n, c->q, samples, u);
+    if (c->pageable) {
+        const hipError_t e = staged_corr_sample(c, u, samples);
+        if (e != hipSuccess) return e;
+    } else {
+        hipLaunchKernelGGL(corr_sample_kernel, dim3((samples + 3) / 4), dim3(256), 0, c->compute, c->cv, c->d,
+                           c->n, c->q, samples, u);
+    }
     hipLaunchKernelGGL(sumsq_kernel, dim3(1), dim3(1024), 0, c->compute, u, c->d, c->scalars + S_CORR);
     return hipGetLastError();
 }

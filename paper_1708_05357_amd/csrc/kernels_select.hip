@@ -491,7 +491,35 @@ __global__ __launch_bounds__(256) void copy_columns_kernel(const float *src, int
     }
 }
 
+// The same copy for a batch of columns that host threads staged in pinned memory: column k of the
+// batch goes to the slot planned for the (k0 + k)-th missing column.
+__global__ __launch_bounds__(256) void copy_staged_kernel(const float4 *stage, int64_t lds4, float *slots,
+                                                          int64_t ld_s, int64_t d4ceil, const int32_t *fill_slot,
+                                                          int64_t count)
+{
+    for (int64_t k = blockIdx.x; k < count; k += gridDim.x) {
+        const float4 *s4 = stage + k * lds4;
+        float4 *t4 = reinterpret_cast<float4 *>(slots + (int64_t)fill_slot[k] * ld_s);
+        int64_t r = threadIdx.x;
+        for (; r + 768 < d4ceil; r += 1024) {
+            const float4 a0 = s4[r], a1 = s4[r + 256], a2 = s4[r + 512], a3 = s4[r + 768];
+            t4[r] = a0; t4[r + 256] = a1; t4[r + 512] = a2; t4[r + 768] = a3;
+        }
+        for (; r < d4ceil; r += 256) t4[r] = s4[r];
+    }
+}
+
 }  // namespace
+
+// Staged columns are 16-byte aligned and padded to a multiple of four floats, and so are the slots
+// (ld_s is a multiple of 64), so whole 16-byte chunks are copied: ceil(d/4) of them.
+hipError_t launch_copy_batch(duhl_ctx *c, const StageBatch &b)
+{
+    hipLaunchKernelGGL(copy_staged_kernel, dim3(c->copy_blocks), dim3(256), 0, c->copy,
+                       reinterpret_cast<const float4 *>(b.stage), b.lds / 4, c->slots, c->ld_s, (c->d + 3) / 4,
+                       c->fill_slot + b.k0, b.count);
+    return hipGetLastError();
+}
 
 hipError_t launch_score(duhl_ctx *c, int scheme, int64_t m, uint64_t arg)
 {

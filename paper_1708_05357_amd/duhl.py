@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libduhl.so")
 
 LASSO, SVM, ELASTIC_NET = 0, 1, 2
-RESIDENT_DEVICE, RESIDENT_HOST = 0, 1
+RESIDENT_DEVICE, RESIDENT_HOST, RESIDENT_HOST_PAGEABLE = 0, 1, 2
 ALPHA, V, Z, P, SQNORM = 0, 1, 2, 3, 4
 CD_SEQUENTIAL, CD_ASYNC, CD_ATOMIC = 0, 1, 2
 SELECT_GAP, SELECT_RANDOM, SELECT_BLOCK = 0, 1, 2
@@ -26,7 +26,7 @@ EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_wait_limit", "duhl_set_data_
            "duhl_select_rule_apply", "duhl_host_sample_begin", "duhl_host_sample_end",
            "duhl_commit_swap", "duhl_cd_epoch", "duhl_run", "duhl_objective", "duhl_recompute_v", "duhl_get",
            "duhl_set", "duhl_device_ptr", "duhl_probe_stream_read", "duhl_selection_threshold",
-           "duhl_resident_columns",
+           "duhl_resident_columns", "duhl_swap_stats",
            "duhl_working_set_size", "duhl_last_error",
            "duhl_destroy"]
 
@@ -83,6 +83,7 @@ def load():
     lib.duhl_device_ptr.argtypes = [p, i32, C.POINTER(p)]
     lib.duhl_selection_threshold.argtypes = [p, C.POINTER(C.c_float)]
     lib.duhl_resident_columns.argtypes = [p, C.POINTER(i64)]
+    lib.duhl_swap_stats.argtypes = [p, C.POINTER(i64), C.POINTER(dbl)]
     lib.duhl_working_set_size.argtypes = [p]
     lib.duhl_working_set_size.restype = i64
     lib.duhl_last_error.argtypes = [p]
@@ -178,6 +179,8 @@ class Duhl:
         assert tuple(cols.shape) == (self.n, self.d)
         if residency == RESIDENT_HOST:
             assert cols.device.type == "cpu" and cols.is_pinned()
+        if residency == RESIDENT_HOST_PAGEABLE:
+            assert cols.device.type == "cpu"
         self._keep = (cols, target)
         self._chk(self.lib.duhl_set_data_dense(self._h, C.c_void_p(cols.data_ptr()), cols.stride(0),
                                                residency, _dptr(target, torch.float32), float(lam)))
@@ -297,6 +300,12 @@ class Duhl:
         out = C.c_int64(0)
         self._chk(self.lib.duhl_resident_columns(self._h, C.byref(out)))
         return out.value
+
+    def swap_stats(self):
+        """(columns copied, milliseconds on the copy stream) of the last committed selection."""
+        cols, ms = C.c_int64(0), C.c_double(0.0)
+        self._chk(self.lib.duhl_swap_stats(self._h, C.byref(cols), C.byref(ms)))
+        return cols.value, ms.value
 
     # -- state ------------------------------------------------------------------------------
     def working_set_size(self):

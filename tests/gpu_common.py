@@ -13,7 +13,7 @@ def to_np(t):
 class Pair:
     """The same seeded problem in the HIP library (self.g) and in the CPU oracle (self.o)."""
 
-    def __init__(self, prob, budget=None, host_resident=False, ld=None, chunk_cols=None):
+    def __init__(self, prob, budget=None, host_resident=False, ld=None, chunk_cols=None, pageable=False):
         self.prob = prob
         model = {"lasso": duhl.LASSO, "svm": duhl.SVM, "enet": duhl.ELASTIC_NET}[prob["model"]]
         self.model = model
@@ -37,7 +37,9 @@ class Pair:
                     self.pieces.append(piece[:, :d])
                 self.g.set_data_dense_chunks(self.pieces, self.target, prob["lam"])
             else:
-                if host_resident:
+                if host_resident and pageable:                      # ordinary host memory, staged by the library
+                    store = torch.empty((n, ld_eff), dtype=torch.float32)
+                elif host_resident:
                     store = torch.empty((n, ld_eff), dtype=torch.float32, pin_memory=True)
                 else:
                     store = torch.empty((n, ld_eff), dtype=torch.float32, device=dev)
@@ -46,7 +48,8 @@ class Pair:
                 store[:, :d].copy_(prob["cols"])
                 self.cols = store[:, :d]
                 self.g.set_data_dense(self.cols, self.target, prob["lam"],
-                                      duhl.RESIDENT_HOST if host_resident else duhl.RESIDENT_DEVICE)
+                                      (duhl.RESIDENT_HOST_PAGEABLE if pageable else duhl.RESIDENT_HOST)
+                                      if host_resident else duhl.RESIDENT_DEVICE)
             self.o = orc.Oracle(model, to_np(prob["target"]), prob["lam"],
                                 cols=np.ascontiguousarray(to_np(prob["cols"])), eta=eta)
         else:

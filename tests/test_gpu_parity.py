@@ -584,10 +584,24 @@ def test_host_resident_matrix_in_pieces(G):
     run_host_resident(G, prob, 60, rounds=3, chunk_cols=400)      # one piece through the table
 
 
-def run_host_resident(G, prob, m, rounds=10, chunk_cols=None, ld=None):
+@pytest.mark.parametrize("d,n,m,ld,stage_mb", [(1028, 400, 60, None, None), (1027, 400, 60, 1031, None),
+                                                (100000, 160, 30, None, None), (5000, 900, 200, None, 1)])
+def test_pageable_host_matrix_through_staging_buffers(G, monkeypatch, d, n, m, ld, stage_mb):
+    """The host matrix in ordinary memory that the device cannot read (Assumption 1 of Sec. 3 on a
+    machine that cannot pin everything): the first pass, index-list gap passes and the column swap of
+    Alg. 2 go through the library's pinned staging buffers, a background thread doing the swap.  Same
+    iterates, slots and gaps as with pinned memory; ragged and padded columns; staging buffers of
+    1 MB, so that a pass takes many batches and the buffers are reused."""
+    if stage_mb is not None:
+        monkeypatch.setenv("DUHL_STAGE_MB", str(stage_mb))
+    run_host_resident(G, lasso_problem(d, n, 0.1, 0.1, seed=24), m, rounds=4, ld=ld, pageable=True)
+
+
+def run_host_resident(G, prob, m, rounds=10, chunk_cols=None, ld=None, pageable=False):
     from paper_1708_05357_amd import duhl
     for budget in (2 * m, m + 7):                  # overlapping copies / in-place replacement
-        p = G.Pair(prob, budget=budget, host_resident=True, chunk_cols=chunk_cols, ld=ld)
+        p = G.Pair(prob, budget=budget, host_resident=True, chunk_cols=chunk_cols, ld=ld, pageable=pageable)
+        np.testing.assert_allclose(p.g.get(duhl.SQNORM), p.o.q, rtol=2e-6)
         p.o.gaps()
         G.assert_gaps_close(p.g.get(duhl.Z), p.o.z)
         rng = np.random.default_rng(2)

@@ -120,14 +120,14 @@ def test_stale_gap_memory_windows_on_device_data(G):
     p.close()
 
 
-@pytest.mark.parametrize("threads", [0, 3])
-def test_host_resident_rounds_converge_to_the_oracle(G, threads):
+@pytest.mark.parametrize("threads,pageable", [(0, False), (3, False), (0, True), (3, True)])
+def test_host_resident_rounds_converge_to_the_oracle(G, threads, pageable):
     """Alg. 2 with the matrix in pinned host memory: residents refreshed from their slots, a
     window of the others over the link (threads = 0) or by host threads while the passes run."""
     from paper_1708_05357_amd import duhl
     prob = _lasso(1200, 900, 0.05, 0.1, seed=45)
     n, m = prob["n"], 120
-    p = G.Pair(prob, budget=2 * m, host_resident=True)
+    p = G.Pair(prob, budget=2 * m, host_resident=True, pageable=pageable)
     perm = torch.randperm(n, generator=torch.Generator().manual_seed(5)).to(torch.int32).cuda()
     before = p.g.objective()
     st = p.g.run(m, 200, passes=2, mode=duhl.CD_ASYNC, sample=perm, sample_per_round=n // 5,
@@ -147,7 +147,7 @@ def test_host_resident_rounds_converge_to_the_oracle(G, threads):
     o2.close()
     p.close()
     # the stopping rule with confirmation: ends on the true total gap, evaluated over the link
-    p = G.Pair(prob, budget=2 * m, host_resident=True)
+    p = G.Pair(prob, budget=2 * m, host_resident=True, pageable=pageable)
     all_idx = G.dev_i32(np.arange(n))
     tol = 1e-4 * p.g.gap(all_idx)
     st = p.g.run(m, 3000, passes=2, mode=duhl.CD_ASYNC, sample=perm, sample_per_round=n // 5,
@@ -376,7 +376,7 @@ def test_stale_memory_rounds_match_the_oracle_round_by_round(G, kind):
     p.close()
 
 
-@pytest.mark.parametrize("chunk_cols", [None, 128])
+@pytest.mark.parametrize("chunk_cols", [None, 128, "pageable"])
 def test_delayed_rounds_with_unit_a_threads_match_the_oracle_round_by_round(G, chunk_cols):
     """Alg. 2 as printed, on a matrix in host memory: unit B (the GPU) selects by eq. (13) and runs its
     passes while unit A's host threads evaluate z_j = gap_j(alpha^(t)) for the round's window; those
@@ -398,7 +398,8 @@ def test_delayed_rounds_with_unit_a_threads_match_the_oracle_round_by_round(G, c
     p.o.gaps()
     P_prev = None
     for rounds in range(1, 10):
-        q = G.Pair(prob, budget=m, host_resident=True, chunk_cols=chunk_cols)
+        pageable = chunk_cols == "pageable"                    # ordinary host memory, staged by the library
+        q = G.Pair(prob, budget=m, host_resident=True, chunk_cols=None if pageable else chunk_cols, pageable=pageable)
         st = q.g.run(m, rounds, passes=passes, mode=duhl.CD_SEQUENTIAL, sample=G.dev_i32(perm),
                      sample_per_round=per_round, host_threads=3, host_wait_all=True)
         assert st["rounds"] == rounds
