@@ -29,11 +29,33 @@ def log(msg):
     """Progress lines go to stderr; stdout carries the one JSON line."""
     print(f"[bench {time.strftime('%H:%M:%S')}] {msg}", file=sys.stderr, flush=True)
 
-# HBM bytes per launch of the dominant kernel from the hardware counters (FETCH_SIZE x 2.000 KiB +
-# WRITE_SIZE x 1.000 KiB, scaled by a plain 4 GiB copy): profiles/pmc_*.txt.
-COUNTER_TRAFFIC_BYTES = {"cfg5": {"gap": 50_163_074 * 2 * 1024 + 3_106 * 1024,
-                                  "cd_pass": 4 * ((1_255_897 + 25_139) * 2 * 1024 + (50_187 + 195) * 1024)},
-                         "cfg3": {"gap": 323_719 * 2 * 1024 + 13_100 * 1024}}     # the dot kernel of the pass
+# HBM bytes per launch of the dominant kernels as the hardware counters see them: measured by the
+# profiling step (pmc_traffic.py, two rocprofv3 --pmc runs of this file) and kept in a tracked file.
+TRAFFIC_FILE = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles", "traffic.json")
+
+
+def counter_traffic(workload, which, kernels):
+    """Counter-measured bytes of `which` ("gap": per launch, "cd_pass": per pass) for the workload,
+    or None if it was not profiled.  The file names the kernels it was made for: if those are no
+    longer the kernels this benchmark measures, the figure is stale and the run stops."""
+    if not os.path.exists(TRAFFIC_FILE):
+        return None
+    with open(TRAFFIC_FILE) as f:
+        entry = json.load(f).get(workload, {}).get(which)
+    if entry is None:
+        return None
+    if list(entry["kernels"]) != list(kernels):
+        raise SystemExit(f"profiles/traffic.json holds {which} traffic of {entry['kernels']} for {workload}, but "
+                         f"bench.py measures {kernels}: run the profiling step again (pmc_traffic.py)")
+    return entry["bytes_per_launch" if which == "gap" else "bytes_per_pass"]
+
+
+def dominant_kernels(prob, cd_mode):
+    """Names of the kernels behind the two roofline objects, as the profiler prints them."""
+    if "cols" in prob:
+        return ["gap_dense_kernel"], (["cd_dense_worker_kernel", "merge_workers_kernel"] if cd_mode == "async"
+                                      else ["cd_dense_atomic_kernel"])
+    return ["csr_sliced_dot_kernel", "csr_blocked_finish_kernel"], ["cd_csr_plan_kernel", "cd_csr_async_kernel"]
 
 
 def build_problem(name, device, scale, piece_gib=8.0, host_memory="pageable"):
@@ -78,6 +100,85 @@ def make_ctx(prob, budget):
             g.set_data_csr(prob["rowptr"], prob["colidx"], prob["val"], prob["target"], prob["lam"])
     set_data()
     return g, set_data
+
+
+def make_samples(prob, gap_sample=1.0):
+    """The coordinates whose gap-memory entries a round refreshes beside the working set, when not
+    all are: 5 % of the columns per round with host residency (Section 5.1) -- a window that slides
+    over one random permutation, so every column is refreshed once in 20 rounds -- or the fraction
+    asked for with device residency.  Returns (windows as device lists, the same list for unit A's
+    host threads), or (None, None) when every gap is refreshed every round."""
+    import torch
+    if not (prob["host_resident"] or gap_sample < 1.0):
+        return None, None
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1)
+    windows = 20 if prob["host_resident"] else max(1, int(round(1.0 / max(gap_sample, 1e-6))))
+    k = max(1, prob["n"] // windows)
+    perm = torch.randperm(prob["n"], generator=gen, device="cuda").to(torch.int32)
+    perm = torch.cat([perm, perm[:k]]).contiguous()
+    sample_idx = [perm[(r * k) % prob["n"]:(r * k) % prob["n"] + k] for r in range(windows)]
+    hp = perm[:prob["n"]].cpu().numpy()
+    return sample_idx, {"perm": np.concatenate([hp, hp[:k]]), "cursor": 0, "k": k, "n": prob["n"]}
+
+
+def measure_brief(name, rounds=10, host_threads=12):
+    """One of the other workloads in the same process, with its default settings: a few timed rounds
+    from alpha = 0 (per-phase times from events on the compute stream) and the time to total gap 1e-3."""
+    import gc
+    import torch
+    from paper_1708_05357_amd import duhl
+    prob = build_problem(name, "cuda", 1.0)
+    m, host = prob["m"], prob["host_resident"]
+    g, set_data = make_ctx(prob, 2 * m if host else m)
+    passes = 8 if host else 1
+    threads = host_threads if host else 0
+    sample_idx, sample_host = make_samples(prob)
+    for s in range(2):
+        one_step(g, prob, m, s, sample_idx=sample_idx, passes=passes, host_threads=threads, sample_host=sample_host)
+    set_data()
+    if sample_host is not None:
+        sample_host["cursor"] = 0
+    torch.cuda.synchronize()
+    evs = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] for _ in range(rounds)]
+    swap_log = [] if host else None
+    t0 = time.time()
+    for s in range(rounds):
+        one_step(g, prob, m, s, evs[s], sample_idx, passes=passes, swap_log=swap_log, host_threads=threads,
+                 sample_host=sample_host)
+    torch.cuda.synchronize()
+    elapsed = time.time() - t0
+    med = lambda x: sorted(x)[len(x) // 2]
+    gap_ms = med([e[0].elapsed_time(e[1]) for e in evs])
+    cd_ms = med([e[2].elapsed_time(e[3]) for e in evs]) / passes
+    gap_bytes, cd_bytes = algorithmic_bytes(prob, m)
+    if host:
+        gap_bytes = 4.0 * prob["d"] * g.resident_columns()
+    out = {"workload": f"{prob['model']} d={prob['d']} n={prob['n']} m={m}"
+                       + (" host-resident (pageable memory)" if host else ""),
+           "rounds": rounds, "passes_per_round": passes,
+           "ms_per_round": elapsed / rounds * 1e3, "gap_ms": gap_ms, "cd_pass_ms": cd_ms,
+           "gap_GBps": gap_bytes / (gap_ms * 1e-3) / 1e9, "gap_frac": gap_bytes / (gap_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+           "cd_updates_per_s": m / (cd_ms * 1e-3), "cd_GBps": cd_bytes / (cd_ms * 1e-3) / 1e9,
+           "cd_frac": cd_bytes / (cd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+    if host:
+        sw = [x for x in swap_log if "columns" in x]
+        out["columns_swapped_per_round"] = [x["columns"] for x in sw]
+        out["copy_ms_per_round"] = [round(x["copy_ms"], 3) for x in sw]
+    if sample_host is not None:
+        sample_host["cursor"] = 0
+    ttg = time_to_gap(g, set_data, prob, m, 1e-3, 400, passes=passes, sample_idx=sample_idx, host_threads=threads,
+                      sample_host=sample_host)
+    out["time_to_gap_s"] = ttg["abs_1e-3_s"]
+    out["time_to_gap_rounds"] = ttg["rounds"]
+    out["time_to_rel_gap_s"] = ttg["rel_1e-3_s"]
+    g.close()
+    del g, set_data, prob, sample_idx, sample_host
+    gc.collect()
+    torch.cuda.empty_cache()
+    if hasattr(torch._C, "_host_emptyCache"):
+        torch._C._host_emptyCache()
+    return out
 
 
 def algorithmic_bytes(prob, m):
@@ -411,6 +512,8 @@ def main():
                     help="device slots per working-set column (host residency)")
     ap.add_argument("--no-cpu", action="store_true")
     ap.add_argument("--no-ttg", action="store_true")
+    ap.add_argument("--no-others", action="store_true",
+                    help="default workload only: leave out the short runs of the other workloads")
     ap.add_argument("--cpu-ttg", type=float, default=0.0,
                     help="also time the oracle to total gap 1e-3 on one host core, for at most this many "
                          "seconds per scheme (whole workload in host memory: cfg1-cfg3 only)")
@@ -456,20 +559,7 @@ def main():
     g, set_data = make_ctx(prob, budget)
     mode = duhl.CD_ASYNC if args.cd_mode == "async" else duhl.CD_ATOMIC
     rule = {"gap": duhl.SELECT_GAP, "random": duhl.SELECT_RANDOM, "block": duhl.SELECT_BLOCK}[args.select_rule]
-    sample_idx = sample_host = None
-    if prob["host_resident"] or args.gap_sample < 1.0:
-        # 5 % of the columns per round, refreshed from host memory (Section 5.1): a window that
-        # slides over one random permutation, so every column is refreshed once in 20 rounds
-        # (device residency: the fraction asked for)
-        gen = torch.Generator(device="cuda")
-        gen.manual_seed(1)
-        windows = 20 if prob["host_resident"] else max(1, int(round(1.0 / max(args.gap_sample, 1e-6))))
-        k = max(1, prob["n"] // windows)
-        perm = torch.randperm(prob["n"], generator=gen, device="cuda").to(torch.int32)
-        perm = torch.cat([perm, perm[:k]]).contiguous()
-        sample_idx = [perm[(r * k) % prob["n"]:(r * k) % prob["n"] + k] for r in range(windows)]
-        hp = perm[:prob["n"]].cpu().numpy()
-        sample_host = {"perm": np.concatenate([hp, hp[:k]]), "cursor": 0, "k": k, "n": prob["n"]}
+    sample_idx, sample_host = make_samples(prob, args.gap_sample)
     log(f"warm-up: {args.warmup} rounds")
     for s in range(args.warmup):
         one_step(g, prob, m, s, sample_idx=sample_idx, mode=mode, inflight=args.inflight, rule=rule,
@@ -525,6 +615,7 @@ def main():
     if "cols" in prob and not prob["host_resident"] and prob["cols"].is_contiguous():
         stream_gbps = prob["cols"].numel() * 4.0 / (g.probe_stream_read(prob["cols"], reps=3) * 1e-3) / 1e9
     final_obj = g.objective()
+    gap_kernels, cd_kernels = dominant_kernels(prob, args.cd_mode)
 
     out = {
         "metric": "coordinate updates/s (whole round: gap pass + top-m + CD pass)",
@@ -551,20 +642,18 @@ def main():
                    # host residency: the first round's selection waits for the whole working set to
                    # arrive over the link, which dominates the mean
                    "select_ms_median": sorted(sel_ms)[len(sel_ms) // 2]},
-        "roofline": {"kernel": "gap_dense_kernel" if "cols" in prob
-                     else "csr_sliced_dot_kernel + csr_blocked_finish_kernel",
+        "roofline": {"kernel": " + ".join(gap_kernels),
                      "bound": "hbm", "achieved": gap_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": gap_gbps / HBM_PEAK_GBPS,
-                     "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload, {}).get("gap")
+                     "traffic": counter_traffic(args.workload, "gap", gap_kernels)
                      if args.scale == 1.0 and sample_idx is None else None,
                      "algorithmic_bytes": gap_bytes, "avg_launch_ms": avg(gap_ms),
                      "stream_read_GBps": stream_gbps,
                      "frac_of_stream_read": gap_gbps / stream_gbps if stream_gbps else None},
-        "roofline_cd": {"kernel": "cd_dense_worker_kernel + merge_workers_kernel (one pass)"
-                        if "cols" in prob and args.cd_mode == "async" else "cd atomic kernel (one pass)",
+        "roofline_cd": {"kernel": " + ".join(cd_kernels) + " (one pass)",
                         "bound": "hbm", "achieved": cd_gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                         "frac": cd_gbps / HBM_PEAK_GBPS,
-                        "traffic": COUNTER_TRAFFIC_BYTES.get(args.workload, {}).get("cd_pass")
+                        "traffic": counter_traffic(args.workload, "cd_pass", cd_kernels)
                         if args.scale == 1.0 and args.cd_mode == "async" and args.inflight == 0 else None,
                         "algorithmic_bytes": cd_bytes, "avg_launch_ms": avg(cd_ms),
                         "frac_of_stream_read": cd_gbps / stream_gbps if stream_gbps else None},
@@ -620,6 +709,19 @@ def main():
         else:
             out["cpu_time_to_gap"] = cpu_time_to_gap(prob, m, 1e-3, args.cpu_ttg)
     g.close()
+    if args.workload == "cfg5" and not args.no_others and args.scale == 1.0:
+        # the other workloads of the method, each with its default settings, in the same process
+        import gc
+        del g, set_data, prob, sample_idx, sample_host, evs
+        gc.collect()
+        torch.cuda.empty_cache()
+        out["other_workloads"] = {}
+        for name in ("cfg1", "cfg2", "cfg3", "cfg4"):
+            log(f"other workloads: {name}")
+            try:
+                out["other_workloads"][name] = measure_brief(name, host_threads=args.host_sampler_threads)
+            except (RuntimeError, MemoryError) as e:         # e.g. not enough host memory for the 80 GB matrix
+                out["other_workloads"][name] = {"skipped": str(e)[:200]}
     if args.copy_calibration_gib > 0:
         nfl = int(args.copy_calibration_gib * (1 << 30) / 4)
         src = torch.ones(nfl, dtype=torch.float32, device="cuda")
