@@ -41,7 +41,10 @@ extern "C" {
 
 typedef struct duhl_ctx duhl_ctx;
 
-typedef enum { DUHL_LASSO = 0, DUHL_SVM = 1, DUHL_ELASTIC_NET = 2 } duhl_model;
+/* (Every enumeration of an argument ends in a *_ENUM_MAX member: it widens the type's range to all of
+ * int, so that a caller's invalid value reaches the library's own check -- and is answered with
+ * DUHL_EINVAL -- instead of being undefined behaviour in the C++ behind this header.) */
+typedef enum { DUHL_LASSO = 0, DUHL_SVM = 1, DUHL_ELASTIC_NET = 2, DUHL_MODEL_ENUM_MAX = 0x7fffffff } duhl_model;
 
 typedef enum {
     DUHL_OK = 0,
@@ -57,21 +60,23 @@ typedef enum {
     DUHL_RESIDENT_DEVICE = 0, /* whole matrix in HBM; the working set is an index list        */
     DUHL_RESIDENT_HOST = 1,   /* matrix in pinned, device-mapped host memory; the library
                                  keeps budget_cols columns in device slots and swaps          */
-    DUHL_RESIDENT_HOST_PAGEABLE = 2 /* matrix in ordinary host memory that the device cannot read (for
+    DUHL_RESIDENT_HOST_PAGEABLE = 2, /* matrix in ordinary host memory that the device cannot read (for
                                  machines that cannot pin all of it): as DUHL_RESIDENT_HOST, but
                                  every column that crosses the host link is first copied by host
                                  threads into pinned staging buffers (3 x 64 MB for the gap passes,
                                  3 x 64 MB for the column swap, owned by the library)           */
+    DUHL_RESIDENCY_ENUM_MAX = 0x7fffffff
 } duhl_residency;
 
-typedef enum { DUHL_ALPHA = 0, DUHL_V = 1, DUHL_Z = 2, DUHL_P = 3, DUHL_SQNORM = 4 } duhl_what;
+typedef enum { DUHL_ALPHA = 0, DUHL_V = 1, DUHL_Z = 2, DUHL_P = 3, DUHL_SQNORM = 4, DUHL_WHAT_ENUM_MAX = 0x7fffffff } duhl_what;
 
 /* Visiting scheme of duhl_cd_epoch. */
 typedef enum {
     DUHL_CD_SEQUENTIAL = 0, /* one coordinate at a time, in the given order (Algorithm 3)     */
     DUHL_CD_ASYNC = 1,      /* many coordinates at once, the library's fastest scheme          */
-    DUHL_CD_ATOMIC = 2      /* many coordinates at once, one atomic update of v per step
+    DUHL_CD_ATOMIC = 2,     /* many coordinates at once, one atomic update of v per step
                                (the thread-block-per-coordinate scheme of Appendix D)          */
+    DUHL_CD_MODE_ENUM_MAX = 0x7fffffff
 } duhl_cd_mode;
 
 /* Create a context for a problem with columns of length d (1 <= d < 2^29) and n coordinates
@@ -188,7 +193,8 @@ duhl_status duhl_select(duhl_ctx *ctx, int64_t m, int32_t *P_out, int64_t *n_swa
  * reference schemes the paper compares against: DUHL_SELECT_RANDOM draws a uniformly random
  * subset of size m (Section 5.1; arg = seed), DUHL_SELECT_BLOCK takes the arg-th contiguous block
  * of m coordinates, wrapping around at n (the sequential block scheme of Section 5.2). */
-typedef enum { DUHL_SELECT_GAP = 0, DUHL_SELECT_RANDOM = 1, DUHL_SELECT_BLOCK = 2 } duhl_select_rule;
+typedef enum { DUHL_SELECT_GAP = 0, DUHL_SELECT_RANDOM = 1, DUHL_SELECT_BLOCK = 2,
+               DUHL_SELECT_RULE_ENUM_MAX = 0x7fffffff } duhl_select_rule;
 
 /* duhl_select with a choice of rule; everything else (pending set, copies, outputs, rho of eq. (7)
  * evaluated on the gap memory z for the chosen set) as for duhl_select. */
