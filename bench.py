@@ -148,6 +148,7 @@ def measure_brief(name, rounds=10, host_threads=12):
                  sample_host=sample_host)
     torch.cuda.synchronize()
     elapsed = time.time() - t0
+    steps_kept = g.cd_stats()[2]
     med = lambda x: sorted(x)[len(x) // 2]
     gap_ms = med([e[0].elapsed_time(e[1]) for e in evs])
     cd_ms = med([e[2].elapsed_time(e[3]) for e in evs]) / passes
@@ -156,7 +157,8 @@ def measure_brief(name, rounds=10, host_threads=12):
         gap_bytes = 4.0 * prob["d"] * g.resident_columns()
     out = {"workload": f"{prob['model']} d={prob['d']} n={prob['n']} m={m}"
                        + (" host-resident (pageable memory)" if host else ""),
-           "rounds": rounds, "passes_per_round": passes,
+           "rounds": rounds, "passes_per_round": passes, "updates_per_s": steps_kept / elapsed,
+           "steps_kept": steps_kept, "steps_enqueued": m * passes * rounds,
            "ms_per_round": elapsed / rounds * 1e3, "gap_ms": gap_ms, "cd_pass_ms": cd_ms,
            "gap_GBps": gap_bytes / (gap_ms * 1e-3) / 1e9, "gap_frac": gap_bytes / (gap_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
            "cd_updates_per_s": m / (cd_ms * 1e-3), "cd_GBps": cd_bytes / (cd_ms * 1e-3) / 1e9,
@@ -588,6 +590,12 @@ def main():
         refreshed += one_step(g, prob, m, s, evs[s], sample_idx, mode, args.inflight, swap_log, rule, args.passes,
                               args.host_sampler_threads, sample_host, auto)
     total_passes = args.passes * args.steps if auto is None else sum(auto["passes"])
+    # Coordinate steps that count: those of the passes the guard let stand, as the device counted them
+    # (a pass undone because the objective rose is work thrown away, and a pass enqueued before the
+    # host knew of a halving solves only part of its working set).  Per-update atomics are unguarded.
+    guard_undone, guard_inflight, steps_kept = g.cd_stats()
+    steps_done = steps_kept if args.cd_mode == "async" and os.environ.get("DUHL_CD_GUARD", "1") != "0" \
+        else m * total_passes
     passes_timed = None if auto is None else list(auto["passes"])
     torch.cuda.synchronize()
     elapsed = time.time() - t0
@@ -611,7 +619,7 @@ def main():
     # columns goes with the median pass time, not the mean)
     gap_time = sorted(gap_ms)[len(gap_ms) // 2] if prob["host_resident"] else avg(gap_ms)
     gap_gbps = gap_bytes / (gap_time * 1e-3) / 1e9
-    cd_gbps = cd_bytes * total_passes / args.steps / (avg(cd_ms) * 1e-3) / 1e9
+    cd_gbps = cd_bytes * (steps_done / m) / args.steps / (avg(cd_ms) * 1e-3) / 1e9
     final_gap = g.gap() if not prob["host_resident"] else None   # (fresh z; rounds are over)
     # yardstick: a plain read-only streaming kernel over the same device memory the gap pass reads
     stream_gbps = None
@@ -622,7 +630,7 @@ def main():
 
     out = {
         "metric": "coordinate updates/s (whole round: gap pass + top-m + CD pass)",
-        "value": m * total_passes / elapsed,
+        "value": steps_done / elapsed,
         "unit": "coordinate updates/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": elapsed / args.steps * 1e3,
@@ -638,7 +646,7 @@ def main():
                    "resident_columns": g.resident_columns() if prob["host_resident"] else None},
         "phases": {"gap_ms": avg(gap_ms), "select_ms": avg(sel_ms), "cd_ms": avg(cd_ms),
                    "gap_GBps": gap_gbps, "gap_frac_of_hbm_peak": gap_gbps / HBM_PEAK_GBPS,
-                   "cd_updates_per_s": m * total_passes / args.steps / (avg(cd_ms) * 1e-3), "cd_GBps": cd_gbps,
+                   "cd_updates_per_s": steps_done / args.steps / (avg(cd_ms) * 1e-3), "cd_GBps": cd_gbps,
                    "cd_frac_of_hbm_peak": cd_gbps / HBM_PEAK_GBPS,
                    "gap_ms_min": min(gap_ms), "cd_ms_min": min(cd_ms), "cd_ms_max": max(cd_ms),
                    "gap_ms_median": sorted(gap_ms)[len(gap_ms) // 2], "cd_ms_median": sorted(cd_ms)[len(cd_ms) // 2],
@@ -661,6 +669,10 @@ def main():
                         "algorithmic_bytes": cd_bytes, "avg_launch_ms": avg(cd_ms),
                         "frac_of_stream_read": cd_gbps / stream_gbps if stream_gbps else None},
         "after_timed_rounds": {"total_gap": final_gap, "objective": final_obj},
+        # the device-side guard of the concurrent passes: passes undone because the objective had risen
+        # (since the data were set for the timed rounds), and the bound on concurrent steps now
+        "cd_guard": {"passes_undone": guard_undone, "max_inflight_now": guard_inflight, "steps_kept": steps_kept,
+                     "steps_enqueued": m * total_passes},
         "gen_s": prob["gen_s"],
     }
     if host:

@@ -128,6 +128,15 @@ duhl_status finish_set_data(duhl_ctx *c, const float *target, double lambda)
     c->m_cur = c->m_next = 0;
     c->pending = c->swap_exclusive = false;
     c->pass_counter = 0;
+    if (c->guard) {                                 // a new problem: the bound on concurrent steps starts afresh
+        HIPCHK(c, launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(c->guard), sizeof(GuardState) / 4, 0));
+        // (the first passes from alpha = 0 are the ones in which every coordinate moves, and steps
+        // collide most: they start with half the bound, which the guard doubles after four passes)
+        HIPCHK(c, launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(&c->guard->shift), 1, 1));
+        c->h_trips[0] = 0;
+        c->h_trips[1] = 1;
+    }
+    c->guard_shift = c->cd_guard ? 1 : 0;
     c->have_data = true;
     // column norms and a first full gap pass in one read of the matrix
     HIPCHK(c, launch_gap(c, nullptr, c->n, false, true));
@@ -272,6 +281,7 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->cd_units = env_int("DUHL_CD_UNITS", 0);
     c->cd_spin_limit = env_int("DUHL_CD_SPIN_LIMIT", 1 << 22);
     if (c->cd_spin_limit < 0) c->cd_spin_limit = 0;
+    c->cd_guard = env_int("DUHL_CD_GUARD", 1);
     c->select_spin_limit = env_int("DUHL_SELECT_SPIN_LIMIT", 1 << 22);
     if (c->select_spin_limit < 0) c->select_spin_limit = 0;
     c->select_groups = env_int("DUHL_SELECT_GROUPS", 0);
@@ -498,6 +508,25 @@ duhl_status duhl_cd_epoch(duhl_ctx *c, duhl_cd_mode mode, const int32_t *order, 
     return DUHL_OK;
 }
 
+duhl_status duhl_cd_stats(duhl_ctx *c, int64_t *passes_undone, int64_t *inflight_now, int64_t *steps_kept)
+{
+    if (!c) return DUHL_EINVAL;
+    if (!c->have_data) return fail(c, DUHL_ESTATE, "no data set");
+    HIPCHK(c, hipSetDevice(c->device));
+    HIPCHK(c, hipStreamSynchronize(c->compute));
+    if (passes_undone) *passes_undone = c->h_trips ? (int64_t)*static_cast<volatile uint32_t *>(c->h_trips) : 0;
+    if (inflight_now) *inflight_now = c->m_cur > 0 ? default_inflight(c, c->m_cur) : 0;
+    if (steps_kept) {
+        *steps_kept = 0;
+        if (c->guard) {
+            GuardState gs;
+            HIPCHK(c, hipMemcpy(&gs, c->guard, sizeof gs, hipMemcpyDeviceToHost));
+            *steps_kept = (int64_t)gs.steps_kept;
+        }
+    }
+    return DUHL_OK;
+}
+
 duhl_status duhl_objective(duhl_ctx *c, double *objective)
 {
     if (!c) return DUHL_EINVAL;
@@ -686,6 +715,11 @@ void duhl_destroy(duhl_ctx *c)
     (void)hipFree(c->blk_gt); (void)hipFree(c->blk_eq); (void)hipFree(c->mark);
     (void)hipFree(c->dv); (void)hipFree(c->dirty); (void)hipFree(c->score); (void)hipFree(c->xch);
     (void)hipFree(c->cd_plan);
+    (void)hipFree(c->guard_wbook);
+    (void)hipFree(c->guard); (void)hipFree(c->guard_part); (void)hipFree(c->snap_pass_v); (void)hipFree(c->alpha_old);
+    if (c->h_trips) (void)hipHostFree(c->h_trips);
+    for (hipEvent_t ev : c->ev_pass)
+        if (ev) (void)hipEventDestroy(ev);
     (void)hipFree(c->snap_alpha); (void)hipFree(c->snap_v);
     if (c->h_scalars) (void)hipHostFree(c->h_scalars);
     if (c->h_u32) (void)hipHostFree(c->h_u32);

@@ -136,6 +136,22 @@ __device__ __forceinline__ float cd_new_alpha(const ModelConst &mc, float c, flo
     }
 }
 
+// The terms of the objective that depend on alpha_j alone (Appendix C / D): lambda |alpha| (Lasso),
+// lambda (eta/2 alpha^2 + (1-eta)|alpha|) (elastic net), -(1/n) y alpha (SVM dual).
+template <int MODEL>
+__device__ __forceinline__ float objective_term(const ModelConst &mc, float alpha, float y)
+{
+    if (MODEL == DUHL_LASSO) return mc.Lam * mc.inv_d * fabsf(alpha);
+    if (MODEL == DUHL_ELASTIC_NET)
+        return mc.inv_d * fmaf(0.5f * mc.lam_eta * alpha, alpha, mc.lam_l1 * fabsf(alpha));
+    return -mc.inv_n * y * alpha;
+}
+// Factor of ||v||^2 in the objective: 1/(2d), or 1/(2 lambda n^2) for the SVM dual.
+inline double quad_scale(const ModelConst &mc)
+{
+    return mc.model == DUHL_SVM ? 0.5 * (double)mc.inv_lam_n * (double)mc.inv_n : 0.5 * (double)mc.inv_d;
+}
+
 // 16-byte load of matrix data that is read once per pass: the non-temporal hint keeps the stream
 // from displacing v and the other small arrays in the caches (measured: 6.7-7.0 TB/s against
 // 6.0-6.3 TB/s for plain loads on a 32 GB read).
@@ -230,6 +246,19 @@ struct SelectState {
     uint32_t pad[2];
 };
 
+// Device state of the guard of the concurrent passes: exact coordinate steps never raise the
+// objective, so a pass after which it is higher was spoilt by steps that collided, and is undone.
+struct GuardState {
+    double dreg;            // the pass so far: change of the objective's terms in alpha (regulariser / linear term)
+    double last_delta;      // objective change of the last guarded pass (as measured, before any undoing)
+    uint32_t arrived;       // workgroups of the finishing kernel that are done (the last one decides)
+    uint32_t trips;         // passes undone since the data were set
+    uint32_t shift;         // halvings of the bound on concurrent steps now asked for: +1 per undone pass,
+    uint32_t clean;         // -1 after four passes in a row (counted here) that were let stand
+    unsigned long long steps_pass;   // coordinate steps taken by the pass so far
+    unsigned long long steps_kept;   // coordinate steps of all passes that were let stand, since the data were set
+};
+
 }  // namespace duhl
 
 struct duhl_ctx {
@@ -283,6 +312,22 @@ struct duhl_ctx {
     uint32_t sel_bar;           // value the selection kernel's barrier counter has before its next launch
     uint64_t *xch;              // exchange slots of workers that span several compute units
     float *snap_alpha, *snap_v; // duhl_run's last good iterate (allocated on first use)
+    // guard of the concurrent passes (allocated on first use)
+    duhl::GuardState *guard;
+    double *guard_part;         // per-workgroup partial sums of ||v||^2 before and after the pass
+    int64_t guard_part_cap;
+    float *snap_pass_v;         // v at the start of the pass
+    double2 *guard_wbook;       // per dense worker: its books of the sub-pass (see MergeGuard)
+    uint64_t *alpha_old;        // per position of the visiting order: (stamp of the pass, alpha_j before it moved)
+    uint32_t guard_stamp;       // stamp of the last guarded pass; never reset while the context lives
+    int64_t alpha_old_cap;
+    uint32_t *h_trips;          // pinned, device-writable: GuardState::trips and ::shift as the host may read
+    uint32_t *h_trips_dev;      // them without waiting ([0], [1])
+    int cd_guard;               // 0: guard switched off (DUHL_CD_GUARD)
+    int guard_shift;            // halvings of the library's bound on concurrent steps that the host applies
+    hipEvent_t ev_pass[2];      // behind the last two guarded passes: while the bound is halved the host stays
+    uint64_t guard_passes;      // at most two passes ahead of the device, so that it sees the bound recover
+    uint64_t ev_pass_no[2];     // 1 + the number of the pass each event was recorded behind (0: none)
     void *cd_plan;              // sparse sub-passes: one record per position of the visiting order
     int64_t cd_plan_cap;
     uint32_t xseq;              // next free sequence number for those slots

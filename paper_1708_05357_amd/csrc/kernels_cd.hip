@@ -131,6 +131,17 @@ __device__ __forceinline__ void buffer_store4(__amdgpu_buffer_rsrc_t rs, int vof
     raw.w = __float_as_int(x.w);
     __builtin_amdgcn_raw_buffer_store_b128(raw, rs, voff, soff, 0);
 }
+// 16 bytes written through to device-coherent memory (the store's cache-policy operand carries the
+// agent-scope bit), for data that another workgroup of the same launch reads or overwrites.
+__device__ __forceinline__ void coherent_store4(__amdgpu_buffer_rsrc_t rs, int byte_off, float4 x)
+{
+    v4i_t raw;
+    raw.x = __float_as_int(x.x);
+    raw.y = __float_as_int(x.y);
+    raw.z = __float_as_int(x.z);
+    raw.w = __float_as_int(x.w);
+    __builtin_amdgcn_raw_buffer_store_b128(raw, rs, byte_off, 0, 16);
+}
 __device__ __forceinline__ float4 live_load4(__amdgpu_buffer_rsrc_t rs, int byte_off)
 {
     const v4i_t raw = __builtin_amdgcn_raw_buffer_load_b128(rs, byte_off, 0, 16);
@@ -239,6 +250,21 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_atomic_kernel(cons
 }
 
 
+// A worker (or a group of lanes of the sparse kernel) sits a sub-pass out when the guard asks for
+// fewer concurrent steps than the host knew of when it cut the pass into sub-passes: the host reads
+// the guard's books without waiting and may be many passes ahead of the device.  With e halvings
+// outstanding only every 2^e-th worker takes its share, so a sub-pass solves 1/2^e of its
+// coordinates -- the pass still descends, on a random part of the working set -- until the host
+// catches up and cuts its passes finer.
+__device__ __forceinline__ bool guard_sits_out(const GuardState *st, int host_shift, int64_t worker)
+{
+    if (!st) return false;
+    // (a plain, cached load: the word only changes at the end of a pass, i.e. between kernels)
+    const int dev_shift = (int)st->shift;
+    const int e = dev_shift - host_shift;
+    return e > 0 && (worker & ((1ll << e) - 1)) != 0;
+}
+
 // ---- workers that span several compute units -----------------------------------------------------
 // The CUS workgroups of one worker each hold a slice of the private v and of every column; per
 // coordinate they exchange their partial dot products through a pair of 8-byte slots per
@@ -307,7 +333,8 @@ __device__ __forceinline__ float partner_sum(float mine, uint64_t *slots, int pa
 template <int MODEL, int T, int NR, int NL, bool CACHE_X, bool EXT = false, bool XVEC = true, int CUS = 1>
 __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
     const CdArgs a, const int64_t t_begin, const int64_t t_end, float *dv, const int64_t dv_stride,
-    int32_t *dirty, uint64_t *xch, const uint32_t seq_base, uint32_t *abort_flag, const int spin_limit)
+    int32_t *dirty, uint64_t *xch, const uint32_t seq_base, uint32_t *abort_flag, const int spin_limit,
+    uint64_t *alpha_old, const uint32_t stamp, const GuardState *guard, const int host_shift, double2 *wbook)
 {
     static_assert(CUS == 1 || (T == 1024 && !EXT && CACHE_X), "multi-unit workers: cached, on chip");
     constexpr int BLOCK = T == 64 ? 256 : T;
@@ -362,9 +389,13 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
     float vt = tid < tail ? a.v[(d4 << 2) + tid] : 0.0f;
     bool moved = false;
     int parity = 0;
-    for (int64_t t = t_begin + w; t < t_end; t += nworkers) {
+    float dreg = 0.0f;                                 // guard: change of the objective's terms in alpha
+    const bool idle = guard_sits_out(guard, host_shift, w);      // (the same in all parts of a worker)
+    unsigned int nsteps = 0;
+    for (int64_t t = t_begin + w; t < t_end && !idle; t += nworkers) {
         const int j = __builtin_amdgcn_readfirstlane((int)coord_at(a, t));
         if (j < 0) continue;
+        ++nsteps;
         const float *col = a.cv.col(j);
         const __amdgpu_buffer_rsrc_t rs_x =
             __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(col + slice), 0, vec_bytes, 0x00020000);
@@ -482,9 +513,19 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
             }
             vt = fmaf(xt, delta, vt);
             moved = true;
-            if (tid == 0 && part == 0) a.alpha[j] = now;
+            if (tid == 0 && part == 0) {
+                a.alpha[j] = now;
+                if (alpha_old) {                       // what undoing the pass needs, and what it is judged by
+                    alpha_old[t] = ((uint64_t)stamp << 32) | __float_as_uint(old);
+                    dreg += objective_term<MODEL>(a.mc, now, y) - objective_term<MODEL>(a.mc, old, y);
+                }
+            }
         }
     }
+    // the worker's books for the guard: what its steps changed in the objective's terms in alpha, and
+    // how many it took (one slot per worker, added up by the merge: thousands of atomic adds on one
+    // word at the end of a kernel cost more than the whole merge)
+    if (wbook && tid == 0 && part == 0) wbook[w] = make_double2((double)dreg, (double)nsteps);
     if (moved) {                                       // this worker's change of v
         int offo = off;
 #pragma unroll
@@ -523,11 +564,98 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
 // 16 partial sums are added in wavefront order.  dirty[] is uniform, so skipping a clean worker is
 // a scalar branch.  The buffers' rows are dv_stride (a multiple of 64) floats apart and hold
 // nothing meaningful past d, so the last chunk is cut to d when it is added.
+// The guard rides on this kernel.  The first merge of a pass keeps v as it was (snap) and its sum of
+// squares; the last merge adds up the new sum of squares, and the workgroup that finishes last
+// compares the objective before and after the pass: quad * (||v_new||^2 - ||v_old||^2) + the change of
+// the terms in alpha that the workers accumulated.  Exact steps cannot raise it; if it rose (beyond
+// rounding), steps collided, and that workgroup puts v and the pass's alpha_j back and counts a trip,
+// which the host reads (without waiting) before its next pass and halves its bound on concurrent steps.
+struct MergeGuard {
+    GuardState *st;            // nullptr: no guard
+    double *part;              // [0, blocks): old sums of squares, [blocks, 2 blocks): new ones
+    float *snap;               // v at the start of the pass
+    const uint64_t *alpha_old; // per position of the visiting order: (stamp of the pass that moved alpha_j, its old value)
+    uint32_t stamp;            // this pass's stamp: older entries belong to coordinates that did not move now
+    uint32_t *host_trips;      // host-visible copy of st->trips
+    double quad;               // factor of ||v||^2 in the objective
+    int first, last;           // this merge ends the first / the last sub-pass of the pass
+    int host_shift;            // halvings the host had applied when it cut the pass into sub-passes
+    double2 *wbook;            // per worker: (change of the objective's terms in alpha, steps taken) in the sub-pass
+};
+
+// The judgement of a pass, by one thread: did the objective rise (beyond rounding; a NaN counts)?
+// Keeps the guard's books: an undone pass is counted and asks for half as many concurrent steps
+// (shift + 1); four passes in a row that stand ask for twice as many again.  Both numbers are
+// mirrored into host-visible memory, which the host reads without waiting before it enqueues a pass.
+__device__ __forceinline__ bool guard_verdict(GuardState *st, uint32_t *host_words, double delta, double scale,
+                                              unsigned long long steps)
+{
+    const bool rose = !(delta <= 1e-6 * scale + 1e-30);
+    st->last_delta = delta;
+    st->dreg = 0.0;
+    st->arrived = 0;
+    st->steps_pass = 0;
+    if (!rose) st->steps_kept += steps;
+    uint32_t shift = st->shift;
+    if (rose) {
+        const uint32_t trips = st->trips + 1;
+        st->trips = trips;
+        __hip_atomic_store(host_words, trips, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+        if (shift < 30) ++shift;
+        st->clean = 0;
+    } else if (shift > 0 && ++st->clean >= 4) {
+        --shift;
+        st->clean = 0;
+    }
+    if (shift != st->shift) {
+        __hip_atomic_store(&st->shift, shift, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(host_words + 1, shift, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+    }
+    return rose;
+}
+
+__device__ __forceinline__ void guard_finish(const MergeGuard &g, const CdArgs &a, float *v, int64_t d)
+{
+    // (entered by every thread of the last workgroup to finish; all other workgroups' device-scope
+    // writes of v, snap and their partial sums were complete before their arrival was counted)
+    __shared__ double red[2][16];
+    __shared__ int verdict;
+    const int nb = gridDim.x;
+    double so = 0.0, sn = 0.0;
+    for (int i = threadIdx.x; i < nb; i += 1024) {
+        so += __hip_atomic_load(&g.part[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sn += __hip_atomic_load(&g.part[nb + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    so = wave_sum(so);
+    sn = wave_sum(sn);
+    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = so; red[1][threadIdx.x >> 6] = sn; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double o = 0.0, n = 0.0;
+        for (int w = 0; w < 16; ++w) { o += red[0][w]; n += red[1][w]; }
+        const double dreg = __hip_atomic_load(&g.st->dreg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const unsigned long long steps = __hip_atomic_load(&g.st->steps_pass, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        verdict = guard_verdict(g.st, g.host_trips, g.quad * (n - o) + dreg, g.quad * o + fabs(dreg), steps) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!verdict) return;
+    for (int64_t i = threadIdx.x; i < d; i += 1024)
+        __hip_atomic_store(&v[i], __hip_atomic_load(&g.snap[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    for (int64_t t = threadIdx.x; t < a.count; t += 1024) {
+        const uint64_t e = g.alpha_old[t];
+        if ((uint32_t)(e >> 32) != g.stamp) continue;
+        const int64_t j = coord_at(a, t);
+        if (j >= 0) a.alpha[j] = __uint_as_float((uint32_t)e);
+    }
+}
+
 __global__ __launch_bounds__(1024) void merge_workers_kernel(float *v, int64_t d, const float *dv,
                                                              int64_t dv_stride, const int32_t *dirty,
-                                                             int nworkers)
+                                                             int nworkers, const MergeGuard g, const CdArgs a)
 {
     __shared__ float4 part[16][64];
+    __shared__ int is_last;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int64_t k4 = (int64_t)blockIdx.x * 64 + lane;            // chunk of four elements
     const bool in = 4 * k4 < d;
@@ -535,28 +663,112 @@ __global__ __launch_bounds__(1024) void merge_workers_kernel(float *v, int64_t d
     const int64_t stride4 = dv_stride >> 2;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     auto add = [](float4 &x, const float4 y) { x.x += y.x; x.y += y.y; x.z += y.z; x.w += y.w; };
-    int g = w;
-    for (; g + 16 * 7 < nworkers; g += 16 * 8) {
+    int wk = w;
+    for (; wk + 16 * 7 < nworkers; wk += 16 * 8) {
         float4 t[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            t[u] = dirty[g + 16 * u] ? p[(int64_t)(g + 16 * u) * stride4] : make_float4(0.f, 0.f, 0.f, 0.f);
+            t[u] = dirty[wk + 16 * u] ? p[(int64_t)(wk + 16 * u) * stride4] : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
         for (int u = 0; u < 8; ++u) add(s, t[u]);
     }
-    for (; g < nworkers; g += 16)
-        if (dirty[g]) add(s, p[(int64_t)g * stride4]);
+    for (; wk < nworkers; wk += 16)
+        if (dirty[wk]) add(s, p[(int64_t)wk * stride4]);
     part[w][lane] = s;
     __syncthreads();
-    if (w == 0 && in) {
-        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (w == 0) {
+        double s_old = 0.0, s_new = 0.0;
+        if (in) {
+            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-        for (int u = 0; u < 16; ++u) add(t, part[u][lane]);
-        const int64_t k = 4 * k4;
-        if (t.x != 0.0f) v[k] += t.x;
-        if (k + 1 < d && t.y != 0.0f) v[k + 1] += t.y;
-        if (k + 2 < d && t.z != 0.0f) v[k + 2] += t.z;
-        if (k + 3 < d && t.w != 0.0f) v[k + 3] += t.w;
+            for (int u = 0; u < 16; ++u) add(t, part[u][lane]);
+            const int64_t k = 4 * k4;
+            if (!g.st) {
+                if (t.x != 0.0f) v[k] += t.x;
+                if (k + 1 < d && t.y != 0.0f) v[k + 1] += t.y;
+                if (k + 2 < d && t.z != 0.0f) v[k + 2] += t.z;
+                if (k + 3 < d && t.w != 0.0f) v[k + 3] += t.w;
+            } else {
+                float o[4], nw[4];
+                const float tt[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const bool ok = k + e < d;
+                    o[e] = ok ? v[k + e] : 0.0f;
+                    nw[e] = o[e] + tt[e];
+                    s_old += (double)o[e] * (double)o[e];
+                    s_new += (double)nw[e] * (double)nw[e];
+                }
+                // In the merge that ends the pass, v (and snap) go straight to device-coherent memory:
+                // the workgroup that judges the pass may have to overwrite v after all others, and
+                // does so without any cache-wide fence.  Whole 16-byte chunks in one store each
+                // (device-scope stores of single words are partial writes to memory, eight times slower).
+                const bool whole = k + 3 < d;
+                if (g.last && whole) {
+                    const int off = (int)(k * 4);
+                    coherent_store4(__builtin_amdgcn_make_buffer_rsrc(v, 0, (int)((d >> 2) << 4), 0x00020000), off,
+                                    make_float4(nw[0], nw[1], nw[2], nw[3]));
+                    if (g.first)
+                        coherent_store4(__builtin_amdgcn_make_buffer_rsrc(g.snap, 0, (int)((d >> 2) << 4), 0x00020000),
+                                        off, make_float4(o[0], o[1], o[2], o[3]));
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (k + e >= d) continue;
+                        if (g.last) {
+                            __hip_atomic_store(&v[k + e], nw[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            if (g.first) __hip_atomic_store(&g.snap[k + e], o[e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        } else {
+                            if (tt[e] != 0.0f) v[k + e] = nw[e];
+                            if (g.first) g.snap[k + e] = o[e];
+                        }
+                    }
+                }
+            }
+        }
+        if (g.st) {
+            s_old = wave_sum(s_old);
+            s_new = wave_sum(s_new);
+            if (lane == 0) {
+                if (g.first) __hip_atomic_store(&g.part[blockIdx.x], s_old, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (g.last)
+                    __hip_atomic_store(&g.part[gridDim.x + blockIdx.x], s_new, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    if (g.st && blockIdx.x == 0) {
+        // the workers' books of this sub-pass go into the pass's totals (one workgroup per merge does
+        // this, and merges follow each other, so plain arithmetic on the totals is safe; they are
+        // written at device scope because another workgroup of the last merge reads them)
+        __shared__ double bk[2][16];
+        double dr = 0.0, st = 0.0;
+        for (int i = threadIdx.x; i < nworkers; i += 1024) {
+            const double2 b = g.wbook[i];
+            dr += b.x;
+            st += b.y;
+        }
+        dr = wave_sum(dr);
+        st = wave_sum(st);
+        if (lane == 0) { bk[0][w] = dr; bk[1][w] = st; }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double x = 0.0, y = 0.0;
+            for (int u = 0; u < 16; ++u) { x += bk[0][u]; y += bk[1][u]; }
+            __hip_atomic_store(&g.st->dreg, g.st->dreg + x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __hip_atomic_store(&g.st->steps_pass, g.st->steps_pass + (unsigned long long)y, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+    if (g.st && g.last) {
+        // The workgroup that arrives last judges the pass.  No cache-wide fence: what one workgroup
+        // writes for another (partial sums, v, snap) is written with device-scope stores, the
+        // workgroup barrier lets them complete before the arrival is counted, and they are read with
+        // device-scope loads.
+        __syncthreads();
+        if (threadIdx.x == 0)
+            is_last = __hip_atomic_fetch_add(&g.st->arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == gridDim.x - 1;
+        __syncthreads();
+        if (is_last) guard_finish(g, a, v, d);
     }
 }
 
@@ -571,8 +783,22 @@ __global__ __launch_bounds__(1024) void merge_workers_kernel(float *v, int64_t d
 // For the sub-passes the chain of dependent round trips to memory -- order -> row -> entries -> v ->
 // adds -- is cut by one: cd_csr_plan_kernel resolves order and row for the whole pass beforehand.
 template <int MODEL>
-__global__ __launch_bounds__(256) void cd_csr_plan_kernel(const CdArgs a)
+__global__ __launch_bounds__(256) void cd_csr_plan_kernel(const CdArgs a, float *snap, double *part_old)
 {
+    if (snap) {
+        // guard of the pass: keep v as it is now, and its sum of squares (one partial per workgroup)
+        __shared__ double sh[4];
+        double sq = 0.0;
+        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < a.d; i += (int64_t)gridDim.x * 256) {
+            const float x = a.v[i];
+            snap[i] = x;
+            sq += (double)x * (double)x;
+        }
+        sq = wave_sum(sq);
+        if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = sq;
+        __syncthreads();
+        if (threadIdx.x == 0) part_old[blockIdx.x] = (sh[0] + sh[1]) + (sh[2] + sh[3]);
+    }
     const int64_t t = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= a.count) return;
     const int64_t j = coord_at(a, t);
@@ -587,9 +813,74 @@ __global__ __launch_bounds__(256) void cd_csr_plan_kernel(const CdArgs a)
     a.plan[t] = p;
 }
 
+// The guard at the end of a sparse pass (see MergeGuard): the new sum of squares of v and the change
+// of the objective's terms in alpha (old values from the plan), per workgroup; the workgroup that
+// finishes last compares the objective with the one before the pass and, if it rose, puts v and
+// the pass's alpha_j back.
+template <int MODEL>
+__global__ __launch_bounds__(1024) void cd_csr_guard_kernel(const CdArgs a, const MergeGuard g, const int nold)
+{
+    __shared__ double red[2][16];
+    __shared__ int is_last, verdict;
+    const int nb = gridDim.x;
+    double sq = 0.0, dreg = 0.0;
+    for (int64_t i = (int64_t)blockIdx.x * 1024 + threadIdx.x; i < a.d; i += (int64_t)nb * 1024) {
+        const double x = (double)a.v[i];
+        sq += x * x;
+    }
+    for (int64_t t = (int64_t)blockIdx.x * 1024 + threadIdx.x; t < a.count; t += (int64_t)nb * 1024) {
+        const CdPlan p = a.plan[t];
+        if (p.j >= 0)
+            dreg += (double)(objective_term<MODEL>(a.mc, a.alpha[p.j], p.y) - objective_term<MODEL>(a.mc, p.alpha, p.y));
+    }
+    sq = wave_sum(sq);
+    dreg = wave_sum(dreg);
+    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = sq; red[1][threadIdx.x >> 6] = dreg; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double x = 0.0, y = 0.0;
+        for (int w = 0; w < 16; ++w) { x += red[0][w]; y += red[1][w]; }
+        __hip_atomic_store(&g.part[nold + blockIdx.x], x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&g.part[nold + nb + blockIdx.x], y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();                                   // (the two stores have completed)
+    if (threadIdx.x == 0)
+        is_last = __hip_atomic_fetch_add(&g.st->arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)nb - 1;
+    __syncthreads();
+    if (!is_last) return;
+    double so = 0.0, sn = 0.0, dr = 0.0;
+    for (int i = threadIdx.x; i < nold; i += 1024) so += g.part[i];          // written by an earlier kernel
+    for (int i = threadIdx.x; i < nb; i += 1024) {
+        sn += __hip_atomic_load(&g.part[nold + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        dr += __hip_atomic_load(&g.part[nold + nb + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    so = wave_sum(so);
+    sn = wave_sum(sn);
+    dr = wave_sum(dr);
+    __shared__ double fin[3][16];
+    if ((threadIdx.x & 63) == 0) { fin[0][threadIdx.x >> 6] = so; fin[1][threadIdx.x >> 6] = sn; fin[2][threadIdx.x >> 6] = dr; }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double o = 0.0, n = 0.0, r = 0.0;
+        for (int w = 0; w < 16; ++w) { o += fin[0][w]; n += fin[1][w]; r += fin[2][w]; }
+        // (steps of a sparse pass: the positions of the plan, less the share of the groups that sat out)
+        const int e = (int)g.st->shift - g.host_shift;
+        verdict = guard_verdict(g.st, g.host_trips, g.quad * (n - o) + r, g.quad * o + fabs(r),
+                                (unsigned long long)(a.count >> (e > 0 ? e : 0))) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!verdict) return;
+    for (int64_t i = threadIdx.x; i < a.d; i += 1024) a.v[i] = g.snap[i];
+    for (int64_t t = threadIdx.x; t < a.count; t += 1024) {
+        const CdPlan p = a.plan[t];
+        if (p.j >= 0) a.alpha[p.j] = p.alpha;
+    }
+}
+
 // One exact step on the coordinate at position t of the visiting order, by a group of G lanes.
 template <int MODEL, int G, bool LIVE>
-__device__ __forceinline__ void csr_step(const CdArgs &a, int64_t t, int sub)
+__device__ __forceinline__ void csr_step(const CdArgs &a, int64_t t, int sub, const CdPlan &p)
 {
     int64_t j, beg, end;
     float old, qj, y;
@@ -604,7 +895,6 @@ __device__ __forceinline__ void csr_step(const CdArgs &a, int64_t t, int sub)
         qj = a.q[j];
         y = MODEL == DUHL_SVM ? a.target[j] : 0.0f;
     } else {
-        const CdPlan p = a.plan[t];
         j = p.j;
         if (j < 0) return;
         beg = p.beg;
@@ -655,13 +945,22 @@ __device__ __forceinline__ void csr_step(const CdArgs &a, int64_t t, int sub)
 }
 
 template <int MODEL, int G, bool LIVE>
-__global__ __launch_bounds__(256) void cd_csr_async_kernel(const CdArgs a, const int64_t t_begin, const int64_t t_end)
+__global__ __launch_bounds__(256) void cd_csr_async_kernel(const CdArgs a, const int64_t t_begin, const int64_t t_end,
+                                                           const GuardState *guard, const int host_shift)
 {
     const int sub = threadIdx.x % G;
     const int64_t ngroups = a.groups;              // idle groups of the last workgroup leave at once
     const int64_t first = (int64_t)blockIdx.x * (256 / G) + threadIdx.x / G;
     if (first >= ngroups) return;
-    for (int64_t t = t_begin + first; t < t_end; t += ngroups) csr_step<MODEL, G, LIVE>(a, t, sub);
+    // (the first plan record is asked for before the guard's word, so that the two loads overlap)
+    int64_t t = t_begin + first;
+    CdPlan p{};
+    if (!LIVE && t < t_end) p = a.plan[t];
+    if (guard_sits_out(guard, host_shift, first)) return;
+    for (; t < t_end; t += ngroups) {
+        if (!LIVE && t != t_begin + first) p = a.plan[t];
+        csr_step<MODEL, G, LIVE>(a, t, sub, p);
+    }
 }
 
 // ---- sequential ----------------------------------------------------------------------------------
@@ -733,6 +1032,93 @@ __global__ __launch_bounds__(64) void cd_csr_seq_kernel(const CdArgs a)
         if (lane == 0 && delta != 0.0f) a.alpha[j] = now;
         __syncthreads();
     }
+}
+
+// The host's view of the guard before it enqueues a pass: how many halvings of the library's bound on
+// concurrent steps the device asks for, read as it stands in host-visible memory -- no wait, so it
+// may lag behind the device by the passes in flight (what is missing the kernels make up for by
+// letting workers sit out, see guard_sits_out).
+void guard_update(duhl_ctx *c)
+{
+    if (!c->h_trips) return;
+    // While the bound is halved -- after set_data, or after a pass was undone -- the host does not run
+    // more than two passes ahead of the device: it waits for the pass before the last one, and so
+    // learns within two passes that the guard has doubled the bound again.  With the full bound in
+    // force nothing is waited for.
+    const int slot = (int)(c->guard_passes & 1);         // where the pass before the last one left its event
+    if (c->guard_shift > 0 && c->guard_passes >= 2 && c->ev_pass_no[slot] == c->guard_passes - 1)
+        (void)hipEventSynchronize(c->ev_pass[slot]);
+    c->guard_shift = (int)static_cast<volatile uint32_t *>(c->h_trips)[1];
+}
+
+// Marks the end of a guarded pass on the compute stream (see guard_update) -- only while the bound is
+// halved: an event between two passes costs about as much as a kernel launch.
+void guard_mark_pass(duhl_ctx *c)
+{
+    if (!c->guard) return;
+    const int slot = (int)(c->guard_passes & 1);
+    if (c->guard_shift > 0) {
+        hipEvent_t &ev = c->ev_pass[slot];
+        if (!ev && hipEventCreateWithFlags(&ev, hipEventDisableTiming) != hipSuccess) ev = nullptr;
+        if (ev && hipEventRecord(ev, c->compute) == hipSuccess) c->ev_pass_no[slot] = c->guard_passes + 1;
+    }
+    c->guard_passes++;
+}
+
+// Buffers of the guard (first use), and its arguments for a pass over `count` positions that needs
+// `nparts` per-workgroup partial sums.  st == nullptr in the result: no guard.
+hipError_t guard_prepare(duhl_ctx *c, int64_t count, int64_t nparts, MergeGuard *g, bool want_alpha_old = true)
+{
+    *g = MergeGuard{};
+    if (!c->cd_guard) return hipSuccess;
+    hipError_t e = hipSuccess;
+    if (!c->guard) {
+        e = hipMalloc(reinterpret_cast<void **>(&c->guard), sizeof(GuardState));
+        if (e == hipSuccess)
+            e = launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(c->guard), sizeof(GuardState) / 4, 0);
+        if (e == hipSuccess) e = hipMalloc(reinterpret_cast<void **>(&c->snap_pass_v), sizeof(float) * (size_t)(c->d + 4));
+        if (e == hipSuccess)
+            e = hipHostMalloc(reinterpret_cast<void **>(&c->h_trips), 2 * sizeof(uint32_t), hipHostMallocMapped);
+        if (e == hipSuccess) e = launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(&c->guard->shift), 1, c->guard_shift);
+        if (e == hipSuccess) {
+            c->h_trips[0] = 0;
+            c->h_trips[1] = (uint32_t)c->guard_shift;
+            e = hipHostGetDevicePointer(reinterpret_cast<void **>(&c->h_trips_dev), c->h_trips, 0);
+        }
+        if (e != hipSuccess) return e;
+    }
+    if (nparts > c->guard_part_cap) {
+        (void)hipFree(c->guard_part);
+        c->guard_part = nullptr;
+        c->guard_part_cap = 0;
+        e = hipMalloc(reinterpret_cast<void **>(&c->guard_part), sizeof(double) * (size_t)nparts);
+        if (e != hipSuccess) return e;
+        c->guard_part_cap = nparts;
+    }
+    if (want_alpha_old && count > c->alpha_old_cap) {
+        (void)hipFree(c->alpha_old);
+        c->alpha_old = nullptr;
+        c->alpha_old_cap = 0;
+        e = hipMalloc(reinterpret_cast<void **>(&c->alpha_old), sizeof(uint64_t) * (size_t)count);
+        if (e == hipSuccess) e = launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(c->alpha_old), 2 * count, 0);
+        if (e != hipSuccess) return e;
+        c->alpha_old_cap = count;
+    }
+    g->stamp = ++c->guard_stamp;
+    if (g->stamp == 0) g->stamp = ++c->guard_stamp;      // 0 marks entries that were never written
+    g->st = c->guard;
+    g->part = c->guard_part;
+    g->snap = c->snap_pass_v;
+    g->alpha_old = c->alpha_old;
+    g->host_trips = c->h_trips_dev;
+    g->quad = quad_scale(c->mc);
+    g->host_shift = c->guard_shift;
+    if (want_alpha_old && !c->guard_wbook) {               // dense workers: one slot each
+        e = hipMalloc(reinterpret_cast<void **>(&c->guard_wbook), sizeof(double2) * (size_t)(c->dv_workers + 16));
+        if (e != hipSuccess) return e;
+    }
+    g->wbook = c->guard_wbook;
+    return hipSuccess;
 }
 
 uint64_t splitmix64(uint64_t &s)
@@ -817,6 +1203,10 @@ int64_t inflight_limit(const duhl_ctx *c, int64_t count, int max_inflight)
         int64_t loose = (int64_t)(2.0 * (double)count / sigma((double)count));
         if (loose > count / 4) loose = count / 4;
         lim = lo > loose ? lo : loose;
+        // every pass that the guard had to undo halves the bound; four passes in a row that it let
+        // stand double it again (see guard_update)
+        lim >>= c->guard_shift < 40 ? c->guard_shift : 40;
+        if (lim < 1) lim = 1;
         // equal sub-passes rather than a short last one
         if (lim >= 1 && lim < count) {
             const int64_t S = (count + lim - 1) / lim;
@@ -841,10 +1231,10 @@ hipError_t launch_atomic(duhl_ctx *c, const CdArgs &a, int max_inflight, bool ve
         b.groups = inflight;
         if (G == 64)
             hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 64, true>), dim3(grid), dim3(256), 0, c->compute, b,
-                               (int64_t)0, a.count);
+                               (int64_t)0, a.count, (const GuardState *)nullptr, 0);
         else
             hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 16, true>), dim3(grid), dim3(256), 0, c->compute, b,
-                               (int64_t)0, a.count);
+                               (int64_t)0, a.count, (const GuardState *)nullptr, 0);
         return hipGetLastError();
     }
     const int T = threads_per_coordinate(c);
@@ -875,16 +1265,29 @@ hipError_t launch_csr_subpasses(duhl_ctx *c, const CdArgs &a, int max_inflight)
     }
     CdArgs b = a;
     b.plan = static_cast<CdPlan *>(c->cd_plan);
-    hipLaunchKernelGGL(cd_csr_plan_kernel<MODEL>, dim3((a.count + 255) / 256), dim3(256), 0, c->compute, b);
+    // guard: the plan kernel also keeps v and its sum of squares, a last kernel judges the pass
+    const int64_t plan_blocks = (a.count + 255) / 256;
+    int64_t end_blocks = ((a.d > a.count ? a.d : a.count) + 4095) / 4096;
+    if (end_blocks > 256) end_blocks = 256;
+    if (end_blocks < 1) end_blocks = 1;
+    MergeGuard g;
+    const hipError_t ge = guard_prepare(c, a.count, plan_blocks + 2 * end_blocks, &g, false);
+    if (ge != hipSuccess) return ge;
+    hipLaunchKernelGGL(cd_csr_plan_kernel<MODEL>, dim3(plan_blocks), dim3(256), 0, c->compute, b,
+                       g.st ? g.snap : nullptr, g.part);
     b.groups = inflight < cap ? inflight : cap;
     const int64_t grid = (b.groups + 256 / G - 1) / (256 / G);
     for (int64_t t0 = 0; t0 < a.count; t0 += inflight) {
         const int64_t t1 = t0 + inflight < a.count ? t0 + inflight : a.count;
         if (G == 64)
-            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 64, false>), dim3(grid), dim3(256), 0, c->compute, b, t0, t1);
+            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 64, false>), dim3(grid), dim3(256), 0, c->compute, b, t0, t1,
+                               (const GuardState *)g.st, c->guard_shift);
         else
-            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 16, false>), dim3(grid), dim3(256), 0, c->compute, b, t0, t1);
+            hipLaunchKernelGGL((cd_csr_async_kernel<MODEL, 16, false>), dim3(grid), dim3(256), 0, c->compute, b, t0, t1,
+                               (const GuardState *)g.st, c->guard_shift);
     }
+    if (g.st)
+        hipLaunchKernelGGL(cd_csr_guard_kernel<MODEL>, dim3(end_blocks), dim3(1024), 0, c->compute, b, g, (int)plan_blocks);
     return hipGetLastError();
 }
 
@@ -896,16 +1299,23 @@ hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
     // Workers per sub-pass: enough to fill the chip; several coordinates per worker once the
     // sub-pass is large, which keeps the private buffers a small fraction of the traffic.
     const int64_t cap = c->dv_workers;
+    const int64_t mblocks = (c->d + 255) / 256;
+    MergeGuard g;
+    const hipError_t ge = guard_prepare(c, a.count, 2 * mblocks, &g);
+    if (ge != hipSuccess) return ge;
     for (int64_t t0 = 0; t0 < a.count; t0 += inflight) {
         const int64_t t1 = t0 + inflight < a.count ? t0 + inflight : a.count;
         const int64_t len = t1 - t0;
         int64_t workers = len >= 4 * (int64_t)c->num_cu ? len / 4 : (len < c->num_cu ? len : c->num_cu);
         if (workers > cap) workers = cap;
         const int64_t grid = (workers + PER - 1) / PER;
+        g.first = t0 == 0;
+        g.last = t1 == a.count;
         hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, T, NR, NL, CACHE_X, EXT, XVEC>), dim3(grid), dim3(BLOCK), 0,
-                           c->compute, a, t0, t1, c->dv, c->dv_stride, c->dirty, nullptr, 0u, nullptr, 0);
-        hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 255) / 256), dim3(1024), 0, c->compute, a.v,
-                           c->d, c->dv, c->dv_stride, c->dirty, (int)(grid * PER));
+                           c->compute, a, t0, t1, c->dv, c->dv_stride, c->dirty, nullptr, 0u, nullptr, 0,
+                           g.st ? c->alpha_old : nullptr, g.stamp, g.st, c->guard_shift, g.wbook);
+        hipLaunchKernelGGL(merge_workers_kernel, dim3(mblocks), dim3(1024), 0, c->compute, a.v,
+                           c->d, c->dv, c->dv_stride, c->dirty, (int)(grid * PER), g, a);
     }
     return hipGetLastError();
 }
@@ -917,15 +1327,22 @@ hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
 template <int MODEL, int NR, int NL, int CUS, bool XVEC>
 hipError_t launch_multi_t(duhl_ctx *c, const CdArgs &a, int64_t inflight, int64_t workers)
 {
+    const int64_t mblocks = (c->d + 255) / 256;
+    MergeGuard g;
+    const hipError_t ge = guard_prepare(c, a.count, 2 * mblocks, &g);
+    if (ge != hipSuccess) return ge;
     for (int64_t t0 = 0; t0 < a.count; t0 += inflight) {
         const int64_t t1 = t0 + inflight < a.count ? t0 + inflight : a.count;
         const int64_t per_worker = (t1 - t0 + workers - 1) / workers;
+        g.first = t0 == 0;
+        g.last = t1 == a.count;
         hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, 1024, NR, NL, true, false, XVEC, CUS>),
                            dim3(workers * CUS), dim3(1024), 0, c->compute, a, t0, t1, c->dv, c->dv_stride,
-                           c->dirty, c->xch, c->xseq, &c->sel->cd_abort, c->cd_spin_limit);
+                           c->dirty, c->xch, c->xseq, &c->sel->cd_abort, c->cd_spin_limit,
+                           g.st ? c->alpha_old : nullptr, g.stamp, g.st, c->guard_shift, g.wbook);
         c->xseq += (uint32_t)per_worker + 2u;          // sequence numbers never repeat back to back
-        hipLaunchKernelGGL(merge_workers_kernel, dim3((c->d + 255) / 256), dim3(1024), 0, c->compute, a.v,
-                           c->d, c->dv, c->dv_stride, c->dirty, (int)workers);
+        hipLaunchKernelGGL(merge_workers_kernel, dim3(mblocks), dim3(1024), 0, c->compute, a.v,
+                           c->d, c->dv, c->dv_stride, c->dirty, (int)workers, g, a);
     }
     return hipGetLastError();
 }
@@ -1027,10 +1444,18 @@ hipError_t launch_cd_model(duhl_ctx *c, duhl_cd_mode mode, const CdArgs &a, int 
             hipLaunchKernelGGL((cd_dense_seq_kernel<MODEL, false>), dim3(1), dim3(1024), 0, c->compute, a);
         return hipGetLastError();
     }
-    if (mode == DUHL_CD_ASYNC && c->sparse) return launch_csr_subpasses<MODEL>(c, a, max_inflight);
+    if (mode == DUHL_CD_ASYNC) guard_update(c);
+    if (mode == DUHL_CD_ASYNC && c->sparse) {
+        const hipError_t err = launch_csr_subpasses<MODEL>(c, a, max_inflight);
+        guard_mark_pass(c);
+        return err;
+    }
     if (mode == DUHL_CD_ASYNC) {
         hipError_t err = hipSuccess;
-        if (launch_workers<MODEL>(c, a, max_inflight, vec, &err)) return err;
+        if (launch_workers<MODEL>(c, a, max_inflight, vec, &err)) {
+            guard_mark_pass(c);
+            return err;
+        }
     }
     return launch_atomic<MODEL>(c, a, max_inflight, vec);
 }

@@ -24,7 +24,7 @@ OK, EINVAL, ENOMEM, EHIP, ESTATE, EBUDGET = 0, -1, -2, -3, -4, -5
 EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_wait_limit", "duhl_set_data_dense", "duhl_set_data_dense_chunks", "duhl_set_data_csr", "duhl_gap", "duhl_select",
            "duhl_gap_dense_static",
            "duhl_select_rule_apply", "duhl_host_sample_begin", "duhl_host_sample_end",
-           "duhl_commit_swap", "duhl_cd_epoch", "duhl_run", "duhl_objective", "duhl_recompute_v", "duhl_get",
+           "duhl_commit_swap", "duhl_cd_epoch", "duhl_cd_stats", "duhl_run", "duhl_objective", "duhl_recompute_v", "duhl_get",
            "duhl_set", "duhl_device_ptr", "duhl_probe_stream_read", "duhl_selection_threshold",
            "duhl_resident_columns", "duhl_swap_stats",
            "duhl_working_set_size", "duhl_last_error",
@@ -76,6 +76,7 @@ def load():
     lib.duhl_host_sample_end.argtypes = [p, i32, C.POINTER(i64)]
     lib.duhl_commit_swap.argtypes = [p]
     lib.duhl_cd_epoch.argtypes = [p, i32, p, i64, C.c_uint64, i32]
+    lib.duhl_cd_stats.argtypes = [p, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
     lib.duhl_objective.argtypes = [p, C.POINTER(dbl)]
     lib.duhl_recompute_v.argtypes = [p]
     lib.duhl_get.argtypes = [p, i32, p, i64]
@@ -248,6 +249,13 @@ class Duhl:
         count = 0 if order is None else order.numel()
         self._chk(self.lib.duhl_cd_epoch(self._h, mode, self._list(order), count,
                                          C.c_uint64(seed), int(max_inflight)))
+
+    def cd_stats(self):
+        """(passes undone by the guard since the data were set, the library's bound on concurrent steps
+        now, coordinate steps of the passes that were let stand)."""
+        undone, now, kept = C.c_int64(0), C.c_int64(0), C.c_int64(0)
+        self._chk(self.lib.duhl_cd_stats(self._h, C.byref(undone), C.byref(now), C.byref(kept)))
+        return undone.value, now.value, kept.value
 
     def run(self, m, max_rounds, passes=1, mode=CD_ASYNC, gap_tol=-1.0, max_inflight=0, rule=SELECT_GAP,
             seed=0, check_every=1, sample=None, sample_per_round=0, host_threads=0, confirm=False,
