@@ -171,6 +171,7 @@ def measure_brief(name, rounds=10, host_threads=12):
         sample_host["cursor"] = 0
     ttg = time_to_gap(g, set_data, prob, m, 1e-3, 400, passes=passes, sample_idx=sample_idx, host_threads=threads,
                       sample_host=sample_host)
+    out["cd_guard"] = dict(zip(("passes_damped", "max_inflight_now"), g.cd_stats()[:2]))
     out["time_to_gap_s"] = ttg["abs_1e-3_s"]
     out["time_to_gap_rounds"] = ttg["rounds"]
     out["time_to_rel_gap_s"] = ttg["rel_1e-3_s"]
@@ -504,7 +505,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "fig5svm", "sec51lasso", "sec51svm"])
+    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg2clustered", "cfg3", "cfg4", "cfg5", "fig5svm", "sec51lasso",
+                                                            "sec51svm"])
     ap.add_argument("--scale", type=float, default=1.0, help="shrink n (and m) at fixed d")
     ap.add_argument("--host-memory", default="pageable", choices=["pageable", "pinned"],
                     help="host residency (cfg4): the matrix in ordinary host memory, staged by the library "
@@ -593,7 +595,7 @@ def main():
     # Coordinate steps that count: those of the passes the guard let stand, as the device counted them
     # (a pass undone because the objective rose is work thrown away, and a pass enqueued before the
     # host knew of a halving solves only part of its working set).  Per-update atomics are unguarded.
-    guard_undone, guard_inflight, steps_kept = g.cd_stats()
+    guard_undone, guard_inflight, steps_kept, _ = g.cd_stats()
     steps_done = steps_kept if args.cd_mode == "async" and os.environ.get("DUHL_CD_GUARD", "1") != "0" \
         else m * total_passes
     passes_timed = None if auto is None else list(auto["passes"])
@@ -671,7 +673,7 @@ def main():
         "after_timed_rounds": {"total_gap": final_gap, "objective": final_obj},
         # the device-side guard of the concurrent passes: passes undone because the objective had risen
         # (since the data were set for the timed rounds), and the bound on concurrent steps now
-        "cd_guard": {"passes_undone": guard_undone, "max_inflight_now": guard_inflight, "steps_kept": steps_kept,
+        "cd_guard": {"passes_damped": guard_undone, "max_inflight_now": guard_inflight, "steps_kept": steps_kept,
                      "steps_enqueued": m * total_passes},
         "gen_s": prob["gen_s"],
     }
@@ -731,7 +733,7 @@ def main():
         gc.collect()
         torch.cuda.empty_cache()
         out["other_workloads"] = {}
-        for name in ("cfg1", "cfg2", "cfg3", "cfg4"):
+        for name in ("cfg1", "cfg2", "cfg2clustered", "cfg3", "cfg4"):
             log(f"other workloads: {name}")
             try:
                 out["other_workloads"][name] = measure_brief(name, host_threads=args.host_sampler_threads)

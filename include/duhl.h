@@ -240,15 +240,24 @@ duhl_status duhl_commit_swap(duhl_ctx *ctx);
  * sigma(L) <= 2 (concurrent exact steps still contract), or 2*count/sigma(count) capped at count/4
  * if that is more.  Strongly correlated columns tolerate fewer concurrent steps -- in particular
  * groups of near-duplicate columns that a selection by gap gathers, which the mean correlation does
- * not show.  DUHL_CD_ASYNC is therefore guarded on the device: exact coordinate steps never raise
- * the objective, so each pass compares the objective before and after (sums that its own kernels
- * form on the way), and a pass after which it is higher is undone -- v and the alpha_j it visited
- * go back to what they were -- and counted; the library's own bound (max_inflight = 0) is halved
- * for every pass undone, and doubled again after four passes in a row that stood.  The host learns
- * of it without waiting; in passes it had already enqueued with the old bound, part of the workers
- * sit each sub-pass out instead, so that such a pass solves a random half (quarter, ...) of its
- * working set: the objective never increases from pass to pass, whatever the data, and keeps
- * descending however far the host runs ahead of the device.  duhl_cd_stats reports the counts.
+ * not show.  DUHL_CD_ASYNC is therefore guarded on the device.  Each pass is judged as one step
+ * from the old iterate to the new one: from sums that its own kernels form on the way -- <v, dv>,
+ * ||dv||^2 and the change of the objective's terms in alpha -- the guard finds theta*, the point on
+ * that line where a bound on the objective (exact in its quadratic part, the chord of its convex
+ * terms in alpha) is smallest.  Sequential exact steps give theta* >= 1; k-fold overshoot of
+ * colliding steps gives about 1/k, and below 1/2 the pass has raised the objective.  A pass with
+ * theta* < 0.55 is scaled back to theta* -- v and the alpha_j it visited are blended with their old
+ * values, so the objective never rises from pass to pass, whatever the data -- and counted, and the
+ * bound on concurrent steps (the library's own, or max_inflight) is halved; it is doubled again
+ * after 4 passes with theta* >= 0.8 and no damped one between them, then after 8, 16, ... (a level
+ * that failed once is tried again ever later).  v is held in fp32: a pass whose ||dv||^2 does not stand clear of the
+ * rounding of v (steps below about 1e-3 of ||v||, near convergence) cannot be judged this way;
+ * it is undone only if the objective rose by more than 1e-6 of its value and otherwise changes
+ * nothing in the books once a pass has been damped, so the bound found while the steps were large
+ * stays in force.  The host
+ * learns of a halving without waiting; in passes it had already enqueued with the old bound, part
+ * of the workers sit each sub-pass out instead, so that such a pass solves a random half
+ * (quarter, ...) of its working set.  duhl_cd_stats reports the counts.
  * DUHL_CD_ATOMIC is not guarded.
  *   DUHL_CD_ATOMIC  each step reads the live v and adds a_j*delta to it with fp32 atomics;
  *                   iterates depend on timing.
@@ -268,14 +277,16 @@ duhl_status duhl_commit_swap(duhl_ctx *ctx);
 duhl_status duhl_cd_epoch(duhl_ctx *ctx, duhl_cd_mode mode, const int32_t *order,
                           int64_t n_order, uint64_t seed, int max_inflight);
 
-/* The guard of DUHL_CD_ASYNC (see duhl_cd_epoch), since the data were set: passes_undone = passes
- * put back because the objective had risen; inflight_now = the bound on concurrent steps the
- * library would choose now for a pass over the current working set (max_inflight = 0);
- * steps_kept = coordinate steps taken by the passes that were let stand (a pass enqueued before the
+/* The guard of DUHL_CD_ASYNC (see duhl_cd_epoch), since the data were set: passes_damped = passes
+ * scaled back (or undone) because their steps overshot; inflight_now = the bound on concurrent steps
+ * the library would choose now for a pass over the current working set (max_inflight = 0);
+ * steps_kept = coordinate steps taken by the passes that were not undone (a pass enqueued before the
  * host knew of a halving solves only part of its working set, see duhl_cd_epoch; dense data:
- * counted, sparse data: the pass's length less the share that sat out).  All host, each may be NULL.
+ * counted, sparse data: the pass's length less the share that sat out); last_theta = theta* of the
+ * last guarded pass (1 if it could not be judged).  All host, each may be NULL.
  * Waits for the compute stream. */
-duhl_status duhl_cd_stats(duhl_ctx *ctx, int64_t *passes_undone, int64_t *inflight_now, int64_t *steps_kept);
+duhl_status duhl_cd_stats(duhl_ctx *ctx, int64_t *passes_damped, int64_t *inflight_now, int64_t *steps_kept,
+                          double *last_theta);
 
 /* The outer loop, run natively: Algorithm 1 with the selection of eq. (11) when every gap is
  * refreshed each round, Algorithm 2 (selection by eq. (13) on a gap memory that may be stale,

@@ -282,6 +282,7 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->cd_spin_limit = env_int("DUHL_CD_SPIN_LIMIT", 1 << 22);
     if (c->cd_spin_limit < 0) c->cd_spin_limit = 0;
     c->cd_guard = env_int("DUHL_CD_GUARD", 1);
+    c->guard_tol = 1e-6;
     c->select_spin_limit = env_int("DUHL_SELECT_SPIN_LIMIT", 1 << 22);
     if (c->select_spin_limit < 0) c->select_spin_limit = 0;
     c->select_groups = env_int("DUHL_SELECT_GROUPS", 0);
@@ -508,21 +509,22 @@ duhl_status duhl_cd_epoch(duhl_ctx *c, duhl_cd_mode mode, const int32_t *order, 
     return DUHL_OK;
 }
 
-duhl_status duhl_cd_stats(duhl_ctx *c, int64_t *passes_undone, int64_t *inflight_now, int64_t *steps_kept)
+duhl_status duhl_cd_stats(duhl_ctx *c, int64_t *passes_damped, int64_t *inflight_now, int64_t *steps_kept,
+                          double *last_theta)
 {
     if (!c) return DUHL_EINVAL;
     if (!c->have_data) return fail(c, DUHL_ESTATE, "no data set");
     HIPCHK(c, hipSetDevice(c->device));
     HIPCHK(c, hipStreamSynchronize(c->compute));
-    if (passes_undone) *passes_undone = c->h_trips ? (int64_t)*static_cast<volatile uint32_t *>(c->h_trips) : 0;
+    if (passes_damped) *passes_damped = c->h_trips ? (int64_t)*static_cast<volatile uint32_t *>(c->h_trips) : 0;
     if (inflight_now) *inflight_now = c->m_cur > 0 ? default_inflight(c, c->m_cur) : 0;
-    if (steps_kept) {
-        *steps_kept = 0;
-        if (c->guard) {
-            GuardState gs;
-            HIPCHK(c, hipMemcpy(&gs, c->guard, sizeof gs, hipMemcpyDeviceToHost));
-            *steps_kept = (int64_t)gs.steps_kept;
-        }
+    if (steps_kept) *steps_kept = 0;
+    if (last_theta) *last_theta = 1.0;
+    if ((steps_kept || last_theta) && c->guard) {
+        GuardState gs;
+        HIPCHK(c, hipMemcpy(&gs, c->guard, sizeof gs, hipMemcpyDeviceToHost));
+        if (steps_kept) *steps_kept = (int64_t)gs.steps_kept;
+        if (last_theta && gs.steps_kept + gs.trips > 0) *last_theta = gs.last_theta;
     }
     return DUHL_OK;
 }

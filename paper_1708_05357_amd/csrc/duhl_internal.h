@@ -146,6 +146,16 @@ __device__ __forceinline__ float objective_term(const ModelConst &mc, float alph
         return mc.inv_d * fmaf(0.5f * mc.lam_eta * alpha, alpha, mc.lam_l1 * fabsf(alpha));
     return -mc.inv_n * y * alpha;
 }
+// objective_term(now) - objective_term(old) without the cancellation of two rounded terms.
+template <int MODEL>
+__device__ __forceinline__ double objective_term_change(const ModelConst &mc, float now, float old, float y)
+{
+    const double dn = (double)now, dol = (double)old;
+    if (MODEL == DUHL_LASSO) return (double)mc.Lam * (double)mc.inv_d * (fabs(dn) - fabs(dol));
+    if (MODEL == DUHL_ELASTIC_NET)
+        return (double)mc.inv_d * (0.5 * (double)mc.lam_eta * (dn - dol) * (dn + dol) + (double)mc.lam_l1 * (fabs(dn) - fabs(dol)));
+    return -(double)mc.inv_n * (double)y * (dn - dol);
+}
 // Factor of ||v||^2 in the objective: 1/(2d), or 1/(2 lambda n^2) for the SVM dual.
 inline double quad_scale(const ModelConst &mc)
 {
@@ -246,17 +256,25 @@ struct SelectState {
     uint32_t pad[2];
 };
 
-// Device state of the guard of the concurrent passes: exact coordinate steps never raise the
-// objective, so a pass after which it is higher was spoilt by steps that collided, and is undone.
+// Device state of the guard of the concurrent passes.  Exact coordinate steps never raise the
+// objective; steps taken at once on columns that are alike overshoot together.  The guard looks at
+// the pass as one step from (alpha, v) to (alpha + D, v + Dv): along that line the objective is
+// bounded by  theta * lin + theta^2 * curv  above its old value (the quadratic part exactly, the
+// convex terms in alpha by their chord), which is smallest at theta* = -lin / (2 curv).  theta* >= 1
+// is what sequential steps give; theta* near 1/k means k-fold overshoot, and below 1/2 the pass
+// has raised the objective.
 struct GuardState {
     double dreg;            // the pass so far: change of the objective's terms in alpha (regulariser / linear term)
-    double last_delta;      // objective change of the last guarded pass (as measured, before any undoing)
+    double last_delta;      // objective change of the last guarded pass (as measured, before any damping)
+    double last_theta;      // theta* of the last guarded pass (1 when too small a step to tell)
     uint32_t arrived;       // workgroups of the finishing kernel that are done (the last one decides)
-    uint32_t trips;         // passes undone since the data were set
-    uint32_t shift;         // halvings of the bound on concurrent steps now asked for: +1 per undone pass,
-    uint32_t clean;         // -1 after four passes in a row (counted here) that were let stand
+    uint32_t trips;         // passes damped (scaled back to theta* < 1, or undone) since the data were set
+    uint32_t shift;         // halvings of the bound on concurrent steps now asked for: +1 per damped pass,
+    uint32_t clean;         // -1 after `need` passes in a row (counted here) with theta* near 1
+    uint32_t need;          // 0 stands for 4; doubles with every damped pass (a level that failed is tried again later and later)
+    uint32_t pad;
     unsigned long long steps_pass;   // coordinate steps taken by the pass so far
-    unsigned long long steps_kept;   // coordinate steps of all passes that were let stand, since the data were set
+    unsigned long long steps_kept;   // coordinate steps of all passes that were not undone, since the data were set
 };
 
 }  // namespace duhl
@@ -324,6 +342,7 @@ struct duhl_ctx {
     uint32_t *h_trips;          // pinned, device-writable: GuardState::trips and ::shift as the host may read
     uint32_t *h_trips_dev;      // them without waiting ([0], [1])
     int cd_guard;               // 0: guard switched off (DUHL_CD_GUARD)
+    double guard_tol;           // relative rise of the objective that still counts as rounding
     int guard_shift;            // halvings of the library's bound on concurrent steps that the host applies
     hipEvent_t ev_pass[2];      // behind the last two guarded passes: while the bound is halved the host stays
     uint64_t guard_passes;      // at most two passes ahead of the device, so that it sees the bound recover

@@ -389,7 +389,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
     float vt = tid < tail ? a.v[(d4 << 2) + tid] : 0.0f;
     bool moved = false;
     int parity = 0;
-    float dreg = 0.0f;                                 // guard: change of the objective's terms in alpha
+    double dreg = 0.0;                                 // guard: change of the objective's terms in alpha
     const bool idle = guard_sits_out(guard, host_shift, w);      // (the same in all parts of a worker)
     unsigned int nsteps = 0;
     for (int64_t t = t_begin + w; t < t_end && !idle; t += nworkers) {
@@ -517,7 +517,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
                 a.alpha[j] = now;
                 if (alpha_old) {                       // what undoing the pass needs, and what it is judged by
                     alpha_old[t] = ((uint64_t)stamp << 32) | __float_as_uint(old);
-                    dreg += objective_term<MODEL>(a.mc, now, y) - objective_term<MODEL>(a.mc, old, y);
+                    dreg += objective_term_change<MODEL>(a.mc, now, old, y);
                 }
             }
         }
@@ -525,7 +525,7 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
     // the worker's books for the guard: what its steps changed in the objective's terms in alpha, and
     // how many it took (one slot per worker, added up by the merge: thousands of atomic adds on one
     // word at the end of a kernel cost more than the whole merge)
-    if (wbook && tid == 0 && part == 0) wbook[w] = make_double2((double)dreg, (double)nsteps);
+    if (wbook && tid == 0 && part == 0) wbook[w] = make_double2(dreg, (double)nsteps);
     if (moved) {                                       // this worker's change of v
         int offo = off;
 #pragma unroll
@@ -565,45 +565,74 @@ __global__ __launch_bounds__(T == 64 ? 256 : T) void cd_dense_worker_kernel(
 // a scalar branch.  The buffers' rows are dv_stride (a multiple of 64) floats apart and hold
 // nothing meaningful past d, so the last chunk is cut to d when it is added.
 // The guard rides on this kernel.  The first merge of a pass keeps v as it was (snap) and its sum of
-// squares; the last merge adds up the new sum of squares, and the workgroup that finishes last
-// compares the objective before and after the pass: quad * (||v_new||^2 - ||v_old||^2) + the change of
-// the terms in alpha that the workers accumulated.  Exact steps cannot raise it; if it rose (beyond
-// rounding), steps collided, and that workgroup puts v and the pass's alpha_j back and counts a trip,
-// which the host reads (without waiting) before its next pass and halves its bound on concurrent steps.
+// squares; the last merge adds up <snap, v - snap> and ||v - snap||^2, and the workgroup that finishes
+// last judges the pass from them and from the change of the terms in alpha that the workers
+// accumulated (see GuardState).  A pass that overshot is scaled back to its best point on the line
+// from the old iterate -- v and the pass's alpha_j are blended with their old values -- and counts a
+// trip, which the host reads (without waiting) before its next pass and halves its bound on
+// concurrent steps.
 struct MergeGuard {
     GuardState *st;            // nullptr: no guard
-    double *part;              // [0, blocks): old sums of squares, [blocks, 2 blocks): new ones
+    double *part;              // per workgroup: [0, blocks) old sums of squares, then <snap, dv>, then ||dv||^2
     float *snap;               // v at the start of the pass
     const uint64_t *alpha_old; // per position of the visiting order: (stamp of the pass that moved alpha_j, its old value)
     uint32_t stamp;            // this pass's stamp: older entries belong to coordinates that did not move now
     uint32_t *host_trips;      // host-visible copy of st->trips
     double quad;               // factor of ||v||^2 in the objective
+    double tol;                // a rise below tol * (objective's magnitude) is taken for rounding
+    double per_step;           // roundings that one coordinate step causes per element of v, on average
     int first, last;           // this merge ends the first / the last sub-pass of the pass
     int host_shift;            // halvings the host had applied when it cut the pass into sub-passes
     double2 *wbook;            // per worker: (change of the objective's terms in alpha, steps taken) in the sub-pass
 };
 
-// The judgement of a pass, by one thread: did the objective rise (beyond rounding; a NaN counts)?
-// Keeps the guard's books: an undone pass is counted and asks for half as many concurrent steps
-// (shift + 1); four passes in a row that stand ask for twice as many again.  Both numbers are
-// mirrored into host-visible memory, which the host reads without waiting before it enqueues a pass.
-__device__ __forceinline__ bool guard_verdict(GuardState *st, uint32_t *host_words, double delta, double scale,
-                                              unsigned long long steps)
+// The judgement of a pass, by one thread; returns the factor theta by which the pass is to be kept
+// (1: as it is, 0: undone).  o = ||v_old||^2, pd = <v_old, dv>, pq = ||dv||^2, dreg = change of the
+// terms in alpha.  v is held in fp32: every step rounds it, so <v_old, dv> carries noise of about
+// eps/2 * o * sqrt(roundings per element / d), and theta* is only read when ||dv||^2 stands well
+// above that; a pass too small to tell leaves the books as they are (the bound found while the steps
+// were large stays).  Keeps the guard's books: a pass with theta* < 0.55 is damped, counted, and asks
+// for half as many concurrent steps (shift + 1); `need` passes with theta* >= 0.8 and no damped one
+// between them ask for twice as many again, and need doubles with every damped pass.  trips and shift are mirrored into host-visible
+// memory, which the host reads without waiting before it enqueues a pass.
+__device__ __forceinline__ double guard_verdict(GuardState *st, uint32_t *host_words, const MergeGuard &g, double inv_d,
+                                                double o, double pd, double pq, double dreg, unsigned long long steps)
 {
-    const bool rose = !(delta <= 1e-6 * scale + 1e-30);
+    const double lin = 2.0 * g.quad * pd + dreg, curv = g.quad * pq;
+    const double delta = lin + curv;                              // the objective's change at theta = 1
+    const double rounds = fmax(1.0, (double)steps * g.per_step);
+    const double noise = 0.5 * 1.1920929e-7 * o * sqrt(rounds * inv_d);
+    double theta = 1.0;
+    bool told = false;
+    if (!(fabs(lin) < 1e300) || !(curv < 1e300)) {
+        theta = 0.0;                                              // not a number, or infinite
+    } else if (pq > 16.0 * noise) {
+        told = true;
+        theta = fmin(1.0, fmax(0.0, -lin / (2.0 * curv)));
+    } else if (delta > g.tol * (g.quad * o + fabs(dreg))) {
+        theta = 0.0;                                              // a rise that rounding does not explain
+    }
     st->last_delta = delta;
+    st->last_theta = theta;
     st->dreg = 0.0;
     st->arrived = 0;
     st->steps_pass = 0;
-    if (!rose) st->steps_kept += steps;
+    const bool damp = theta < 0.55;
+    // credit towards a larger bound: a pass that was seen to step about right -- or, while no pass
+    // has ever been damped, any pass (the halved bound of the start is then only a precaution)
+    const bool credit = told ? theta >= 0.8 : st->trips == 0;
+    if (!damp) theta = 1.0;                                       // (past 1/2 the full step still descends)
+    if (theta > 0.0) st->steps_kept += steps;
     uint32_t shift = st->shift;
-    if (rose) {
+    const uint32_t need = st->need ? st->need : 4u;
+    if (damp) {
         const uint32_t trips = st->trips + 1;
         st->trips = trips;
         __hip_atomic_store(host_words, trips, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
         if (shift < 30) ++shift;
         st->clean = 0;
-    } else if (shift > 0 && ++st->clean >= 4) {
+        st->need = need < 1024u ? 2u * need : need;
+    } else if (credit && shift > 0 && ++st->clean >= need) {
         --shift;
         st->clean = 0;
     }
@@ -611,42 +640,49 @@ __device__ __forceinline__ bool guard_verdict(GuardState *st, uint32_t *host_wor
         __hip_atomic_store(&st->shift, shift, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(host_words + 1, shift, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
-    return rose;
+    return theta;
 }
 
 __device__ __forceinline__ void guard_finish(const MergeGuard &g, const CdArgs &a, float *v, int64_t d)
 {
     // (entered by every thread of the last workgroup to finish; all other workgroups' device-scope
     // writes of v, snap and their partial sums were complete before their arrival was counted)
-    __shared__ double red[2][16];
-    __shared__ int verdict;
+    __shared__ double red[3][16];
+    __shared__ double verdict;
     const int nb = gridDim.x;
-    double so = 0.0, sn = 0.0;
+    double so = 0.0, sd = 0.0, sq = 0.0;
     for (int i = threadIdx.x; i < nb; i += 1024) {
         so += __hip_atomic_load(&g.part[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sn += __hip_atomic_load(&g.part[nb + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sd += __hip_atomic_load(&g.part[nb + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sq += __hip_atomic_load(&g.part[2 * nb + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     so = wave_sum(so);
-    sn = wave_sum(sn);
-    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = so; red[1][threadIdx.x >> 6] = sn; }
+    sd = wave_sum(sd);
+    sq = wave_sum(sq);
+    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = so; red[1][threadIdx.x >> 6] = sd; red[2][threadIdx.x >> 6] = sq; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        double o = 0.0, n = 0.0;
-        for (int w = 0; w < 16; ++w) { o += red[0][w]; n += red[1][w]; }
+        double o = 0.0, pd = 0.0, pq = 0.0;
+        for (int w = 0; w < 16; ++w) { o += red[0][w]; pd += red[1][w]; pq += red[2][w]; }
         const double dreg = __hip_atomic_load(&g.st->dreg, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         const unsigned long long steps = __hip_atomic_load(&g.st->steps_pass, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        verdict = guard_verdict(g.st, g.host_trips, g.quad * (n - o) + dreg, g.quad * o + fabs(dreg), steps) ? 1 : 0;
+        verdict = guard_verdict(g.st, g.host_trips, g, 1.0 / (double)d, o, pd, pq, dreg, steps);
     }
     __syncthreads();
-    if (!verdict) return;
-    for (int64_t i = threadIdx.x; i < d; i += 1024)
-        __hip_atomic_store(&v[i], __hip_atomic_load(&g.snap[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const float theta = (float)verdict;
+    if (theta >= 1.0f) return;
+    for (int64_t i = threadIdx.x; i < d; i += 1024) {
+        const float was = __hip_atomic_load(&g.snap[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const float is = __hip_atomic_load(&v[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&v[i], theta > 0.0f ? fmaf(theta, is - was, was) : was, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     for (int64_t t = threadIdx.x; t < a.count; t += 1024) {
         const uint64_t e = g.alpha_old[t];
         if ((uint32_t)(e >> 32) != g.stamp) continue;
         const int64_t j = coord_at(a, t);
-        if (j >= 0) a.alpha[j] = __uint_as_float((uint32_t)e);
+        if (j < 0) continue;
+        const float was = __uint_as_float((uint32_t)e);
+        a.alpha[j] = theta > 0.0f ? fmaf(theta, a.alpha[j] - was, was) : was;
     }
 }
 
@@ -677,7 +713,7 @@ __global__ __launch_bounds__(1024) void merge_workers_kernel(float *v, int64_t d
     part[w][lane] = s;
     __syncthreads();
     if (w == 0) {
-        double s_old = 0.0, s_new = 0.0;
+        double s_old = 0.0, s_lin = 0.0, s_sq = 0.0;
         if (in) {
             float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
@@ -697,7 +733,26 @@ __global__ __launch_bounds__(1024) void merge_workers_kernel(float *v, int64_t d
                     o[e] = ok ? v[k + e] : 0.0f;
                     nw[e] = o[e] + tt[e];
                     s_old += (double)o[e] * (double)o[e];
-                    s_new += (double)nw[e] * (double)nw[e];
+                }
+                if (g.last) {
+                    // against v at the start of the pass (this merge's own input if it is also the first)
+                    float4 was = make_float4(o[0], o[1], o[2], o[3]);
+                    if (!g.first) {
+                        if (k + 3 < d) was = *reinterpret_cast<const float4 *>(g.snap + k);
+                        else {
+                            was.x = g.snap[k];
+                            was.y = k + 1 < d ? g.snap[k + 1] : 0.0f;
+                            was.z = k + 2 < d ? g.snap[k + 2] : 0.0f;
+                            was.w = 0.0f;
+                        }
+                    }
+                    const float ws[4] = {was.x, was.y, was.z, was.w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const double dv_e = k + e < d ? (double)nw[e] - (double)ws[e] : 0.0;
+                        s_lin += (double)ws[e] * dv_e;
+                        s_sq += dv_e * dv_e;
+                    }
                 }
                 // In the merge that ends the pass, v (and snap) go straight to device-coherent memory:
                 // the workgroup that judges the pass may have to overwrite v after all others, and
@@ -728,11 +783,16 @@ __global__ __launch_bounds__(1024) void merge_workers_kernel(float *v, int64_t d
         }
         if (g.st) {
             s_old = wave_sum(s_old);
-            s_new = wave_sum(s_new);
+            if (g.last) {
+                s_lin = wave_sum(s_lin);
+                s_sq = wave_sum(s_sq);
+            }
             if (lane == 0) {
                 if (g.first) __hip_atomic_store(&g.part[blockIdx.x], s_old, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (g.last)
-                    __hip_atomic_store(&g.part[gridDim.x + blockIdx.x], s_new, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (g.last) {
+                    __hip_atomic_store(&g.part[gridDim.x + blockIdx.x], s_lin, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_store(&g.part[2 * gridDim.x + blockIdx.x], s_sq, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
             }
         }
     }
@@ -813,68 +873,85 @@ __global__ __launch_bounds__(256) void cd_csr_plan_kernel(const CdArgs a, float 
     a.plan[t] = p;
 }
 
-// The guard at the end of a sparse pass (see MergeGuard): the new sum of squares of v and the change
-// of the objective's terms in alpha (old values from the plan), per workgroup; the workgroup that
-// finishes last compares the objective with the one before the pass and, if it rose, puts v and
-// the pass's alpha_j back.
+// The guard at the end of a sparse pass (see MergeGuard): <snap, v - snap>, ||v - snap||^2 and the
+// change of the objective's terms in alpha (old values from the plan), per workgroup; the workgroup
+// that finishes last judges the pass and, if it overshot, blends v and the pass's alpha_j with
+// their old values.
 template <int MODEL>
 __global__ __launch_bounds__(1024) void cd_csr_guard_kernel(const CdArgs a, const MergeGuard g, const int nold)
 {
-    __shared__ double red[2][16];
-    __shared__ int is_last, verdict;
+    __shared__ double red[3][16];
+    __shared__ int is_last;
+    __shared__ double verdict;
     const int nb = gridDim.x;
-    double sq = 0.0, dreg = 0.0;
+    double sd = 0.0, sq = 0.0, dreg = 0.0;
     for (int64_t i = (int64_t)blockIdx.x * 1024 + threadIdx.x; i < a.d; i += (int64_t)nb * 1024) {
-        const double x = (double)a.v[i];
-        sq += x * x;
+        const double was = (double)g.snap[i];
+        const double dv = (double)a.v[i] - was;
+        sd += was * dv;
+        sq += dv * dv;
     }
     for (int64_t t = (int64_t)blockIdx.x * 1024 + threadIdx.x; t < a.count; t += (int64_t)nb * 1024) {
         const CdPlan p = a.plan[t];
-        if (p.j >= 0)
-            dreg += (double)(objective_term<MODEL>(a.mc, a.alpha[p.j], p.y) - objective_term<MODEL>(a.mc, p.alpha, p.y));
+        if (p.j >= 0) dreg += objective_term_change<MODEL>(a.mc, a.alpha[p.j], p.alpha, p.y);
     }
+    sd = wave_sum(sd);
     sq = wave_sum(sq);
     dreg = wave_sum(dreg);
-    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = sq; red[1][threadIdx.x >> 6] = dreg; }
+    if ((threadIdx.x & 63) == 0) { red[0][threadIdx.x >> 6] = sd; red[1][threadIdx.x >> 6] = sq; red[2][threadIdx.x >> 6] = dreg; }
     __syncthreads();
     if (threadIdx.x == 0) {
-        double x = 0.0, y = 0.0;
-        for (int w = 0; w < 16; ++w) { x += red[0][w]; y += red[1][w]; }
+        double x = 0.0, y = 0.0, z = 0.0;
+        for (int w = 0; w < 16; ++w) { x += red[0][w]; y += red[1][w]; z += red[2][w]; }
         __hip_atomic_store(&g.part[nold + blockIdx.x], x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __hip_atomic_store(&g.part[nold + nb + blockIdx.x], y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(&g.part[nold + 2 * nb + blockIdx.x], z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
-    __syncthreads();                                   // (the two stores have completed)
+    __syncthreads();                                   // (the stores have completed)
     if (threadIdx.x == 0)
         is_last = __hip_atomic_fetch_add(&g.st->arrived, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == (uint32_t)nb - 1;
     __syncthreads();
     if (!is_last) return;
-    double so = 0.0, sn = 0.0, dr = 0.0;
+    double so = 0.0, dr = 0.0;
+    sd = sq = 0.0;
     for (int i = threadIdx.x; i < nold; i += 1024) so += g.part[i];          // written by an earlier kernel
     for (int i = threadIdx.x; i < nb; i += 1024) {
-        sn += __hip_atomic_load(&g.part[nold + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        dr += __hip_atomic_load(&g.part[nold + nb + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sd += __hip_atomic_load(&g.part[nold + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sq += __hip_atomic_load(&g.part[nold + nb + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        dr += __hip_atomic_load(&g.part[nold + 2 * nb + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     __syncthreads();
     so = wave_sum(so);
-    sn = wave_sum(sn);
+    sd = wave_sum(sd);
+    sq = wave_sum(sq);
     dr = wave_sum(dr);
-    __shared__ double fin[3][16];
-    if ((threadIdx.x & 63) == 0) { fin[0][threadIdx.x >> 6] = so; fin[1][threadIdx.x >> 6] = sn; fin[2][threadIdx.x >> 6] = dr; }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        double o = 0.0, n = 0.0, r = 0.0;
-        for (int w = 0; w < 16; ++w) { o += fin[0][w]; n += fin[1][w]; r += fin[2][w]; }
-        // (steps of a sparse pass: the positions of the plan, less the share of the groups that sat out)
-        const int e = (int)g.st->shift - g.host_shift;
-        verdict = guard_verdict(g.st, g.host_trips, g.quad * (n - o) + r, g.quad * o + fabs(r),
-                                (unsigned long long)(a.count >> (e > 0 ? e : 0))) ? 1 : 0;
+    __shared__ double fin[4][16];
+    if ((threadIdx.x & 63) == 0) {
+        fin[0][threadIdx.x >> 6] = so;
+        fin[1][threadIdx.x >> 6] = sd;
+        fin[2][threadIdx.x >> 6] = sq;
+        fin[3][threadIdx.x >> 6] = dr;
     }
     __syncthreads();
-    if (!verdict) return;
-    for (int64_t i = threadIdx.x; i < a.d; i += 1024) a.v[i] = g.snap[i];
+    if (threadIdx.x == 0) {
+        double o = 0.0, pd = 0.0, pq = 0.0, r = 0.0;
+        for (int w = 0; w < 16; ++w) { o += fin[0][w]; pd += fin[1][w]; pq += fin[2][w]; r += fin[3][w]; }
+        // (steps of a sparse pass: the positions of the plan, less the share of the groups that sat out)
+        const int e = (int)g.st->shift - g.host_shift;
+        verdict = guard_verdict(g.st, g.host_trips, g, 1.0 / (double)a.d, o, pd, pq, r,
+                                (unsigned long long)(a.count >> (e > 0 ? e : 0)));
+    }
+    __syncthreads();
+    const float theta = (float)verdict;
+    if (theta >= 1.0f) return;
+    // (other workgroups of this kernel only read v and alpha, and are done)
+    for (int64_t i = threadIdx.x; i < a.d; i += 1024) {
+        const float was = g.snap[i];
+        a.v[i] = theta > 0.0f ? fmaf(theta, a.v[i] - was, was) : was;
+    }
     for (int64_t t = threadIdx.x; t < a.count; t += 1024) {
         const CdPlan p = a.plan[t];
-        if (p.j >= 0) a.alpha[p.j] = p.alpha;
+        if (p.j >= 0) a.alpha[p.j] = theta > 0.0f ? fmaf(theta, a.alpha[p.j] - p.alpha, p.alpha) : p.alpha;
     }
 }
 
@@ -1112,6 +1189,9 @@ hipError_t guard_prepare(duhl_ctx *c, int64_t count, int64_t nparts, MergeGuard 
     g->alpha_old = c->alpha_old;
     g->host_trips = c->h_trips_dev;
     g->quad = quad_scale(c->mc);
+    g->tol = c->guard_tol;
+    // a dense step rounds every element of the worker's v once; a sparse one the elements of its row
+    g->per_step = c->sparse && c->n > 0 && c->d > 0 ? (double)c->nnz / ((double)c->n * (double)c->d) : 1.0;
     g->host_shift = c->guard_shift;
     if (want_alpha_old && !c->guard_wbook) {               // dense workers: one slot each
         e = hipMalloc(reinterpret_cast<void **>(&c->guard_wbook), sizeof(double2) * (size_t)(c->dv_workers + 16));
@@ -1183,7 +1263,8 @@ int64_t inflight_limit(const duhl_ctx *c, int64_t count, int max_inflight)
 {
     int64_t lim;
     if (max_inflight > 0) {
-        lim = max_inflight;
+        lim = max_inflight;                              // the caller's bound, halved like the library's own
+        lim >>= c->guard_shift < 40 ? c->guard_shift : 40;
     } else {
         // Two estimates, the larger wins.  (i) The largest group L whose block-Jacobi step is
         // still a contraction: sigma(L) = (1 + sqrt(L/d))^2 + (L - 1) * mean cosine <= 2 (the
@@ -1271,7 +1352,7 @@ hipError_t launch_csr_subpasses(duhl_ctx *c, const CdArgs &a, int max_inflight)
     if (end_blocks > 256) end_blocks = 256;
     if (end_blocks < 1) end_blocks = 1;
     MergeGuard g;
-    const hipError_t ge = guard_prepare(c, a.count, plan_blocks + 2 * end_blocks, &g, false);
+    const hipError_t ge = guard_prepare(c, a.count, plan_blocks + 3 * end_blocks, &g, false);
     if (ge != hipSuccess) return ge;
     hipLaunchKernelGGL(cd_csr_plan_kernel<MODEL>, dim3(plan_blocks), dim3(256), 0, c->compute, b,
                        g.st ? g.snap : nullptr, g.part);
@@ -1301,7 +1382,7 @@ hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
     const int64_t cap = c->dv_workers;
     const int64_t mblocks = (c->d + 255) / 256;
     MergeGuard g;
-    const hipError_t ge = guard_prepare(c, a.count, 2 * mblocks, &g);
+    const hipError_t ge = guard_prepare(c, a.count, 3 * mblocks, &g);
     if (ge != hipSuccess) return ge;
     for (int64_t t0 = 0; t0 < a.count; t0 += inflight) {
         const int64_t t1 = t0 + inflight < a.count ? t0 + inflight : a.count;
@@ -1329,7 +1410,7 @@ hipError_t launch_multi_t(duhl_ctx *c, const CdArgs &a, int64_t inflight, int64_
 {
     const int64_t mblocks = (c->d + 255) / 256;
     MergeGuard g;
-    const hipError_t ge = guard_prepare(c, a.count, 2 * mblocks, &g);
+    const hipError_t ge = guard_prepare(c, a.count, 3 * mblocks, &g);
     if (ge != hipSuccess) return ge;
     for (int64_t t0 = 0; t0 < a.count; t0 += inflight) {
         const int64_t t1 = t0 + inflight < a.count ? t0 + inflight : a.count;

@@ -76,7 +76,7 @@ def load():
     lib.duhl_host_sample_end.argtypes = [p, i32, C.POINTER(i64)]
     lib.duhl_commit_swap.argtypes = [p]
     lib.duhl_cd_epoch.argtypes = [p, i32, p, i64, C.c_uint64, i32]
-    lib.duhl_cd_stats.argtypes = [p, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]
+    lib.duhl_cd_stats.argtypes = [p, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64), C.POINTER(C.c_double)]
     lib.duhl_objective.argtypes = [p, C.POINTER(dbl)]
     lib.duhl_recompute_v.argtypes = [p]
     lib.duhl_get.argtypes = [p, i32, p, i64]
@@ -251,11 +251,11 @@ class Duhl:
                                          C.c_uint64(seed), int(max_inflight)))
 
     def cd_stats(self):
-        """(passes undone by the guard since the data were set, the library's bound on concurrent steps
-        now, coordinate steps of the passes that were let stand)."""
-        undone, now, kept = C.c_int64(0), C.c_int64(0), C.c_int64(0)
-        self._chk(self.lib.duhl_cd_stats(self._h, C.byref(undone), C.byref(now), C.byref(kept)))
-        return undone.value, now.value, kept.value
+        """(passes damped by the guard since the data were set, the library's bound on concurrent steps
+        now, coordinate steps of the passes that were not undone, theta* of the last guarded pass)."""
+        damped, now, kept, theta = C.c_int64(0), C.c_int64(0), C.c_int64(0), C.c_double(1.0)
+        self._chk(self.lib.duhl_cd_stats(self._h, C.byref(damped), C.byref(now), C.byref(kept), C.byref(theta)))
+        return damped.value, now.value, kept.value, theta.value
 
     def run(self, m, max_rounds, passes=1, mode=CD_ASYNC, gap_tol=-1.0, max_inflight=0, rule=SELECT_GAP,
             seed=0, check_every=1, sample=None, sample_per_round=0, host_threads=0, confirm=False,

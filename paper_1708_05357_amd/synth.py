@@ -85,20 +85,23 @@ def lasso_dense(d, n, support_frac, c_lambda, seed=0, device="cpu", out=None, bl
             "alpha_star": alpha_star}
 
 
-def lasso_clustered(d, n, clusters, spread, support_frac=0.05, c_lambda=0.1, seed=0, noise=0.01):
+def lasso_clustered(d, n, clusters, spread, support_frac=0.05, c_lambda=0.1, seed=0, noise=0.01, device="cpu"):
     """Dense Lasso instance whose columns come in `clusters` groups of near-duplicates: column j is
     the centre of group j mod clusters plus `spread` times N(0,1) noise, scaled to unit norm (cosine
     within a group about 1/(1+spread^2), between groups about 0).  Features of real datasets are
     often this alike; a working set chosen by gap then gathers whole groups.  alpha*, b and lambda
-    as in lasso_dense.  CPU tensors."""
-    g = _gen(seed, "cpu")
-    centres = torch.randn((clusters, d), generator=g, dtype=torch.float32)
-    cols = centres[torch.arange(n) % clusters] + spread * torch.randn((n, d), generator=g, dtype=torch.float32)
+    as in lasso_dense."""
+    dev = torch.device(device)
+    g = _gen(seed, dev)
+    centres = torch.randn((clusters, d), generator=g, dtype=torch.float32, device=dev)
+    cols = torch.randn((n, d), generator=g, dtype=torch.float32, device=dev)
+    cols *= spread
+    cols += centres[torch.arange(n, device=dev) % clusters]
     cols /= cols.norm(dim=1, keepdim=True)
     k = int(math.floor(support_frac * n))
-    alpha_star = torch.zeros(n, dtype=torch.float32)
-    alpha_star[torch.randperm(n, generator=g)[:k]] = torch.randn(k, generator=g, dtype=torch.float32)
-    b = cols.t() @ alpha_star + noise * torch.randn(d, generator=g, dtype=torch.float32)
+    alpha_star = torch.zeros(n, dtype=torch.float32, device=dev)
+    alpha_star[torch.randperm(n, generator=g, device=dev)[:k]] = torch.randn(k, generator=g, dtype=torch.float32, device=dev)
+    b = cols.t() @ alpha_star + noise * torch.randn(d, generator=g, dtype=torch.float32, device=dev)
     lam = c_lambda * float((cols @ b).abs().max()) / d
     return {"model": "lasso", "d": d, "n": n, "cols": cols.contiguous(), "target": b, "lam": lam,
             "alpha_star": alpha_star}
@@ -182,6 +185,10 @@ CONFIGS = {
                  m=20_000, rounds=20, host_resident=True),
     "cfg5": dict(kind="lasso_dense", d=50_000, n=500_000, support_frac=0.005, c_lambda=0.05,
                  m=50_000, rounds=20),
+    # the 2 GB workload with correlated features, as real feature matrices have them (Section 5.3 uses
+    # image features): 1,250 groups of 40 near-duplicate columns (cosine about 0.9 within a group)
+    "cfg2clustered": dict(kind="lasso_clustered", d=10_000, n=50_000, clusters=1_250, spread=0.3,
+                          support_frac=0.02, c_lambda=0.05, m=5_000, rounds=50),
     # the shape of the paper's large-scale SVM experiment (Section 5.3: 40,000 samples with 200,704
     # dense single-precision features, 30 GB, a quarter of them on the accelerator)
     "fig5svm": dict(kind="svm_dense", n=40_000, d=200_704, m=10_000, rounds=20),
@@ -205,6 +212,8 @@ def make(name, seed=0, device="cpu", scale=1.0, out=None):
         m = max(1, int(m * scale))
     if kind == "lasso_dense":
         p = lasso_dense(seed=seed, device=device, out=out, **cfg)
+    elif kind == "lasso_clustered":
+        p = lasso_clustered(seed=seed, device=device, **cfg)
     elif kind == "svm_dense":
         p = svm_dense(seed=seed, device=device, **cfg)
     else:
