@@ -163,6 +163,11 @@ def measure_brief(name, rounds=10, host_threads=12):
            "gap_GBps": gap_bytes / (gap_ms * 1e-3) / 1e9, "gap_frac": gap_bytes / (gap_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
            "cd_updates_per_s": m / (cd_ms * 1e-3), "cd_GBps": cd_bytes / (cd_ms * 1e-3) / 1e9,
            "cd_frac": cd_bytes / (cd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+    if "val" in prob:
+        nnz_pass = float(prob["val"].numel()) / prob["n"] * (steps_kept / (passes * rounds))
+        rate = g.probe_scatter_add(20_000_000, reps=3)
+        out["cd_scatter_add_bound"] = {"adds_per_pass": nnz_pass, "adds_per_s_measured_peak": rate,
+                                       "floor_ms": nnz_pass / rate * 1e3, "frac": nnz_pass / rate * 1e3 / cd_ms}
     if host:
         sw = [x for x in swap_log if "columns" in x]
         out["columns_swapped_per_round"] = [x["columns"] for x in sw]
@@ -629,6 +634,15 @@ def main():
         stream_gbps = prob["cols"].numel() * 4.0 / (g.probe_stream_read(prob["cols"], reps=3) * 1e-3) / 1e9
     final_obj = g.objective()
     gap_kernels, cd_kernels = dominant_kernels(prob, args.cd_mode)
+    # yardstick of the CSR pass: one fp32 atomic add to v per non-zero of every row stepped on; the
+    # device performs such adds at a fixed rate, measured here on this problem's own v
+    scatter = None
+    if "val" in prob:
+        nnz_pass = float(prob["val"].numel()) / prob["n"] * m * (steps_done / (m * total_passes))
+        rate = g.probe_scatter_add(20_000_000, reps=3)
+        pass_ms = avg(cd_ms) / (total_passes / args.steps)
+        scatter = {"adds_per_pass": nnz_pass, "adds_per_s_measured_peak": rate, "floor_ms": nnz_pass / rate * 1e3,
+                   "achieved_adds_per_s": nnz_pass / (pass_ms * 1e-3), "frac": nnz_pass / rate * 1e3 / pass_ms}
 
     out = {
         "metric": "coordinate updates/s (whole round: gap pass + top-m + CD pass)",
@@ -669,7 +683,8 @@ def main():
                         "traffic": counter_traffic(args.workload, "cd_pass", cd_kernels)
                         if args.scale == 1.0 and args.cd_mode == "async" and args.inflight == 0 else None,
                         "algorithmic_bytes": cd_bytes, "avg_launch_ms": avg(cd_ms),
-                        "frac_of_stream_read": cd_gbps / stream_gbps if stream_gbps else None},
+                        "frac_of_stream_read": cd_gbps / stream_gbps if stream_gbps else None,
+                        "scatter_add_bound": scatter},
         "after_timed_rounds": {"total_gap": final_gap, "objective": final_obj},
         # the device-side guard of the concurrent passes: passes undone because the objective had risen
         # (since the data were set for the timed rounds), and the bound on concurrent steps now

@@ -377,6 +377,14 @@ duhl_status duhl_device_ptr(duhl_ctx *ctx, duhl_what what, void **ptr);
 duhl_status duhl_probe_stream_read(duhl_ctx *ctx, const void *dev, int64_t bytes, int reps,
                                    double *best_ms);
 
+/* Measurement aid, no part of the method: `ops` (rounded up to a multiple of the grid) fp32 atomic
+ * adds of +0 to pseudo-random elements of v -- which leave v as it is -- `reps` times on the
+ * compute stream; adds_per_s (host) = the best rate.  It is the yardstick of the concurrent pass on
+ * CSR data (Appendix D's update of v, one atomic add per non-zero of a step's row): the device
+ * performs such adds at a fixed rate however many threads issue them, and a pass cannot take less
+ * than its non-zeros divided by that rate.  Waits.  DUHL_ESTATE before the data are set. */
+duhl_status duhl_probe_scatter_add(duhl_ctx *ctx, int64_t ops, int reps, double *adds_per_s);
+
 /* The threshold of the last selection (eq. (13)): the smallest score among the selected
  * coordinates -- for DUHL_SELECT_GAP the m-th largest entry of the gap memory z as the selection
  * saw it (entries equal to it are taken in index order until m are chosen).  threshold: host.

@@ -415,6 +415,7 @@ hipError_t launch_corr_sample(duhl_ctx *c, float *u, int samples);
 hipError_t launch_validate(duhl_ctx *c);
 hipError_t launch_check_norms(duhl_ctx *c);
 hipError_t launch_stream_read(duhl_ctx *c, const void *dev, int64_t bytes, float *sink);
+hipError_t launch_scatter_add(duhl_ctx *c, int64_t ops, int64_t *done);
 hipError_t launch_fill_i32(hipStream_t s, int32_t *p, int64_t n, int32_t value);
 hipError_t launch_fill_f32(hipStream_t s, float *p, int64_t n, float value);
 hipError_t launch_sum_partials(duhl_ctx *c, int64_t count, int scalar_slot);

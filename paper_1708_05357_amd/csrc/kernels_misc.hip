@@ -294,6 +294,30 @@ hipError_t launch_stream_read(duhl_ctx *c, const void *dev, int64_t bytes, float
     return hipGetLastError();
 }
 
+// Scatter yardstick: fp32 atomic adds of +0 to pseudo-random elements of x (which they leave as it
+// is), `per` from each of the grid's threads -- the memory operation behind the concurrent steps on
+// CSR data, with nothing else around it.
+__global__ __launch_bounds__(256) void scatter_add_kernel(float *x, uint32_t n, int per)
+{
+    const uint32_t tid = blockIdx.x * 256u + threadIdx.x;
+    for (int k = 0; k < per; ++k) {
+        uint32_t h = tid * 0x9e3779b9u + (uint32_t)k * 0x85ebca6bu;
+        h ^= h >> 16; h *= 0x7feb352du; h ^= h >> 15; h *= 0x846ca68bu; h ^= h >> 16;
+        (void)__hip_atomic_fetch_add(x + h % n, 0.0f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+hipError_t launch_scatter_add(duhl_ctx *c, int64_t ops, int64_t *done)
+{
+    const int64_t threads = (int64_t)c->num_cu * 8 * 256;
+    int64_t per = (ops + threads - 1) / threads;
+    if (per < 1) per = 1;
+    if (per > (1 << 20)) per = 1 << 20;
+    *done = per * threads;
+    hipLaunchKernelGGL(scatter_add_kernel, dim3(c->num_cu * 8), dim3(256), 0, c->compute, c->v, (uint32_t)c->d, (int)per);
+    return hipGetLastError();
+}
+
 hipError_t launch_validate(duhl_ctx *c)
 {
     const int64_t len = c->d > c->n ? c->d : c->n;

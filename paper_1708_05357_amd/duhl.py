@@ -25,7 +25,7 @@ EXPORTS = ["duhl_create", "duhl_set_eta", "duhl_set_wait_limit", "duhl_set_data_
            "duhl_gap_dense_static",
            "duhl_select_rule_apply", "duhl_host_sample_begin", "duhl_host_sample_end",
            "duhl_commit_swap", "duhl_cd_epoch", "duhl_cd_stats", "duhl_run", "duhl_objective", "duhl_recompute_v", "duhl_get",
-           "duhl_set", "duhl_device_ptr", "duhl_probe_stream_read", "duhl_selection_threshold",
+           "duhl_set", "duhl_device_ptr", "duhl_probe_stream_read", "duhl_probe_scatter_add", "duhl_selection_threshold",
            "duhl_resident_columns", "duhl_swap_stats",
            "duhl_working_set_size", "duhl_last_error",
            "duhl_destroy"]
@@ -92,6 +92,7 @@ def load():
     lib.duhl_destroy.argtypes = [p]
     lib.duhl_destroy.restype = None
     lib.duhl_probe_stream_read.argtypes = [p, p, i64, i32, C.POINTER(dbl)]
+    lib.duhl_probe_scatter_add.argtypes = [p, i64, i32, C.POINTER(dbl)]
     lib.duhl_run.argtypes = [p, C.POINTER(RunOpts), C.POINTER(RunStats)]
     lib.duhl_gap_dense_static.argtypes = [i32, i64, i64, p, i64, p, p, p, dbl, dbl, dbl, p, i64, p, p, i32, p,
                                           C.c_char_p, i64]
@@ -296,6 +297,12 @@ class Duhl:
         self._chk(self.lib.duhl_probe_stream_read(self._h, C.c_void_p(tensor.data_ptr()), nbytes, int(reps),
                                                   C.byref(ms)))
         return ms.value
+
+    def probe_scatter_add(self, ops, reps=3):
+        """Best rate (adds per second) of fp32 atomic adds to random elements of v (adds of +0: v stays)."""
+        rate = C.c_double(0.0)
+        self._chk(self.lib.duhl_probe_scatter_add(self._h, int(ops), int(reps), C.byref(rate)))
+        return rate.value
 
     def selection_threshold(self):
         """Smallest score of the last selection: the m-th largest entry of z it saw (eq. (13))."""
