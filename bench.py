@@ -245,7 +245,7 @@ def one_step(g, prob, m, step, ev=None, sample_idx=None, mode=1, inflight=0, swa
         perm, cur, k = sample_host["perm"], sample_host["cursor"], sample_host["k"]
         g.host_sample_begin(perm[cur:cur + k], host_threads)
     for k in range(passes):                     # passes per round: the accuracy knob theta (Section 5.2)
-        g.cd_epoch(mode, seed=step * (passes if auto is None else 8) + k, max_inflight=inflight)
+        g.cd_epoch(mode, seed=step * (passes if auto is None else 1000) + k, max_inflight=inflight)
     if ev:
         ev[3].record()
     if on_host:
@@ -539,6 +539,7 @@ def main():
                          "up to 8, as fit beside the round's column copies; default 1, and 8 with host "
                          "residency, where the passes are also the time unit A's sampler has per round")
     ap.add_argument("--min-passes", type=int, default=1, help="lower bound for --passes 0")
+    ap.add_argument("--max-passes", type=int, default=8, help="upper bound for --passes 0")
     ap.add_argument("--gap-sample", type=float, default=1.0,
                     help="device residency: refresh only the working set and this fraction of all "
                          "coordinates per round (stale gap memory, Section 4.1) instead of every gap")
@@ -555,7 +556,11 @@ def main():
     if args.host_sampler_threads < 0:
         args.host_sampler_threads = 12
     if args.passes is None:
-        args.passes = 8 if args.workload == "cfg4" else 1
+        # host residency: at least 8 passes per round, and as many more as fit beside the round's column
+        # copies (theta sized to the copy, Section 5.2) -- the device would otherwise wait for the link
+        args.passes = 0 if args.workload == "cfg4" else 1
+        if args.workload == "cfg4":
+            args.min_passes, args.max_passes = max(args.min_passes, 8), max(args.max_passes, 96)
     import torch
     from paper_1708_05357_amd import duhl
     assert torch.cuda.is_available(), "bench.py needs a GPU"
@@ -582,7 +587,7 @@ def main():
         e1.record(g.compute_stream)
         torch.cuda.synchronize()
         # 55 GB/s: what the copy kernel sustains on the host link of the test machines
-        auto = {"cd_ms": e0.elapsed_time(e1), "link_GBps": 55.0, "max_passes": 8, "passes": [],
+        auto = {"cd_ms": e0.elapsed_time(e1), "link_GBps": 55.0, "max_passes": args.max_passes, "passes": [],
                 "min_passes": args.min_passes}
     set_data()                                  # back to alpha = 0: the timed rounds are rounds 1..K
     torch.cuda.synchronize()
@@ -729,7 +734,8 @@ def main():
         if prob["host_resident"]:
             perm_dev = torch.as_tensor(sample_host["perm"][:prob["n"]], device="cuda").contiguous()
         out["time_to_gap_native"] = time_to_gap_native(g, set_data, prob, m, 1e-3, mode, args.inflight, rule,
-                                                       args.passes, perm_dev, args.host_sampler_threads)
+                                                       args.passes if args.passes > 0 else args.min_passes, perm_dev,
+                                                       args.host_sampler_threads)
     if not args.no_cpu:
         log("CPU baseline (oracle, one thread, about 20 s)")
         out["cpu_baseline"] = cpu_baseline(prob, m)

@@ -282,6 +282,7 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->cd_spin_limit = env_int("DUHL_CD_SPIN_LIMIT", 1 << 22);
     if (c->cd_spin_limit < 0) c->cd_spin_limit = 0;
     c->cd_guard = env_int("DUHL_CD_GUARD", 1);
+    c->keep_first_pass = env_int("DUHL_KEEP_FIRST_PASS", 1);
     c->guard_tol = 1e-6;
     c->select_spin_limit = env_int("DUHL_SELECT_SPIN_LIMIT", 1 << 22);
     if (c->select_spin_limit < 0) c->select_spin_limit = 0;

@@ -253,7 +253,8 @@ struct SelectState {
     uint32_t n_evict;    // evictable slots found
     uint32_t error;      // validation flags
     uint32_t cd_abort;   // set by a workgroup that gave up waiting for others (selection barrier, CD partners)
-    uint32_t pad[2];
+    uint32_t n_kept;     // slots claimed by the columns kept during the first pass over a staged matrix
+    uint32_t pad;
 };
 
 // Device state of the guard of the concurrent passes.  Exact coordinate steps never raise the
@@ -341,6 +342,8 @@ struct duhl_ctx {
     int64_t alpha_old_cap;
     uint32_t *h_trips;          // pinned, device-writable: GuardState::trips and ::shift as the host may read
     uint32_t *h_trips_dev;      // them without waiting ([0], [1])
+    int keep_first_pass;        // 0: the first pass over a staged matrix keeps no columns (DUHL_KEEP_FIRST_PASS)
+    int64_t kept_first_pass;    // columns that pass left in device slots
     int cd_guard;               // 0: guard switched off (DUHL_CD_GUARD)
     double guard_tol;           // relative rise of the objective that still counts as rounding
     int guard_shift;            // halvings of the library's bound on concurrent steps that the host applies
@@ -446,6 +449,7 @@ hipError_t launch_gap_batch(duhl_ctx *c, const StageBatch &b, const int32_t *idx
 hipError_t launch_corr_batch(duhl_ctx *c, const StageBatch &b, const int32_t *idx, float *u);
 hipError_t launch_accumulate_batch(duhl_ctx *c, const StageBatch &b, const int32_t *idx);
 hipError_t launch_copy_batch(duhl_ctx *c, const StageBatch &b);
+hipError_t launch_keep_batch(duhl_ctx *c, const StageBatch &b, int64_t first, float tau);
 
 hipError_t csr_blocked_build(duhl_ctx *c);
 void csr_blocked_free(duhl_ctx *c);

@@ -10,6 +10,7 @@
 // compute stream; a background thread drives the column swap on the copy stream, so that
 // duhl_select returns at once and the passes on the current working set overlap the copies (Figure 2).
 // A buffer is refilled only after the kernel that read it has finished (one event per buffer).
+#include <algorithm>
 #include <atomic>
 #include <condition_variable>
 #include <cstdlib>
@@ -297,12 +298,45 @@ hipError_t staged_gap(duhl_ctx *c, const int32_t *idx, int64_t first, int64_t co
         if (e != hipSuccess) return e;
         list = st->list.data();
     }
+    // The first pass over the whole matrix (set_data) also fills the device slots: once the gaps of
+    // the first twentieth of the columns are out, their (1 - f)-quantile is taken for the threshold
+    // above which a fraction f of all columns lies -- f chosen to fill about 0.9 of the slots -- and
+    // every later batch leaves its columns above it on the device (launch_keep_batch).
+    const bool keep = with_norms && !idx && first == 0 && count == c->n && c->keep_first_pass && c->slots;
+    const int64_t probe = keep ? std::max<int64_t>(std::min<int64_t>(c->n, 2048), c->n / 20) : 0;
+    bool have_tau = false;
+    float tau = 0.0f;
+    if (keep) {
+        hipError_t e = launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(&c->sel->n_kept), 1, 0);
+        if (e != hipSuccess) return e;
+    }
     bool first_batch = true;
-    return staged_pass(c, st->fg, c->compute, list, first, count, [&](const StageBatch &b) {
-        const hipError_t e = launch_gap_batch(c, b, idx, first, with_norms, first_batch);
+    hipError_t e = staged_pass(c, st->fg, c->compute, list, first, count, [&](const StageBatch &b) {
+        hipError_t e = hipSuccess;
+        if (keep && !have_tau && b.k0 >= probe && c->n > b.k0) {
+            std::vector<float> zs((size_t)b.k0);
+            e = hipMemcpyAsync(zs.data(), c->z, sizeof(float) * zs.size(), hipMemcpyDeviceToHost, c->compute);
+            if (e == hipSuccess) e = hipStreamSynchronize(c->compute);
+            if (e != hipSuccess) return e;
+            double f = 0.9 * (double)c->budget / (double)(c->n - b.k0);
+            if (f > 1.0) f = 1.0;
+            size_t rank = (size_t)((1.0 - f) * (double)zs.size());
+            if (rank >= zs.size()) rank = zs.size() - 1;
+            std::nth_element(zs.begin(), zs.begin() + (std::ptrdiff_t)rank, zs.end());
+            tau = zs[rank];
+            have_tau = true;
+        }
+        e = launch_gap_batch(c, b, idx, first, with_norms, first_batch);
         first_batch = false;
+        if (e == hipSuccess && have_tau) e = launch_keep_batch(c, b, first, tau);
         return e;
     });
+    if (e == hipSuccess && keep) {
+        e = hipMemcpyAsync(c->h_u32 + 3, &c->sel->n_kept, sizeof(uint32_t), hipMemcpyDeviceToHost, c->compute);
+        if (e == hipSuccess) e = hipStreamSynchronize(c->compute);
+        if (e == hipSuccess) c->kept_first_pass = c->h_u32[3] < (uint32_t)c->budget ? c->h_u32[3] : c->budget;
+    }
+    return e;
 }
 
 // A host-made list of coordinates, also put on the device for the kernels.

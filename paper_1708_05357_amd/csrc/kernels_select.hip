@@ -424,14 +424,16 @@ __global__ void find_fill_kernel(const int32_t *P, int64_t m, const int32_t *col
     const int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (k < m && col_slot[P[k]] < 0) fill_col[atomicAdd(&st->n_fill, 1u)] = P[k];
 }
-// Slots that are empty or hold a column outside the marked (protected) sets.
+// Slots that are empty (occupied == false) or hold a column outside the marked (protected) sets
+// (occupied == true): launched for the empty ones first, so that no column is given up while a slot
+// is free.
 __global__ void find_evict_kernel(const int32_t *slot_col, int64_t budget, const uint8_t *mark,
-                                  SelectState *st, int32_t *evict_slot)
+                                  SelectState *st, int32_t *evict_slot, bool occupied)
 {
     const int64_t s = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (s < budget) {
         const int32_t j = slot_col[s];
-        if (j < 0 || mark[j] == 0) evict_slot[atomicAdd(&st->n_evict, 1u)] = (int32_t)s;
+        if (occupied ? (j >= 0 && mark[j] == 0) : j < 0) evict_slot[atomicAdd(&st->n_evict, 1u)] = (int32_t)s;
     }
 }
 // Pair the k-th missing column with the k-th evictable slot.  The evicted column loses its slot
@@ -509,7 +511,56 @@ __global__ __launch_bounds__(256) void copy_staged_kernel(const float4 *stage, i
     }
 }
 
+// While the first pass over a staged matrix has a batch on hand (its gaps are just out), the columns
+// whose gap reaches tau go into free device slots -- one workgroup per column claims the next slot
+// until `limit` are taken -- so that the first working sets find most of their columns already on
+// the device instead of crossing the host link a second time.
+__global__ __launch_bounds__(256) void keep_staged_kernel(const float4 *stage, int64_t lds4, float *slots, int64_t ld_s,
+                                                          int64_t d4ceil, const float *z, int64_t first, int64_t count,
+                                                          float tau, SelectState *st, uint32_t limit,
+                                                          int32_t *slot_col, int32_t *col_slot)
+{
+    __shared__ int claimed;
+    for (int64_t k = blockIdx.x; k < count; k += gridDim.x) {
+        const int64_t i = first + k;
+        if (threadIdx.x == 0) {
+            int s = -1;
+            // (the counter may run past the limit; claims beyond it are void)
+            const float zi = z[i];                  // (a gap of exactly zero never qualifies: most of a Lasso's are)
+            if (zi >= tau && zi > 0.0f && st->n_kept < limit) {
+                const uint32_t got = atomicAdd(&st->n_kept, 1u);
+                if (got < limit) s = (int)got;
+            }
+            claimed = s;
+        }
+        __syncthreads();
+        const int s = claimed;
+        __syncthreads();
+        if (s < 0) continue;
+        const float4 *s4 = stage + k * lds4;
+        float4 *t4 = reinterpret_cast<float4 *>(slots + (int64_t)s * ld_s);
+        int64_t r = threadIdx.x;
+        for (; r + 768 < d4ceil; r += 1024) {
+            const float4 a0 = s4[r], a1 = s4[r + 256], a2 = s4[r + 512], a3 = s4[r + 768];
+            t4[r] = a0; t4[r + 256] = a1; t4[r + 512] = a2; t4[r + 768] = a3;
+        }
+        for (; r < d4ceil; r += 256) t4[r] = s4[r];
+        if (threadIdx.x == 0) {
+            slot_col[s] = (int32_t)i;
+            col_slot[i] = s;
+        }
+    }
+}
+
 }  // namespace
+
+hipError_t launch_keep_batch(duhl_ctx *c, const StageBatch &b, int64_t first, float tau)
+{
+    hipLaunchKernelGGL(keep_staged_kernel, dim3(c->copy_blocks * 4), dim3(256), 0, c->compute,
+                       reinterpret_cast<const float4 *>(b.stage), b.lds / 4, c->slots, c->ld_s, (c->d + 3) / 4, c->z,
+                       first + b.k0, b.count, tau, c->sel, (uint32_t)c->budget, c->slot_col, c->col_slot);
+    return hipGetLastError();
+}
 
 // Staged columns are 16-byte aligned and padded to a multiple of four floats, and so are the slots
 // (ld_s is a multiple of 64), so whole 16-byte chunks are copied: ceil(d/4) of them.
@@ -593,7 +644,9 @@ hipError_t launch_plan_swap(duhl_ctx *c, bool overlap_safe, bool want_count)
     hipLaunchKernelGGL(find_fill_kernel, dim3((m + T - 1) / T), dim3(T), 0, s, c->P_next, m,
                        c->col_slot, c->sel, c->fill_col);
     hipLaunchKernelGGL(find_evict_kernel, dim3((c->budget + T - 1) / T), dim3(T), 0, s, c->slot_col,
-                       c->budget, c->mark, c->sel, c->evict_slot);
+                       c->budget, c->mark, c->sel, c->evict_slot, false);
+    hipLaunchKernelGGL(find_evict_kernel, dim3((c->budget + T - 1) / T), dim3(T), 0, s, c->slot_col,
+                       c->budget, c->mark, c->sel, c->evict_slot, true);
     hipLaunchKernelGGL(apply_plan_kernel, dim3((m + T - 1) / T), dim3(T), 0, s, c->sel, c->fill_col,
                        c->evict_slot, c->fill_slot, c->slot_col, c->col_slot, m);
     return hipGetLastError();

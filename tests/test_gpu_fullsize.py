@@ -261,8 +261,12 @@ def test_cfg4_shape_host_resident_sampled_columns_and_swap(G, memory, scale):
     np.testing.assert_allclose(g.get(duhl.SQNORM), 1.0, rtol=1e-5)
     check_gaps(np.sort(rng.choice(n, 400, replace=False)))
     sample = G.dev_i32(np.sort(rng.choice(n, n // 20, replace=False)))
+    # (pageable memory: the first pass has left the columns with the largest gaps in device slots,
+    # so most of the first working set is already there)
+    kept = g.resident_columns()
     nsw, rho = g.select(m)
-    assert nsw == m
+    print(f"first selection: {nsw} of {m} columns to copy, {kept} kept by the first pass", flush=True)
+    assert nsw == m if memory == "pinned" else 0 < nsw < m // 2
     g.commit_swap()
     for rnd in range(3):
         print("round", rnd, flush=True)
