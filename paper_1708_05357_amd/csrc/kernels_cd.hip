@@ -686,38 +686,52 @@ __device__ __forceinline__ void guard_finish(const MergeGuard &g, const CdArgs &
     }
 }
 
+// CH = 16 is the same for short vectors, where 256 elements per workgroup would leave most of the
+// device idle: a workgroup owns 16 chunks, and the four quarters of a wavefront read four workers'
+// buffers at a time (their sums meet in wavefront 0 by three more shuffles).
+template <int CH>
 __global__ __launch_bounds__(1024) void merge_workers_kernel(float *v, int64_t d, const float *dv,
                                                              int64_t dv_stride, const int32_t *dirty,
                                                              int nworkers, const MergeGuard g, const CdArgs a)
 {
+    constexpr int SUBS = 64 / CH;                                  // workers per wavefront load
     __shared__ float4 part[16][64];
     __shared__ int is_last;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int64_t k4 = (int64_t)blockIdx.x * 64 + lane;            // chunk of four elements
+    const int sub = lane / CH;
+    const int64_t k4 = (int64_t)blockIdx.x * CH + lane % CH;       // chunk of four elements
     const bool in = 4 * k4 < d;
     const float4 *p = reinterpret_cast<const float4 *>(dv) + (in ? k4 : 0);
     const int64_t stride4 = dv_stride >> 2;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     auto add = [](float4 &x, const float4 y) { x.x += y.x; x.y += y.y; x.z += y.z; x.w += y.w; };
-    int wk = w;
-    for (; wk + 16 * 7 < nworkers; wk += 16 * 8) {
+    constexpr int STEP = 16 * SUBS;
+    int wk = w * SUBS + sub;
+    for (; wk + STEP * 7 < nworkers; wk += STEP * 8) {
         float4 t[8];
 #pragma unroll
         for (int u = 0; u < 8; ++u)
-            t[u] = dirty[wk + 16 * u] ? p[(int64_t)(wk + 16 * u) * stride4] : make_float4(0.f, 0.f, 0.f, 0.f);
+            t[u] = dirty[wk + STEP * u] ? p[(int64_t)(wk + STEP * u) * stride4] : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
         for (int u = 0; u < 8; ++u) add(s, t[u]);
     }
-    for (; wk < nworkers; wk += 16)
+    for (; wk < nworkers; wk += STEP)
         if (dirty[wk]) add(s, p[(int64_t)wk * stride4]);
     part[w][lane] = s;
     __syncthreads();
     if (w == 0) {
         double s_old = 0.0, s_lin = 0.0, s_sq = 0.0;
-        if (in) {
-            float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
+        float4 t = make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-            for (int u = 0; u < 16; ++u) add(t, part[u][lane]);
+        for (int u = 0; u < 16; ++u) add(t, part[u][lane]);
+#pragma unroll
+        for (int o = CH; o < 64; o <<= 1) {                        // the quarters hold different workers' sums
+            t.x += __shfl_xor(t.x, o, 64);
+            t.y += __shfl_xor(t.y, o, 64);
+            t.z += __shfl_xor(t.z, o, 64);
+            t.w += __shfl_xor(t.w, o, 64);
+        }
+        if (in && sub == 0) {
             const int64_t k = 4 * k4;
             if (!g.st) {
                 if (t.x != 0.0f) v[k] += t.x;
@@ -1372,6 +1386,19 @@ hipError_t launch_csr_subpasses(duhl_ctx *c, const CdArgs &a, int max_inflight)
     return hipGetLastError();
 }
 
+// The merge takes 64 elements per workgroup instead of 256 while that still leaves compute units idle.
+inline bool merge_narrow(const duhl_ctx *c) { return (c->d + 255) / 256 < c->num_cu / 2; }
+inline int64_t merge_blocks(const duhl_ctx *c) { return merge_narrow(c) ? (c->d + 63) / 64 : (c->d + 255) / 256; }
+inline void launch_merge(duhl_ctx *c, int64_t mblocks, int nworkers, const MergeGuard &g, const CdArgs &a)
+{
+    if (merge_narrow(c))
+        hipLaunchKernelGGL(merge_workers_kernel<16>, dim3(mblocks), dim3(1024), 0, c->compute, a.v, c->d, c->dv,
+                           c->dv_stride, c->dirty, nworkers, g, a);
+    else
+        hipLaunchKernelGGL(merge_workers_kernel<64>, dim3(mblocks), dim3(1024), 0, c->compute, a.v, c->d, c->dv,
+                           c->dv_stride, c->dirty, nworkers, g, a);
+}
+
 template <int MODEL, int T, int NR, int NL, bool CACHE_X, bool EXT, bool XVEC>
 hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
 {
@@ -1380,7 +1407,7 @@ hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
     // Workers per sub-pass: enough to fill the chip; several coordinates per worker once the
     // sub-pass is large, which keeps the private buffers a small fraction of the traffic.
     const int64_t cap = c->dv_workers;
-    const int64_t mblocks = (c->d + 255) / 256;
+    const int64_t mblocks = merge_blocks(c);
     MergeGuard g;
     const hipError_t ge = guard_prepare(c, a.count, 3 * mblocks, &g);
     if (ge != hipSuccess) return ge;
@@ -1395,8 +1422,7 @@ hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
         hipLaunchKernelGGL((cd_dense_worker_kernel<MODEL, T, NR, NL, CACHE_X, EXT, XVEC>), dim3(grid), dim3(BLOCK), 0,
                            c->compute, a, t0, t1, c->dv, c->dv_stride, c->dirty, nullptr, 0u, nullptr, 0,
                            g.st ? c->alpha_old : nullptr, g.stamp, g.st, c->guard_shift, g.wbook);
-        hipLaunchKernelGGL(merge_workers_kernel, dim3(mblocks), dim3(1024), 0, c->compute, a.v,
-                           c->d, c->dv, c->dv_stride, c->dirty, (int)(grid * PER), g, a);
+        launch_merge(c, mblocks, (int)(grid * PER), g, a);
     }
     return hipGetLastError();
 }
@@ -1408,7 +1434,7 @@ hipError_t launch_workers_t(duhl_ctx *c, const CdArgs &a, int64_t inflight)
 template <int MODEL, int NR, int NL, int CUS, bool XVEC>
 hipError_t launch_multi_t(duhl_ctx *c, const CdArgs &a, int64_t inflight, int64_t workers)
 {
-    const int64_t mblocks = (c->d + 255) / 256;
+    const int64_t mblocks = merge_blocks(c);
     MergeGuard g;
     const hipError_t ge = guard_prepare(c, a.count, 3 * mblocks, &g);
     if (ge != hipSuccess) return ge;
@@ -1422,8 +1448,7 @@ hipError_t launch_multi_t(duhl_ctx *c, const CdArgs &a, int64_t inflight, int64_
                            c->dirty, c->xch, c->xseq, &c->sel->cd_abort, c->cd_spin_limit,
                            g.st ? c->alpha_old : nullptr, g.stamp, g.st, c->guard_shift, g.wbook);
         c->xseq += (uint32_t)per_worker + 2u;          // sequence numbers never repeat back to back
-        hipLaunchKernelGGL(merge_workers_kernel, dim3(mblocks), dim3(1024), 0, c->compute, a.v,
-                           c->d, c->dv, c->dv_stride, c->dirty, (int)workers, g, a);
+        launch_merge(c, mblocks, (int)workers, g, a);
     }
     return hipGetLastError();
 }
