@@ -130,6 +130,8 @@ def measure_brief(name, rounds=10, host_threads=12):
     from paper_1708_05357_amd import duhl
     prob = build_problem(name, "cuda", 1.0)
     m, host = prob["m"], prob["host_resident"]
+    if not host:
+        rounds = 2 * rounds      # (short rounds: enough of them that the median is past the halved bound of the start)
     g, set_data = make_ctx(prob, 2 * m if host else m)
     passes = 8 if host else 1
     threads = host_threads if host else 0

@@ -132,11 +132,11 @@ duhl_status finish_set_data(duhl_ctx *c, const float *target, double lambda)
         HIPCHK(c, launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(c->guard), sizeof(GuardState) / 4, 0));
         // (the first passes from alpha = 0 are the ones in which every coordinate moves, and steps
         // collide most: they start with half the bound, which the guard doubles after four passes)
-        HIPCHK(c, launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(&c->guard->shift), 1, 1));
+        HIPCHK(c, launch_fill_i32(c->compute, reinterpret_cast<int32_t *>(&c->guard->shift), 1, c->guard_start));
         c->h_trips[0] = 0;
-        c->h_trips[1] = 1;
+        c->h_trips[1] = (uint32_t)c->guard_start;
     }
-    c->guard_shift = c->cd_guard ? 1 : 0;
+    c->guard_shift = c->cd_guard ? c->guard_start : 0;
     c->have_data = true;
     // column norms and a first full gap pass in one read of the matrix
     HIPCHK(c, launch_gap(c, nullptr, c->n, false, true));
@@ -284,6 +284,7 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->cd_guard = env_int("DUHL_CD_GUARD", 1);
     c->keep_first_pass = env_int("DUHL_KEEP_FIRST_PASS", 1);
     c->guard_tol = 1e-6;
+    c->guard_start = env_int("DUHL_GUARD_START", 1);
     c->select_spin_limit = env_int("DUHL_SELECT_SPIN_LIMIT", 1 << 22);
     if (c->select_spin_limit < 0) c->select_spin_limit = 0;
     c->select_groups = env_int("DUHL_SELECT_GROUPS", 0);

@@ -346,6 +346,7 @@ struct duhl_ctx {
     int64_t kept_first_pass;    // columns that pass left in device slots
     int cd_guard;               // 0: guard switched off (DUHL_CD_GUARD)
     double guard_tol;           // relative rise of the objective that still counts as rounding
+    int guard_start;            // halvings of the bound in force right after set_data
     int guard_shift;            // halvings of the library's bound on concurrent steps that the host applies
     hipEvent_t ev_pass[2];      // behind the last two guarded passes: while the bound is halved the host stays
     uint64_t guard_passes;      // at most two passes ahead of the device, so that it sees the bound recover
