@@ -9,9 +9,9 @@ Two runs, one counter each (rocprofv3 does not split counters over passes; no tr
 
     cd /tmp && export TMPDIR=/tmp
     rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/pmc_f -o f -- \
-        python3 bench.py --workload cfg5 --steps 3 --warmup 1 --no-cpu --no-ttg --no-others --copy-calibration-gib 4
+        python3 bench.py --workload cfg5 --steps 10 --warmup 2 --no-cpu --no-ttg --no-others --copy-calibration-gib 4
     rocprofv3 --pmc WRITE_SIZE --output-format csv -d gpurun_out/pmc_w -o w -- \
-        python3 bench.py --workload cfg5 --steps 3 --warmup 1 --no-cpu --no-ttg --no-others --copy-calibration-gib 4
+        python3 bench.py --workload cfg5 --steps 10 --warmup 2 --no-cpu --no-ttg --no-others --copy-calibration-gib 4
     python3 pmc_traffic.py --workload cfg5 --fetch gpurun_out/pmc_f --write gpurun_out/pmc_w
 
 --copy-calibration-gib appends plain device copies of known size; the largest copy dispatch gives
