@@ -585,13 +585,17 @@ def test_host_resident_matrix_in_pieces(G):
 
 
 @pytest.mark.parametrize("d,n,m,ld,stage_mb", [(1028, 400, 60, None, None), (1027, 400, 60, 1031, None),
-                                                (100000, 160, 30, None, None), (5000, 900, 200, None, 1)])
+                                                (100000, 160, 30, None, None), (5000, 900, 200, None, 1),
+                                                (300, 6000, 600, None, 1)])
 def test_pageable_host_matrix_through_staging_buffers(G, monkeypatch, d, n, m, ld, stage_mb):
     """The host matrix in ordinary memory that the device cannot read (Assumption 1 of Sec. 3 on a
     machine that cannot pin everything): the first pass, index-list gap passes and the column swap of
     Alg. 2 go through the library's pinned staging buffers, a background thread doing the swap.  Same
     iterates, slots and gaps as with pinned memory; ragged and padded columns; staging buffers of
-    1 MB, so that a pass takes many batches and the buffers are reused."""
+    1 MB, so that a pass takes many batches and the buffers are reused.  The last case has enough
+    columns (more than 2,048) for the first pass to leave those with the largest gaps in the device
+    slots: the first working set then finds part of its columns there, and every later read of
+    them -- gaps of the residents, the passes -- must see the right data."""
     if stage_mb is not None:
         monkeypatch.setenv("DUHL_STAGE_MB", str(stage_mb))
     run_host_resident(G, lasso_problem(d, n, 0.1, 0.1, seed=24), m, rounds=4, ld=ld, pageable=True)
@@ -606,8 +610,12 @@ def run_host_resident(G, prob, m, rounds=10, chunk_cols=None, ld=None, pageable=
         G.assert_gaps_close(p.g.get(duhl.Z), p.o.z)
         rng = np.random.default_rng(2)
         all_idx = G.dev_i32(np.arange(prob["n"]))
+        kept = p.g.resident_columns()              # (pageable memory: what the first pass left in the slots)
+        assert 0 <= kept <= budget and (kept == 0 or (pageable and prob["n"] > 2048))
         nsw, rho = p.g.select(m)
-        assert nsw == m
+        assert m - kept <= nsw <= m
+        if pageable and prob["n"] > 2048:
+            assert kept > 0 and nsw < m
         p.g.commit_swap()
         for rnd in range(rounds):
             P = p.g.get(duhl.P)
