@@ -348,6 +348,9 @@ def test_plain_cd_epoch_never_raises_the_objective(G, case):
     assert (rounds - undone) * m <= kept <= rounds * m
     assert 0.0 <= theta <= 1.0
     a, v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+    if prob["model"] == "svm":                              # a damped pass is a convex combination: the box holds
+        ya = a * G.to_np(prob["target"])
+        assert ya.min() >= -1e-6 and ya.max() <= 1.0 + 1e-6
     keep = p.o.alpha.copy()
     p.o.set_state(a.astype(np.float64))                     # v = A alpha (- b) still holds (App. D)
     scale = max(np.abs(p.o.v).max(), np.abs(G.to_np(prob["target"])).max() if prob["model"] != "svm" else 0.0, 1e-30)
