@@ -305,7 +305,8 @@ def test_default_pass_reaches_the_gap_on_clustered_columns_as_fast_as_sequential
     p.close()
 
 
-@pytest.mark.parametrize("case", ["clustered", "lasso_x40", "svm_x40", "sparse_x16", "short_columns"])
+@pytest.mark.parametrize("case", ["clustered", "lasso_x40", "svm_x40", "sparse_x16", "short_columns",
+                                  "lasso_x40_d20000", "lasso_x40_d100000"])
 def test_plain_cd_epoch_never_raises_the_objective(G, case):
     """The six named calls alone, on data that the library's bound on concurrent steps gets wrong:
     groups of near-duplicate columns, exact duplicates (dense and sparse), and a working set forty
@@ -327,6 +328,14 @@ def test_plain_cd_epoch_never_raises_the_objective(G, case):
             prob["target"] = prob["target"].repeat_interleave(rep)
             prob["lam"] = 1.0 / prob["n"]
         m = prob["n"] // 5
+    elif case in ("lasso_x40_d20000", "lasso_x40_d100000"):
+        # the same with columns long enough for the workers of 1,024 threads, and for those that span
+        # two compute units
+        rep, base = 40, (30 if case == "lasso_x40_d20000" else 16)
+        prob = dict(synth.lasso_dense(20000 if case == "lasso_x40_d20000" else 100000, base, 0.2, 0.1, seed=4))
+        prob["cols"] = prob["cols"].repeat_interleave(rep, dim=0).contiguous()
+        prob["n"] = base * rep
+        m, rounds = prob["n"] // 5, 100
     elif case == "sparse_x16":
         prob = _duplicated_sparse_rows(16)
         m = prob["n"] // 5
