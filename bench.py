@@ -334,7 +334,8 @@ def time_to_gap(g, set_data, prob, m, target, max_rounds, mode=1, inflight=0, sa
             "passes_per_round": passes if passes > 0 else auto["passes"]}
 
 
-def time_to_gap_native(g, set_data, prob, m, target, mode, inflight, rule, passes, sample_perm, host_threads):
+def time_to_gap_native(g, set_data, prob, m, target, mode, inflight, rule, passes, sample_perm, host_threads,
+                       extra_passes=0):
     """The same measurement with the round loop run by the library (duhl_run): no interpreter
     between the steps, one read-back of the gap-memory sum per round as the stopping test.  With
     a device-resident matrix that sum is the total gap of a fresh full pass.  With host residency
@@ -352,11 +353,12 @@ def time_to_gap_native(g, set_data, prob, m, target, mode, inflight, rule, passe
         kw = {}
         if prob["host_resident"]:
             kw = dict(sample=sample_perm, sample_per_round=max(1, prob["n"] // 20), host_threads=host_threads,
-                      confirm=True)
+                      confirm=True, max_extra_passes=extra_passes)
         st = g.run(m, 400, passes=passes, mode=mode, gap_tol=tol, max_inflight=inflight, rule=rule,
                    seed=1000, **kw)
         out[f"{name}_1e-3_s"] = st["seconds"] if st["converged"] else None
         out[f"{name}_rounds"] = st["rounds"]
+        out[f"{name}_passes"] = st["passes"]
         out[f"{name}_gap_memory_sum"] = st["gap_memory_sum"]
         out[f"{name}_confirmations"] = st["confirmations"]
         if prob["host_resident"]:
@@ -737,7 +739,8 @@ def main():
             perm_dev = torch.as_tensor(sample_host["perm"][:prob["n"]], device="cuda").contiguous()
         out["time_to_gap_native"] = time_to_gap_native(g, set_data, prob, m, 1e-3, mode, args.inflight, rule,
                                                        args.passes if args.passes > 0 else args.min_passes, perm_dev,
-                                                       args.host_sampler_threads)
+                                                       args.host_sampler_threads,
+                                                       extra_passes=(args.max_passes - args.min_passes) if args.passes == 0 else 0)
     if not args.no_cpu:
         log("CPU baseline (oracle, one thread, about 20 s)")
         out["cpu_baseline"] = cpu_baseline(prob, m)

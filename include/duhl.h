@@ -335,6 +335,11 @@ typedef struct duhl_run_opts {
                                    window before the round ends (reproducible rounds: which entries
                                    are refreshed no longer depends on timing); 0 stops them when the
                                    passes and copies are done, as unit A is stopped in Algorithm 2 */
+    int max_extra_passes;       /* host residency, copies running beside the passes: after the round's
+                                   `passes`, up to this many more, one at a time, for as long as the
+                                   round's column copies are still in flight (theta sized to the copy,
+                                   Section 5.2: unit B works on until its next working set has arrived).
+                                   0: none */
 } duhl_run_opts;
 
 typedef struct duhl_run_stats {

@@ -248,6 +248,16 @@ duhl_status set_data_dense_pieces(duhl_ctx *c, const float *const *pieces, int64
 
 }  // namespace
 
+namespace duhl {
+bool swap_in_flight(duhl_ctx *c)
+{
+    if (!c->pending || c->res != DUHL_RESIDENT_HOST || !c->ev_copy) return false;
+    // (pageable memory: the background thread records the event only after its last batch)
+    if (c->pageable && c->stager && !stager_swap_done(c)) return true;
+    return hipEventQuery(c->ev_copy) == hipErrorNotReady;
+}
+}  // namespace duhl
+
 extern "C" {
 
 duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, int64_t budget_cols,

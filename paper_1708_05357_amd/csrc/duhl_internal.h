@@ -444,6 +444,9 @@ hipError_t staged_accumulate_v(duhl_ctx *c);
 // are enqueued and ev_copy is recorded.
 hipError_t stager_swap_begin(duhl_ctx *c);
 hipError_t stager_swap_join(duhl_ctx *c);
+bool stager_swap_done(duhl_ctx *c);
+// Host residency: are the column copies of the pending selection still running?
+bool swap_in_flight(duhl_ctx *c);
 // kernels of other files that the staged passes launch
 hipError_t launch_gap_batch(duhl_ctx *c, const StageBatch &b, const int32_t *idx, int64_t first, bool with_norms,
                             bool first_batch);

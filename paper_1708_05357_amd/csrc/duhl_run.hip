@@ -63,8 +63,9 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
     if (!c) return DUHL_EINVAL;
     if (!o || !out) return set_error(c, DUHL_EINVAL, "options or statistics pointer is NULL");
     if (!c->have_data) return set_error(c, DUHL_ESTATE, "no data set");
-    if (o->passes < 1 || o->max_rounds < 0 || o->check_every < 0 || o->max_inflight < 0)
-        return set_error(c, DUHL_EINVAL, "passes >= 1, max_rounds >= 0, check_every >= 0, max_inflight >= 0 required");
+    if (o->passes < 1 || o->max_rounds < 0 || o->check_every < 0 || o->max_inflight < 0 || o->max_extra_passes < 0)
+        return set_error(c, DUHL_EINVAL,
+                         "passes >= 1, max_rounds >= 0, check_every >= 0, max_inflight >= 0, max_extra_passes >= 0 required");
     if (std::isnan(o->gap_tol)) return set_error(c, DUHL_EINVAL, "gap_tol is NaN");
     const bool host = c->res == DUHL_RESIDENT_HOST;
     const bool threads = o->host_threads > 0;
@@ -184,6 +185,17 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
         }
         for (int k = 0; k < o->passes && st == DUHL_OK; ++k)
             st = duhl_cd_epoch(c, o->mode, nullptr, 0, o->seed + (uint64_t)(rnd * o->passes + k), inflight);
+        // theta sized to the copy: unit B works on while its next working set is still arriving.  One
+        // pass at a time, each waited for, so that the host does not enqueue passes for longer than
+        // the copies last.
+        int extra = 0;
+        while (overlap && st == DUHL_OK && extra < o->max_extra_passes) {
+            if (hipStreamSynchronize(c->compute) != hipSuccess) { st = DUHL_EHIP; break; }
+            if (!duhl::swap_in_flight(c)) break;
+            st = duhl_cd_epoch(c, o->mode, nullptr, 0,
+                               (o->seed ^ 0x9e3779b97f4a7c15ull) + (uint64_t)(rnd * 1024 + extra), inflight);
+            ++extra;
+        }
         if (threads) {
             // unit A samples for as long as unit B works (Algorithm 2): until the passes and the copies are done
             if (st == DUHL_OK && hipStreamSynchronize(c->compute) != hipSuccess) st = DUHL_EHIP;
@@ -205,7 +217,7 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
             if (st != DUHL_OK) return st;
         }
         s.rounds = rnd + 1;
-        s.passes += o->passes;
+        s.passes += o->passes + extra;
     }
     if (hipStreamSynchronize(c->compute) != hipSuccess) return set_error(c, DUHL_EHIP, "stream synchronisation failed");
     s.inflight_last = inflight;

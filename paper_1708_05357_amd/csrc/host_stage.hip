@@ -405,6 +405,13 @@ hipError_t stager_swap_begin(duhl_ctx *c)
     return hipSuccess;
 }
 
+bool stager_swap_done(duhl_ctx *c)
+{
+    duhl_stager *st = c->stager;
+    std::lock_guard<std::mutex> lk(st->mu);
+    return st->job_done;
+}
+
 hipError_t stager_swap_join(duhl_ctx *c)
 {
     duhl_stager *st = c->stager;

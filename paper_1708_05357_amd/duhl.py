@@ -38,7 +38,8 @@ class RunOpts(C.Structure):
                 ("rule", C.c_int), ("seed", C.c_uint64), ("max_rounds", C.c_int64), ("gap_tol", C.c_double),
                 ("check_every", C.c_int), ("sample_dev", C.c_void_p), ("sample_host", C.c_void_p),
                 ("sample_len", C.c_int64), ("sample_per_round", C.c_int64), ("host_threads", C.c_int),
-                ("confirm", C.c_int), ("adapt_inflight", C.c_int), ("host_wait_all", C.c_int)]
+                ("confirm", C.c_int), ("adapt_inflight", C.c_int), ("host_wait_all", C.c_int),
+                ("max_extra_passes", C.c_int)]
 
 
 class RunStats(C.Structure):
@@ -260,13 +261,14 @@ class Duhl:
 
     def run(self, m, max_rounds, passes=1, mode=CD_ASYNC, gap_tol=-1.0, max_inflight=0, rule=SELECT_GAP,
             seed=0, check_every=1, sample=None, sample_per_round=0, host_threads=0, confirm=False,
-            adapt_inflight=True, host_wait_all=False):
+            adapt_inflight=True, host_wait_all=False, max_extra_passes=0):
         """The native round loop.  sample: int32 device tensor with the coordinates whose gaps are
         refreshed window by window (None: see duhl_run); returns a dict of the statistics."""
         o = RunOpts(m=int(m), passes=int(passes), mode=mode, max_inflight=int(max_inflight), rule=rule,
                     seed=int(seed), max_rounds=int(max_rounds), gap_tol=float(gap_tol),
                     check_every=int(check_every), host_threads=int(host_threads), confirm=1 if confirm else 0,
-                    adapt_inflight=1 if adapt_inflight else 0, host_wait_all=1 if host_wait_all else 0)
+                    adapt_inflight=1 if adapt_inflight else 0, host_wait_all=1 if host_wait_all else 0,
+                    max_extra_passes=int(max_extra_passes))
         keep = None
         if sample is not None:
             assert sample.dtype == torch.int32 and sample.is_contiguous() and sample.is_cuda

@@ -497,6 +497,35 @@ def test_stale_memory_rounds_match_the_oracle_round_by_round(G, kind):
     p.close()
 
 
+@pytest.mark.parametrize("pageable", [False, True])
+def test_extra_passes_while_the_copies_are_in_flight(G, pageable):
+    """theta sized to the copy (Sec. 5.2) in the native loop: with max_extra_passes the rounds run
+    further passes on the current set for as long as the next set's columns are still arriving, and
+    none once they are there.  How many depends on timing; what must hold: between passes and
+    passes + max_extra_passes per round, none without host residency, v = A alpha - b, and the
+    objective no higher than without them after the same rounds on the same sets (sequential exact
+    steps never raise it, App. D)."""
+    from paper_1708_05357_amd import duhl
+    prob = _lasso(60000, 300, 0.1, 0.1, seed=50)
+    m, rounds = 40, 5
+    p = G.Pair(prob, budget=2 * m, host_resident=True, pageable=pageable)
+    o0 = p.g.objective()
+    st = p.g.run(m, rounds, passes=1, mode=duhl.CD_SEQUENTIAL, max_extra_passes=12)
+    assert st["rounds"] == rounds and rounds <= st["passes"] <= rounds * 13
+    print(f"passes run in {rounds} rounds: {st['passes']}")
+    a, v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+    p.o.set_state(a.astype(np.float64))
+    assert np.abs(v - p.o.v).max() <= 1e-5 * max(np.abs(p.o.v).max(), 1e-30)
+    assert p.g.objective() < o0
+    with pytest.raises(duhl.DuhlError):
+        p.g.run(m, 1, max_extra_passes=-1)
+    p.close()
+    q = G.Pair(prob)                                        # the matrix on the device: nothing to wait for
+    st = q.g.run(m, rounds, passes=2, mode=duhl.CD_SEQUENTIAL, max_extra_passes=12)
+    assert st["passes"] == 2 * rounds
+    q.close()
+
+
 @pytest.mark.parametrize("chunk_cols", [None, 128, "pageable"])
 def test_delayed_rounds_with_unit_a_threads_match_the_oracle_round_by_round(G, chunk_cols):
     """Alg. 2 as printed, on a matrix in host memory: unit B (the GPU) selects by eq. (13) and runs its
