@@ -257,7 +257,9 @@ duhl_status duhl_commit_swap(duhl_ctx *ctx);
  * stays in force.  The host
  * learns of a halving without waiting; in passes it had already enqueued with the old bound, part
  * of the workers sit each sub-pass out instead, so that such a pass solves a random half
- * (quarter, ...) of its working set.  duhl_cd_stats reports the counts.
+ * (quarter, ...) of its working set.  After duhl_set_data_* the bound starts halved for the Lasso and
+ * the elastic net (from alpha = 0 every coordinate moves and the first pass is the one that
+ * overshoots), in full for the SVM dual.  duhl_cd_stats reports the counts.
  * DUHL_CD_ATOMIC is not guarded.
  *   DUHL_CD_ATOMIC  each step reads the live v and adds a_j*delta to it with fp32 atomics;
  *                   iterates depend on timing.

@@ -294,7 +294,10 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->cd_guard = env_int("DUHL_CD_GUARD", 1);
     c->keep_first_pass = env_int("DUHL_KEEP_FIRST_PASS", 1);
     c->guard_tol = 1e-6;
-    c->guard_start = env_int("DUHL_GUARD_START", 1);
+    // From alpha = 0 every coordinate of a Lasso moves, by steps of any size, and the first concurrent
+    // pass is the one that overshoots: it starts with half the bound.  The steps of the SVM dual are
+    // clipped to the box and its first passes were never seen to overshoot: full bound.
+    c->guard_start = env_int("DUHL_GUARD_START", model == DUHL_SVM ? 0 : 1);
     c->select_spin_limit = env_int("DUHL_SELECT_SPIN_LIMIT", 1 << 22);
     if (c->select_spin_limit < 0) c->select_spin_limit = 0;
     c->select_groups = env_int("DUHL_SELECT_GROUPS", 0);
