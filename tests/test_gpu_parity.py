@@ -601,6 +601,21 @@ def test_pageable_host_matrix_through_staging_buffers(G, monkeypatch, d, n, m, l
     run_host_resident(G, lasso_problem(d, n, 0.1, 0.1, seed=24), m, rounds=4, ld=ld, pageable=True)
 
 
+def test_first_pass_keeping_can_be_switched_off(G, monkeypatch):
+    """DUHL_KEEP_FIRST_PASS=0: the first pass over a staged matrix leaves the slots empty and the first
+    working set crosses the link whole; the rounds are the same."""
+    monkeypatch.setenv("DUHL_STAGE_MB", "1")
+    monkeypatch.setenv("DUHL_KEEP_FIRST_PASS", "0")
+    from paper_1708_05357_amd import duhl
+    prob = lasso_problem(300, 6000, 0.1, 0.1, seed=24)
+    p = G.Pair(prob, budget=1200, host_resident=True, pageable=True)
+    assert p.g.resident_columns() == 0
+    nsw, rho = p.g.select(600)
+    assert nsw == 600
+    p.g.commit_swap()
+    p.close()
+
+
 def run_host_resident(G, prob, m, rounds=10, chunk_cols=None, ld=None, pageable=False):
     from paper_1708_05357_amd import duhl
     for budget in (2 * m, m + 7):                  # overlapping copies / in-place replacement
@@ -1032,6 +1047,51 @@ def test_stream_read_probe(G):
         g.probe_stream_read(x[1:], reps=1)               # not 16-byte aligned
     with pytest.raises(duhl.DuhlError):
         g.probe_stream_read(x, reps=0)
+    g.close()
+
+
+def test_scatter_add_probe_leaves_v_alone(G):
+    """The second measurement aid: atomic adds of +0 to random elements of v.  v keeps its bits, the
+    rate is a positive number, and the call needs data and sane arguments."""
+    from paper_1708_05357_amd import duhl
+    g = duhl.Duhl(duhl.LASSO, 1000, 64, 16)
+    with pytest.raises(duhl.DuhlError) as e:
+        g.probe_scatter_add(1000)
+    assert e.value.status == duhl.ESTATE
+    prob = lasso_problem(1000, 64, 0.2, 0.1, seed=3)
+    g.set_data_dense(prob["cols"].cuda(), prob["target"].cuda(), prob["lam"])
+    g.gap(want_sum=False)
+    g.select(16, want_stats=False)
+    g.commit_swap()
+    g.cd_epoch(duhl.CD_SEQUENTIAL)
+    before = g.get(duhl.V).copy()
+    rate = g.probe_scatter_add(2_000_000, reps=2)
+    assert 1e8 < rate < 1e13
+    assert np.array_equal(before.view(np.uint32), g.get(duhl.V).view(np.uint32))
+    for ops, reps in ((0, 1), (1000, 0)):
+        with pytest.raises(duhl.DuhlError) as e:
+            g.probe_scatter_add(ops, reps=reps)
+        assert e.value.status == duhl.EINVAL
+    g.close()
+
+
+def test_guard_books_need_data_and_start_empty(G):
+    from paper_1708_05357_amd import duhl
+    g = duhl.Duhl(duhl.LASSO, 100, 40, 10)
+    with pytest.raises(duhl.DuhlError) as e:
+        g.cd_stats()
+    assert e.value.status == duhl.ESTATE
+    prob = lasso_problem(100, 40, 0.2, 0.1, seed=3)
+    g.set_data_dense(prob["cols"].cuda(), prob["target"].cuda(), prob["lam"])
+    assert g.cd_stats() == (0, 0, 0, 1.0)               # no working set, no pass yet
+    g.gap(want_sum=False)
+    g.select(10, want_stats=False)
+    g.commit_swap()
+    g.cd_epoch(duhl.CD_ASYNC, seed=1)
+    damped, bound, kept, theta = g.cd_stats()
+    assert damped in (0, 1) and 1 <= bound <= 10 and kept in (0, 10) and 0.0 <= theta <= 1.0
+    g.set_data_dense(prob["cols"].cuda(), prob["target"].cuda(), prob["lam"])     # the books start afresh
+    assert g.cd_stats()[0] == 0 and g.cd_stats()[2] == 0
     g.close()
 
 
