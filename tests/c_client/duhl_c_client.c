@@ -116,6 +116,8 @@ int duhl_c_client_argument_checks(void)
     EXPECT(duhl_selection_threshold(NULL, buf), DUHL_EINVAL);
     EXPECT(duhl_resident_columns(NULL, &n_out), DUHL_EINVAL);
     EXPECT(duhl_swap_stats(NULL, &n_out, &sum), DUHL_EINVAL);
+    EXPECT(duhl_cd_stats(NULL, &n_out, &n_out, &n_out, &sum), DUHL_EINVAL);
+    EXPECT(duhl_probe_scatter_add(NULL, 1000, 1, &sum), DUHL_EINVAL);
     if (duhl_working_set_size(NULL) != 0) return 101;
     if (duhl_last_error(NULL) == NULL) return 102;
     duhl_destroy(NULL);
