@@ -514,7 +514,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg2clustered", "cfg3", "cfg4", "cfg5", "fig5svm", "sec51lasso",
+    ap.add_argument("--workload", default="cfg5", choices=["cfg1", "cfg2", "cfg2clustered", "cfg3", "cfg4", "cfg5", "cfg5clustered", "fig5svm", "sec51lasso",
                                                             "sec51svm"])
     ap.add_argument("--scale", type=float, default=1.0, help="shrink n (and m) at fixed d")
     ap.add_argument("--host-memory", default="pageable", choices=["pageable", "pinned"],

@@ -37,13 +37,17 @@ def _segments(out, j0, j1):
 
 
 def lasso_dense(d, n, support_frac, c_lambda, seed=0, device="cpu", out=None, block_cols=None,
-                noise=0.01):
+                noise=0.01, clusters=0, spread=0.0):
     """Dense Lasso instance.
 
     Entries of A ~ N(0,1), every column scaled to unit L2 norm; alpha* has floor(support_frac*n)
     non-zeros at uniformly random positions with N(0,1) values; b = A alpha* + N(0, noise^2).
     The regulariser is set through Lambda = lambda*d = c_lambda * ||A^T b||_inf, so that the
     returned ``lam`` is the lambda of the paper's objective ||A alpha - b||^2/(2d) + lambda||alpha||_1.
+
+    clusters > 0: the columns come in that many groups of near-duplicates instead -- column j is the
+    centre of group j mod clusters (N(0,1) entries) plus ``spread`` times N(0,1) noise, scaled to
+    unit norm (see lasso_clustered, the all-at-once version for small instances).
 
     ``out`` (optional) is a preallocated float32 (n, d) tensor to fill -- on the device, or in
     pinned host memory for the out-of-budget case --, or a list of such tensors that hold the
@@ -66,9 +70,13 @@ def lasso_dense(d, n, support_frac, c_lambda, seed=0, device="cpu", out=None, bl
     alpha_star = torch.zeros(n, dtype=torch.float32, device=dev)
     alpha_star[support] = torch.randn(k, generator=g, device=dev, dtype=torch.float32)
     b = torch.zeros(d, dtype=torch.float32, device=dev)
+    centres = torch.randn((clusters, d), generator=g, dtype=torch.float32, device=dev) if clusters > 0 else None
     for j0 in range(0, n, block_cols):
         j1 = min(n, j0 + block_cols)
         x = torch.randn((j1 - j0, d), generator=g, device=dev, dtype=torch.float32)
+        if centres is not None:
+            x *= spread
+            x += centres[torch.arange(j0, j1, device=dev) % clusters]
         x /= x.norm(dim=1, keepdim=True)
         b += x.t() @ alpha_star[j0:j1]
         for piece, a, e in _segments(out, j0, j1):
@@ -189,6 +197,10 @@ CONFIGS = {
     # image features): 1,250 groups of 40 near-duplicate columns (cosine about 0.9 within a group)
     "cfg2clustered": dict(kind="lasso_clustered", d=10_000, n=50_000, clusters=1_250, spread=0.3,
                           support_frac=0.02, c_lambda=0.05, m=5_000, rounds=50),
+    # the 100 GB workload with columns in 12,500 groups of 40 near-duplicates (on demand only:
+    # `bench.py --workload cfg5clustered`)
+    "cfg5clustered": dict(kind="lasso_dense", d=50_000, n=500_000, support_frac=0.005, c_lambda=0.05,
+                          clusters=12_500, spread=0.3, m=50_000, rounds=20),
     # the shape of the paper's large-scale SVM experiment (Section 5.3: 40,000 samples with 200,704
     # dense single-precision features, 30 GB, a quarter of them on the accelerator)
     "fig5svm": dict(kind="svm_dense", n=40_000, d=200_704, m=10_000, rounds=20),
