@@ -53,8 +53,10 @@ def counter_traffic(workload, which, kernels):
 def dominant_kernels(prob, cd_mode):
     """Names of the kernels behind the two roofline objects, as the profiler prints them."""
     if "cols" in prob:
-        return ["gap_dense_kernel"], (["cd_dense_worker_kernel", "merge_workers_kernel"] if cd_mode == "async"
-                                      else ["cd_dense_atomic_kernel"])
+        # (columns of more than 51,200 entries: the gap pass that keeps v on chip, in parts of 100 KB)
+        gap = ["gap_dense_kernel"] if prob["d"] * 4 <= 2 * 102400 else ["gap_dense_lds_kernel", "gap_lds_finish_kernel"]
+        return gap, (["cd_dense_worker_kernel", "merge_workers_kernel"] if cd_mode == "async"
+                     else ["cd_dense_atomic_kernel"])
     return ["csr_sliced_dot_kernel", "csr_blocked_finish_kernel"], ["cd_csr_plan_kernel", "cd_csr_async_kernel"]
 
 

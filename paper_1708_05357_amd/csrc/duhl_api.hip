@@ -291,6 +291,7 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->cd_units = env_int("DUHL_CD_UNITS", 0);
     c->cd_spin_limit = env_int("DUHL_CD_SPIN_LIMIT", 1 << 22);
     if (c->cd_spin_limit < 0) c->cd_spin_limit = 0;
+    c->gap_lds = env_int("DUHL_GAP_LDS", 1);
     c->cd_guard = env_int("DUHL_CD_GUARD", 1);
     c->keep_first_pass = env_int("DUHL_KEEP_FIRST_PASS", 1);
     c->guard_tol = 1e-6;
@@ -761,6 +762,7 @@ void duhl_destroy(duhl_ctx *c)
     (void)hipFree(c->dv); (void)hipFree(c->dirty); (void)hipFree(c->score); (void)hipFree(c->xch);
     (void)hipFree(c->cd_plan);
     (void)hipFree(c->guard_wbook);
+    (void)hipFree(c->gap_pdot);
     (void)hipFree(c->guard); (void)hipFree(c->guard_part); (void)hipFree(c->snap_pass_v); (void)hipFree(c->alpha_old);
     if (c->h_trips) (void)hipHostFree(c->h_trips);
     for (hipEvent_t ev : c->ev_pass)

@@ -344,6 +344,9 @@ struct duhl_ctx {
     uint32_t *h_trips_dev;      // them without waiting ([0], [1])
     int keep_first_pass;        // 0: the first pass over a staged matrix keeps no columns (DUHL_KEEP_FIRST_PASS)
     int64_t kept_first_pass;    // columns that pass left in device slots
+    int gap_lds;                // 0: the dense gap pass never keeps v on chip (DUHL_GAP_LDS)
+    float *gap_pdot;            // partial dot products of that pass when v takes several parts
+    int64_t gap_pdot_cap;
     int cd_guard;               // 0: guard switched off (DUHL_CD_GUARD)
     double guard_tol;           // relative rise of the objective that still counts as rounding
     int guard_start;            // halvings of the bound in force right after set_data

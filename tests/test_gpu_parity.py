@@ -29,11 +29,14 @@ def lasso_problem(d, n, frac=0.1, c=0.1, seed=0):
 
 # ------------------------------------------------------------------------------------ gaps
 @pytest.mark.parametrize("d,n,ld", [(1000, 500, None), (1003, 37, None), (64, 9, None), (1, 5, None),
-                                    (257, 130, 300), (4100, 67, 4104), (10, 3, 13)])
+                                    (257, 130, 300), (4100, 67, 4104), (10, 3, 13),
+                                    (60000, 1400, None), (60002, 1500, 60004)])
 def test_dense_lasso_gaps_match_oracle(G, d, n, ld):
     """App. E (Lasso): z from the first pass of set_data, from a full pass at a later state, and
     from an index-list refresh; sizes cover whole tiles, ragged tails, unaligned leading
-    dimensions (scalar path) and fewer columns than one wavefront group."""
+    dimensions (scalar path) and fewer columns than one wavefront group.  The last two have
+    columns long enough (three parts of v) for the pass that keeps v on chip, one of them with
+    d % 4 != 0."""
     from paper_1708_05357_amd import duhl
     p = G.Pair(lasso_problem(d, n, 0.2, 0.1, seed=d + n), ld=ld)
     np.testing.assert_allclose(p.g.get(duhl.SQNORM), p.o.q, rtol=2e-6)
@@ -69,7 +72,8 @@ def test_dense_lasso_gaps_match_oracle(G, d, n, ld):
 def test_svm_gaps_match_oracle_dense_and_csr(G):
     """App. E (SVM): all gaps equal 1/n at alpha = 0; parity after some passes, both storages."""
     from paper_1708_05357_amd import duhl, synth
-    for prob in (synth.svm_dense(300, 41, seed=3), synth.svm_csr(1500, 400, 0.02, seed=4)):
+    for prob in (synth.svm_dense(300, 41, seed=3), synth.svm_csr(1500, 400, 0.02, seed=4),
+                 synth.svm_dense(1400, 60000, seed=5)):          # long columns: v on chip, three parts
         p = G.Pair(prob)
         n = prob["n"]
         np.testing.assert_allclose(p.g.get(duhl.Z), np.full(n, 1.0 / n), rtol=1e-6)
