@@ -369,6 +369,15 @@ def time_to_gap_native(g, set_data, prob, m, target, mode, inflight, rule, passe
         else:
             out[f"{name}_true_total_gap"] = g.gap()
     out["passes_per_round"] = passes
+    if not prob["host_resident"]:
+        # the same loop choosing its own passes per round (options passes = 0: one pass in the first
+        # round, then round(sqrt(refresh time / pass time)) + 1)
+        set_data()
+        torch.cuda.synchronize()
+        st = g.run(m, 400, passes=0, mode=mode, gap_tol=target, max_inflight=inflight, rule=rule, seed=1000)
+        out["auto_passes"] = {"abs_1e-3_s": st["seconds"] if st["converged"] else None, "rounds": st["rounds"],
+                              "passes": st["passes"], "passes_per_round": st["passes_per_round"],
+                              "true_total_gap": g.gap()}
     return out
 
 

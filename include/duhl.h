@@ -312,7 +312,11 @@ duhl_status duhl_cd_stats(duhl_ctx *ctx, int64_t *passes_damped, int64_t *inflig
  * Requires data, no pending selection; 1 <= m <= min(n, budget_cols). */
 typedef struct duhl_run_opts {
     int64_t m;                  /* working-set size                                              */
-    int passes;                 /* theta of Section 5.2: passes per round, >= 1                  */
+    int passes;                 /* theta of Section 5.2: passes per round, >= 1.  0: chosen by the loop --
+                                   the first round runs one pass and times its two phases (refresh +
+                                   selection: G, one pass: C); from the second round on
+                                   round(sqrt(G/C)) + 1 passes, at most 8 (a selection that costs many
+                                   passes is worth several of them, cf. Section 5.2); host residency: 8 */
     duhl_cd_mode mode;
     int max_inflight;           /* as for duhl_cd_epoch                                          */
     duhl_select_rule rule;
@@ -356,6 +360,7 @@ typedef struct duhl_run_stats {
     double seconds;             /* wall time of the call                                         */
     int inflight_halvings;      /* times adapt_inflight went back and halved the bound           */
     int inflight_last;          /* max_inflight in force at the end (0: the library's own bound) */
+    int passes_per_round;       /* passes per round in force at the end (what passes = 0 chose)  */
 } duhl_run_stats;
 
 duhl_status duhl_run(duhl_ctx *ctx, const duhl_run_opts *opts, duhl_run_stats *stats);

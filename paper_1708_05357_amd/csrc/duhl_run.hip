@@ -63,9 +63,9 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
     if (!c) return DUHL_EINVAL;
     if (!o || !out) return set_error(c, DUHL_EINVAL, "options or statistics pointer is NULL");
     if (!c->have_data) return set_error(c, DUHL_ESTATE, "no data set");
-    if (o->passes < 1 || o->max_rounds < 0 || o->check_every < 0 || o->max_inflight < 0 || o->max_extra_passes < 0)
+    if (o->passes < 0 || o->max_rounds < 0 || o->check_every < 0 || o->max_inflight < 0 || o->max_extra_passes < 0)
         return set_error(c, DUHL_EINVAL,
-                         "passes >= 1, max_rounds >= 0, check_every >= 0, max_inflight >= 0, max_extra_passes >= 0 required");
+                         "passes >= 0, max_rounds >= 0, check_every >= 0, max_inflight >= 0, max_extra_passes >= 0 required");
     if (std::isnan(o->gap_tol)) return set_error(c, DUHL_EINVAL, "gap_tol is NaN");
     const bool host = c->res == DUHL_RESIDENT_HOST;
     const bool threads = o->host_threads > 0;
@@ -86,7 +86,25 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
     int inflight = o->max_inflight;                         // 0: the library's own bound
     double good_objective = 0.0;
     bool have_good = false;
+    // passes per round; 0 in the options: one in the first round, whose two phases are timed, then
+    // by the rule stated with the options (host residency: 8, the passes are also the time unit A's
+    // threads and the column copies have)
+    int passes = o->passes > 0 ? o->passes : (host ? 8 : 1);
+    bool timing = o->passes == 0 && !host;
+    struct Events {                                         // destroyed on every way out
+        hipEvent_t e[3] = {nullptr, nullptr, nullptr};
+        ~Events()
+        {
+            for (hipEvent_t x : e)
+                if (x) (void)hipEventDestroy(x);
+        }
+    } events;
+    hipEvent_t *ev = events.e;
+    if (timing)
+        for (int k = 0; k < 3; ++k)
+            if (hipEventCreate(&ev[k]) != hipSuccess) timing = false;
     for (int64_t rnd = 0; rnd < o->max_rounds; ++rnd) {
+        if (timing && rnd == 0 && hipEventRecord(ev[0], c->compute) != hipSuccess) timing = false;
         // -- guard of the concurrent passes ----------------------------------------------------
         // Exact coordinate steps never raise the objective; steps taken concurrently can, when the
         // columns worked on at once are more alike than the bound on their number assumed (e.g. a
@@ -171,6 +189,7 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
             }
         }
         // -- passes over the working set, next to the column copies when they may overlap ----
+        if (timing && rnd == 0 && hipEventRecord(ev[1], c->compute) != hipSuccess) timing = false;
         const bool overlap = host && c->m_cur > 0 && !c->swap_exclusive;
         if (!overlap) {
             st = duhl_commit_swap(c);
@@ -183,8 +202,18 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
             st = duhl_host_sample_begin(c, o->sample_host + cursor, begun, o->host_threads);
             if (st != DUHL_OK) return st;
         }
-        for (int k = 0; k < o->passes && st == DUHL_OK; ++k)
-            st = duhl_cd_epoch(c, o->mode, nullptr, 0, o->seed + (uint64_t)(rnd * o->passes + k), inflight);
+        for (int k = 0; k < passes && st == DUHL_OK; ++k)
+            st = duhl_cd_epoch(c, o->mode, nullptr, 0, o->seed + (uint64_t)(rnd * 64 + k), inflight);
+        if (timing && rnd == 0 && st == DUHL_OK) {
+            float g_ms = 0.0f, c_ms = 0.0f;
+            if (hipEventRecord(ev[2], c->compute) == hipSuccess && hipEventSynchronize(ev[2]) == hipSuccess &&
+                hipEventElapsedTime(&g_ms, ev[0], ev[1]) == hipSuccess &&
+                hipEventElapsedTime(&c_ms, ev[1], ev[2]) == hipSuccess && c_ms > 0.0f) {
+                const long t = std::lround(std::sqrt((double)g_ms / (double)c_ms)) + 1;
+                passes = (int)(t < 1 ? 1 : (t > 8 ? 8 : t));
+            }
+            timing = false;
+        }
         // theta sized to the copy: unit B works on while its next working set is still arriving.  One
         // pass at a time, each waited for, so that the host does not enqueue passes for longer than
         // the copies last.
@@ -217,10 +246,11 @@ extern "C" duhl_status duhl_run(duhl_ctx *c, const duhl_run_opts *o, duhl_run_st
             if (st != DUHL_OK) return st;
         }
         s.rounds = rnd + 1;
-        s.passes += o->passes + extra;
+        s.passes += (rnd == 0 && o->passes == 0 && !host ? 1 : passes) + extra;
     }
     if (hipStreamSynchronize(c->compute) != hipSuccess) return set_error(c, DUHL_EHIP, "stream synchronisation failed");
     s.inflight_last = inflight;
+    s.passes_per_round = passes;
     s.seconds = std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
     *out = s;
     return DUHL_OK;

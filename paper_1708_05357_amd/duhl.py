@@ -46,7 +46,7 @@ class RunStats(C.Structure):
     _fields_ = [("rounds", C.c_int64), ("passes", C.c_int64), ("converged", C.c_int), ("confirmations", C.c_int),
                 ("gap_memory_sum", C.c_double), ("rho", C.c_double), ("columns_swapped", C.c_int64),
                 ("host_sampled", C.c_int64), ("seconds", C.c_double), ("inflight_halvings", C.c_int),
-                ("inflight_last", C.c_int)]
+                ("inflight_last", C.c_int), ("passes_per_round", C.c_int)]
 
 
 class DuhlError(RuntimeError):
@@ -262,7 +262,8 @@ class Duhl:
     def run(self, m, max_rounds, passes=1, mode=CD_ASYNC, gap_tol=-1.0, max_inflight=0, rule=SELECT_GAP,
             seed=0, check_every=1, sample=None, sample_per_round=0, host_threads=0, confirm=False,
             adapt_inflight=True, host_wait_all=False, max_extra_passes=0):
-        """The native round loop.  sample: int32 device tensor with the coordinates whose gaps are
+        """The native round loop (passes = 0: the loop chooses the passes per round from the measured cost
+        of a refresh and of a pass).  sample: int32 device tensor with the coordinates whose gaps are
         refreshed window by window (None: see duhl_run); returns a dict of the statistics."""
         o = RunOpts(m=int(m), passes=int(passes), mode=mode, max_inflight=int(max_inflight), rule=rule,
                     seed=int(seed), max_rounds=int(max_rounds), gap_tol=float(gap_tol),

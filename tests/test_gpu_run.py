@@ -497,6 +497,29 @@ def test_stale_memory_rounds_match_the_oracle_round_by_round(G, kind):
     p.close()
 
 
+def test_native_loop_chooses_its_passes_per_round(G):
+    """passes = 0 in the options: one pass in the first round, then a number between 1 and 8 from the
+    measured cost of a refresh and of a pass; the loop converges to the same optimum (objective of
+    the oracle's rounds to 1e-5) and accounts for its passes."""
+    from paper_1708_05357_amd import duhl
+    prob = _lasso(3000, 4000, 0.05, 0.1, seed=61)
+    m = 400
+    p = G.Pair(prob)
+    st = p.g.run(m, 200, passes=0, mode=duhl.CD_ASYNC, gap_tol=1e-6, seed=3)
+    assert st["converged"] == 1
+    ppr = st["passes_per_round"]
+    assert 1 <= ppr <= 8
+    assert st["passes"] == 1 + (st["rounds"] - 1) * ppr
+    print(f"passes per round chosen: {ppr}; {st['rounds']} rounds, {st['passes']} passes")
+    rng = np.random.default_rng(0)
+    for _ in range(200):
+        p.o.round(m, passes=1, rng=rng)
+    assert abs(p.g.objective() - p.o.objective()) <= 1e-5 * abs(p.o.objective())
+    with pytest.raises(duhl.DuhlError):
+        p.g.run(m, 1, passes=-1)
+    p.close()
+
+
 @pytest.mark.parametrize("pageable", [False, True])
 def test_extra_passes_while_the_copies_are_in_flight(G, pageable):
     """theta sized to the copy (Sec. 5.2) in the native loop: with max_extra_passes the rounds run
