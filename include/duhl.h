@@ -146,7 +146,10 @@ duhl_status duhl_set_data_csr(duhl_ctx *ctx, const int64_t *rowptr, const int32_
  * duplicates) lists the `count` coordinates to refresh; idx == NULL refreshes all n coordinates (device residency) or every
  * column currently held in a device slot (host residency), and count is then ignored.  Other
  * entries of z keep their (stale) values.  gap_sum (host, may be NULL): sum of the entries
- * written, the total gap when all were asked for; non-NULL makes the call wait. */
+ * written, the total gap when all were asked for; non-NULL makes the call wait.
+ * Device residency, idx == NULL, and alpha, v, z untouched since duhl_set_data_* (no pass, no
+ * duhl_set, no device pointer to them handed out): z still holds the gaps of set_data's own full
+ * pass, and the call returns their sum without computing them again. */
 duhl_status duhl_gap(duhl_ctx *ctx, const int32_t *idx, int64_t count, double *gap_sum);
 
 /* duhl_gap for callers that cannot allocate device memory -- code under HIP graph capture, tight

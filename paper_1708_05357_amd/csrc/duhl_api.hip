@@ -165,6 +165,15 @@ duhl_status finish_set_data(duhl_ctx *c, const float *target, double lambda)
     }
     HIPCHK(c, hipStreamSynchronize(c->compute));
     HIPCHK(c, hipGetLastError());
+    // the first pass has left every gap at alpha = 0 in z: a full duhl_gap before anything moves
+    // would only compute the same again
+    c->z_fresh = false;
+    if (c->res == DUHL_RESIDENT_DEVICE && !c->ptr_escaped) {
+        duhl_status st = read_scalars(c, S_GAP_SUM, 1);
+        if (st != DUHL_OK) return st;
+        c->z_fresh_sum = c->h_scalars[S_GAP_SUM];
+        c->z_fresh = true;
+    }
     return DUHL_OK;
 }
 
@@ -344,6 +353,7 @@ duhl_status duhl_set_eta(duhl_ctx *c, double eta)
     if (c->model != DUHL_ELASTIC_NET) return fail(c, DUHL_EINVAL, "eta applies to DUHL_ELASTIC_NET only");
     if (!(eta > 0.0) || !(eta <= 1.0)) return fail(c, DUHL_EINVAL, "eta must be in (0, 1]");
     c->eta = eta;
+    c->z_fresh = false;
     return DUHL_OK;
 }
 
@@ -417,6 +427,10 @@ duhl_status duhl_gap(duhl_ctx *c, const int32_t *idx, int64_t count, double *gap
     if (!c) return DUHL_EINVAL;
     if (!c->have_data) return fail(c, DUHL_ESTATE, "no data set");
     if (idx && (count < 0 || count > c->n)) return fail(c, DUHL_EINVAL, "count out of range");
+    if (!idx && c->z_fresh) {                       // nothing has moved since set_data's own full pass
+        if (gap_sum) *gap_sum = c->z_fresh_sum;
+        return DUHL_OK;
+    }
     HIPCHK(c, hipSetDevice(c->device));
     if (idx)
         HIPCHK(c, launch_gap(c, idx, count, false, false));
@@ -520,6 +534,7 @@ duhl_status duhl_cd_epoch(duhl_ctx *c, duhl_cd_mode mode, const int32_t *order, 
     if (order && n_order < 0) return fail(c, DUHL_EINVAL, "n_order is negative");
     if (max_inflight < 0) return fail(c, DUHL_EINVAL, "max_inflight is negative");
     HIPCHK(c, hipSetDevice(c->device));
+    c->z_fresh = false;
     HIPCHK(c, launch_cd(c, mode, order, n_order, seed, max_inflight));
     c->pass_counter++;
     return DUHL_OK;
@@ -568,6 +583,7 @@ duhl_status duhl_recompute_v(duhl_ctx *c)
     if (!c) return DUHL_EINVAL;
     if (!c->have_data) return fail(c, DUHL_ESTATE, "no data set");
     HIPCHK(c, hipSetDevice(c->device));
+    c->z_fresh = false;
     HIPCHK(c, launch_init_v(c));
     HIPCHK(c, launch_accumulate_v(c));
     return DUHL_OK;
@@ -670,6 +686,7 @@ duhl_status duhl_set(duhl_ctx *c, duhl_what what, const void *src, int64_t len)
     if (len != n) return fail(c, DUHL_EINVAL, "len (%lld) must be %lld", (long long)len, (long long)n);
     HIPCHK(c, hipSetDevice(c->device));
     HIPCHK(c, hipStreamSynchronize(c->compute));
+    c->z_fresh = false;
     HIPCHK(c, hipMemcpy(p, src, el * (size_t)n, hipMemcpyHostToDevice));
     return DUHL_OK;
 }
@@ -681,6 +698,10 @@ duhl_status duhl_device_ptr(duhl_ctx *c, duhl_what what, void **ptr)
     void *p; int64_t n; size_t el;
     duhl_status st = locate(c, what, &p, &n, &el);
     if (st != DUHL_OK) return st;
+    if (what == DUHL_ALPHA || what == DUHL_V || what == DUHL_Z) {   // the caller may write through it
+        c->ptr_escaped = true;
+        c->z_fresh = false;
+    }
     *ptr = p;
     return DUHL_OK;
 }

@@ -344,6 +344,9 @@ struct duhl_ctx {
     uint32_t *h_trips_dev;      // them without waiting ([0], [1])
     int keep_first_pass;        // 0: the first pass over a staged matrix keeps no columns (DUHL_KEEP_FIRST_PASS)
     int64_t kept_first_pass;    // columns that pass left in device slots
+    bool z_fresh;               // device residency: every z_i is the gap at the current (alpha, v) -- true from
+    double z_fresh_sum;         // set_data's pass until alpha, v or z change -- and this is their sum
+    bool ptr_escaped;           // the caller holds a device pointer to alpha, v or z: never assume z fresh
     int gap_lds;                // 0: the dense gap pass never keeps v on chip (DUHL_GAP_LDS)
     float *gap_pdot;            // partial dot products of that pass when v takes several parts
     int64_t gap_pdot_cap;

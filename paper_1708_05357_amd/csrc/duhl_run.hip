@@ -42,6 +42,7 @@ duhl_status snapshot(duhl_ctx *c, bool restore)
         e = hipMemcpyAsync(restore ? c->v : c->snap_v, restore ? c->snap_v : c->v, sizeof(float) * (size_t)c->d,
                            hipMemcpyDeviceToDevice, c->compute);
     if (e != hipSuccess) return set_error(c, e == hipErrorOutOfMemory ? DUHL_ENOMEM : DUHL_EHIP, hipGetErrorString(e));
+    if (restore) c->z_fresh = false;
     return DUHL_OK;
 }
 

@@ -1054,6 +1054,42 @@ def test_stream_read_probe(G):
     g.close()
 
 
+def test_first_gap_call_reuses_the_pass_of_set_data_and_nothing_later(G):
+    """set_data's own pass leaves every gap at alpha = 0 in z; a full duhl_gap before anything has moved
+    returns their sum without a second pass (z untouched: a poisoned entry written behind the
+    library's back through a device pointer is the only way to tell, and handing such a pointer out
+    switches the shortcut off).  After a pass, a duhl_set or duhl_recompute_v the gaps are computed."""
+    from paper_1708_05357_amd import duhl
+    prob = lasso_problem(500, 300, 0.2, 0.1, seed=12)
+    p = G.Pair(prob)
+    total0 = p.o.gaps()
+    assert p.g.gap() == pytest.approx(total0, rel=1e-4)
+    G.assert_gaps_close(p.g.get(duhl.Z), p.o.z)
+    z_dev = p.g.device_view(duhl.Z)                       # from here on every call computes
+    z_dev[7] = -5.0
+    assert p.g.gap() == pytest.approx(total0, rel=1e-4)
+    assert p.g.get(duhl.Z)[7] >= 0.0
+    p.close()
+    for change in ("pass", "set", "recompute"):
+        p = G.Pair(prob)
+        if change == "pass":
+            p.g.select(60)
+            p.g.commit_swap()
+            p.g.cd_epoch(duhl.CD_SEQUENTIAL)
+        elif change == "set":
+            a = np.zeros(prob["n"], dtype=np.float32)
+            a[3] = 0.25
+            p.g.set(duhl.ALPHA, a)
+            p.g.recompute_v()
+        else:
+            p.g.recompute_v()
+        p.sync_oracle_to_gpu_state()
+        total = p.g.gap()
+        assert total == pytest.approx(p.o.gaps(), rel=1e-4, abs=1e-7)
+        G.assert_gaps_close(p.g.get(duhl.Z), p.o.z, floor=G.gap_floor(p))
+        p.close()
+
+
 def test_scatter_add_probe_leaves_v_alone(G):
     """The second measurement aid: atomic adds of +0 to random elements of v.  v keeps its bits, the
     rate is a positive number, and the call needs data and sane arguments."""

@@ -106,7 +106,7 @@ def test_stale_gap_memory_windows_on_device_data(G):
     # windows wrap: a list that is not a multiple of the window, and bad arguments
     p.g.run(m, 5, sample=perm[:1000].contiguous(), sample_per_round=300)
     for bad in (dict(sample=perm, sample_per_round=0), dict(sample=perm, sample_per_round=n + 1),
-                dict(passes=0), dict(check_every=-1)):
+                dict(passes=-1), dict(check_every=-1)):
         with pytest.raises(duhl.DuhlError) as e:
             p.g.run(m, 2, **bad)
         assert e.value.status == duhl.EINVAL
