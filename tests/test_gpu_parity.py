@@ -824,6 +824,43 @@ def test_list_entries_outside_the_problem_are_skipped(G):
         p.close()
 
 
+def test_long_column_gap_pass_skips_bad_entries_and_matches_the_other_kernel(G, monkeypatch):
+    """The gap pass that keeps v on chip (columns of more than 51,200 entries, long lists): entries
+    of the list that name no coordinate write nothing, a list shorter than one workgroup's share
+    falls back to the other kernel, and both kernels give the same gaps to fp32 rounding."""
+    from paper_1708_05357_amd import duhl
+    prob = lasso_problem(52000, 1500, 0.1, 0.1, seed=33)
+    n = prob["n"]
+    p = G.Pair(prob)
+    p.g.select(300)
+    p.g.commit_swap()
+    p.g.cd_epoch(duhl.CD_SEQUENTIAL)
+    p.sync_oracle_to_gpu_state()
+    p.o.gaps()
+    floor = G.gap_floor(p)
+    rng = np.random.default_rng(5)
+    good = rng.permutation(n)[:1400].astype(np.int32)
+    mixed = good.copy()
+    mixed[::7] = np.array([-1, n, 2 ** 31 - 1, -2 ** 31], dtype=np.int64)[np.arange(mixed[::7].size) % 4].astype(np.int32)
+    kept = np.setdiff1d(np.arange(1400), np.arange(0, 1400, 7))
+    p.g.set(duhl.Z, np.full(n, -1.0, dtype=np.float32))
+    part = p.g.gap(G.dev_i32(mixed))
+    z = p.g.get(duhl.Z)
+    written = np.flatnonzero(z >= 0)
+    assert np.array_equal(np.sort(written), np.sort(good[kept]))
+    G.assert_gaps_close(z[good[kept]], p.o.z[good[kept]], floor=floor[good[kept]], label="long columns, list with bad entries")
+    assert part == pytest.approx(float(p.o.z[good[kept]].sum()), rel=1e-4, abs=float(floor.sum()))
+    z_lds = p.g.get(duhl.Z).copy()
+    short = good[:100]                                      # 100 x 3 parts: fewer than 16 workgroups' worth
+    p.g.set(duhl.Z, np.full(n, -1.0, dtype=np.float32))
+    p.g.gap(G.dev_i32(short), want_sum=False)
+    z_short = p.g.get(duhl.Z)
+    both = np.intersect1d(short, good[kept])
+    assert np.count_nonzero(z_short >= 0) == 100
+    assert np.abs(z_short[both] - z_lds[both]).max() <= 2.0 * floor[both].max() + 1e-6 * np.abs(z_lds[both]).max()
+    p.close()
+
+
 def test_zero_columns_and_empty_rows(G):
     """Degenerate coordinates: a zero column (Lasso -> alpha_j = 0) and an empty CSR row
     (SVM -> alpha_j = y_j), both schemes."""
