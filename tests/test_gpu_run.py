@@ -497,6 +497,41 @@ def test_stale_memory_rounds_match_the_oracle_round_by_round(G, kind):
     p.close()
 
 
+def test_state_dumped_and_restored_continues_the_same_run(G):
+    """Checkpoint and resume with the getters and setters: alpha and z are dumped after three rounds,
+    a new context gets the data, alpha, v rebuilt from alpha (duhl_recompute_v) and z, and three more
+    rounds there give the iterates of six uninterrupted rounds (sequential steps, 1e-5: v rebuilt
+    from alpha differs from the running v by rounding only)."""
+    from paper_1708_05357_amd import duhl
+    prob = _lasso(700, 500, 0.1, 0.1, seed=70)
+    m = 80
+
+    def rounds(g, k):
+        for _ in range(k):
+            g.gap(want_sum=False)
+            g.select(m, want_stats=False)
+            g.commit_swap()
+            g.cd_epoch(duhl.CD_SEQUENTIAL)
+
+    p = G.Pair(prob)
+    rounds(p.g, 6)
+    want_a, want_v = p.g.get(duhl.ALPHA), p.g.get(duhl.V)
+    p.close()
+    q = G.Pair(prob)
+    rounds(q.g, 3)
+    dump_a, dump_z = q.g.get(duhl.ALPHA), q.g.get(duhl.Z)
+    q.close()
+    r = G.Pair(prob)
+    r.g.set(duhl.ALPHA, dump_a)
+    r.g.recompute_v()
+    r.g.set(duhl.Z, dump_z)
+    rounds(r.g, 3)
+    a, v = r.g.get(duhl.ALPHA), r.g.get(duhl.V)
+    assert np.abs(a - want_a).max() <= 1e-5 * np.abs(want_a).max()
+    assert np.abs(v - want_v).max() <= 1e-5 * np.abs(want_v).max()
+    r.close()
+
+
 def test_native_loop_chooses_its_passes_per_round(G):
     """passes = 0 in the options: one pass in the first round, then a number between 1 and 8 from the
     measured cost of a refresh and of a pass; the loop converges to the same optimum (objective of
