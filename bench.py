@@ -53,8 +53,11 @@ def counter_traffic(workload, which, kernels):
 def dominant_kernels(prob, cd_mode):
     """Names of the kernels behind the two roofline objects, as the profiler prints them."""
     if "cols" in prob:
-        # (columns of more than 51,200 entries: the gap pass that keeps v on chip, in parts of 100 KB)
-        gap = ["gap_dense_kernel"] if prob["d"] * 4 <= 2 * 102400 else ["gap_dense_lds_kernel", "gap_lds_finish_kernel"]
+        # (columns of more than 25,600 entries and at most 49,152 of them per pass: the gap pass that
+        # keeps v on chip, in parts of 100 KB)
+        count = 2 * prob["m"] if prob["host_resident"] else prob["n"]
+        lds = prob["d"] * 4 > 102400 and count <= 49152
+        gap = ["gap_dense_lds_kernel", "gap_lds_finish_kernel"] if lds else ["gap_dense_kernel"]
         return gap, (["cd_dense_worker_kernel", "merge_workers_kernel"] if cd_mode == "async"
                      else ["cd_dense_atomic_kernel"])
     return ["csr_sliced_dot_kernel", "csr_blocked_finish_kernel"], ["cd_csr_plan_kernel", "cd_csr_async_kernel"]

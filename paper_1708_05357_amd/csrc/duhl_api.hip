@@ -301,6 +301,9 @@ duhl_status duhl_create(duhl_ctx **out, duhl_model model, int64_t d, int64_t n, 
     c->cd_spin_limit = env_int("DUHL_CD_SPIN_LIMIT", 1 << 22);
     if (c->cd_spin_limit < 0) c->cd_spin_limit = 0;
     c->gap_lds = env_int("DUHL_GAP_LDS", 1);
+    c->gap_lds_min_parts = env_int("DUHL_GAP_LDS_MIN_PARTS", 2);
+    if (c->gap_lds_min_parts < 2) c->gap_lds_min_parts = 2;   // (one part: the formula would belong in the same kernel)
+    c->gap_lds_max_count = env_int("DUHL_GAP_LDS_MAX_COUNT", 49152);
     c->cd_guard = env_int("DUHL_CD_GUARD", 1);
     c->keep_first_pass = env_int("DUHL_KEEP_FIRST_PASS", 1);
     c->guard_tol = 1e-6;

@@ -348,6 +348,7 @@ struct duhl_ctx {
     double z_fresh_sum;         // set_data's pass until alpha, v or z change -- and this is their sum
     bool ptr_escaped;           // the caller holds a device pointer to alpha, v or z: never assume z fresh
     int gap_lds;                // 0: the dense gap pass never keeps v on chip (DUHL_GAP_LDS)
+    int64_t gap_lds_min_parts, gap_lds_max_count;   // where it does (DUHL_GAP_LDS_MIN_PARTS, DUHL_GAP_LDS_MAX_COUNT)
     float *gap_pdot;            // partial dot products of that pass when v takes several parts
     int64_t gap_pdot_cap;
     int cd_guard;               // 0: guard switched off (DUHL_CD_GUARD)

@@ -303,13 +303,17 @@ struct GapLaunch {
     float *pdot = nullptr;    // dense: room for parts * count partial dot products (nullptr: the kernel
     int64_t pdot_cap = 0;     // with v on chip is only used where one part holds all of v)
     int num_cu = 256;
-    bool lds = false;         // dense: the kernel with v on chip may be used
+    bool lds = false;         // dense: the kernel with v on chip may be used ...
+    int64_t lds_min_parts = 2, lds_max_count = 49152;   // ... for columns this long and lists this short
 };
 
 constexpr int64_t kLdsPartBytes = 102400;     // most of v that a workgroup of gap_dense_lds_kernel keeps on chip
-// Measured: columns of 50,000 entries (2 parts) and 10,000 (1 part) run 1 % and 5 % slower this way than with
-// COLS columns per wavefront; columns of 100,000 (4 parts) 4-21 % faster, of 200,704 (8 parts) 4 % faster.
-constexpr int64_t kLdsMinParts = 3;
+// Where it pays (defaults of DUHL_GAP_LDS_MIN_PARTS / DUHL_GAP_LDS_MAX_COUNT): columns of at least two parts
+// and lists of at most 49,152 entries.  The pass with COLS columns per wavefront has COLS whole columns as
+// its unit of work and is at its best on long lists; measured on lists of 5,000 / 10,000 / 20,000 / 40,000
+// entries, time with v on chip over time with COLS columns per wavefront: 0.85 / 0.91 / 0.99 / 0.96 for
+// columns of 50,000 entries, 0.82 / 0.91 / 1.01 / 0.97 for 100,000, 0.79 / 0.90 / 1.00 / 0.96 for 200,704;
+// 60,000 columns of 100,000 entries 1.04, the 500,000 columns of 50,000 entries of the largest workload 1.01.
 
 // Workgroups the launch of the gap kernels has for `count` list entries (= partial sums written).
 static int64_t gap_grid(const GapLaunch &L, int64_t count)
@@ -334,7 +338,8 @@ static hipError_t launch_gap_model(const GapLaunch &L, const GapArgs &a, int64_t
                                        (!a.cv.col_slot || (aligned16(a.cv.slots) && a.cv.ld_s % 4 == 0));
         // Long lists of long columns: v on chip, one column per wavefront (gap_dense_lds_kernel).
         const int64_t parts = (a.d * 4 + kLdsPartBytes - 1) / kLdsPartBytes;
-        if (L.lds && vec && !NORMS && !a.stage && parts >= kLdsMinParts && a.count * parts >= (int64_t)L.num_cu * 16) {
+        if (L.lds && vec && !NORMS && !a.stage && parts >= L.lds_min_parts && a.count <= L.lds_max_count &&
+            a.count * parts >= (int64_t)L.num_cu * 16) {
             GapArgs b = a;
             b.parts = (int)parts;
             if (L.pdot && parts * a.count <= L.pdot_cap) {
@@ -443,7 +448,9 @@ hipError_t launch_gap(duhl_ctx *c, const int32_t *idx, int64_t count, bool slot_
     L.stream = c->compute;
     L.num_cu = c->num_cu;
     L.lds = c->gap_lds != 0 && !c->sparse && !with_norms;
-    if (L.lds && c->d * 4 > (kLdsMinParts - 1) * kLdsPartBytes) {
+    L.lds_min_parts = c->gap_lds_min_parts;
+    L.lds_max_count = c->gap_lds_max_count;
+    if (L.lds && c->d * 4 > (L.lds_min_parts - 1) * kLdsPartBytes) {
         // room for the partial dot products of a pass whose v does not fit one workgroup's LDS
         const int64_t parts = (c->d * 4 + kLdsPartBytes - 1) / kLdsPartBytes;
         const int64_t most = c->res == DUHL_RESIDENT_HOST && c->budget > c->n ? c->budget : c->n;
