@@ -99,13 +99,6 @@ __device__ __forceinline__ float4 buffer_load4(__amdgpu_buffer_rsrc_t rs, int vo
     return make_float4(__int_as_float(raw.x), __int_as_float(raw.y), __int_as_float(raw.z),
                        __int_as_float(raw.w));
 }
-// The same with the non-temporal hint, for column data that is read once per pass.
-__device__ __forceinline__ float4 buffer_stream4(__amdgpu_buffer_rsrc_t rs, int voff, int soff)
-{
-    const v4i_t raw = __builtin_amdgcn_raw_buffer_load_b128(rs, voff, soff, 2);
-    return make_float4(__int_as_float(raw.x), __int_as_float(raw.y), __int_as_float(raw.z),
-                       __int_as_float(raw.w));
-}
 // Column data whose start is only 4-byte aligned (leading dimension not a multiple of four floats):
 // the same 16 bytes as four dword loads.  STREAM selects the non-temporal hint.
 template <bool XVEC, bool STREAM>
