@@ -146,6 +146,15 @@ def measure_brief(name, rounds=10, host_threads=12):
     sample_idx, sample_host = make_samples(prob)
     for s in range(2):
         one_step(g, prob, m, s, sample_idx=sample_idx, passes=passes, host_threads=threads, sample_host=sample_host)
+    auto = None
+    if host:
+        # as `--workload cfg4` does: at least 8 passes per round, more while the round's copies run
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(g.compute_stream)
+        g.cd_epoch(duhl.CD_ASYNC, seed=99)
+        e1.record(g.compute_stream)
+        torch.cuda.synchronize()
+        auto = {"cd_ms": e0.elapsed_time(e1), "link_GBps": 55.0, "max_passes": 96, "passes": [], "min_passes": passes}
     set_data()
     if sample_host is not None:
         sample_host["cursor"] = 0
@@ -154,27 +163,28 @@ def measure_brief(name, rounds=10, host_threads=12):
     swap_log = [] if host else None
     t0 = time.time()
     for s in range(rounds):
-        one_step(g, prob, m, s, evs[s], sample_idx, passes=passes, swap_log=swap_log, host_threads=threads,
-                 sample_host=sample_host)
+        one_step(g, prob, m, s, evs[s], sample_idx, passes=0 if host else passes, swap_log=swap_log,
+                 host_threads=threads, sample_host=sample_host, auto=auto)
     torch.cuda.synchronize()
     elapsed = time.time() - t0
     steps_kept = g.cd_stats()[2]
     med = lambda x: sorted(x)[len(x) // 2]
     gap_ms = med([e[0].elapsed_time(e[1]) for e in evs])
-    cd_ms = med([e[2].elapsed_time(e[3]) for e in evs]) / passes
+    per_round = auto["passes"] if host else [passes] * rounds
+    cd_ms = med([e[2].elapsed_time(e[3]) / k for e, k in zip(evs, per_round)])
     gap_bytes, cd_bytes = algorithmic_bytes(prob, m)
     if host:
         gap_bytes = 4.0 * prob["d"] * g.resident_columns()
     out = {"workload": f"{prob['model']} d={prob['d']} n={prob['n']} m={m}"
                        + (" host-resident (pageable memory)" if host else ""),
-           "rounds": rounds, "passes_per_round": passes, "updates_per_s": steps_kept / elapsed,
-           "steps_kept": steps_kept, "steps_enqueued": m * passes * rounds,
+           "rounds": rounds, "passes_per_round": per_round if host else passes, "updates_per_s": steps_kept / elapsed,
+           "steps_kept": steps_kept, "steps_enqueued": m * sum(per_round),
            "ms_per_round": elapsed / rounds * 1e3, "gap_ms": gap_ms, "cd_pass_ms": cd_ms,
            "gap_GBps": gap_bytes / (gap_ms * 1e-3) / 1e9, "gap_frac": gap_bytes / (gap_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS,
            "cd_updates_per_s": m / (cd_ms * 1e-3), "cd_GBps": cd_bytes / (cd_ms * 1e-3) / 1e9,
            "cd_frac": cd_bytes / (cd_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
     if "val" in prob:
-        nnz_pass = float(prob["val"].numel()) / prob["n"] * (steps_kept / (passes * rounds))
+        nnz_pass = float(prob["val"].numel()) / prob["n"] * (steps_kept / sum(per_round))
         rate = g.probe_scatter_add(20_000_000, reps=3)
         out["cd_scatter_add_bound"] = {"adds_per_pass": nnz_pass, "adds_per_s_measured_peak": rate,
                                        "floor_ms": nnz_pass / rate * 1e3, "frac": nnz_pass / rate * 1e3 / cd_ms}
@@ -182,10 +192,14 @@ def measure_brief(name, rounds=10, host_threads=12):
         sw = [x for x in swap_log if "columns" in x]
         out["columns_swapped_per_round"] = [x["columns"] for x in sw]
         out["copy_ms_per_round"] = [round(x["copy_ms"], 3) for x in sw]
+        out["hidden_frac_per_round"] = [round(min(x["copy_ms"], e[2].elapsed_time(e[3])) / x["copy_ms"], 3)
+                                        if x["overlapped"] and x["copy_ms"] > 0 else 0.0 for x, e in zip(sw, evs)]
     if sample_host is not None:
         sample_host["cursor"] = 0
-    ttg = time_to_gap(g, set_data, prob, m, 1e-3, 400, passes=passes, sample_idx=sample_idx, host_threads=threads,
-                      sample_host=sample_host)
+    if auto is not None:
+        auto["passes"] = []
+    ttg = time_to_gap(g, set_data, prob, m, 1e-3, 400, passes=0 if host else passes, sample_idx=sample_idx,
+                      host_threads=threads, sample_host=sample_host, auto=auto)
     out["cd_guard"] = dict(zip(("passes_damped", "max_inflight_now"), g.cd_stats()[:2]))
     out["time_to_gap_s"] = ttg["abs_1e-3_s"]
     out["time_to_gap_rounds"] = ttg["rounds"]
