@@ -1355,7 +1355,7 @@ hipError_t launch_csr_subpasses(duhl_ctx *c, const CdArgs &a, int max_inflight)
     b.plan = static_cast<CdPlan *>(c->cd_plan);
     // guard: the plan kernel also keeps v and its sum of squares, a last kernel judges the pass
     const int64_t plan_blocks = (a.count + 255) / 256;
-    int64_t end_blocks = ((a.d > a.count ? a.d : a.count) + 4095) / 4096;
+    int64_t end_blocks = ((a.d > a.count ? a.d : a.count) + 1023) / 1024;
     if (end_blocks > 256) end_blocks = 256;
     if (end_blocks < 1) end_blocks = 1;
     MergeGuard g;
